@@ -1,0 +1,199 @@
+/*
+ * sgc.h -- C ABI of libsgc: cluster-shared KV-cache prefill attention for MI355X (gfx950).
+ *
+ * The library implements the GPU hot path of SubGCache (arXiv 2505.10951):
+ *   - Sec. 3.4 "Subgraph-level Cache Reuse": for every query cluster the prompt of its
+ *     representative subgraph is run ONCE and the per-layer attention K/V are kept in GPU
+ *     memory as a cluster-wise KV cache (sgc_prefix_prefill); every query of the cluster then
+ *     appends its own question tokens to that cached prompt (sgc_suffix_prefill_batched); when
+ *     the cluster is served the cache is released (sgc_cache_free_cluster).
+ *   - Sec. 3.2 "Query Clustering": clustering yields one cluster label per in-batch query;
+ *     sgc_assign_clusters turns the labels into the grouping the kernels run on.
+ * The paper processes clusters and queries one after another; this library runs all queries of
+ * all clusters of a batch in one launch per layer.
+ *
+ * What is computed (the paper does not write attention down; this is the textbook form):
+ *   scaled-dot-product attention, softmax over the visible keys, rotary position embedding in
+ *   the rotate-half pairing (channel t pairs with t + head_dim/2, angle = position *
+ *   rope_base^(-2t/head_dim)), grouped-query heads (KV head = query head / (n_q_heads /
+ *   n_kv_heads)).  Prefix token j sits at position j.  Suffix token i of a query whose cluster
+ *   has a prefix of P tokens sits at position P + i and sees all P cached keys plus suffix keys
+ *   0..i of its own query; it never sees another query's tokens.
+ *
+ * Conventions
+ *   - Every function returns SGC_OK (0) or a negative sgc_status.  Nothing throws, aborts or
+ *     prints.  sgc_last_error() gives a readable message for the last failure on that context.
+ *   - "dev" pointers are device (HBM) addresses, 16-byte aligned, owned by the caller (for
+ *     example torch tensors); "host" pointers are ordinary host memory.  The library keeps no
+ *     reference to q/k/v/o buffers after the call's work has been enqueued on the stream; the
+ *     caller must keep them alive until that stream work has finished.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Launches are
+ *     asynchronous on it.
+ *   - Argument checking happens on the host before anything is enqueued.
+ *   - The library allocates small device-side metadata of its own (rotary table, page tables,
+ *     plan arrays, fp8 scales) the first time a launch needs them; the big buffers (page pool,
+ *     q/k/v/o) are always the caller's.
+ *   - Token-major tensor layout everywhere at the boundary: [tokens][heads][head_dim], row-major,
+ *     contiguous, element type io_dtype.
+ *   - A context, its caches and plans are not thread-safe; use them from one host thread at a time.
+ */
+#ifndef SGC_H
+#define SGC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SGC_OK = 0,
+    SGC_EINVAL = -1,       /* NULL / misaligned pointer, value out of range */
+    SGC_ENOMEM = -2,       /* page pool exhausted, or a host/device allocation failed */
+    SGC_ESHAPE = -3,       /* shapes inconsistent with the context or the cache */
+    SGC_EUNSUPPORTED = -4, /* head_dim / dtype combination no kernel covers */
+    SGC_EHIP = -5,         /* a HIP runtime call failed (message has the HIP error string) */
+    SGC_ESTATE = -6        /* object used in the wrong state (cluster not allocated, ...) */
+} sgc_status;
+
+typedef enum { SGC_F32 = 0, SGC_BF16 = 1, SGC_FP8_E4M3 = 2 } sgc_dtype;
+
+/* Which attention kernel family sgc_*_prefill use. */
+typedef enum {
+    SGC_KERNEL_AUTO = 0,    /* MFMA when it covers the shape, else generic */
+    SGC_KERNEL_GENERIC = 1, /* fp32-arithmetic kernel, any supported shape/dtype */
+    SGC_KERNEL_MFMA = 2     /* bf16 MFMA kernel: io bf16, kv bf16|fp8, head_dim 128 */
+} sgc_kernel_kind;
+
+/* Plain data, filled by the caller.  struct_size = sizeof(sgc_attn_params). */
+typedef struct {
+    uint32_t struct_size;
+    int32_t n_q_heads;     /* Hq, multiple of n_kv_heads */
+    int32_t n_kv_heads;    /* Hkv */
+    int32_t head_dim;      /* d: 64 or 128 */
+    int32_t n_layers;      /* layers the cache holds, >= 1 */
+    int32_t page_tokens;   /* tokens per cache page: 16 */
+    int32_t io_dtype;      /* sgc_dtype of q/k/v/o: SGC_F32 or SGC_BF16 */
+    int32_t kv_dtype;      /* sgc_dtype of the cache: io_dtype, or SGC_FP8_E4M3 with io bf16 */
+    float rope_base;       /* e.g. 10000, 500000; 0 = no rotation (inputs already rotated) */
+    float softmax_scale;   /* 0 = 1/sqrt(head_dim) */
+    int32_t max_position;  /* hint: largest prefix_len + suffix_len expected (rotary table size);
+                              0 = grow on demand */
+    int32_t kernel;        /* sgc_kernel_kind */
+} sgc_attn_params;
+
+typedef struct sgc_ctx sgc_ctx;
+typedef struct sgc_cache sgc_cache;
+typedef struct sgc_plan sgc_plan;
+
+/* Sizes a caller can read back from a plan (all host integers). */
+typedef struct {
+    int32_t n_queries;
+    int32_t n_clusters;
+    int64_t total_tokens;   /* T = sum of suffix_len */
+    int32_t max_position;   /* max over queries of prefix_len + suffix_len */
+    int32_t tile_rows;      /* rows one workgroup handles (0 until uploaded) */
+    int32_t n_tiles;        /* workgroups in the suffix launch (0 until uploaded) */
+} sgc_plan_info;
+
+const char *sgc_version(void);
+const char *sgc_status_string(int status);
+
+/* ---- context --------------------------------------------------------------------------------
+ * Host-only: validates the parameters, touches no device.  SGC_EUNSUPPORTED for shapes/dtypes no
+ * kernel covers, SGC_EINVAL for malformed values. */
+int sgc_ctx_create(const sgc_attn_params *params, sgc_ctx **out);
+int sgc_ctx_destroy(sgc_ctx *ctx); /* frees the context's device metadata; NULL is a no-op */
+const char *sgc_last_error(const sgc_ctx *ctx);
+
+/* ---- cluster-wise KV cache (Sec. 3.4: one cache per cluster, released after the cluster) -----
+ *
+ * The cache is a pool of fixed-size pages of page_tokens tokens.  One page id addresses one
+ * slab in EVERY layer, holding that page's K and V for all KV heads:
+ *     pool[layer][page][K|V][kv_head][page_tokens * head_dim]      (element type kv_dtype)
+ * A cluster with a prefix of P tokens owns ceil(P / page_tokens) pages; token j lives in the
+ * cluster's page j / page_tokens.  Inside a page K (after rotation) and V are stored in the
+ * order the matrix-core operands are read in, not token-major; use sgc_cache_export /
+ * sgc_cache_import to move between that and the canonical [P][Hkv][d] layout.
+ * With kv_dtype = SGC_FP8_E4M3 each (cluster, layer, kv head) has one fp32 scale for K and one
+ * for V: stored code = round_to_nearest_even(x / scale), scale = max|x| / 448 (1 if all zero),
+ * OCP E4M3 with saturation; K is scaled after rotation.
+ */
+size_t sgc_cache_page_bytes(const sgc_attn_params *params);                 /* one page, one layer */
+size_t sgc_cache_pool_bytes(const sgc_attn_params *params, int64_t total_pages); /* all layers */
+
+/* dev_pool: caller-owned device memory of pool_bytes bytes, 256-byte aligned; the library only
+ * indexes it.  The number of pages is pool_bytes / (n_layers * page_bytes).  Host-only. */
+int sgc_cache_create(sgc_ctx *ctx, void *dev_pool, size_t pool_bytes, int32_t max_clusters,
+                     sgc_cache **out);
+int sgc_cache_destroy(sgc_cache *cache);
+/* Reserve pages for a cluster (host-only bookkeeping).  SGC_ENOMEM if the pool cannot hold it
+ * (nothing is changed then), SGC_ESTATE if the cluster is already allocated. */
+int sgc_cache_alloc_cluster(sgc_cache *cache, int32_t cluster_id, int32_t prefix_len);
+/* Release a cluster's pages.  The caller must make sure no enqueued launch still reads them. */
+int sgc_cache_free_cluster(sgc_cache *cache, int32_t cluster_id);
+int64_t sgc_cache_total_pages(const sgc_cache *cache);
+int64_t sgc_cache_free_pages(const sgc_cache *cache);
+/* Copies up to cap page ids of the cluster into out_pages (may be NULL); returns the number of
+ * pages the cluster owns (>= 0) or a negative status; *out_prefix_len (may be NULL) gets P. */
+int sgc_cache_cluster_pages(const sgc_cache *cache, int32_t cluster_id, int32_t *out_pages,
+                            int32_t cap, int32_t *out_prefix_len);
+
+/* ---- prefix prefill (Sec. 3.4: run the representative prompt once, keep its K/V) -------------
+ * One cluster, one layer.  dev_k, dev_v: [prefix_len][Hkv][d], before rotation.  Rotates K at
+ * positions 0..prefix_len-1 and writes K and V into the cluster's pages (quantising when the
+ * cache is fp8); the unused tail of the last page is zeroed.
+ * dev_q / dev_o: [prefix_len][Hq][d] or both NULL.  When given, o receives the causal
+ * self-attention of the prefix (row i sees keys 0..i, read back from the cache as stored) and
+ * dev_lse (may be NULL) [Hq][prefix_len] fp32 the natural-log log-sum-exp of the scaled scores.
+ * prefix_len must equal the length given to sgc_cache_alloc_cluster. */
+int sgc_prefix_prefill(sgc_ctx *ctx, sgc_cache *cache, int32_t cluster_id, int32_t layer,
+                       const void *dev_q, const void *dev_k, const void *dev_v, void *dev_o,
+                       float *dev_lse, int32_t prefix_len, void *hip_stream);
+
+/* ---- query -> cluster -> cache mapping (Sec. 3.2 labels; Sec. 3.4 cluster-wise serving) ------
+ * Host-only, deterministic.  labels[n] in [0, n_clusters) is query n's cluster, suffix_len[n]
+ * >= 0 its number of question tokens.  Every cluster that has at least one query must be
+ * allocated in `cache` (its prefix length is read from there).
+ * Outputs (caller-allocated host arrays, int32):
+ *   order[n_queries]        queries grouped by cluster, original order kept inside a cluster
+ *   cluster_off[n_clusters+1]  order[cluster_off[c] .. cluster_off[c+1]) are cluster c's queries
+ *   cu_seqlens[n_queries+1] first token row of each query in the packed q/k/v/o arrays, which
+ *                           stay in ORIGINAL query order
+ * *out_plan receives an opaque plan for sgc_suffix_prefill_batched; it stays valid while the
+ * clusters it names keep their allocation. */
+int sgc_assign_clusters(sgc_ctx *ctx, const sgc_cache *cache, int32_t n_queries,
+                        const int32_t *labels, const int32_t *suffix_len, int32_t n_clusters,
+                        int32_t *order, int32_t *cluster_off, int32_t *cu_seqlens,
+                        sgc_plan **out_plan);
+/* Copies the plan's work lists to the device (allocates them).  Optional: the first
+ * sgc_suffix_prefill_batched call does it otherwise.  Synchronises the stream. */
+int sgc_plan_upload(sgc_plan *plan, void *hip_stream);
+int sgc_plan_get_info(const sgc_plan *plan, sgc_plan_info *out);
+int sgc_plan_destroy(sgc_plan *plan);
+
+/* ---- batched suffix prefill (Sec. 3.4: each query appends its tokens to the cached prompt) ---
+ * One launch for every query of every cluster in the plan, one layer.
+ * dev_q, dev_o: [T][Hq][d]; dev_k, dev_v: [T][Hkv][d]; packed in original query order by
+ * cu_seqlens; before rotation.  dev_lse (may be NULL): [Hq][T] fp32, natural log.
+ * o rows are written for every token of every query; nothing else is touched. */
+int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cache, sgc_plan *plan, int32_t layer,
+                               const void *dev_q, const void *dev_k, const void *dev_v,
+                               void *dev_o, float *dev_lse, void *hip_stream);
+
+/* ---- canonical view of a cluster's cache (tests, checkpointing) -----------------------------
+ * dev_k, dev_v: [prefix_len][Hkv][d] in kv_dtype (raw e4m3 codes for fp8); K is the rotated K.
+ * host_k_scale, host_v_scale: [Hkv] fp32 (written by export / read by import; ignored and may
+ * be NULL unless the cache is fp8).  Export synchronises the stream before returning. */
+int sgc_cache_export(sgc_ctx *ctx, const sgc_cache *cache, int32_t cluster_id, int32_t layer,
+                     void *dev_k, void *dev_v, float *host_k_scale, float *host_v_scale,
+                     void *hip_stream);
+int sgc_cache_import(sgc_ctx *ctx, sgc_cache *cache, int32_t cluster_id, int32_t layer,
+                     const void *dev_k, const void *dev_v, const float *host_k_scale,
+                     const float *host_v_scale, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SGC_H */

@@ -1,0 +1,694 @@
+// Host side of libsgc: argument checking, the cluster-wise page allocator, the query->cluster
+// planner and the C ABI.  Follows SubGCache (arXiv 2505.10951) Sec. 3.2 (cluster labels per
+// query) and Sec. 3.4 (one KV cache per cluster: compute once, reuse for every query of the
+// cluster, release).
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <numeric>
+
+#include "sgc_internal.h"
+
+using namespace sgc;
+
+namespace {
+
+thread_local std::string g_err_noctx;
+
+int fail(sgc_ctx *ctx, int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    if (ctx)
+        ctx->err = buf;
+    else
+        g_err_noctx = buf;
+    return code;
+}
+
+int fail_hip(sgc_ctx *ctx, hipError_t e, const char *what)
+{
+    return fail(ctx, SGC_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define SGC_HIP(ctx, call)                                     \
+    do {                                                       \
+        hipError_t e__ = (call);                               \
+        if (e__ != hipSuccess) return fail_hip(ctx, e__, #call); \
+    } while (0)
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool mfma_covers(const sgc_attn_params &p)
+{
+    return p.io_dtype == SGC_BF16 && p.head_dim == 128 && (p.kv_dtype == SGC_BF16 || p.kv_dtype == SGC_FP8_E4M3);
+}
+
+int check_params(const sgc_attn_params *p, sgc_ctx *ctx)
+{
+    if (!p) return fail(ctx, SGC_EINVAL, "params is NULL");
+    if (p->struct_size != sizeof(sgc_attn_params))
+        return fail(ctx, SGC_EINVAL, "params.struct_size %u != %zu", p->struct_size, sizeof(sgc_attn_params));
+    if (p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->n_q_heads % p->n_kv_heads != 0)
+        return fail(ctx, SGC_EINVAL, "n_q_heads %d must be a positive multiple of n_kv_heads %d", p->n_q_heads,
+                    p->n_kv_heads);
+    if (p->n_q_heads > 1024) return fail(ctx, SGC_EINVAL, "n_q_heads %d too large", p->n_q_heads);
+    if (p->head_dim != 64 && p->head_dim != 128)
+        return fail(ctx, SGC_EUNSUPPORTED, "head_dim %d not supported (64 or 128)", p->head_dim);
+    if (p->n_layers < 1) return fail(ctx, SGC_EINVAL, "n_layers %d < 1", p->n_layers);
+    if (p->page_tokens != kPageTokens)
+        return fail(ctx, SGC_EUNSUPPORTED, "page_tokens %d not supported (16)", p->page_tokens);
+    if (p->io_dtype != SGC_F32 && p->io_dtype != SGC_BF16)
+        return fail(ctx, SGC_EUNSUPPORTED, "io_dtype %d not supported (f32 or bf16)", p->io_dtype);
+    if (!(p->kv_dtype == p->io_dtype || (p->kv_dtype == SGC_FP8_E4M3 && p->io_dtype == SGC_BF16)))
+        return fail(ctx, SGC_EUNSUPPORTED, "kv_dtype %d not supported with io_dtype %d", p->kv_dtype, p->io_dtype);
+    if (!(p->rope_base >= 0.0f) || !std::isfinite(p->rope_base))
+        return fail(ctx, SGC_EINVAL, "rope_base must be finite and >= 0");
+    if (!(p->softmax_scale >= 0.0f) || !std::isfinite(p->softmax_scale))
+        return fail(ctx, SGC_EINVAL, "softmax_scale must be finite and >= 0");
+    if (p->max_position < 0) return fail(ctx, SGC_EINVAL, "max_position < 0");
+    if (p->kernel < SGC_KERNEL_AUTO || p->kernel > SGC_KERNEL_MFMA)
+        return fail(ctx, SGC_EINVAL, "kernel %d unknown", p->kernel);
+    if (p->kernel == SGC_KERNEL_MFMA && !mfma_covers(*p))
+        return fail(ctx, SGC_EUNSUPPORTED, "MFMA kernel needs io bf16, kv bf16|fp8, head_dim 128");
+    return SGC_OK;
+}
+
+size_t page_bytes_of(const sgc_attn_params &p)
+{
+    return (size_t)2 * p.n_kv_heads * kPageTokens * p.head_dim * dtype_bytes(p.kv_dtype);
+}
+
+// Makes sure the rotary table covers positions [0, need).
+int ensure_rope(sgc_ctx *ctx, int need, hipStream_t s)
+{
+    if (!(ctx->p.rope_base > 0.0f)) return SGC_OK;
+    if (need <= ctx->rope_len) return SGC_OK;
+    int want = std::max(need, std::max(ctx->p.max_position, 1024));
+    want = (want + 1023) / 1024 * 1024;
+    float2 *t = nullptr;
+    SGC_HIP(ctx, hipMalloc(&t, (size_t)want * (ctx->p.head_dim / 2) * sizeof(float2)));
+    hipError_t e = launch_rope_table(t, want, ctx->p.head_dim, (double)ctx->p.rope_base, s);
+    if (e != hipSuccess) {
+        (void)hipFree(t);
+        return fail_hip(ctx, e, "rope table kernel");
+    }
+    if (ctx->d_rope) {
+        // earlier launches may still read the old table
+        SGC_HIP(ctx, hipDeviceSynchronize());
+        (void)hipFree(ctx->d_rope);
+    }
+    ctx->d_rope = t;
+    ctx->rope_len = want;
+    return SGC_OK;
+}
+
+// Brings the device copy of the page tables up to date with the host allocator.
+int cache_sync(sgc_cache *c, hipStream_t s)
+{
+    sgc_ctx *ctx = c->ctx;
+    if (!c->d_pt_off) {
+        SGC_HIP(ctx, hipMalloc(&c->d_pt_off, sizeof(int32_t) * c->max_clusters));
+        SGC_HIP(ctx, hipMalloc(&c->d_prefix_len, sizeof(int32_t) * c->max_clusters));
+        if (ctx->p.kv_dtype == SGC_FP8_E4M3) {
+            const size_t n = (size_t)c->max_clusters * ctx->p.n_layers * 2 * ctx->p.n_kv_heads;
+            SGC_HIP(ctx, hipMalloc(&c->d_scale, sizeof(float) * n));
+            SGC_HIP(ctx, hipMemset(c->d_scale, 0, sizeof(float) * n));
+        }
+        c->dirty = true;
+    }
+    if (!c->dirty) return SGC_OK;
+    std::vector<int32_t> off(c->max_clusters, 0), plen(c->max_clusters, 0), flat;
+    for (int i = 0; i < c->max_clusters; ++i) {
+        off[i] = (int32_t)flat.size();
+        if (c->cl[i].allocated) {
+            plen[i] = c->cl[i].prefix_len;
+            flat.insert(flat.end(), c->cl[i].pages.begin(), c->cl[i].pages.end());
+        }
+    }
+    // launches already enqueued may still read the old tables
+    SGC_HIP(ctx, hipStreamSynchronize(s));
+    if (flat.size() > c->d_page_table_cap || !c->d_page_table) {
+        if (c->d_page_table) {
+            SGC_HIP(ctx, hipDeviceSynchronize());
+            (void)hipFree(c->d_page_table);
+            c->d_page_table = nullptr;
+        }
+        const size_t cap = std::max<size_t>((size_t)c->geom.total_pages, 16);
+        SGC_HIP(ctx, hipMalloc(&c->d_page_table, sizeof(int32_t) * cap));
+        c->d_page_table_cap = cap;
+    }
+    if (!flat.empty())
+        SGC_HIP(ctx, hipMemcpyAsync(c->d_page_table, flat.data(), sizeof(int32_t) * flat.size(), hipMemcpyHostToDevice, s));
+    SGC_HIP(ctx, hipMemcpyAsync(c->d_pt_off, off.data(), sizeof(int32_t) * off.size(), hipMemcpyHostToDevice, s));
+    SGC_HIP(ctx, hipMemcpyAsync(c->d_prefix_len, plen.data(), sizeof(int32_t) * plen.size(), hipMemcpyHostToDevice, s));
+    SGC_HIP(ctx, hipStreamSynchronize(s));   // the host vectors above go out of scope
+    c->dirty = false;
+    return SGC_OK;
+}
+
+int check_cluster(sgc_ctx *ctx, const sgc_cache *c, int32_t cluster_id, int32_t layer)
+{
+    if (cluster_id < 0 || cluster_id >= c->max_clusters)
+        return fail(ctx, SGC_EINVAL, "cluster_id %d outside [0, %d)", cluster_id, c->max_clusters);
+    if (!c->cl[cluster_id].allocated) return fail(ctx, SGC_ESTATE, "cluster %d is not allocated", cluster_id);
+    if (layer < 0 || layer >= ctx->p.n_layers)
+        return fail(ctx, SGC_EINVAL, "layer %d outside [0, %d)", layer, ctx->p.n_layers);
+    return SGC_OK;
+}
+
+void fill_common_args(AttnArgs &a, sgc_ctx *ctx, const sgc_cache *c, int32_t layer)
+{
+    memset(&a, 0, sizeof(a));
+    a.pool = c->geom;
+    a.layer = layer;
+    a.page_table = c->d_page_table;
+    a.cl_pt_off = c->d_pt_off;
+    a.cl_prefix_len = c->d_prefix_len;
+    a.kv_scale = c->d_scale;
+    a.n_layers = ctx->p.n_layers;
+    a.rope = (ctx->p.rope_base > 0.0f) ? ctx->d_rope : nullptr;
+    a.n_q_heads = ctx->p.n_q_heads;
+    a.n_kv_heads = ctx->p.n_kv_heads;
+    a.group = ctx->p.n_q_heads / ctx->p.n_kv_heads;
+    a.head_dim = ctx->p.head_dim;
+    a.io_dtype = ctx->p.io_dtype;
+    a.scale_log2e = ctx->scale * 1.4426950408889634f;
+}
+
+// Work list of the batched suffix launch.  One unit = (cluster, KV head): all rows of a unit read
+// the same cached K/V.  Units are dealt, heaviest first, to the XCD with the least work so far;
+// workgroup b runs on XCD b % 8, so slot-major interleaving keeps every tile of a unit on one
+// XCD and that unit's K/V in one L2.
+void build_tiles(sgc_plan *pl, int tile_rows)
+{
+    constexpr int kXcd = 8;
+    const sgc_ctx *ctx = pl->ctx;
+    const int g = ctx->p.n_q_heads / ctx->p.n_kv_heads;
+    struct Unit {
+        int cluster, hk;
+        int64_t rows;
+        double work;
+    };
+    std::vector<Unit> units;
+    for (int c = 0; c < pl->n_clusters; ++c) {
+        const int64_t toks = pl->cl_tok_off[c + 1] - pl->cl_tok_off[c];
+        if (toks == 0) continue;
+        for (int hk = 0; hk < ctx->p.n_kv_heads; ++hk) {
+            const int64_t rows = toks * g;
+            const int64_t nt = (rows + tile_rows - 1) / tile_rows;
+            units.push_back({c, hk, rows, (double)nt * (pl->cl_prefix_len[c] + 64.0)});
+        }
+    }
+    std::stable_sort(units.begin(), units.end(), [](const Unit &a, const Unit &b) { return a.work > b.work; });
+    std::vector<std::vector<Tile>> lists(kXcd);
+    double load[kXcd] = {0};
+    for (const Unit &u : units) {
+        int x = 0;
+        for (int i = 1; i < kXcd; ++i)
+            if (load[i] < load[x]) x = i;
+        load[x] += u.work;
+        for (int64_t r = 0; r < u.rows; r += tile_rows)
+            lists[x].push_back({u.cluster, u.hk, (int32_t)r, (int32_t)std::min<int64_t>(tile_rows, u.rows - r)});
+    }
+    size_t slots = 0;
+    for (auto &l : lists) slots = std::max(slots, l.size());
+    pl->tiles.assign(slots * kXcd, Tile{0, 0, 0, 0});
+    for (int x = 0; x < kXcd; ++x)
+        for (size_t s = 0; s < lists[x].size(); ++s) pl->tiles[s * kXcd + x] = lists[x][s];
+    pl->tile_rows = tile_rows;
+}
+
+void plan_free_device(sgc_plan *pl)
+{
+    if (pl->d_blob) (void)hipFree(pl->d_blob);
+    pl->d_blob = nullptr;
+    pl->uploaded = false;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *sgc_version(void) { return "libsgc 0.1 (gfx950)"; }
+
+const char *sgc_status_string(int status)
+{
+    switch (status) {
+        case SGC_OK: return "SGC_OK";
+        case SGC_EINVAL: return "SGC_EINVAL";
+        case SGC_ENOMEM: return "SGC_ENOMEM";
+        case SGC_ESHAPE: return "SGC_ESHAPE";
+        case SGC_EUNSUPPORTED: return "SGC_EUNSUPPORTED";
+        case SGC_EHIP: return "SGC_EHIP";
+        case SGC_ESTATE: return "SGC_ESTATE";
+        default: return "SGC_UNKNOWN";
+    }
+}
+
+const char *sgc_last_error(const sgc_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err_noctx.c_str(); }
+
+int sgc_ctx_create(const sgc_attn_params *params, sgc_ctx **out)
+{
+    if (!out) return fail(nullptr, SGC_EINVAL, "out is NULL");
+    *out = nullptr;
+    int rc = check_params(params, nullptr);
+    if (rc != SGC_OK) return rc;
+    sgc_ctx *ctx = new (std::nothrow) sgc_ctx();
+    if (!ctx) return fail(nullptr, SGC_ENOMEM, "host allocation failed");
+    ctx->p = *params;
+    ctx->scale = params->softmax_scale > 0.0f ? params->softmax_scale : 1.0f / sqrtf((float)params->head_dim);
+    ctx->use_mfma = params->kernel == SGC_KERNEL_MFMA || (params->kernel == SGC_KERNEL_AUTO && mfma_covers(*params));
+    ctx->mfma_variant = 0;
+    if (const char *v = getenv("SGC_MFMA_VARIANT")) {
+        const int n = atoi(v);
+        if (mfma_tile_rows(n) > 0) ctx->mfma_variant = n;
+    }
+    ctx->tile_rows = ctx->use_mfma ? mfma_tile_rows(ctx->mfma_variant) : 0;
+    *out = ctx;
+    return SGC_OK;
+}
+
+int sgc_ctx_destroy(sgc_ctx *ctx)
+{
+    if (!ctx) return SGC_OK;
+    if (ctx->d_rope) (void)hipFree(ctx->d_rope);
+    delete ctx;
+    return SGC_OK;
+}
+
+size_t sgc_cache_page_bytes(const sgc_attn_params *params)
+{
+    if (check_params(params, nullptr) != SGC_OK) return 0;
+    return page_bytes_of(*params);
+}
+
+size_t sgc_cache_pool_bytes(const sgc_attn_params *params, int64_t total_pages)
+{
+    if (check_params(params, nullptr) != SGC_OK || total_pages < 0) return 0;
+    return page_bytes_of(*params) * (size_t)params->n_layers * (size_t)total_pages;
+}
+
+int sgc_cache_create(sgc_ctx *ctx, void *dev_pool, size_t pool_bytes, int32_t max_clusters, sgc_cache **out)
+{
+    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (!out) return fail(ctx, SGC_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!dev_pool) return fail(ctx, SGC_EINVAL, "dev_pool is NULL");
+    if (reinterpret_cast<uintptr_t>(dev_pool) & 255u) return fail(ctx, SGC_EINVAL, "dev_pool must be 256-byte aligned");
+    if (max_clusters <= 0 || max_clusters > (1 << 20)) return fail(ctx, SGC_EINVAL, "max_clusters %d out of range", max_clusters);
+    const size_t pb = page_bytes_of(ctx->p);
+    const int64_t total_pages = (int64_t)(pool_bytes / (pb * (size_t)ctx->p.n_layers));
+    if (total_pages < 1) return fail(ctx, SGC_EINVAL, "pool of %zu bytes holds no page (%zu bytes x %d layers)", pool_bytes, pb, ctx->p.n_layers);
+    if (total_pages > INT32_MAX) return fail(ctx, SGC_EINVAL, "pool too large: %lld pages", (long long)total_pages);
+    sgc_cache *c = new (std::nothrow) sgc_cache();
+    if (!c) return fail(ctx, SGC_ENOMEM, "host allocation failed");
+    c->ctx = ctx;
+    c->pool_bytes = pool_bytes;
+    c->max_clusters = max_clusters;
+    c->geom.pool = static_cast<char *>(dev_pool);
+    c->geom.total_pages = total_pages;
+    c->geom.n_kv_heads = ctx->p.n_kv_heads;
+    c->geom.head_dim = ctx->p.head_dim;
+    c->geom.kv_dtype = ctx->p.kv_dtype;
+    c->geom.kv_bytes = dtype_bytes(ctx->p.kv_dtype);
+    c->geom.head_part_bytes = (int64_t)kPageTokens * ctx->p.head_dim * c->geom.kv_bytes;
+    c->geom.page_bytes = (int64_t)pb;
+    c->geom.layer_bytes = total_pages * (int64_t)pb;
+    c->cl.resize(max_clusters);
+    c->free_list.resize(total_pages);
+    for (int64_t i = 0; i < total_pages; ++i) c->free_list[i] = (int32_t)(total_pages - 1 - i);  // page 0 first
+    *out = c;
+    return SGC_OK;
+}
+
+int sgc_cache_destroy(sgc_cache *c)
+{
+    if (!c) return SGC_OK;
+    if (c->d_page_table) (void)hipFree(c->d_page_table);
+    if (c->d_pt_off) (void)hipFree(c->d_pt_off);
+    if (c->d_prefix_len) (void)hipFree(c->d_prefix_len);
+    if (c->d_scale) (void)hipFree(c->d_scale);
+    delete c;
+    return SGC_OK;
+}
+
+int sgc_cache_alloc_cluster(sgc_cache *c, int32_t cluster_id, int32_t prefix_len)
+{
+    if (!c) return fail(nullptr, SGC_EINVAL, "cache is NULL");
+    sgc_ctx *ctx = c->ctx;
+    if (cluster_id < 0 || cluster_id >= c->max_clusters)
+        return fail(ctx, SGC_EINVAL, "cluster_id %d outside [0, %d)", cluster_id, c->max_clusters);
+    if (prefix_len < 0) return fail(ctx, SGC_EINVAL, "prefix_len %d < 0", prefix_len);
+    sgc_cluster_entry &e = c->cl[cluster_id];
+    if (e.allocated) return fail(ctx, SGC_ESTATE, "cluster %d is already allocated", cluster_id);
+    const int64_t need = ((int64_t)prefix_len + kPageTokens - 1) / kPageTokens;
+    if (need > (int64_t)c->free_list.size())
+        return fail(ctx, SGC_ENOMEM, "cluster %d needs %lld pages, %zu free", cluster_id, (long long)need, c->free_list.size());
+    e.pages.clear();
+    e.pages.reserve(need);
+    for (int64_t i = 0; i < need; ++i) {
+        e.pages.push_back(c->free_list.back());
+        c->free_list.pop_back();
+    }
+    e.prefix_len = prefix_len;
+    e.allocated = true;
+    c->dirty = true;
+    c->generation++;
+    return SGC_OK;
+}
+
+int sgc_cache_free_cluster(sgc_cache *c, int32_t cluster_id)
+{
+    if (!c) return fail(nullptr, SGC_EINVAL, "cache is NULL");
+    sgc_ctx *ctx = c->ctx;
+    if (cluster_id < 0 || cluster_id >= c->max_clusters)
+        return fail(ctx, SGC_EINVAL, "cluster_id %d outside [0, %d)", cluster_id, c->max_clusters);
+    sgc_cluster_entry &e = c->cl[cluster_id];
+    if (!e.allocated) return fail(ctx, SGC_ESTATE, "cluster %d is not allocated", cluster_id);
+    for (auto it = e.pages.rbegin(); it != e.pages.rend(); ++it) c->free_list.push_back(*it);
+    e.pages.clear();
+    e.prefix_len = 0;
+    e.allocated = false;
+    c->dirty = true;
+    c->generation++;
+    return SGC_OK;
+}
+
+int64_t sgc_cache_total_pages(const sgc_cache *c) { return c ? c->geom.total_pages : SGC_EINVAL; }
+int64_t sgc_cache_free_pages(const sgc_cache *c) { return c ? (int64_t)c->free_list.size() : SGC_EINVAL; }
+
+int sgc_cache_cluster_pages(const sgc_cache *c, int32_t cluster_id, int32_t *out_pages, int32_t cap, int32_t *out_prefix_len)
+{
+    if (!c) return fail(nullptr, SGC_EINVAL, "cache is NULL");
+    if (cluster_id < 0 || cluster_id >= c->max_clusters)
+        return fail(c->ctx, SGC_EINVAL, "cluster_id %d outside [0, %d)", cluster_id, c->max_clusters);
+    const sgc_cluster_entry &e = c->cl[cluster_id];
+    if (!e.allocated) return fail(c->ctx, SGC_ESTATE, "cluster %d is not allocated", cluster_id);
+    if (out_prefix_len) *out_prefix_len = e.prefix_len;
+    if (out_pages)
+        for (int32_t i = 0; i < cap && i < (int32_t)e.pages.size(); ++i) out_pages[i] = e.pages[i];
+    return (int)e.pages.size();
+}
+
+// ------------------------------------------------------------------------------------------------
+int sgc_prefix_prefill(sgc_ctx *ctx, sgc_cache *c, int32_t cluster_id, int32_t layer, const void *dev_q,
+                       const void *dev_k, const void *dev_v, void *dev_o, float *dev_lse, int32_t prefix_len,
+                       void *hip_stream)
+{
+    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (!c || c->ctx != ctx) return fail(ctx, SGC_EINVAL, "cache is NULL or belongs to another context");
+    int rc = check_cluster(ctx, c, cluster_id, layer);
+    if (rc != SGC_OK) return rc;
+    if (prefix_len != c->cl[cluster_id].prefix_len)
+        return fail(ctx, SGC_ESHAPE, "prefix_len %d differs from the %d the cluster was allocated with", prefix_len,
+                    c->cl[cluster_id].prefix_len);
+    if ((dev_q == nullptr) != (dev_o == nullptr)) return fail(ctx, SGC_EINVAL, "dev_q and dev_o must both be given or both be NULL");
+    if (dev_lse && !dev_o) return fail(ctx, SGC_EINVAL, "dev_lse given without dev_q/dev_o");
+    if (prefix_len == 0) return SGC_OK;
+    if (!dev_k || !dev_v) return fail(ctx, SGC_EINVAL, "dev_k / dev_v is NULL");
+    if (!aligned16(dev_k) || !aligned16(dev_v) || !aligned16(dev_q) || !aligned16(dev_o) || !aligned16(dev_lse))
+        return fail(ctx, SGC_EINVAL, "device pointers must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if ((rc = ensure_rope(ctx, prefix_len, s)) != SGC_OK) return rc;
+    if ((rc = cache_sync(c, s)) != SGC_OK) return rc;
+
+    int32_t pt_off = 0;
+    for (int i = 0; i < cluster_id; ++i)
+        if (c->cl[i].allocated) pt_off += (int32_t)c->cl[i].pages.size();
+    float *scale_kv = c->d_scale ? c->d_scale + ((size_t)cluster_id * ctx->p.n_layers + layer) * 2 * ctx->p.n_kv_heads : nullptr;
+    SGC_HIP(ctx, launch_prefix_ingest(c->geom, layer, c->d_page_table + pt_off, prefix_len, dev_k, dev_v, ctx->p.io_dtype,
+                                      ctx->p.rope_base > 0.0f ? ctx->d_rope : nullptr, scale_kv, s));
+    if (!dev_q) return SGC_OK;
+
+    AttnArgs a;
+    fill_common_args(a, ctx, c, layer);
+    a.q = dev_q;
+    a.o = dev_o;
+    a.lse = dev_lse;
+    a.lse_stride = prefix_len;
+    a.mode = MODE_PREFIX;
+    a.prefix_cluster = cluster_id;
+    a.prefix_len = prefix_len;
+    if (ctx->use_mfma) {
+        SGC_HIP(ctx, launch_attn_mfma(a, ctx->mfma_variant, s));
+    } else {
+        SGC_HIP(ctx, launch_attn_generic(a, (int64_t)prefix_len * ctx->p.n_q_heads, s));
+    }
+    return SGC_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+int sgc_assign_clusters(sgc_ctx *ctx, const sgc_cache *c, int32_t n_queries, const int32_t *labels,
+                        const int32_t *suffix_len, int32_t n_clusters, int32_t *order, int32_t *cluster_off,
+                        int32_t *cu_seqlens, sgc_plan **out_plan)
+{
+    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (out_plan) *out_plan = nullptr;
+    if (!c || c->ctx != ctx) return fail(ctx, SGC_EINVAL, "cache is NULL or belongs to another context");
+    if (n_queries < 0) return fail(ctx, SGC_EINVAL, "n_queries %d < 0", n_queries);
+    if (n_clusters <= 0 || n_clusters > c->max_clusters)
+        return fail(ctx, SGC_EINVAL, "n_clusters %d outside [1, %d]", n_clusters, c->max_clusters);
+    if (n_queries > 0 && (!labels || !suffix_len)) return fail(ctx, SGC_EINVAL, "labels / suffix_len is NULL");
+    if (!order && n_queries > 0) return fail(ctx, SGC_EINVAL, "order is NULL");
+    if (!cluster_off || !cu_seqlens) return fail(ctx, SGC_EINVAL, "cluster_off / cu_seqlens is NULL");
+
+    // counting pass, with every check done before any output is written
+    std::vector<int32_t> count(n_clusters, 0);
+    int64_t total = 0;
+    for (int32_t n = 0; n < n_queries; ++n) {
+        const int32_t lab = labels[n];
+        if (lab < 0 || lab >= n_clusters) return fail(ctx, SGC_EINVAL, "labels[%d] = %d outside [0, %d)", n, lab, n_clusters);
+        if (suffix_len[n] < 0) return fail(ctx, SGC_EINVAL, "suffix_len[%d] = %d < 0", n, suffix_len[n]);
+        if (!c->cl[lab].allocated) return fail(ctx, SGC_ESTATE, "query %d names cluster %d, which is not allocated", n, lab);
+        count[lab]++;
+        total += suffix_len[n];
+    }
+    if (total * (int64_t)(ctx->p.n_q_heads / ctx->p.n_kv_heads) > INT32_MAX || total > INT32_MAX / 2)
+        return fail(ctx, SGC_EINVAL, "batch too large: %lld suffix tokens", (long long)total);
+
+    cluster_off[0] = 0;
+    for (int32_t k = 0; k < n_clusters; ++k) cluster_off[k + 1] = cluster_off[k] + count[k];
+    std::vector<int32_t> cursor(cluster_off, cluster_off + n_clusters);
+    for (int32_t n = 0; n < n_queries; ++n) order[cursor[labels[n]]++] = n;   // stable: ascending n inside a cluster
+    cu_seqlens[0] = 0;
+    for (int32_t n = 0; n < n_queries; ++n) cu_seqlens[n + 1] = cu_seqlens[n] + suffix_len[n];
+
+    if (!out_plan) return SGC_OK;
+    sgc_plan *pl = new (std::nothrow) sgc_plan();
+    if (!pl) return fail(ctx, SGC_ENOMEM, "host allocation failed");
+    pl->ctx = ctx;
+    pl->cache = c;
+    pl->n_queries = n_queries;
+    pl->n_clusters = n_clusters;
+    pl->total_tokens = total;
+    pl->order.assign(order, order + n_queries);
+    pl->cluster_off.assign(cluster_off, cluster_off + n_clusters + 1);
+    pl->cl_prefix_len.resize(n_clusters);
+    for (int32_t k = 0; k < n_clusters; ++k) pl->cl_prefix_len[k] = c->cl[k].allocated ? c->cl[k].prefix_len : 0;
+    pl->cl_tok_off.assign(n_clusters + 1, 0);
+    pl->tok_src.resize(total);
+    pl->tok_qpos.resize(total);
+    pl->tok_sq.resize(total);
+    pl->sq_src0.resize(n_queries);
+    pl->sq_len.resize(n_queries);
+    pl->sq_tok0.resize(n_queries);
+    pl->sq_cluster.resize(n_queries);
+    int32_t t = 0, maxpos = 0;
+    for (int32_t k = 0; k < n_clusters; ++k) {
+        pl->cl_tok_off[k] = t;
+        for (int32_t sq = cluster_off[k]; sq < cluster_off[k + 1]; ++sq) {
+            const int32_t n = order[sq];
+            pl->sq_src0[sq] = cu_seqlens[n];
+            pl->sq_len[sq] = suffix_len[n];
+            pl->sq_tok0[sq] = t;
+            pl->sq_cluster[sq] = k;
+            for (int32_t i = 0; i < suffix_len[n]; ++i, ++t) {
+                pl->tok_src[t] = cu_seqlens[n] + i;
+                pl->tok_qpos[t] = i;
+                pl->tok_sq[t] = sq;
+            }
+            if (suffix_len[n] > 0) maxpos = std::max(maxpos, pl->cl_prefix_len[k] + suffix_len[n]);
+        }
+    }
+    pl->cl_tok_off[n_clusters] = t;
+    pl->max_position = maxpos;
+    *out_plan = pl;
+    return SGC_OK;
+}
+
+int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
+{
+    if (!pl) return fail(nullptr, SGC_EINVAL, "plan is NULL");
+    sgc_ctx *ctx = pl->ctx;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int want_rows = ctx->use_mfma ? ctx->tile_rows : 0;
+    if (pl->uploaded && pl->tile_rows == want_rows) return SGC_OK;
+    plan_free_device(pl);
+    pl->tiles.clear();
+    pl->tile_rows = 0;
+    if (want_rows > 0) build_tiles(pl, want_rows);
+
+    struct Piece {
+        const void *src;
+        size_t bytes;
+        const void **dst;
+    };
+    Piece pieces[] = {
+        {pl->cl_tok_off.data(), pl->cl_tok_off.size() * 4, (const void **)&pl->d_cl_tok_off},
+        {pl->tok_src.data(), pl->tok_src.size() * 4, (const void **)&pl->d_tok_src},
+        {pl->tok_qpos.data(), pl->tok_qpos.size() * 4, (const void **)&pl->d_tok_qpos},
+        {pl->tok_sq.data(), pl->tok_sq.size() * 4, (const void **)&pl->d_tok_sq},
+        {pl->sq_src0.data(), pl->sq_src0.size() * 4, (const void **)&pl->d_sq_src0},
+        {pl->sq_len.data(), pl->sq_len.size() * 4, (const void **)&pl->d_sq_len},
+        {pl->sq_tok0.data(), pl->sq_tok0.size() * 4, (const void **)&pl->d_sq_tok0},
+        {pl->sq_cluster.data(), pl->sq_cluster.size() * 4, (const void **)&pl->d_sq_cluster},
+        {pl->tiles.data(), pl->tiles.size() * sizeof(Tile), (const void **)&pl->d_tiles},
+    };
+    size_t total = 0;
+    for (const Piece &p : pieces) total += (p.bytes + 255) / 256 * 256 + 256;
+    SGC_HIP(ctx, hipMalloc(&pl->d_blob, total));
+    size_t off = 0;
+    for (const Piece &p : pieces) {
+        *p.dst = pl->d_blob + off;
+        if (p.bytes) SGC_HIP(ctx, hipMemcpyAsync(pl->d_blob + off, p.src, p.bytes, hipMemcpyHostToDevice, s));
+        off += (p.bytes + 255) / 256 * 256 + 256;
+    }
+    SGC_HIP(ctx, hipStreamSynchronize(s));
+    pl->uploaded = true;
+    return SGC_OK;
+}
+
+int sgc_plan_get_info(const sgc_plan *pl, sgc_plan_info *out)
+{
+    if (!pl || !out) return fail(pl ? pl->ctx : nullptr, SGC_EINVAL, "plan / out is NULL");
+    out->n_queries = pl->n_queries;
+    out->n_clusters = pl->n_clusters;
+    out->total_tokens = pl->total_tokens;
+    out->max_position = pl->max_position;
+    out->tile_rows = pl->tile_rows;
+    out->n_tiles = (int32_t)pl->tiles.size();
+    return SGC_OK;
+}
+
+int sgc_plan_destroy(sgc_plan *pl)
+{
+    if (!pl) return SGC_OK;
+    plan_free_device(pl);
+    delete pl;
+    return SGC_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int32_t layer, const void *dev_q,
+                               const void *dev_k, const void *dev_v, void *dev_o, float *dev_lse, void *hip_stream)
+{
+    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (!cc || cc->ctx != ctx) return fail(ctx, SGC_EINVAL, "cache is NULL or belongs to another context");
+    if (!pl || pl->ctx != ctx || pl->cache != cc) return fail(ctx, SGC_EINVAL, "plan is NULL or was made for another context/cache");
+    if (layer < 0 || layer >= ctx->p.n_layers) return fail(ctx, SGC_EINVAL, "layer %d outside [0, %d)", layer, ctx->p.n_layers);
+    sgc_cache *c = const_cast<sgc_cache *>(cc);   // device mirrors are refreshed lazily
+    for (int32_t k = 0; k < pl->n_clusters; ++k) {
+        if (pl->cluster_off[k + 1] == pl->cluster_off[k]) continue;
+        if (!c->cl[k].allocated || c->cl[k].prefix_len != pl->cl_prefix_len[k])
+            return fail(ctx, SGC_ESTATE, "cluster %d changed since the plan was made", k);
+    }
+    if (pl->total_tokens == 0) return SGC_OK;
+    if (!dev_q || !dev_k || !dev_v || !dev_o) return fail(ctx, SGC_EINVAL, "dev_q / dev_k / dev_v / dev_o is NULL");
+    if (!aligned16(dev_q) || !aligned16(dev_k) || !aligned16(dev_v) || !aligned16(dev_o) || !aligned16(dev_lse))
+        return fail(ctx, SGC_EINVAL, "device pointers must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int rc;
+    if ((rc = ensure_rope(ctx, pl->max_position, s)) != SGC_OK) return rc;
+    if ((rc = cache_sync(c, s)) != SGC_OK) return rc;
+    if ((rc = sgc_plan_upload(pl, hip_stream)) != SGC_OK) return rc;
+
+    AttnArgs a;
+    fill_common_args(a, ctx, c, layer);
+    a.q = dev_q;
+    a.k = dev_k;
+    a.v = dev_v;
+    a.o = dev_o;
+    a.lse = dev_lse;
+    a.lse_stride = pl->total_tokens;
+    a.mode = MODE_SUFFIX;
+    a.tiles = pl->d_tiles;
+    a.n_tiles = (int32_t)pl->tiles.size();
+    a.cl_tok_off = pl->d_cl_tok_off;
+    a.tok_src = pl->d_tok_src;
+    a.tok_qpos = pl->d_tok_qpos;
+    a.tok_sq = pl->d_tok_sq;
+    a.sq_src0 = pl->d_sq_src0;
+    a.sq_len = pl->d_sq_len;
+    a.sq_tok0 = pl->d_sq_tok0;
+    a.sq_cluster = pl->d_sq_cluster;
+    a.total_tokens = pl->total_tokens;
+    if (ctx->use_mfma) {
+        SGC_HIP(ctx, launch_attn_mfma(a, ctx->mfma_variant, s));
+    } else {
+        SGC_HIP(ctx, launch_attn_generic(a, pl->total_tokens * ctx->p.n_q_heads, s));
+    }
+    return SGC_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+static int export_import(sgc_ctx *ctx, sgc_cache *c, int32_t cluster_id, int32_t layer, void *dev_k, void *dev_v,
+                         float *host_k_scale, float *host_v_scale, void *hip_stream, bool is_export)
+{
+    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (!c || c->ctx != ctx) return fail(ctx, SGC_EINVAL, "cache is NULL or belongs to another context");
+    int rc = check_cluster(ctx, c, cluster_id, layer);
+    if (rc != SGC_OK) return rc;
+    const int32_t P = c->cl[cluster_id].prefix_len;
+    const bool fp8 = ctx->p.kv_dtype == SGC_FP8_E4M3;
+    if (fp8 && (!host_k_scale || !host_v_scale)) return fail(ctx, SGC_EINVAL, "fp8 cache: scale arrays are NULL");
+    if (P > 0 && (!dev_k || !dev_v)) return fail(ctx, SGC_EINVAL, "dev_k / dev_v is NULL");
+    if (!aligned16(dev_k) || !aligned16(dev_v)) return fail(ctx, SGC_EINVAL, "device pointers must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if ((rc = cache_sync(c, s)) != SGC_OK) return rc;
+    int32_t pt_off = 0;
+    for (int i = 0; i < cluster_id; ++i)
+        if (c->cl[i].allocated) pt_off += (int32_t)c->cl[i].pages.size();
+    const int Hkv = ctx->p.n_kv_heads;
+    float *d_sc = c->d_scale ? c->d_scale + ((size_t)cluster_id * ctx->p.n_layers + layer) * 2 * Hkv : nullptr;
+    if (is_export) {
+        if (P > 0) SGC_HIP(ctx, launch_cache_export(c->geom, layer, c->d_page_table + pt_off, P, dev_k, dev_v, s));
+        if (fp8) {
+            SGC_HIP(ctx, hipMemcpyAsync(host_k_scale, d_sc, sizeof(float) * Hkv, hipMemcpyDeviceToHost, s));
+            SGC_HIP(ctx, hipMemcpyAsync(host_v_scale, d_sc + Hkv, sizeof(float) * Hkv, hipMemcpyDeviceToHost, s));
+        }
+        SGC_HIP(ctx, hipStreamSynchronize(s));
+    } else {
+        if (P > 0) SGC_HIP(ctx, launch_cache_import(c->geom, layer, c->d_page_table + pt_off, P, dev_k, dev_v, s));
+        if (fp8) {
+            SGC_HIP(ctx, hipMemcpyAsync(d_sc, host_k_scale, sizeof(float) * Hkv, hipMemcpyHostToDevice, s));
+            SGC_HIP(ctx, hipMemcpyAsync(d_sc + Hkv, host_v_scale, sizeof(float) * Hkv, hipMemcpyHostToDevice, s));
+            SGC_HIP(ctx, hipStreamSynchronize(s));
+        }
+    }
+    return SGC_OK;
+}
+
+int sgc_cache_export(sgc_ctx *ctx, const sgc_cache *cache, int32_t cluster_id, int32_t layer, void *dev_k, void *dev_v,
+                     float *host_k_scale, float *host_v_scale, void *hip_stream)
+{
+    return export_import(ctx, const_cast<sgc_cache *>(cache), cluster_id, layer, dev_k, dev_v, host_k_scale, host_v_scale,
+                         hip_stream, true);
+}
+
+int sgc_cache_import(sgc_ctx *ctx, sgc_cache *cache, int32_t cluster_id, int32_t layer, const void *dev_k, const void *dev_v,
+                     const float *host_k_scale, const float *host_v_scale, void *hip_stream)
+{
+    return export_import(ctx, cache, cluster_id, layer, const_cast<void *>(dev_k), const_cast<void *>(dev_v),
+                         const_cast<float *>(host_k_scale), const_cast<float *>(host_v_scale), hip_stream, false);
+}
+
+}  // extern "C"

@@ -1,0 +1,186 @@
+// Internal declarations shared by the host code and the kernels of libsgc.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "sgc.h"
+
+namespace sgc {
+
+constexpr int kPageTokens = 16;
+
+// ---- page-internal element order -------------------------------------------------------------
+// A page holds 16 tokens of one KV head: a K part and a V part of 16 * d elements each.  Both
+// are stored in the order the 32x32x16 matrix-core instruction reads its A operand in, so a
+// page can be copied into LDS linearly and read back conflict-free as 1 KiB operand blocks.
+//
+// K part: [d/16][2][16 tokens][8 channels]; block (kb, h) holds channels kb*16 + h*8 .. +7.
+//   A lane of the QK^T product (operand row = key, 8 consecutive channels) finds its 8
+//   elements contiguous.
+// V part: [d/32][2][32 channels][8 tokens]; block (db, h) holds channels db*32 .. +31 and the 8
+//   tokens {4h + (i & 3) + 8 (i >> 2) : i = 0..7}.  This is the set of keys one lane of the
+//   32x32 score accumulator holds in 8 consecutive registers, so the probabilities can feed the
+//   PV product without any cross-lane movement, and V is already transposed (operand row =
+//   channel, 8 keys contiguous).
+__host__ __device__ inline int k_page_index(int tok, int c)
+{
+    return ((((c >> 4) * 2 + ((c >> 3) & 1)) * kPageTokens) + tok) * 8 + (c & 7);
+}
+__host__ __device__ inline int v_page_index(int tok, int c)
+{
+    const int h = (tok >> 2) & 1;
+    const int i = (tok & 3) | ((tok >> 3) << 2);
+    return ((((c >> 5) * 2 + h) * 32) + (c & 31)) * 8 + i;
+}
+
+__host__ __device__ inline int dtype_bytes(int dt) { return dt == SGC_F32 ? 4 : (dt == SGC_BF16 ? 2 : 1); }
+
+// Geometry of the page pool, passed by value to kernels.
+struct PoolGeom {
+    char *pool;            // device base of the whole pool
+    int64_t total_pages;   // pages per layer
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t kv_dtype;
+    int32_t kv_bytes;      // bytes per element
+    int64_t head_part_bytes;   // 16 * d * kv_bytes: K (or V) of one head in one page
+    int64_t page_bytes;        // 2 * Hkv * head_part_bytes
+    int64_t layer_bytes;       // total_pages * page_bytes
+    __host__ __device__ inline char *k_part(int layer, int page, int hk) const
+    {
+        return pool + layer * layer_bytes + (int64_t)page * page_bytes + (int64_t)hk * head_part_bytes;
+    }
+    __host__ __device__ inline char *v_part(int layer, int page, int hk) const
+    {
+        return pool + layer * layer_bytes + (int64_t)page * page_bytes +
+               (int64_t)(n_kv_heads + hk) * head_part_bytes;
+    }
+};
+
+// One workgroup's share of an attention launch.
+struct Tile {
+    int32_t cluster;   // cluster id (index into the cache's per-cluster arrays)
+    int32_t hk;        // KV head
+    int32_t row0;      // first row inside the (cluster, hk) row space; row = token * g + head-in-group
+    int32_t n_rows;    // valid rows in this tile (0 = padding tile, exit at once)
+};
+
+enum { MODE_SUFFIX = 0, MODE_PREFIX = 1 };
+
+// Everything an attention kernel needs, by value.
+struct AttnArgs {
+    const void *q, *k, *v;   // token-major q [*][Hq][d], k/v [*][Hkv][d] (io dtype), before rotation
+    void *o;                 // [*][Hq][d]
+    float *lse;              // [Hq][lse_stride] or null
+    int64_t lse_stride;
+    PoolGeom pool;
+    int32_t layer;
+    const int32_t *page_table;    // flat page ids
+    const int32_t *cl_pt_off;     // [max_clusters] first entry of the cluster in page_table
+    const int32_t *cl_prefix_len; // [max_clusters]
+    const float *kv_scale;        // [max_clusters][n_layers][2][Hkv] or null (fp8 cache only)
+    int32_t n_layers;
+    const float2 *rope;           // [rope_len][d/2] (cos, sin) or null when rotation is off
+    const Tile *tiles;
+    int32_t n_tiles;
+    // suffix mode: sorted-token and sorted-query tables (sorted = grouped by cluster)
+    const int32_t *cl_tok_off;    // [n_clusters + 1] first sorted token of each cluster
+    const int32_t *tok_src;       // [T] row of the token in the caller's packed arrays
+    const int32_t *tok_qpos;      // [T] index of the token inside its query
+    const int32_t *tok_sq;        // [T] sorted query index of the token
+    const int32_t *sq_src0;       // [n_queries] first packed row of the query
+    const int32_t *sq_len;        // [n_queries] suffix length
+    const int32_t *sq_tok0;       // [n_queries] first sorted token of the query
+    const int32_t *sq_cluster;    // [n_queries]
+    int64_t total_tokens;
+    // prefix mode
+    int32_t prefix_cluster;
+    int32_t prefix_len;
+    int32_t mode;
+    int32_t n_q_heads, n_kv_heads, group, head_dim;
+    int32_t io_dtype;
+    float scale_log2e;            // softmax_scale * log2(e)
+};
+
+}  // namespace sgc
+
+// ---- host objects behind the opaque handles --------------------------------------------------
+struct sgc_ctx {
+    sgc_attn_params p;
+    float scale;
+    bool use_mfma;
+    int mfma_variant;      // kernel shape choice, see sgc_attn_mfma.hip
+    int tile_rows;         // rows per workgroup of the chosen attention kernel
+    std::string err;
+    float2 *d_rope = nullptr;
+    int rope_len = 0;
+};
+
+struct sgc_cluster_entry {
+    bool allocated = false;
+    int32_t prefix_len = 0;
+    std::vector<int32_t> pages;
+};
+
+struct sgc_cache {
+    sgc_ctx *ctx;
+    sgc::PoolGeom geom;
+    size_t pool_bytes;
+    int32_t max_clusters;
+    std::vector<sgc_cluster_entry> cl;
+    std::vector<int32_t> free_list;   // stack; back() is handed out next
+    uint64_t generation = 0;          // bumped by alloc/free
+    // device mirrors (built lazily)
+    bool dirty = true;
+    int32_t *d_page_table = nullptr;
+    size_t d_page_table_cap = 0;
+    int32_t *d_pt_off = nullptr;
+    int32_t *d_prefix_len = nullptr;
+    float *d_scale = nullptr;         // fp8 only: [max_clusters][n_layers][2][Hkv]
+};
+
+struct sgc_plan {
+    sgc_ctx *ctx;
+    const sgc_cache *cache;
+    int32_t n_queries, n_clusters;
+    int64_t total_tokens;
+    int32_t max_position;
+    std::vector<int32_t> order, cluster_off;
+    std::vector<int32_t> cl_prefix_len;       // snapshot at assign time, [n_clusters]
+    std::vector<int32_t> cl_tok_off;
+    std::vector<int32_t> tok_src, tok_qpos, tok_sq;
+    std::vector<int32_t> sq_src0, sq_len, sq_tok0, sq_cluster;
+    std::vector<sgc::Tile> tiles;
+    int32_t tile_rows = 0;
+    bool uploaded = false;
+    char *d_blob = nullptr;                   // one device allocation holding every array below
+    const int32_t *d_cl_tok_off = nullptr, *d_tok_src = nullptr, *d_tok_qpos = nullptr, *d_tok_sq = nullptr;
+    const int32_t *d_sq_src0 = nullptr, *d_sq_len = nullptr, *d_sq_tok0 = nullptr, *d_sq_cluster = nullptr;
+    const sgc::Tile *d_tiles = nullptr;
+};
+
+// ---- kernel launchers (defined in the .hip files) --------------------------------------------
+namespace sgc {
+
+// Builds the (cos, sin) table for positions [0, n_pos) in double precision, stored as fp32.
+hipError_t launch_rope_table(float2 *table, int n_pos, int head_dim, double base, hipStream_t s);
+
+// Prefix ingest: rotate K, (quantise), write K and V of one cluster/layer into its pages.
+hipError_t launch_prefix_ingest(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len,
+                                const void *k, const void *v, int io_dtype, const float2 *rope,
+                                float *d_scale_kv /* [2][Hkv] or null */, hipStream_t s);
+hipError_t launch_cache_export(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len,
+                               void *k, void *v, hipStream_t s);
+hipError_t launch_cache_import(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len,
+                               const void *k, const void *v, hipStream_t s);
+
+hipError_t launch_attn_generic(const AttnArgs &a, int64_t n_rows, hipStream_t s);
+// Rows per workgroup of MFMA kernel variant `variant`, or 0 if the variant does not exist.
+int mfma_tile_rows(int variant);
+hipError_t launch_attn_mfma(const AttnArgs &a, int variant, hipStream_t s);
+
+}  // namespace sgc

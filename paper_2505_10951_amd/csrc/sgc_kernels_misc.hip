@@ -1,0 +1,497 @@
+// Support kernels of libsgc (gfx950): rotary table, prefix K/V ingest into cache pages,
+// canonical export/import of a cluster's cache, and the generic fp32-arithmetic attention kernel
+// (one wavefront per output row) that serves shapes the MFMA kernel does not cover.
+//
+// SubGCache (arXiv 2505.10951) Sec. 3.4: the representative prompt's K/V are computed once per
+// cluster and kept in GPU memory; each query's question tokens are appended to it.
+#include <hip/hip_runtime.h>
+#include <math.h>
+
+#include <algorithm>
+
+#include "sgc_internal.h"
+
+namespace sgc {
+
+namespace {
+
+constexpr int kWave = 64;
+
+// ---- element load/store helpers ------------------------------------------------------------
+__device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+__device__ inline uint16_t f32_to_bf16(float x)   // round to nearest even; NaN stays NaN
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// OCP E4M3 (bias 7, largest finite 448, no infinities): nearest, ties to even, saturating.
+__device__ inline uint8_t f32_to_e4m3(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    const uint8_t sign = (uint8_t)((u >> 24) & 0x80u);
+    const uint32_t au = u & 0x7FFFFFFFu;
+    if (au > 0x7F800000u) return 0x7F;
+    const float a = __uint_as_float(au);
+    if (a >= 448.0f) return sign | 0x7E;
+    if (a < 0.015625f) {                        // below 2^-6: fixed spacing 2^-9
+        return sign | (uint8_t)__float2int_rn(a * 512.0f);
+    }
+    uint32_t r = au + 0x7FFFFu + ((au >> 20) & 1u);   // round 23 -> 3 mantissa bits
+    r >>= 20;                                         // [exponent8 | mantissa3]
+    uint32_t code = r - ((127u - 7u) << 3);
+    if (code > 0x7Eu) code = 0x7Eu;
+    return sign | (uint8_t)code;
+}
+
+__device__ inline float e4m3_to_f32(uint8_t c)
+{
+    const uint32_t e = (c >> 3) & 15u, m = c & 7u;
+    float mag;
+    if (e == 0)
+        mag = (float)m * 0.001953125f;   // m * 2^-9
+    else if (e == 15 && m == 7)
+        mag = __uint_as_float(0x7FC00000u);
+    else
+        mag = __uint_as_float(((e + 120u) << 23) | (m << 20));
+    return (c & 0x80) ? -mag : mag;
+}
+
+// 8 consecutive elements starting at element index `idx` (multiple of 8) of a typed array.
+__device__ inline void load8(const void *base, int64_t idx, int dtype, float out[8])
+{
+    if (dtype == SGC_F32) {
+        const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(base) + idx);
+        const float4 a = p[0], b = p[1];
+        out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+        out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+    } else if (dtype == SGC_BF16) {
+        const uint4 a = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + idx);
+        const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = __uint_as_float(w[i] << 16);
+            out[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    } else {
+        const uint2 a = *reinterpret_cast<const uint2 *>(static_cast<const uint8_t *>(base) + idx);
+        const uint32_t w[2] = {a.x, a.y};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = e4m3_to_f32((uint8_t)(w[i >> 2] >> (8 * (i & 3))));
+    }
+}
+
+__device__ inline float load1(const void *base, int64_t idx, int dtype)
+{
+    if (dtype == SGC_F32) return static_cast<const float *>(base)[idx];
+    if (dtype == SGC_BF16) return bf16_to_f32(static_cast<const uint16_t *>(base)[idx]);
+    return e4m3_to_f32(static_cast<const uint8_t *>(base)[idx]);
+}
+
+// Stores x into the cache element type; fp8 stores the code of x / scale.
+__device__ inline void store1(void *base, int64_t idx, int dtype, float x, float scale)
+{
+    if (dtype == SGC_F32)
+        static_cast<float *>(base)[idx] = x;
+    else if (dtype == SGC_BF16)
+        static_cast<uint16_t *>(base)[idx] = f32_to_bf16(x);
+    else
+        static_cast<uint8_t *>(base)[idx] = f32_to_e4m3(x / scale);
+}
+
+__device__ inline void store8(void *base, int64_t idx, int dtype, const float x[8], float scale)
+{
+    if (dtype == SGC_F32) {
+        float4 *p = reinterpret_cast<float4 *>(static_cast<float *>(base) + idx);
+        p[0] = make_float4(x[0], x[1], x[2], x[3]);
+        p[1] = make_float4(x[4], x[5], x[6], x[7]);
+    } else if (dtype == SGC_BF16) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16(x[2 * i]) | ((uint32_t)f32_to_bf16(x[2 * i + 1]) << 16);
+        *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(base) + idx) = make_uint4(w[0], w[1], w[2], w[3]);
+    } else {
+        uint32_t w[2] = {0, 0};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i >> 2] |= (uint32_t)f32_to_e4m3(x[i] / scale) << (8 * (i & 3));
+        *reinterpret_cast<uint2 *>(static_cast<uint8_t *>(base) + idx) = make_uint2(w[0], w[1]);
+    }
+}
+
+// Rotated pair of 8-channel chunks: x1 holds channels c0..c0+7, x2 channels c0+d/2.. of one head
+// vector; tab points at the (cos, sin) entries of this position for channels c0..c0+7.
+__device__ inline void rope8(float x1[8], float x2[8], const float2 *tab)
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float2 cs = tab[i];
+        const float a = x1[i], b = x2[i];
+        x1[i] = a * cs.x - b * cs.y;
+        x2[i] = b * cs.x + a * cs.y;
+    }
+}
+
+// ---- rotary table ----------------------------------------------------------------------------
+__global__ void rope_table_kernel(float2 *table, int n_pos, int half, double base, double inv_d)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)n_pos * half) return;
+    const int pos = (int)(idx / half), t = (int)(idx % half);
+    const double theta = pow(base, -2.0 * (double)t * inv_d);
+    double s, c;
+    sincos((double)pos * theta, &s, &c);
+    table[idx] = make_float2((float)c, (float)s);
+}
+
+// ---- prefix ingest ---------------------------------------------------------------------------
+// Pass 0 (fp8 only): per-head max |rotated K| and max |V| into amax[2][Hkv] via integer atomicMax
+// on the bit patterns of non-negative floats.
+__global__ void ingest_amax_kernel(const void *k, const void *v, int io_dtype, int P, int Hkv, int d,
+                                   const float2 *rope, float *amax)
+{
+    const int pg = blockIdx.x, hk = blockIdx.y;
+    const int half = d / 2, pairs = d / 16;
+    float mk = 0.f, mv = 0.f;
+    for (int it = threadIdx.x; it < kPageTokens * pairs; it += blockDim.x) {
+        const int tok = it / pairs, cc = it % pairs;
+        const int j = pg * kPageTokens + tok;
+        if (j >= P) continue;
+        float x1[8], x2[8], y1[8], y2[8];
+        const int64_t row = ((int64_t)j * Hkv + hk) * d;
+        load8(k, row + cc * 8, io_dtype, x1);
+        load8(k, row + half + cc * 8, io_dtype, x2);
+        if (rope) rope8(x1, x2, rope + (int64_t)j * half + cc * 8);
+        load8(v, row + cc * 8, io_dtype, y1);
+        load8(v, row + half + cc * 8, io_dtype, y2);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            mk = fmaxf(mk, fmaxf(fabsf(x1[i]), fabsf(x2[i])));
+            mv = fmaxf(mv, fmaxf(fabsf(y1[i]), fabsf(y2[i])));
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        mk = fmaxf(mk, __shfl_xor(mk, o));
+        mv = fmaxf(mv, __shfl_xor(mv, o));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        atomicMax(reinterpret_cast<unsigned int *>(amax + hk), __float_as_uint(mk));
+        atomicMax(reinterpret_cast<unsigned int *>(amax + Hkv + hk), __float_as_uint(mv));
+    }
+}
+
+__global__ void fill_zero_kernel(float *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
+__global__ void amax_to_scale_kernel(float *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = p[i] > 0.f ? p[i] / 448.0f : 1.0f;
+}
+
+// One workgroup per (page, KV head): rotate K, convert, write K and V parts in page order.
+// Tokens past the prefix end are written as zeros so that a whole page can always be read.
+__global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *pages, int P, const void *k, const void *v,
+                                    int io_dtype, const float2 *rope, const float *scale_kv)
+{
+    const int pg = blockIdx.x, hk = blockIdx.y;
+    const int d = g.head_dim, Hkv = g.n_kv_heads, half = d / 2, pairs = d / 16;
+    const int page = pages[pg];
+    char *kp = g.k_part(layer, page, hk);
+    char *vp = g.v_part(layer, page, hk);
+    float sc_k = 1.f, sc_v = 1.f;   // fp8: the per-head scales the codes are divided by
+    if (g.kv_dtype == SGC_FP8_E4M3) {
+        sc_k = scale_kv[hk];
+        sc_v = scale_kv[Hkv + hk];
+    }
+    for (int it = threadIdx.x; it < kPageTokens * pairs; it += blockDim.x) {
+        const int tok = it / pairs, cc = it % pairs;
+        const int j = pg * kPageTokens + tok;
+        float x1[8], x2[8], y1[8], y2[8];
+        if (j < P) {
+            const int64_t row = ((int64_t)j * Hkv + hk) * d;
+            load8(k, row + cc * 8, io_dtype, x1);
+            load8(k, row + half + cc * 8, io_dtype, x2);
+            if (rope) rope8(x1, x2, rope + (int64_t)j * half + cc * 8);
+            load8(v, row + cc * 8, io_dtype, y1);
+            load8(v, row + half + cc * 8, io_dtype, y2);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x1[i] = x2[i] = y1[i] = y2[i] = 0.f;
+        }
+        store8(kp, k_page_index(tok, cc * 8), g.kv_dtype, x1, sc_k);
+        store8(kp, k_page_index(tok, half + cc * 8), g.kv_dtype, x2, sc_k);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            store1(vp, v_page_index(tok, cc * 8 + i), g.kv_dtype, y1[i], sc_v);
+            store1(vp, v_page_index(tok, half + cc * 8 + i), g.kv_dtype, y2[i], sc_v);
+        }
+    }
+}
+
+// ---- export / import: raw element moves between page order and [P][Hkv][d] --------------------
+template <typename T>
+__global__ void cache_export_kernel(PoolGeom g, int layer, const int32_t *pages, int P, T *k, T *v)
+{
+    const int d = g.head_dim, Hkv = g.n_kv_heads;
+    const int64_t n = (int64_t)P * Hkv * d;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int c = (int)(idx % d);
+        const int hk = (int)((idx / d) % Hkv);
+        const int j = (int)(idx / ((int64_t)d * Hkv));
+        const int page = pages[j / kPageTokens], tok = j % kPageTokens;
+        k[idx] = reinterpret_cast<const T *>(g.k_part(layer, page, hk))[k_page_index(tok, c)];
+        v[idx] = reinterpret_cast<const T *>(g.v_part(layer, page, hk))[v_page_index(tok, c)];
+    }
+}
+
+template <typename T>
+__global__ void cache_import_kernel(PoolGeom g, int layer, const int32_t *pages, int P, const T *k, const T *v)
+{
+    const int d = g.head_dim, Hkv = g.n_kv_heads;
+    const int n_pages = (P + kPageTokens - 1) / kPageTokens;
+    const int64_t n = (int64_t)n_pages * kPageTokens * Hkv * d;   // whole pages: the tail is zeroed
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int c = (int)(idx % d);
+        const int hk = (int)((idx / d) % Hkv);
+        const int j = (int)(idx / ((int64_t)d * Hkv));
+        const int page = pages[j / kPageTokens], tok = j % kPageTokens;
+        const T kk = j < P ? k[idx] : T(0);
+        const T vv = j < P ? v[idx] : T(0);
+        reinterpret_cast<T *>(g.k_part(layer, page, hk))[k_page_index(tok, c)] = kk;
+        reinterpret_cast<T *>(g.v_part(layer, page, hk))[v_page_index(tok, c)] = vv;
+    }
+}
+
+// ---- generic attention: one wavefront per (token, query head) row ----------------------------
+// Lane l walks keys l, l + 64, ... keeping its own running (max, sum, weighted V); the 64 partial
+// states are merged at the end.  All arithmetic is fp32; scores are kept in the log2 domain.
+template <int D>
+__global__ void __launch_bounds__(256) attn_generic_kernel(AttnArgs a)
+{
+    __shared__ float q_s[4][D];
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int64_t row = (int64_t)blockIdx.x * 4 + wave;
+    const int Hq = a.n_q_heads, Hkv = a.n_kv_heads, g = a.group, half = D / 2;
+    const int64_t n_rows = (a.mode == MODE_SUFFIX ? a.total_tokens : (int64_t)a.prefix_len) * Hq;
+    const bool live = row < n_rows;     // dead waves still reach the barrier below
+
+    int h = 0, hk = 0, cluster = 0, P = 0, qpos = 0, n_cache = 0, n_self = 0;
+    int64_t src = 0, self_src0 = 0;
+    if (live) {
+        const int64_t tau = row / Hq;
+        h = (int)(row % Hq);
+        hk = h / g;
+        if (a.mode == MODE_SUFFIX) {
+            const int sq = a.tok_sq[tau];
+            cluster = a.sq_cluster[sq];
+            P = a.cl_prefix_len[cluster];
+            qpos = a.tok_qpos[tau];
+            src = a.tok_src[tau];
+            self_src0 = a.sq_src0[sq];
+            n_cache = P;
+            n_self = qpos + 1;
+        } else {
+            cluster = a.prefix_cluster;
+            P = 0;                 // position of row = its own index
+            qpos = (int)tau;
+            src = tau;
+            n_cache = qpos + 1;
+            n_self = 0;
+        }
+    }
+    const int pos = P + qpos;
+    // rotated query row into LDS (lanes 0 .. D/16-1 handle one chunk pair each)
+    if (live && lane < D / 16) {
+        float x1[8], x2[8];
+        const int64_t qrow = (src * Hq + h) * D;
+        load8(a.q, qrow + lane * 8, a.io_dtype, x1);
+        load8(a.q, qrow + half + lane * 8, a.io_dtype, x2);
+        if (a.rope) rope8(x1, x2, a.rope + (int64_t)pos * half + lane * 8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            q_s[wave][lane * 8 + i] = x1[i];
+            q_s[wave][half + lane * 8 + i] = x2[i];
+        }
+    }
+    __syncthreads();
+    if (!live) return;
+
+    float k_scale = 1.f, v_scale = 1.f;
+    if (a.kv_scale) {
+        const float *sc = a.kv_scale + ((int64_t)cluster * a.n_layers + a.layer) * 2 * Hkv;
+        k_scale = sc[hk];
+        v_scale = sc[Hkv + hk];
+    }
+    float m = -1e30f, l = 0.f, acc[D];
+#pragma unroll
+    for (int c = 0; c < D; ++c) acc[c] = 0.f;
+    const int32_t *pt = a.page_table + a.cl_pt_off[cluster];
+    const int kvd = a.pool.kv_dtype;
+
+    // cached keys
+    for (int j = lane; j < n_cache; j += kWave) {
+        const int page = pt[j / kPageTokens], tok = j % kPageTokens;
+        const char *kp = a.pool.k_part(a.layer, page, hk);
+        const char *vp = a.pool.v_part(a.layer, page, hk);
+        float s = 0.f;
+#pragma unroll
+        for (int cc = 0; cc < D / 8; ++cc) {
+            float kk[8];
+            load8(kp, k_page_index(tok, cc * 8), kvd, kk);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s += q_s[wave][cc * 8 + i] * kk[i];
+        }
+        s *= a.scale_log2e * k_scale;
+        float p, alpha = 1.f;
+        if (s > m) {
+            alpha = exp2f(m - s);
+            m = s;
+            p = 1.f;
+        } else {
+            p = exp2f(s - m);
+        }
+        l = l * alpha + p;
+        const float pv = p * v_scale;
+#pragma unroll
+        for (int c = 0; c < D; ++c) acc[c] = acc[c] * alpha + pv * load1(vp, v_page_index(tok, c), kvd);
+    }
+    // the query's own suffix keys 0..qpos, rotated at P + j
+    for (int j = lane; j < n_self; j += kWave) {
+        const int64_t krow = ((self_src0 + j) * Hkv + hk) * D;
+        float s = 0.f;
+#pragma unroll
+        for (int cc = 0; cc < D / 16; ++cc) {
+            float x1[8], x2[8];
+            load8(a.k, krow + cc * 8, a.io_dtype, x1);
+            load8(a.k, krow + half + cc * 8, a.io_dtype, x2);
+            if (a.rope) rope8(x1, x2, a.rope + (int64_t)(P + j) * half + cc * 8);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s += q_s[wave][cc * 8 + i] * x1[i] + q_s[wave][half + cc * 8 + i] * x2[i];
+        }
+        s *= a.scale_log2e;
+        float p, alpha = 1.f;
+        if (s > m) {
+            alpha = exp2f(m - s);
+            m = s;
+            p = 1.f;
+        } else {
+            p = exp2f(s - m);
+        }
+        l = l * alpha + p;
+#pragma unroll
+        for (int cc = 0; cc < D / 8; ++cc) {
+            float vv[8];
+            load8(a.v, krow + cc * 8, a.io_dtype, vv);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[cc * 8 + i] = acc[cc * 8 + i] * alpha + p * vv[i];
+        }
+    }
+    // merge the 64 partial states
+    float M = m;
+    for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+    const float f = exp2f(m - M);
+    l *= f;
+    for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
+    const float inv_l = 1.0f / l;
+    const int64_t orow = (src * Hq + h) * D;
+#pragma unroll
+    for (int c = 0; c < D; ++c) {
+        float x = acc[c] * f;
+        for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+        if (lane == (c & 63)) {
+            const float y = x * inv_l;
+            if (a.io_dtype == SGC_F32)
+                static_cast<float *>(a.o)[orow + c] = y;
+            else
+                static_cast<uint16_t *>(a.o)[orow + c] = f32_to_bf16(y);
+        }
+    }
+    if (a.lse && lane == 0) {
+        const int64_t col = a.mode == MODE_SUFFIX ? src : (int64_t)qpos;
+        a.lse[(int64_t)h * a.lse_stride + col] = (M + log2f(l)) * 0.6931471805599453f;
+    }
+}
+
+}  // namespace
+
+// ---- launchers -------------------------------------------------------------------------------
+hipError_t launch_rope_table(float2 *table, int n_pos, int head_dim, double base, hipStream_t s)
+{
+    const int half = head_dim / 2;
+    const int64_t n = (int64_t)n_pos * half;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, table, n_pos, half, base,
+                       1.0 / (double)head_dim);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefix_ingest(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len, const void *k,
+                                const void *v, int io_dtype, const float2 *rope, float *d_scale_kv, hipStream_t s)
+{
+    const int n_pages = (prefix_len + kPageTokens - 1) / kPageTokens;
+    if (n_pages == 0) return hipSuccess;
+    const dim3 grid(n_pages, g.n_kv_heads);
+    if (g.kv_dtype == SGC_FP8_E4M3) {
+        const int n = 2 * g.n_kv_heads;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((n + 63) / 64), dim3(64), 0, s, d_scale_kv, n);
+        hipLaunchKernelGGL(ingest_amax_kernel, grid, dim3(128), 0, s, k, v, io_dtype, prefix_len, g.n_kv_heads, g.head_dim,
+                           rope, d_scale_kv);
+        hipLaunchKernelGGL(amax_to_scale_kernel, dim3((n + 63) / 64), dim3(64), 0, s, d_scale_kv, n);
+    }
+    hipLaunchKernelGGL(ingest_write_kernel, grid, dim3(128), 0, s, g, layer, d_pages, prefix_len, k, v, io_dtype, rope,
+                       (const float *)d_scale_kv);
+    return hipGetLastError();
+}
+
+hipError_t launch_cache_export(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len, void *k, void *v,
+                               hipStream_t s)
+{
+    const int64_t n = (int64_t)prefix_len * g.n_kv_heads * g.head_dim;
+    const unsigned blocks = (unsigned)std::min<int64_t>((n + 255) / 256, 65536);
+    if (g.kv_bytes == 4)
+        hipLaunchKernelGGL(cache_export_kernel<uint32_t>, dim3(blocks), dim3(256), 0, s, g, layer, d_pages, prefix_len,
+                           (uint32_t *)k, (uint32_t *)v);
+    else if (g.kv_bytes == 2)
+        hipLaunchKernelGGL(cache_export_kernel<uint16_t>, dim3(blocks), dim3(256), 0, s, g, layer, d_pages, prefix_len,
+                           (uint16_t *)k, (uint16_t *)v);
+    else
+        hipLaunchKernelGGL(cache_export_kernel<uint8_t>, dim3(blocks), dim3(256), 0, s, g, layer, d_pages, prefix_len,
+                           (uint8_t *)k, (uint8_t *)v);
+    return hipGetLastError();
+}
+
+hipError_t launch_cache_import(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len, const void *k,
+                               const void *v, hipStream_t s)
+{
+    const int n_pages = (prefix_len + kPageTokens - 1) / kPageTokens;
+    const int64_t n = (int64_t)n_pages * kPageTokens * g.n_kv_heads * g.head_dim;
+    const unsigned blocks = (unsigned)std::min<int64_t>((n + 255) / 256, 65536);
+    if (g.kv_bytes == 4)
+        hipLaunchKernelGGL(cache_import_kernel<uint32_t>, dim3(blocks), dim3(256), 0, s, g, layer, d_pages, prefix_len,
+                           (const uint32_t *)k, (const uint32_t *)v);
+    else if (g.kv_bytes == 2)
+        hipLaunchKernelGGL(cache_import_kernel<uint16_t>, dim3(blocks), dim3(256), 0, s, g, layer, d_pages, prefix_len,
+                           (const uint16_t *)k, (const uint16_t *)v);
+    else
+        hipLaunchKernelGGL(cache_import_kernel<uint8_t>, dim3(blocks), dim3(256), 0, s, g, layer, d_pages, prefix_len,
+                           (const uint8_t *)k, (const uint8_t *)v);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_generic(const AttnArgs &a, int64_t n_rows, hipStream_t s)
+{
+    if (n_rows <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((n_rows + 3) / 4);
+    if (a.head_dim == 64)
+        hipLaunchKernelGGL(attn_generic_kernel<64>, dim3(blocks), dim3(256), 0, s, a);
+    else
+        hipLaunchKernelGGL(attn_generic_kernel<128>, dim3(blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace sgc

@@ -1,0 +1,83 @@
+"""Test-side helpers: run the CPU oracle on a synthetic workload, and an emulation of the GPU's
+rounding points (numpy, dense) used only to calibrate how tight a tolerance can be."""
+from __future__ import annotations
+
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+
+from oracle import oracle as orc
+from paper_2505_10951_amd.workloads import Workload, round_to_bf16
+
+
+def oracle_caches(w: Workload, layer: int = 0, clusters: Optional[Sequence[int]] = None) -> Dict[int, tuple]:
+    """cluster -> (cache_k, cache_v) as the attention reads them (fp8: oracle-quantised, dequantised)."""
+    out = {}
+    for c in (range(w.n_clusters) if clusters is None else clusters):
+        k, v = w.prefix_kv(c, layer)
+        ck, cv, _, _ = orc.prefix_prefill(None, k, v, w.rope_base)
+        if w.kv_dtype == "fp8_e4m3":
+            _, _, ck = orc.quantise_e4m3(ck)
+            _, _, cv = orc.quantise_e4m3(cv)
+        out[c] = (ck, cv)
+    return out
+
+
+def oracle_suffix(w: Workload, layer: int = 0, queries: Optional[Sequence[int]] = None, caches=None):
+    """Oracle output for the chosen queries (default all).  Returns (rows, o_ref [len(rows)][Hq][d],
+    lse_ref [Hq][len(rows)]): `rows` indexes the packed token rows of the full batch."""
+    queries = list(range(w.n_queries)) if queries is None else list(queries)
+    cu = w.cu_seqlens
+    need = sorted({int(w.labels[n]) for n in queries})
+    caches = oracle_caches(w, layer, need) if caches is None else caches
+    nc = w.n_clusters
+    empty = np.zeros((0, w.n_kv_heads, w.head_dim))
+    cks = [caches[c][0] if c in caches else empty for c in range(nc)]
+    cvs = [caches[c][1] if c in caches else empty for c in range(nc)]
+    qs, ks, vs, rows, sub_cu = [], [], [], [], [0]
+    for n in queries:
+        q, k, v = w.suffix_qkv_query(n, layer)
+        qs.append(q), ks.append(k), vs.append(v)
+        rows.extend(range(int(cu[n]), int(cu[n + 1])))
+        sub_cu.append(sub_cu[-1] + q.shape[0])
+    if sub_cu[-1] == 0:
+        return np.zeros(0, dtype=np.int64), np.zeros((0, w.n_q_heads, w.head_dim)), np.zeros((w.n_q_heads, 0))
+    o, lse = orc.suffix_prefill_batched(w.labels[queries], np.array(sub_cu), cks, cvs, np.concatenate(qs),
+                                        np.concatenate(ks), np.concatenate(vs), w.rope_base)
+    return np.array(rows, dtype=np.int64), o, lse
+
+
+def bf16_rounding_floor(w: Workload, n: int, layer: int = 0) -> float:
+    """max |o_rounded - o_exact| for query n when the rotated Q and K, the probabilities and the output
+    are rounded to bf16 where a bf16 matrix-core kernel has to round them (dense numpy, fp64 otherwise).
+    A measure of the error any such kernel carries; used to set a tolerance, not as a reference."""
+    c = int(w.labels[n])
+    pk, pv = w.prefix_kv(c, layer)
+    q, k, v = w.suffix_qkv_query(n, layer)
+    P, S = pk.shape[0], q.shape[0]
+    g = w.n_q_heads // w.n_kv_heads
+    r = lambda x: round_to_bf16(np.asarray(x, dtype=np.float32)).astype(np.float64)
+    kr = np.concatenate([orc.rope_numpy(pk, np.arange(P), w.rope_base), orc.rope_numpy(k, P + np.arange(S), w.rope_base)])
+    qr = orc.rope_numpy(q, P + np.arange(S), w.rope_base)
+    vv = np.concatenate([pv, v]).astype(np.float64)
+    mask = np.arange(P + S)[None, :] <= (P + np.arange(S))[:, None]
+
+    def attend(qx, kx, round_p):
+        s = np.einsum("ihc,jhc->hij", qx, np.repeat(kx, g, axis=1)) / np.sqrt(w.head_dim)
+        s = np.where(mask[None], s, -np.inf)
+        e = np.exp(s - s.max(axis=-1, keepdims=True))
+        z = e.sum(axis=-1, keepdims=True)
+        if round_p:
+            e = r(e)
+        return np.einsum("hij,jhc->ihc", e / z, np.repeat(vv, g, axis=1))
+
+    exact = attend(qr, kr, False)
+    rounded = r(attend(r(qr), r(kr), True))
+    return float(np.abs(rounded - exact).max())
+
+
+def err_stats(o_gpu: np.ndarray, o_ref: np.ndarray) -> Dict[str, float]:
+    d = np.abs(o_gpu.astype(np.float64) - o_ref)
+    rms = float(np.sqrt(np.mean(o_ref ** 2))) if o_ref.size else 0.0
+    return {"max_abs": float(d.max()) if d.size else 0.0, "rms_ref": rms,
+            "rel": float(d.max() / rms) if d.size and rms > 0 else 0.0}

@@ -1,0 +1,353 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU fp64 oracle on the same
+seeded inputs, element by element.  Tolerances: 2e-2 max-abs for bf16 in / fp32 accumulate,
+6e-2 with an fp8 cache (the stated bars), 2e-5 for the fp32 path, plus a calibrated tighter bar
+(a few times the error any bf16 kernel carries) so that a wrong mask or index cannot hide."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2505_10951_amd import sgc, workloads
+from paper_2505_10951_amd.harness import Session, run_workload, to_device, to_host_f32
+
+from ref_util import bf16_rounding_floor, err_stats, oracle_caches, oracle_suffix
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16, TOL_FP8, TOL_F32 = 2e-2, 6e-2, 2e-5
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _check_suffix(w, out, queries=None, tol=TOL_BF16, tight=None, lse_tol=None):
+    rows, o_ref, lse_ref = oracle_suffix(w, 0, queries)
+    st = err_stats(out["o"][rows], o_ref)
+    _say(f"  {w.name}: rows {len(rows)} max_abs {st['max_abs']:.3e} rel {st['rel']:.3e} (tol {tol:g}, tight {tight})")
+    assert np.isfinite(out["o"]).all()
+    assert st["max_abs"] <= tol
+    if tight is not None:
+        assert st["max_abs"] <= tight
+    if out.get("lse") is not None:
+        lerr = np.abs(out["lse"][:, rows] - lse_ref).max() if len(rows) else 0.0
+        _say(f"  lse max_abs {lerr:.3e}")
+        assert lerr <= (lse_tol if lse_tol is not None else max(tol, 1e-4))
+    return st
+
+
+def _check_bookkeeping(w, out):
+    o_ref, off_ref, cu_ref = orc.assign_clusters(w.labels, w.suffix_len, w.n_clusters)
+    assert np.array_equal(out["order"], o_ref) and np.array_equal(out["cluster_off"], off_ref)
+    assert np.array_equal(out["cu_seqlens"], cu_ref)
+
+
+# ---- configs[0]: tiny fp32 MHA layer, in full --------------------------------------------------
+def test_config0_tiny_f32_full():
+    w = workloads.config(0)
+    _say("config 0", w.name, "T", w.total_suffix_tokens)
+    out = run_workload(w)
+    _check_bookkeeping(w, out)
+    _check_suffix(w, out, tol=TOL_F32, lse_tol=2e-5)
+
+
+@pytest.mark.parametrize("io,kv,d", [("f32", "f32", 128), ("bf16", "bf16", 64), ("bf16", "fp8_e4m3", 64)])
+def test_generic_kernel_other_shapes(io, kv, d):
+    w = workloads.custom(f"generic_{io}_{kv}_{d}", n_q_heads=4, n_kv_heads=2, head_dim=d, rope_base=10000.0, io_dtype=io,
+                         kv_dtype=kv, prefix_len=[70, 33, 0], queries_per_cluster=3, suffix_range=(1, 20), seed=77)
+    out = run_workload(w, kernel=sgc.SGC_KERNEL_GENERIC)
+    _check_suffix(w, out, tol={"f32": TOL_F32, "bf16": TOL_BF16, "fp8_e4m3": TOL_FP8}[kv])
+
+
+# ---- bf16 MFMA kernel: scaled-down cases spanning several tiles and ragged tails ----------------
+def _small_gqa(seed=5, **kw):
+    base = dict(n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=500000.0, io_dtype="bf16",
+                prefix_len=[200, 71, 128], cluster_sizes=[5, 3, 4], suffix_range=(1, 70), seed=seed, k_outlier_scale=8.0)
+    base.update(kw)
+    return workloads.custom("small_gqa", **base)
+
+
+def test_mfma_small_gqa_full():
+    w = _small_gqa()
+    _say("small gqa T", w.total_suffix_tokens, "suffix", w.suffix_len.tolist())
+    out = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
+    _check_bookkeeping(w, out)
+    floor = max(bf16_rounding_floor(w, n) for n in (0, 3, 7))
+    _say(f"  bf16 rounding floor {floor:.3e}")
+    _check_suffix(w, out, tol=TOL_BF16, tight=max(4 * floor, 2e-3))
+
+
+def test_mfma_small_mha_ragged():
+    w = workloads.custom("small_mha", n_q_heads=4, n_kv_heads=4, head_dim=128, rope_base=10000.0, io_dtype="bf16",
+                         prefix_len=[300, 17, 64, 1], cluster_sizes=[9, 1, 2, 4], suffix_range=(24, 96), seed=9)
+    out = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
+    floor = max(bf16_rounding_floor(w, n) for n in (0, 5))
+    _check_suffix(w, out, tol=TOL_BF16, tight=max(4 * floor, 2e-3))
+
+
+def test_mfma_matches_generic_kernel():
+    w = _small_gqa(seed=21)
+    a = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
+    b = run_workload(w, kernel=sgc.SGC_KERNEL_GENERIC)
+    d = np.abs(a["o"] - b["o"]).max()
+    _say(f"  mfma vs generic max_abs {d:.3e}")
+    assert d <= 1e-2
+    assert np.abs(a["lse"] - b["lse"]).max() <= 2e-2
+
+
+def test_mfma_edge_cases():
+    # empty cluster, zero-length queries, P = 0, P one short of / one past a page and a 64-key tile,
+    # single-token queries, a query longer than one key tile
+    plen = [0, 15, 16, 17, 63, 64, 65, 1]
+    labels = np.array([0, 0, 1, 2, 3, 4, 5, 6, 7, 7, 5, 3, 0], dtype=np.int32)
+    slen = np.array([1, 70, 3, 0, 16, 17, 64, 65, 1, 130, 2, 1, 0], dtype=np.int32)
+    w = workloads.custom("edges", n_q_heads=4, n_kv_heads=2, head_dim=128, rope_base=10000.0, io_dtype="bf16",
+                         prefix_len=plen, labels=labels, suffix_len=slen, seed=13)
+    for kernel in (sgc.SGC_KERNEL_MFMA, sgc.SGC_KERNEL_GENERIC):
+        out = run_workload(w, kernel=kernel)
+        _check_bookkeeping(w, out)
+        _check_suffix(w, out, tol=TOL_BF16, tight=6e-3)
+
+
+def test_mfma_all_queries_empty_and_single_row():
+    w = workloads.custom("empty", n_q_heads=4, n_kv_heads=4, head_dim=128, rope_base=10000.0, io_dtype="bf16",
+                         prefix_len=[40], labels=[0, 0], suffix_len=[0, 0], seed=1)
+    out = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
+    assert out["o"].shape[0] == 0
+    w = workloads.custom("one", n_q_heads=1, n_kv_heads=1, head_dim=128, rope_base=10000.0, io_dtype="bf16",
+                         prefix_len=[40], labels=[0], suffix_len=[1], seed=2)
+    out = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
+    _check_suffix(w, out, tol=TOL_BF16, tight=6e-3)
+
+
+def test_mfma_peaky_softmax_one_hot_v_exposes_the_mask():
+    # Q scaled so that softmax concentrates on a few keys; V rows are one-hot in (key index mod d):
+    # channel c of the output is the total probability of keys j = c (mod d).  A key that must not
+    # be seen (later suffix tokens, other queries) shows up as mass in the wrong channel.
+    P, S = 100, 28
+    w = workloads.custom("peaky", n_q_heads=2, n_kv_heads=1, head_dim=128, rope_base=10000.0, io_dtype="bf16",
+                         prefix_len=[P], labels=[0, 0], suffix_len=[S, S], seed=31, q_gain=6.0)
+    eye = np.eye(128, dtype=np.float32)
+
+    with Session(w, kernel=sgc.SGC_KERNEL_MFMA) as s:
+        s.alloc_cluster(0)
+        pk, _ = w.prefix_kv(0)
+        pv = eye[np.arange(P) % 128][:, None, :]
+        s.prefix_prefill(0, 0, k=pk, v=pv)
+        s.assign()
+        q, k, _ = w.suffix_qkv()
+        v = np.concatenate([eye[(P + np.arange(S)) % 128], eye[(P + np.arange(S)) % 128]])[:, None, :]
+        do = s.suffix_prefill(to_device(q, "bf16"), to_device(k, "bf16"), to_device(v, "bf16"))
+        torch.cuda.synchronize()
+        o = to_host_f32(do)
+    ck, cv, _, _ = orc.prefix_prefill(None, pk, pv, w.rope_base)
+    o_ref, _ = orc.suffix_prefill_batched(w.labels, w.cu_seqlens, [ck], [cv], q, k, v, w.rope_base)
+    assert np.abs(o - o_ref).max() <= 1e-2
+    for n in range(2):
+        for i in range(S):
+            row = o[n * S + i]                       # [Hq][d]
+            unseen = np.arange(P + i + 1, 128)       # keys i+1.. of the own suffix and nothing beyond
+            assert np.all(row[:, unseen] == 0), (n, i)
+            assert np.all(np.abs(row.sum(axis=-1) - 1) < 2e-2)
+
+
+def test_batch_composition_does_not_change_a_query():
+    w = _small_gqa(seed=41)
+    full = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
+    cu = w.cu_seqlens
+    keep = [1, 4, 6, 10][::-1]
+    sub = workloads.custom("subset", n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=500000.0, io_dtype="bf16",
+                           prefix_len=w.prefix_len, labels=w.labels[keep], suffix_len=w.suffix_len[keep], seed=41,
+                           k_outlier_scale=8.0)
+    with Session(sub, kernel=sgc.SGC_KERNEL_MFMA) as s:
+        for c in range(sub.n_clusters):
+            s.alloc_cluster(c)
+            s.prefix_prefill(c)
+        s.assign()
+        qs, ks, vs = zip(*[w.suffix_qkv_query(n) for n in keep])
+        do = s.suffix_prefill(*(to_device(np.concatenate(x), "bf16") for x in (qs, ks, vs)))
+        torch.cuda.synchronize()
+        o = to_host_f32(do)
+    at = 0
+    for n in keep:
+        S = int(w.suffix_len[n])
+        ref = full["o"][cu[n]:cu[n + 1]]
+        assert np.abs(o[at:at + S] - ref).max() <= 4e-3, n     # same math, other tile packing
+        at += S
+
+
+def test_repeat_launch_is_bit_identical():
+    w = _small_gqa(seed=43)
+    a = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
+    b = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
+    assert np.array_equal(a["o"], b["o"]) and np.array_equal(a["lse"], b["lse"])
+
+
+# ---- prefix prefill: cache contents and the prefix's own causal attention -----------------------
+@pytest.mark.parametrize("kernel", [sgc.SGC_KERNEL_MFMA, sgc.SGC_KERNEL_GENERIC])
+def test_prefix_prefill_cache_and_causal_output(kernel):
+    w = workloads.custom("prefix", n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=500000.0, io_dtype="bf16",
+                         prefix_len=[333, 64, 5], queries_per_cluster=1, suffix_range=(1, 1), seed=17)
+    with Session(w, kernel=kernel) as s:
+        for c in range(w.n_clusters):
+            s.alloc_cluster(c)
+            do, dlse = s.prefix_prefill(c, 0, with_q=True, want_lse=True)
+            pk, pv = w.prefix_kv(c)
+            ck, cv, o_ref, lse_ref = orc.prefix_prefill(w.prefix_q(c), pk, pv, w.rope_base, want_lse=True)
+            ek, ev, _, _ = s.export_cluster(c)
+            assert np.array_equal(ev, pv)                                     # V is stored as given
+            assert np.abs(ek - ck).max() <= np.abs(ck).max() * 2.0 ** -8      # K: one bf16 rounding
+            st = err_stats(to_host_f32(do), o_ref)
+            _say(f"  prefix cluster {c} P {w.prefix_len[c]} max_abs {st['max_abs']:.3e}")
+            assert st["max_abs"] <= TOL_BF16 and st["max_abs"] <= 8e-3
+            assert np.abs(dlse.cpu().numpy() - lse_ref).max() <= 2e-2
+
+
+def test_prefix_prefill_f32_cache_exact_layout_roundtrip():
+    w = workloads.config(0)
+    with Session(w) as s:
+        s.alloc_cluster(0)
+        s.prefix_prefill(0)
+        pk, pv = w.prefix_kv(0)
+        ck, cv, _, _ = orc.prefix_prefill(None, pk, pv, w.rope_base)
+        ek, ev, _, _ = s.export_cluster(0)
+        assert np.array_equal(ev, pv) and np.abs(ek - ck).max() <= 2e-6
+        # import(export) is the identity on the pages; shuffled physical pages do not matter
+        s.alloc_cluster(1)
+        s.import_cluster(1, 0, ek[:192], ev[:192])
+        ek1, ev1, _, _ = s.export_cluster(1)
+        assert np.array_equal(ek1, ek[:192]) and np.array_equal(ev1, ev[:192])
+
+
+def test_physical_page_order_does_not_matter():
+    w = _small_gqa(seed=47)
+    ref = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
+    with Session(w, kernel=sgc.SGC_KERNEL_MFMA, total_pages=200, max_clusters=8) as s:
+        # fragment the pool: interleave dummy allocations and free them again
+        sgc.sgc_cache_alloc_cluster(s.ctx, s.cache, 5, 40)
+        s.alloc_cluster(1)
+        sgc.sgc_cache_alloc_cluster(s.ctx, s.cache, 6, 100)
+        s.alloc_cluster(0)
+        sgc.sgc_cache_free_cluster(s.ctx, s.cache, 5)
+        s.alloc_cluster(2)
+        sgc.sgc_cache_free_cluster(s.ctx, s.cache, 6)
+        pages = [sgc.sgc_cache_cluster_pages(s.ctx, s.cache, c)[0] for c in range(3)]
+        assert any(np.any(np.diff(p) != 1) for p in pages) or pages[0][0] != 0
+        for c in range(3):
+            s.prefix_prefill(c)
+        s.assign()
+        q, k, v = w.suffix_qkv()
+        do = s.suffix_prefill(*(to_device(x, "bf16") for x in (q, k, v)))
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host_f32(do), ref["o"])
+
+
+# ---- fp8 e4m3 cache --------------------------------------------------------------------------
+def test_fp8_codec_and_quantised_cache_match_oracle():
+    # all 256 codes decode as the oracle says; encoding agrees on every code point and midpoint
+    d, Hkv = 128, 1
+    vals = [orc.e4m3_decode(c) for c in range(0x7F)]
+    mids = [(vals[i] + vals[i + 1]) / 2 for i in range(0x7E)]
+    x = np.array(vals + mids + [448.0] * 3, dtype=np.float64)
+    x = np.concatenate([x, -x])
+    P = -(-x.size // d)
+    flat = np.zeros(P * d)
+    flat[: x.size] = x
+    k = flat.reshape(P, Hkv, d).astype(np.float32)
+    assert np.array_equal(workloads.round_to_bf16(k), k)       # representable: the GPU sees these exact values
+    w = workloads.custom("codec", n_q_heads=1, n_kv_heads=1, head_dim=d, rope_base=0.0, io_dtype="bf16",
+                         kv_dtype="fp8_e4m3", prefix_len=[P], labels=[0], suffix_len=[1], seed=3)
+    with Session(w) as s:
+        s.alloc_cluster(0)
+        s.prefix_prefill(0, 0, k=k, v=k[::-1].copy())
+        ek, ev, ks, vs = s.export_cluster(0)
+    codes, scale, _ = orc.quantise_e4m3(k.astype(np.float64))
+    assert ks[0] == scale[0] == 1.0 and vs[0] == 1.0         # amax = 448
+    assert np.array_equal(ek, codes)
+    assert np.array_equal(ev, codes[::-1])
+
+
+@pytest.mark.parametrize("kernel", [sgc.SGC_KERNEL_MFMA, sgc.SGC_KERNEL_GENERIC])
+def test_fp8_cache_small(kernel):
+    w = workloads.custom("fp8_small", n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=500000.0, io_dtype="bf16",
+                         kv_dtype="fp8_e4m3", prefix_len=[260, 64, 31], cluster_sizes=[4, 2, 3], suffix_range=(1, 80),
+                         seed=23)
+    with Session(w, kernel=kernel) as s:
+        for c in range(w.n_clusters):
+            s.alloc_cluster(c)
+            s.prefix_prefill(c)
+        # the device's quantised cache against the oracle's: scales equal to an ulp, codes equal
+        # except where fp32 rotation lands on the other side of a rounding boundary
+        for c in range(w.n_clusters):
+            pk, pv = w.prefix_kv(c)
+            ck, cv, _, _ = orc.prefix_prefill(None, pk, pv, w.rope_base)
+            kc, ksc, _ = orc.quantise_e4m3(ck)
+            vc, vsc, _ = orc.quantise_e4m3(cv)
+            ek, ev, ks, vs = s.export_cluster(c)
+            assert np.allclose(ks, ksc, rtol=3e-7) and np.array_equal(vs, vsc)
+            assert np.array_equal(ev, vc)
+            diff = ek != kc
+            _say(f"  cluster {c}: K codes differing {diff.mean():.2e}")
+            assert diff.mean() < 5e-3
+            assert np.all(np.abs(ek.astype(np.int16)[diff] - kc.astype(np.int16)[diff]) == 1)
+        s.assign()
+        q, k, v = w.suffix_qkv()
+        do = s.suffix_prefill(*(to_device(x, "bf16") for x in (q, k, v)))
+        torch.cuda.synchronize()
+        out = {"o": to_host_f32(do), "lse": None}
+    _check_suffix(w, out, tol=TOL_FP8, tight=1e-2)
+
+
+def test_fp8_imported_oracle_cache_isolates_the_attention():
+    # load the ORACLE's quantised cache into the pages, so both sides read identical codes
+    w = workloads.custom("fp8_import", n_q_heads=8, n_kv_heads=1, head_dim=128, rope_base=500000.0, io_dtype="bf16",
+                         kv_dtype="fp8_e4m3", prefix_len=[150], cluster_sizes=[3], suffix_range=(5, 40), seed=29)
+    pk, pv = w.prefix_kv(0)
+    ck, cv, _, _ = orc.prefix_prefill(None, pk, pv, w.rope_base)
+    kc, ksc, kdeq = orc.quantise_e4m3(ck)
+    vc, vsc, vdeq = orc.quantise_e4m3(cv)
+    with Session(w, kernel=sgc.SGC_KERNEL_MFMA) as s:
+        s.alloc_cluster(0)
+        s.import_cluster(0, 0, kc, vc, ksc, vsc)
+        s.assign()
+        q, k, v = w.suffix_qkv()
+        do = s.suffix_prefill(*(to_device(x, "bf16") for x in (q, k, v)))
+        torch.cuda.synchronize()
+        o = to_host_f32(do)
+    o_ref, _ = orc.suffix_prefill_batched(w.labels, w.cu_seqlens, [kdeq], [vdeq], q, k, v, w.rope_base)
+    st = err_stats(o, o_ref)
+    _say(f"  fp8 import max_abs {st['max_abs']:.3e}")
+    assert st["max_abs"] <= 6e-3
+
+
+# ---- configs[1..4] at full size, in the benchmark's launch configuration, on sampled queries -----
+def _sampled_queries(w, per_cluster, seed=0):
+    rng = np.random.default_rng(seed)
+    picks = []
+    for c in range(w.n_clusters):
+        members = np.flatnonzero(w.labels == c)
+        if members.size:
+            picks.extend(rng.choice(members, size=min(per_cluster, members.size), replace=False).tolist())
+    return sorted(picks)
+
+
+def test_config1_llama3_8b_layer_full_size_sampled():
+    w = workloads.config(1)
+    _say("config 1", w.name, "T", w.total_suffix_tokens, "flop %.3e" % w.flops())
+    out = run_workload(w)
+    _check_bookkeeping(w, out)
+    qs = _sampled_queries(w, 2)
+    floor = max(bf16_rounding_floor(w, n) for n in qs[:2])
+    _say(f"  bf16 rounding floor {floor:.3e}")
+    _check_suffix(w, out, queries=qs, tol=TOL_BF16, tight=max(4 * floor, 2e-3))
+    assert np.isfinite(out["o"]).all() and np.abs(out["o"]).max() < 8
+
+
+def test_config2_llama2_7b_ragged_full_size_sampled():
+    w = workloads.config(2)
+    _say("config 2", w.name, "T", w.total_suffix_tokens, "flop %.3e" % w.flops())
+    out = run_workload(w, want_lse=False)
+    _check_bookkeeping(w, out)
+    qs = _sampled_queries(w, 1)[:8]
+    _check_suffix(w, out, queries=qs, tol=TOL_BF16, tight=4e-3)
+    assert np.isfinite(out["o"]).all()

@@ -288,7 +288,10 @@ uint8_t sgc_oracle_e4m3_encode(double x)
 /* ---------------------------------------------------------------------------------------
  * Per-KV-head quantisation of one cluster's cached tensor x [P][Hkv][d] (K after rotation, or
  * V): scale[h] = amax_h / 448 rounded to fp32 (amax_h == 0 gives scale 1), code = encode(x /
- * scale).  deq (may be NULL) receives decode(code) * scale, the values attention then reads.
+ * scale).  The scales are fp32 numbers, and the quotient that decides the code is taken in
+ * fp32 as well (x rounded to fp32, divided by the fp32 scale), the precision in which the GPU
+ * takes the same decision.  deq (may be NULL) receives decode(code) * scale, the values
+ * attention then reads.
  * ------------------------------------------------------------------------------------- */
 void sgc_oracle_quantise_e4m3(const double *x, int64_t P, int Hkv, int d, uint8_t *codes,
                               float *scale, double *deq)
@@ -306,7 +309,8 @@ void sgc_oracle_quantise_e4m3(const double *x, int64_t P, int Hkv, int d, uint8_
         for (int64_t j = 0; j < P; ++j)
             for (int c = 0; c < d; ++c) {
                 const size_t idx = ((size_t)j * Hkv + h) * d + c;
-                const uint8_t code = sgc_oracle_e4m3_encode(x[idx] / (double)sc);
+                const float quotient = (float)x[idx] / sc;
+                const uint8_t code = sgc_oracle_e4m3_encode((double)quotient);
                 codes[idx] = code;
                 if (deq) deq[idx] = sgc_oracle_e4m3_decode(code) * (double)sc;
             }

@@ -47,33 +47,49 @@ def oracle_suffix(w: Workload, layer: int = 0, queries: Optional[Sequence[int]] 
     return np.array(rows, dtype=np.int64), o, lse
 
 
-def bf16_rounding_floor(w: Workload, n: int, layer: int = 0) -> float:
-    """max |o_rounded - o_exact| for query n when the rotated Q and K, the probabilities and the output
-    are rounded to bf16 where a bf16 matrix-core kernel has to round them (dense numpy, fp64 otherwise).
-    A measure of the error any such kernel carries; used to set a tolerance, not as a reference."""
-    c = int(w.labels[n])
-    pk, pv = w.prefix_kv(c, layer)
-    q, k, v = w.suffix_qkv_query(n, layer)
+def bf16_floor_arrays(pk, pv, q, k, v, rope_base: float, want_lse: bool = False):
+    """max |o_rounded - o_exact| (and, with want_lse, the same for LSE) of one query's suffix prefill when the
+    rotated Q and K, the probabilities and the output are rounded to bf16 where a bf16 matrix-core kernel has
+    to round them (dense numpy, fp64 otherwise).  A measure of the error any such kernel carries; used to set
+    a tolerance, never as a reference."""
     P, S = pk.shape[0], q.shape[0]
-    g = w.n_q_heads // w.n_kv_heads
+    d = q.shape[-1]
+    g = q.shape[1] // k.shape[1]
     r = lambda x: round_to_bf16(np.asarray(x, dtype=np.float32)).astype(np.float64)
-    kr = np.concatenate([orc.rope_numpy(pk, np.arange(P), w.rope_base), orc.rope_numpy(k, P + np.arange(S), w.rope_base)])
-    qr = orc.rope_numpy(q, P + np.arange(S), w.rope_base)
+    kr = np.concatenate([orc.rope_numpy(pk, np.arange(P), rope_base), orc.rope_numpy(k, P + np.arange(S), rope_base)])
+    qr = orc.rope_numpy(q, P + np.arange(S), rope_base)
     vv = np.concatenate([pv, v]).astype(np.float64)
     mask = np.arange(P + S)[None, :] <= (P + np.arange(S))[:, None]
 
     def attend(qx, kx, round_p):
-        s = np.einsum("ihc,jhc->hij", qx, np.repeat(kx, g, axis=1)) / np.sqrt(w.head_dim)
+        s = np.einsum("ihc,jhc->hij", qx, np.repeat(kx, g, axis=1)) / np.sqrt(d)
         s = np.where(mask[None], s, -np.inf)
         e = np.exp(s - s.max(axis=-1, keepdims=True))
         z = e.sum(axis=-1, keepdims=True)
+        lse = (s.max(axis=-1, keepdims=True) + np.log(z))[..., 0]
         if round_p:
             e = r(e)
-        return np.einsum("hij,jhc->ihc", e / z, np.repeat(vv, g, axis=1))
+        return np.einsum("hij,jhc->ihc", e / z, np.repeat(vv, g, axis=1)), lse
 
-    exact = attend(qr, kr, False)
-    rounded = r(attend(r(qr), r(kr), True))
-    return float(np.abs(rounded - exact).max())
+    exact, lse_exact = attend(qr, kr, False)
+    rounded, lse_rounded = attend(r(qr), r(kr), True)
+    o_floor = float(np.abs(r(rounded) - exact).max())
+    if want_lse:
+        return o_floor, float(np.abs(lse_rounded - lse_exact).max())
+    return o_floor
+
+
+def bf16_rounding_floor(w: Workload, n: int, layer: int = 0, want_lse: bool = False):
+    """bf16_floor_arrays for query n of a workload."""
+    pk, pv = w.prefix_kv(int(w.labels[n]), layer)
+    q, k, v = w.suffix_qkv_query(n, layer)
+    return bf16_floor_arrays(pk, pv, q, k, v, w.rope_base, want_lse)
+
+
+def tight_bar(w: Workload, queries, layer: int = 0, factor: float = 4.0, floor_min: float = 5e-4):
+    """(o_bar, lse_bar): `factor` times the largest bf16 rounding floor over the given queries."""
+    fl = [bf16_rounding_floor(w, n, layer, want_lse=True) for n in queries if w.suffix_len[n] > 0]
+    return factor * max([f[0] for f in fl] + [floor_min]), factor * max([f[1] for f in fl] + [floor_min])
 
 
 def err_stats(o_gpu: np.ndarray, o_ref: np.ndarray) -> Dict[str, float]:

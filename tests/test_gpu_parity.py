@@ -10,7 +10,7 @@ from oracle import oracle as orc
 from paper_2505_10951_amd import sgc, workloads
 from paper_2505_10951_amd.harness import Session, run_workload, to_device, to_host_f32
 
-from ref_util import bf16_rounding_floor, err_stats, oracle_caches, oracle_suffix
+from ref_util import bf16_floor_arrays, bf16_rounding_floor, err_stats, oracle_caches, oracle_suffix, tight_bar
 
 pytestmark = pytest.mark.gpu
 
@@ -30,9 +30,11 @@ def _check_suffix(w, out, queries=None, tol=TOL_BF16, tight=None, lse_tol=None):
     if tight is not None:
         assert st["max_abs"] <= tight
     if out.get("lse") is not None:
+        # LSE carries the bf16 rounding of the rotated Q and K through scores of magnitude |s|:
+        # about |s| * 2^-8; 5e-2 unless the caller calibrated a bound
         lerr = np.abs(out["lse"][:, rows] - lse_ref).max() if len(rows) else 0.0
         _say(f"  lse max_abs {lerr:.3e}")
-        assert lerr <= (lse_tol if lse_tol is not None else max(tol, 1e-4))
+        assert lerr <= (lse_tol if lse_tol is not None else 5e-2)
     return st
 
 
@@ -72,17 +74,16 @@ def test_mfma_small_gqa_full():
     _say("small gqa T", w.total_suffix_tokens, "suffix", w.suffix_len.tolist())
     out = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
     _check_bookkeeping(w, out)
-    floor = max(bf16_rounding_floor(w, n) for n in (0, 3, 7))
-    _say(f"  bf16 rounding floor {floor:.3e}")
-    _check_suffix(w, out, tol=TOL_BF16, tight=max(4 * floor, 2e-3))
+    tight, lse_bar = tight_bar(w, range(w.n_queries))
+    _check_suffix(w, out, tol=TOL_BF16, tight=tight, lse_tol=lse_bar)
 
 
 def test_mfma_small_mha_ragged():
     w = workloads.custom("small_mha", n_q_heads=4, n_kv_heads=4, head_dim=128, rope_base=10000.0, io_dtype="bf16",
                          prefix_len=[300, 17, 64, 1], cluster_sizes=[9, 1, 2, 4], suffix_range=(24, 96), seed=9)
     out = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
-    floor = max(bf16_rounding_floor(w, n) for n in (0, 5))
-    _check_suffix(w, out, tol=TOL_BF16, tight=max(4 * floor, 2e-3))
+    tight, lse_bar = tight_bar(w, range(w.n_queries))
+    _check_suffix(w, out, tol=TOL_BF16, tight=tight, lse_tol=lse_bar)
 
 
 def test_mfma_matches_generic_kernel():
@@ -90,9 +91,10 @@ def test_mfma_matches_generic_kernel():
     a = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
     b = run_workload(w, kernel=sgc.SGC_KERNEL_GENERIC)
     d = np.abs(a["o"] - b["o"]).max()
-    _say(f"  mfma vs generic max_abs {d:.3e}")
-    assert d <= 1e-2
-    assert np.abs(a["lse"] - b["lse"]).max() <= 2e-2
+    tight, lse_bar = tight_bar(w, range(w.n_queries))
+    _say(f"  mfma vs generic max_abs {d:.3e} (bar {tight:.3e})")
+    assert d <= tight
+    assert np.abs(a["lse"] - b["lse"]).max() <= lse_bar
 
 
 def test_mfma_edge_cases():
@@ -103,10 +105,11 @@ def test_mfma_edge_cases():
     slen = np.array([1, 70, 3, 0, 16, 17, 64, 65, 1, 130, 2, 1, 0], dtype=np.int32)
     w = workloads.custom("edges", n_q_heads=4, n_kv_heads=2, head_dim=128, rope_base=10000.0, io_dtype="bf16",
                          prefix_len=plen, labels=labels, suffix_len=slen, seed=13)
+    tight, lse_bar = tight_bar(w, range(w.n_queries))
     for kernel in (sgc.SGC_KERNEL_MFMA, sgc.SGC_KERNEL_GENERIC):
         out = run_workload(w, kernel=kernel)
         _check_bookkeeping(w, out)
-        _check_suffix(w, out, tol=TOL_BF16, tight=6e-3)
+        _check_suffix(w, out, tol=TOL_BF16, tight=tight, lse_tol=lse_bar)
 
 
 def test_mfma_all_queries_empty_and_single_row():
@@ -117,7 +120,7 @@ def test_mfma_all_queries_empty_and_single_row():
     w = workloads.custom("one", n_q_heads=1, n_kv_heads=1, head_dim=128, rope_base=10000.0, io_dtype="bf16",
                          prefix_len=[40], labels=[0], suffix_len=[1], seed=2)
     out = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
-    _check_suffix(w, out, tol=TOL_BF16, tight=6e-3)
+    _check_suffix(w, out, tol=TOL_BF16, tight=tight_bar(w, [0])[0])
 
 
 def test_mfma_peaky_softmax_one_hot_v_exposes_the_mask():
@@ -198,9 +201,12 @@ def test_prefix_prefill_cache_and_causal_output(kernel):
             assert np.array_equal(ev, pv)                                     # V is stored as given
             assert np.abs(ek - ck).max() <= np.abs(ck).max() * 2.0 ** -8      # K: one bf16 rounding
             st = err_stats(to_host_f32(do), o_ref)
-            _say(f"  prefix cluster {c} P {w.prefix_len[c]} max_abs {st['max_abs']:.3e}")
-            assert st["max_abs"] <= TOL_BF16 and st["max_abs"] <= 8e-3
-            assert np.abs(dlse.cpu().numpy() - lse_ref).max() <= 2e-2
+            # the prefix's own attention is a suffix prefill over an empty cache
+            e = np.zeros((0, w.n_kv_heads, w.head_dim))
+            fl_o, fl_lse = bf16_floor_arrays(e, e, w.prefix_q(c), pk, pv, w.rope_base, want_lse=True)
+            _say(f"  prefix cluster {c} P {w.prefix_len[c]} max_abs {st['max_abs']:.3e} (floor {fl_o:.3e})")
+            assert st["max_abs"] <= TOL_BF16 and st["max_abs"] <= 4 * fl_o
+            assert np.abs(dlse.cpu().numpy() - lse_ref).max() <= max(4 * fl_lse, 2e-3)
 
 
 def test_prefix_prefill_f32_cache_exact_layout_roundtrip():
@@ -285,7 +291,7 @@ def test_fp8_cache_small(kernel):
             vc, vsc, _ = orc.quantise_e4m3(cv)
             ek, ev, ks, vs = s.export_cluster(c)
             assert np.allclose(ks, ksc, rtol=3e-7) and np.array_equal(vs, vsc)
-            assert np.array_equal(ev, vc)
+            assert np.array_equal(ev, vc)           # V: same inputs, same fp32 quotient, same codes
             diff = ek != kc
             _say(f"  cluster {c}: K codes differing {diff.mean():.2e}")
             assert diff.mean() < 5e-3
@@ -295,7 +301,7 @@ def test_fp8_cache_small(kernel):
         do = s.suffix_prefill(*(to_device(x, "bf16") for x in (q, k, v)))
         torch.cuda.synchronize()
         out = {"o": to_host_f32(do), "lse": None}
-    _check_suffix(w, out, tol=TOL_FP8, tight=1e-2)
+    _check_suffix(w, out, tol=TOL_FP8, tight=3e-2)
 
 
 def test_fp8_imported_oracle_cache_isolates_the_attention():
@@ -337,9 +343,8 @@ def test_config1_llama3_8b_layer_full_size_sampled():
     out = run_workload(w)
     _check_bookkeeping(w, out)
     qs = _sampled_queries(w, 2)
-    floor = max(bf16_rounding_floor(w, n) for n in qs[:2])
-    _say(f"  bf16 rounding floor {floor:.3e}")
-    _check_suffix(w, out, queries=qs, tol=TOL_BF16, tight=max(4 * floor, 2e-3))
+    tight, lse_bar = tight_bar(w, qs[:4])
+    _check_suffix(w, out, queries=qs, tol=TOL_BF16, tight=tight, lse_tol=lse_bar)
     assert np.isfinite(out["o"]).all() and np.abs(out["o"]).max() < 8
 
 
@@ -349,5 +354,5 @@ def test_config2_llama2_7b_ragged_full_size_sampled():
     out = run_workload(w, want_lse=False)
     _check_bookkeeping(w, out)
     qs = _sampled_queries(w, 1)[:8]
-    _check_suffix(w, out, queries=qs, tol=TOL_BF16, tight=4e-3)
+    _check_suffix(w, out, queries=qs, tol=TOL_BF16, tight=tight_bar(w, qs[:3])[0])
     assert np.isfinite(out["o"]).all()

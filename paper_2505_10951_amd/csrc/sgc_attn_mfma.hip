@@ -256,23 +256,26 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(const AttnArgs a)
     const int n_cache_keys = (MODE == MODE_SUFFIX) ? P : min(P, last_row / g + 1);
     const int n_kt = (n_cache_keys + BN - 1) / BN;
 
-    constexpr int CHUNKS = KV_FP8 ? 1024 : 2048;      // 16-byte global chunks per tile
-    constexpr int CPT = CHUNKS / NT;                  // per thread
-    constexpr int PAGE_PART_CHUNKS = KV_FP8 ? 128 : 256;   // 16-byte chunks of one page's K (or V) part
-    uint4 stage[CPT];
+    // A tile is 8 page parts (K and V of 4 pages).  Each wavefront moves whole 1 KiB runs of a part, so
+    // the page id and every address but the lane offset are wave-uniform (scalar loads, scalar
+    // branches) and nothing in the prefetch waits on a vector load.
+    constexpr int UNITS = KV_FP8 ? 16 : 32;           // 1 KiB global runs per tile
+    constexpr int UPW = UNITS / NW;                   // per wavefront
+    constexpr int RUNS_PER_PART = KV_FP8 ? 2 : 4;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    uint4 stage[UPW];
 
     auto load_tile = [&](int kt) {
 #pragma unroll
-        for (int j = 0; j < CPT; ++j) {
-            const int q = tid + NT * j;
-            const bool is_v = q >= CHUNKS / 2;
-            const int idx = q - (is_v ? CHUNKS / 2 : 0);
-            const int p = idx / PAGE_PART_CHUNKS, cp = idx % PAGE_PART_CHUNKS;
+        for (int j = 0; j < UPW; ++j) {
+            const int u = wave_u + NW * j;
+            const int part = u / RUNS_PER_PART, run = u % RUNS_PER_PART;   // part 0..3: K pages, 4..7: V pages
+            const int p = part & 3;
             const int pn = kt * 4 + p;
             if (pn < n_pages) {
                 const int page = pt[pn];
-                const char *src = is_v ? a.pool.v_part(a.layer, page, hk) : a.pool.k_part(a.layer, page, hk);
-                stage[j] = *reinterpret_cast<const uint4 *>(src + cp * 16);
+                const char *src = (part >= 4) ? a.pool.v_part(a.layer, page, hk) : a.pool.k_part(a.layer, page, hk);
+                stage[j] = *reinterpret_cast<const uint4 *>(src + run * 1024 + lane * 16);
             } else {
                 stage[j] = make_uint4(0, 0, 0, 0);
             }
@@ -280,15 +283,16 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(const AttnArgs a)
     };
     auto store_tile = [&](char *buf) {
 #pragma unroll
-        for (int j = 0; j < CPT; ++j) {
-            const int q = tid + NT * j;
-            const bool is_v = q >= CHUNKS / 2;
-            const int idx = q - (is_v ? CHUNKS / 2 : 0);
-            const int p = idx / PAGE_PART_CHUNKS, cp = idx % PAGE_PART_CHUNKS;
+        for (int j = 0; j < UPW; ++j) {
+            const int u = wave_u + NW * j;
+            const int part = u / RUNS_PER_PART, run = u % RUNS_PER_PART;
+            const int p = part & 3;
+            const bool is_v = part >= 4;
+            const int cp = run * 64 + lane;               // 16-byte chunk inside the page part
             if (!KV_FP8) {
                 int dst;
                 if (is_v) {
-                    dst = K_TILE_BYTES + idx * 16;
+                    dst = K_TILE_BYTES + p * 4096 + cp * 16;
                 } else {
                     const int blk = cp >> 4, tok = cp & 15;     // blk = kb * 2 + hh
                     dst = (((p >> 1) * 8 + (blk >> 1)) * 2 + (blk & 1)) * 512 + ((p & 1) * 16 + tok) * 16;

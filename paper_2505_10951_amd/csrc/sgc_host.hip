@@ -230,7 +230,10 @@ void build_tiles(sgc_plan *pl, int tile_rows)
 void plan_free_device(sgc_plan *pl)
 {
     if (pl->d_blob) (void)hipFree(pl->d_blob);
+    if (pl->d_spool) (void)hipFree(pl->d_spool);
     pl->d_blob = nullptr;
+    pl->d_spool = nullptr;
+    pl->spool_bytes = 0;
     pl->uploaded = false;
 }
 
@@ -498,25 +501,27 @@ int sgc_assign_clusters(sgc_ctx *ctx, const sgc_cache *c, int32_t n_queries, con
     pl->tok_src.resize(total);
     pl->tok_qpos.resize(total);
     pl->tok_sq.resize(total);
-    pl->sq_src0.resize(n_queries);
-    pl->sq_len.resize(n_queries);
-    pl->sq_tok0.resize(n_queries);
-    pl->sq_cluster.resize(n_queries);
-    int32_t t = 0, maxpos = 0;
+    int32_t t = 0, maxpos = 0, spage = 0;
     for (int32_t k = 0; k < n_clusters; ++k) {
         pl->cl_tok_off[k] = t;
-        for (int32_t sq = cluster_off[k]; sq < cluster_off[k + 1]; ++sq) {
-            const int32_t n = order[sq];
-            pl->sq_src0[sq] = cu_seqlens[n];
-            pl->sq_len[sq] = suffix_len[n];
-            pl->sq_tok0[sq] = t;
-            pl->sq_cluster[sq] = k;
-            for (int32_t i = 0; i < suffix_len[n]; ++i, ++t) {
-                pl->tok_src[t] = cu_seqlens[n] + i;
-                pl->tok_qpos[t] = i;
+        for (int32_t i = cluster_off[k]; i < cluster_off[k + 1]; ++i) {
+            const int32_t n = order[i];
+            if (suffix_len[n] == 0) continue;             // the kernels never see empty queries
+            const int32_t sq = (int32_t)pl->sq_len.size();
+            pl->sq_src0.push_back(cu_seqlens[n]);
+            pl->sq_len.push_back(suffix_len[n]);
+            pl->sq_tok0.push_back(t);
+            pl->sq_cluster.push_back(k);
+            pl->sq_page0.push_back(spage);
+            const int32_t np = (suffix_len[n] + kPageTokens - 1) / kPageTokens;
+            for (int32_t pg = 0; pg < np; ++pg) pl->spage_sq.push_back(sq);
+            spage += np;
+            for (int32_t j = 0; j < suffix_len[n]; ++j, ++t) {
+                pl->tok_src[t] = cu_seqlens[n] + j;
+                pl->tok_qpos[t] = j;
                 pl->tok_sq[t] = sq;
             }
-            if (suffix_len[n] > 0) maxpos = std::max(maxpos, pl->cl_prefix_len[k] + suffix_len[n]);
+            maxpos = std::max(maxpos, pl->cl_prefix_len[k] + suffix_len[n]);
         }
     }
     pl->cl_tok_off[n_clusters] = t;
@@ -551,6 +556,8 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
         {pl->sq_len.data(), pl->sq_len.size() * 4, (const void **)&pl->d_sq_len},
         {pl->sq_tok0.data(), pl->sq_tok0.size() * 4, (const void **)&pl->d_sq_tok0},
         {pl->sq_cluster.data(), pl->sq_cluster.size() * 4, (const void **)&pl->d_sq_cluster},
+        {pl->sq_page0.data(), pl->sq_page0.size() * 4, (const void **)&pl->d_sq_page0},
+        {pl->spage_sq.data(), pl->spage_sq.size() * 4, (const void **)&pl->d_spage_sq},
         {pl->tiles.data(), pl->tiles.size() * sizeof(Tile), (const void **)&pl->d_tiles},
     };
     size_t total = 0;
@@ -561,6 +568,11 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
         *p.dst = pl->d_blob + off;
         if (p.bytes) SGC_HIP(ctx, hipMemcpyAsync(pl->d_blob + off, p.src, p.bytes, hipMemcpyHostToDevice, s));
         off += (p.bytes + 255) / 256 * 256 + 256;
+    }
+    if (want_rows > 0 && !pl->spage_sq.empty()) {
+        // suffix page pool: bf16 pages of every query's rotated suffix K and transposed V
+        pl->spool_bytes = pl->spage_sq.size() * (size_t)2 * ctx->p.n_kv_heads * kPageTokens * ctx->p.head_dim * 2;
+        SGC_HIP(ctx, hipMalloc(&pl->d_spool, pl->spool_bytes));
     }
     SGC_HIP(ctx, hipStreamSynchronize(s));
     pl->uploaded = true;
@@ -630,8 +642,11 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
     a.sq_len = pl->d_sq_len;
     a.sq_tok0 = pl->d_sq_tok0;
     a.sq_cluster = pl->d_sq_cluster;
+    a.sq_page0 = pl->d_sq_page0;
+    a.spool = pl->d_spool;
     a.total_tokens = pl->total_tokens;
     if (ctx->use_mfma) {
+        SGC_HIP(ctx, launch_suffix_ingest(a, pl->d_spage_sq, (int)pl->spage_sq.size(), s));
         SGC_HIP(ctx, launch_attn_mfma(a, ctx->mfma_variant, s));
     } else {
         SGC_HIP(ctx, launch_attn_generic(a, pl->total_tokens * ctx->p.n_q_heads, s));

@@ -87,7 +87,8 @@ struct AttnArgs {
     const float2 *rope;           // [rope_len][d/2] (cos, sin) or null when rotation is off
     const Tile *tiles;
     int32_t n_tiles;
-    // suffix mode: sorted-token and sorted-query tables (sorted = grouped by cluster)
+    // suffix mode: sorted-token and sorted-query tables (sorted = grouped by cluster; queries
+    // without tokens are left out of the query tables)
     const int32_t *cl_tok_off;    // [n_clusters + 1] first sorted token of each cluster
     const int32_t *tok_src;       // [T] row of the token in the caller's packed arrays
     const int32_t *tok_qpos;      // [T] index of the token inside its query
@@ -96,6 +97,8 @@ struct AttnArgs {
     const int32_t *sq_len;        // [n_queries] suffix length
     const int32_t *sq_tok0;       // [n_queries] first sorted token of the query
     const int32_t *sq_cluster;    // [n_queries]
+    const int32_t *sq_page0;      // [n_queries] first page of the query in the suffix page pool
+    const char *spool;            // suffix page pool (bf16 pages, same layout as cache pages) or null
     int64_t total_tokens;
     // prefix mode
     int32_t prefix_cluster;
@@ -153,14 +156,18 @@ struct sgc_plan {
     std::vector<int32_t> cl_prefix_len;       // snapshot at assign time, [n_clusters]
     std::vector<int32_t> cl_tok_off;
     std::vector<int32_t> tok_src, tok_qpos, tok_sq;
-    std::vector<int32_t> sq_src0, sq_len, sq_tok0, sq_cluster;
+    std::vector<int32_t> sq_src0, sq_len, sq_tok0, sq_cluster, sq_page0;   // non-empty queries only
+    std::vector<int32_t> spage_sq;            // [total suffix pages] owning query of each suffix page
     std::vector<sgc::Tile> tiles;
     int32_t tile_rows = 0;
     bool uploaded = false;
     char *d_blob = nullptr;                   // one device allocation holding every array below
     const int32_t *d_cl_tok_off = nullptr, *d_tok_src = nullptr, *d_tok_qpos = nullptr, *d_tok_sq = nullptr;
     const int32_t *d_sq_src0 = nullptr, *d_sq_len = nullptr, *d_sq_tok0 = nullptr, *d_sq_cluster = nullptr;
+    const int32_t *d_sq_page0 = nullptr, *d_spage_sq = nullptr;
     const sgc::Tile *d_tiles = nullptr;
+    char *d_spool = nullptr;                  // rotated suffix K / transposed V pages of the batch (MFMA path)
+    size_t spool_bytes = 0;
 };
 
 // ---- kernel launchers (defined in the .hip files) --------------------------------------------
@@ -177,6 +184,10 @@ hipError_t launch_cache_export(const PoolGeom &g, int layer, const int32_t *d_pa
                                void *k, void *v, hipStream_t s);
 hipError_t launch_cache_import(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len,
                                const void *k, const void *v, hipStream_t s);
+
+// Suffix ingest: rotate every query's suffix K at prefix_len + j and write K and V as bf16 pages
+// (cache page layout) into the suffix page pool; one workgroup per (suffix page, KV head).
+hipError_t launch_suffix_ingest(const AttnArgs &a, const int32_t *d_spage_sq, int n_spages, hipStream_t s);
 
 hipError_t launch_attn_generic(const AttnArgs &a, int64_t n_rows, hipStream_t s);
 // Rows per workgroup of MFMA kernel variant `variant`, or 0 if the variant does not exist.

@@ -234,6 +234,48 @@ __global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *pages,
     }
 }
 
+// ---- suffix ingest ---------------------------------------------------------------------------
+// Same page layout as the cache, bf16 only, for the question tokens of every query of the batch
+// (SubGCache Sec. 3.4: the question tokens are appended to the cached prompt, so suffix token j of a
+// query whose cluster has P prefix tokens is rotated at position P + j).  One workgroup per
+// (suffix page, KV head); tokens past the query's end are written as zeros.
+__global__ void suffix_ingest_kernel(AttnArgs a, const int32_t *spage_sq)
+{
+    const int page = blockIdx.x, hk = blockIdx.y;
+    const int Hkv = a.n_kv_heads, d = a.head_dim, half = d / 2, pairs = d / 16;
+    const int sq = spage_sq[page];
+    const int S = a.sq_len[sq];
+    const int64_t src0 = a.sq_src0[sq];
+    const int P = a.cl_prefix_len[a.sq_cluster[sq]];
+    const int tok0 = (page - a.sq_page0[sq]) * kPageTokens;
+    const int64_t part = (int64_t)kPageTokens * d * 2;
+    char *kp = const_cast<char *>(a.spool) + (int64_t)page * 2 * Hkv * part + (int64_t)hk * part;
+    char *vp = kp + (int64_t)Hkv * part;
+    for (int it = threadIdx.x; it < kPageTokens * pairs; it += blockDim.x) {
+        const int tok = it / pairs, cc = it % pairs;
+        const int j = tok0 + tok;
+        float x1[8], x2[8], y1[8], y2[8];
+        if (j < S) {
+            const int64_t row = ((src0 + j) * Hkv + hk) * d;
+            load8(a.k, row + cc * 8, a.io_dtype, x1);
+            load8(a.k, row + half + cc * 8, a.io_dtype, x2);
+            if (a.rope) rope8(x1, x2, a.rope + (int64_t)(P + j) * half + cc * 8);
+            load8(a.v, row + cc * 8, a.io_dtype, y1);
+            load8(a.v, row + half + cc * 8, a.io_dtype, y2);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x1[i] = x2[i] = y1[i] = y2[i] = 0.f;
+        }
+        store8(kp, k_page_index(tok, cc * 8), SGC_BF16, x1, 1.f);
+        store8(kp, k_page_index(tok, half + cc * 8), SGC_BF16, x2, 1.f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            store1(vp, v_page_index(tok, cc * 8 + i), SGC_BF16, y1[i], 1.f);
+            store1(vp, v_page_index(tok, half + cc * 8 + i), SGC_BF16, y2[i], 1.f);
+        }
+    }
+}
+
 // ---- export / import: raw element moves between page order and [P][Hkv][d] --------------------
 template <typename T>
 __global__ void cache_export_kernel(PoolGeom g, int layer, const int32_t *pages, int P, T *k, T *v)
@@ -445,6 +487,13 @@ hipError_t launch_prefix_ingest(const PoolGeom &g, int layer, const int32_t *d_p
     }
     hipLaunchKernelGGL(ingest_write_kernel, grid, dim3(128), 0, s, g, layer, d_pages, prefix_len, k, v, io_dtype, rope,
                        (const float *)d_scale_kv);
+    return hipGetLastError();
+}
+
+hipError_t launch_suffix_ingest(const AttnArgs &a, const int32_t *d_spage_sq, int n_spages, hipStream_t s)
+{
+    if (n_spages <= 0) return hipSuccess;
+    hipLaunchKernelGGL(suffix_ingest_kernel, dim3(n_spages, a.n_kv_heads), dim3(128), 0, s, a, d_spage_sq);
     return hipGetLastError();
 }
 

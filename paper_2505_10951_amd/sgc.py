@@ -11,7 +11,8 @@ from typing import Optional, Sequence, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsgc.so")
+# SGC_LIB_PATH lets a developer load an experimental build of the same library instead
+LIB_PATH = os.environ.get("SGC_LIB_PATH") or os.path.join(_HERE, "libsgc.so")
 
 SGC_OK, SGC_EINVAL, SGC_ENOMEM, SGC_ESHAPE, SGC_EUNSUPPORTED, SGC_EHIP, SGC_ESTATE = 0, -1, -2, -3, -4, -5, -6
 SGC_F32, SGC_BF16, SGC_FP8_E4M3 = 0, 1, 2

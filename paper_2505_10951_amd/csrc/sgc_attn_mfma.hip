@@ -31,6 +31,12 @@ namespace sgc {
 
 namespace {
 
+#ifdef SGC_NO_SCHED_BARRIER
+#define SGC_SCHED_FENCE() do { } while (0)
+#else
+#define SGC_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+#endif
+
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -237,6 +243,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
 #ifdef SGC_PHASE_TIMING
     unsigned ph[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     unsigned long long tlast = 0;
+    const unsigned long long blk_c0 = __builtin_readcyclecounter(), blk_r0 = __builtin_amdgcn_s_memrealtime();
 #endif
 
     // Per-lane LDS offsets of the operand blocks.  K block (nb, kb): lane (m, hh) reads key m of the 32-key
@@ -258,7 +265,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         const char *vbase = buf + lane_voff;
 #pragma unroll
         for (int i = 0; i < 8; ++i) frag[i] = *reinterpret_cast<const bf16x8 *>(kbase + i * 512);
-        __builtin_amdgcn_sched_barrier(0);
+        SGC_SCHED_FENCE();
         SGC_TS(1);
         f32x16 sacc[MI][2];
 #pragma unroll
@@ -278,7 +285,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
                 frag[i & 7] = *reinterpret_cast<const bf16x8 *>(kbase + 2 * PART_BYTES + i * 512);
             else
                 frag[i & 7] = *reinterpret_cast<const bf16x8 *>(vbase + (i - 8) * 1024);
-            __builtin_amdgcn_sched_barrier(0);
+            SGC_SCHED_FENCE();
         }
         SGC_TS(2);
 
@@ -348,7 +355,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             l_part[mi] += psum;
         }
         fresh = false;
-        __builtin_amdgcn_sched_barrier(0);
+        SGC_SCHED_FENCE();
         SGC_TS(3);
         // O^T += V^T P^T: block i = (16-key page pg = i / 4, 32-channel group db = i % 4)
 #pragma unroll
@@ -360,52 +367,18 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
                 oacc[mi][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i & 7], __builtin_bit_cast(bf16x8, w), oacc[mi][db], 0, 0, 0);
             }
             if (i < 8) frag[i & 7] = *reinterpret_cast<const bf16x8 *>(vbase + (i + 8) * 1024);
-            __builtin_amdgcn_sched_barrier(0);
+            SGC_SCHED_FENCE();
         }
         SGC_TS(4);
     };
 
-    // ---- the stream of key tiles: cached prefix tiles, then the suffix tiles of each touched query ----
-    const int n_cache_keys = (MODE == MODE_SUFFIX) ? P : min(P, last_row / g + 1);
-    const int n_kt = (n_cache_keys + BN - 1) / BN;
-    // Iterator over the tile stream: plain scalar state, advanced by the macro below (kept out of a
-    // lambda so that every piece of it stays in scalar registers).  A query's LDS record is read only
-    // when the stream moves on to that query.
-    int it_kt = 0, it_q = sq_lo - 1, it_jt = 0, it_njt = 0, it_pg0 = 0, it_pglast = 0;
-#define SGC_NEXT_TILE(ok, d)                                                                        \
-    do {                                                                                            \
-        (ok) = false;                                                                               \
-        if (it_kt < n_kt) {                                                                         \
-            (d).kind = 0;                                                                           \
-            (d).key0 = it_kt * BN;                                                                  \
-            ++it_kt;                                                                                \
-            (ok) = true;                                                                            \
-        } else if (MODE == MODE_SUFFIX) {                                                           \
-            while (it_jt >= it_njt && it_q < sq_hi) { /* next query with key tiles for this row tile */ \
-                ++it_q;                                                                             \
-                const int2 qi = qinfo[min(it_q - sq_lo, MAX_TILE_QUERIES - 1)];                     \
-                const int S__ = __builtin_amdgcn_readfirstlane(qi.x);                               \
-                it_pg0 = __builtin_amdgcn_readfirstlane(qi.y);                                      \
-                it_pglast = it_pg0 + (S__ - 1) / kPageTokens;                                       \
-                it_njt = ((it_q == sq_hi ? last_qpos : S__ - 1) + BN) / BN;                         \
-                it_jt = 0;                                                                          \
-            }                                                                                       \
-            if (it_jt < it_njt) {                                                                   \
-                (d).kind = 1;                                                                       \
-                (d).key0 = it_jt * BN;                                                              \
-                (d).q = it_q;                                                                       \
-                (d).page0 = it_pg0 + it_jt * 4;                                                     \
-                (d).page_last = it_pglast;                                                          \
-                ++it_jt;                                                                            \
-                (ok) = true;                                                                        \
-            }                                                                                       \
-        }                                                                                           \
-    } while (0)
-
-    // Copy units.  A tile is 32 runs of 1 KiB (fp8 cache: 16 runs of 1 KiB of codes that widen to 2 KiB);
-    // run u = part * 4 + quarter with part 0..3 = K of page 0..3, part 4..7 = V of page 0..3.  Wavefront w
-    // moves runs w, w + NW, ...  A run's address is (scalar) source base + page offset, plus a per-lane
-    // 32-bit offset that is fixed for the launch; page offsets travel as 32-bit counts of 256 bytes.
+    // ---- copy machinery ----------------------------------------------------------------------------
+    // A tile is 32 runs of 1 KiB (fp8 cache: 16 runs of 1 KiB of codes that widen to 2 KiB); run u = part * 4
+    // + quarter with part 0..3 = K of page 0..3, part 4..7 = V of page 0..3.  Wavefront w moves runs
+    // w, w + NW, ...  A run's address is a scalar base (source base + page offset) plus a per-lane 32-bit
+    // offset that is fixed for the launch; page offsets travel as 32-bit counts of 256 bytes, one tile
+    // ahead, in a vector register (lane j < 4 holds page j of the tile) and become scalars by readlane,
+    // so no copy ever waits on a page-table load.
     constexpr int UNITS_BF16 = 32 / NW, UNITS_FP8 = 16 / NW;
     const char *cache_base = a.pool.pool + (int64_t)a.layer * a.pool.layer_bytes + (int64_t)hk * a.pool.head_part_bytes;
     const uint32_t cache_v_off = (uint32_t)(Hkv * a.pool.head_part_bytes);
@@ -415,23 +388,21 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     const uint32_t spool_page_256 = (2u * spool_v_off) >> 8;
     uint4 stage[KV_FP8 ? UNITS_FP8 : 1];
 
-    // Page offsets of a cached tile travel one tile ahead in a vector register (lane j < 4 holds page j)
-    // and are moved to scalars with readlane, so no copy waits on a page-table load.  Indices past the
-    // last page are clamped to it: such keys are masked out of the scores, and what they multiply in
-    // the second product is finite cache content times a zero weight.
-    auto cache_page_offs = [&](int kt) -> uint32_t {
+    // Page indices past the last page are clamped to it: such keys are masked out of the scores, and what
+    // they multiply in the second product is finite cache content times a zero weight.
+    auto cache_page_ids = [&](int kt) -> uint32_t {     // raw page ids; scaled to offsets when used
         if (n_pages == 0) return 0;       // no cached keys: nothing is ever copied from the cache
-        return (uint32_t)pt[min(kt * 4 + (lane & 3), n_pages - 1)] * cache_page_256;
+        return (uint32_t)pt[min(kt * 4 + (lane & 3), n_pages - 1)];
     };
+    const uint32_t lane16 = lane * 16;
     auto issue_copy_bf16 = [&](uint32_t poff, char *buf, const char *base, uint32_t v_off) {
 #pragma unroll
         for (int j = 0; j < UNITS_BF16; ++j) {
             const int u = wave_u + NW * j;
             const int part = u >> 2, quarter = u & 3;
             const uint32_t off256 = __builtin_amdgcn_readlane(poff, part & 3);
-            const char *sbase = base + ((uint64_t)off256 << 8);
-            const uint32_t voff = (part >= 4 ? v_off : 0u) + quarter * 1024 + lane * 16;
-            copy_1k_to_lds(sbase + voff, buf + u * 1024);
+            const char *sbase = base + ((uint64_t)off256 << 8) + (part >= 4 ? v_off : 0u) + quarter * 1024;
+            copy_1k_to_lds(sbase + lane16, buf + u * 1024);
         }
     };
     auto issue_load_fp8 = [&](uint32_t poff) {
@@ -440,9 +411,8 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             const int u = wave_u + NW * j;
             const int part = u >> 1, run = u & 1;       // a part is 2 KiB of codes
             const uint32_t off256 = __builtin_amdgcn_readlane(poff, part & 3);
-            const char *sbase = cache_base + ((uint64_t)off256 << 8);
-            const uint32_t voff = (part >= 4 ? cache_v_off : 0u) + run * 1024 + lane * 16;
-            stage[j] = *reinterpret_cast<const uint4 *>(sbase + voff);
+            const char *sbase = cache_base + ((uint64_t)off256 << 8) + (part >= 4 ? cache_v_off : 0u) + run * 1024;
+            stage[j] = *reinterpret_cast<const uint4 *>(sbase + lane16);
         }
     };
     auto store_fp8 = [&](char *buf) {
@@ -462,27 +432,14 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             *reinterpret_cast<uint4 *>(dst + 16) = o1;
         }
     };
-
-    uint32_t poff_cache = 0;      // page offsets of the next cached tile to copy
-    bool staged_fp8 = false;      // the tile being fetched sits in `stage` (fp8 cache tiles only)
-    auto fetch = [&](const TileDesc &d, char *buf) {
-        const bool cached = d.kind == 0;
-        if (KV_FP8 && cached) {
-            issue_load_fp8(poff_cache);
-            staged_fp8 = true;
-        } else {
-            // one copy routine for both sources; which one is a scalar choice
-            const uint32_t poff = cached ? poff_cache : (uint32_t)min(d.page0 + (lane & 3), d.page_last) * spool_page_256;
-            issue_copy_bf16(poff, buf, cached ? cache_base : spool_base, cached ? cache_v_off : spool_v_off);
-            staged_fp8 = false;
-        }
-        if (cached) poff_cache = cache_page_offs(d.key0 / BN + 1);     // lands before the end-of-step wait
+    auto fetch_cache = [&](uint32_t poff, char *buf) {
+        if (KV_FP8)
+            issue_load_fp8(poff);
+        else
+            issue_copy_bf16(poff, buf, cache_base, cache_v_off);
     };
-    auto land = [&](char *buf) {      // make the fetched tile visible in LDS (before the barrier)
-        if (KV_FP8 && staged_fp8) {
-            store_fp8(buf);
-            staged_fp8 = false;
-        }
+    auto land_cache = [&](char *buf) {      // make the fetched cached tile visible in LDS (before the barrier)
+        if (KV_FP8) store_fp8(buf);
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): direct copies have landed
     };
 
@@ -495,71 +452,109 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             __builtin_amdgcn_s_setprio(0);
     }
 
-    TileDesc cur = {0, 0, 0, 0, 0}, nxt = {0, 0, 0, 0, 0};
-    bool have;
-    SGC_NEXT_TILE(have, cur);
-    if (have) {
-        poff_cache = cache_page_offs(0);
-        fetch(cur, buf0);
-        land(buf0);
-    }
-    __syncthreads();
+    // ---- cached prefix tiles, double buffered ------------------------------------------------------
+    const int n_cache_keys = (MODE == MODE_SUFFIX) ? P : min(P, last_row / g + 1);
+    const int n_kt = (n_cache_keys + BN - 1) / BN;
     int parity = 0;
-    bool v_scaled = !KV_FP8;
+    uint32_t pids = 0;          // page ids of the next cached tile, loaded one step before they are needed
+    if (n_kt > 0) {
+        pids = cache_page_ids(0);
+        fetch_cache(pids * cache_page_256, buf0);
+        pids = cache_page_ids(1);
+        land_cache(buf0);
+    }
+    __syncthreads();       // also: qinfo is in LDS
 #ifdef SGC_PHASE_TIMING
     tlast = __builtin_readcyclecounter();
 #endif
-    while (have) {
+    for (int kt = 0; kt < n_kt; ++kt) {
         char *buf = buf0 + parity * BUF_BYTES;
         char *other = buf0 + (parity ^ 1) * BUF_BYTES;
-        bool more;
-        SGC_NEXT_TILE(more, nxt);
-#ifndef SGC_ABLATE_DMA
-        if (more) fetch(nxt, other);
-#endif
-        SGC_TS(0);
-        {
-            const bool self = cur.kind != 0;
-            const int key0 = cur.key0, q = cur.q;
-            if (self && !v_scaled) {    // fp8 cache: the accumulated cached part takes the V scale once
-#pragma unroll
-                for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                    for (int db = 0; db < 4; ++db)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) oacc[mi][db][r] *= v_scale;
-                v_scaled = true;
-            }
-            bool run, masked;
-            if (!self) {
-                run = key0 < lim_max;               // some row of this wave still sees keys of this tile
-                masked = key0 + BN > lim_min;
-            } else {
-                bool mine = false;                  // does a row of this wave belong to query q and reach key0?
-#pragma unroll
-                for (int mi = 0; mi < MI; ++mi) mine |= valid[mi] && sq[mi] == q && qpos[mi] >= key0;
-                run = q >= wsq_min && q <= wsq_max && __any(mine);
-                masked = true;
-            }
-#ifdef SGC_ABLATE_COMPUTE
-            run = false;
-#endif
-            if (run)
-                process_tile(buf, self ? c_self : c_cache, masked, masked, [&](int mi, int j) {
-                    return self ? (sq[mi] == q && key0 + j <= qpos[mi]) : (key0 + j < lim[mi]);
-                });
+        const bool more = kt + 1 < n_kt;
+        if (more) {
+            fetch_cache(pids * cache_page_256, other);
+            pids = cache_page_ids(kt + 2);       // lands before the end-of-step wait, used a step later
         }
-        if (more) land(other);
+        SGC_TS(0);
+        const int key0 = kt * BN;
+        if (key0 < lim_max) {                    // some row of this wave still sees keys of this tile
+            const bool masked = key0 + BN > lim_min;
+            process_tile(buf, c_cache, masked, masked, [&](int mi, int j) { return key0 + j < lim[mi]; });
+        }
+        if (more) land_cache(other);
         SGC_TS(5);
         __syncthreads();
         SGC_TS(6);
-        cur = nxt;
-        have = more;
         parity ^= 1;
     }
-#undef SGC_NEXT_TILE
+
+    // ---- the suffix keys of every query this row tile touches, double buffered ------------------------
+    bool v_scaled = !KV_FP8;
+    if (MODE == MODE_SUFFIX) {
+        if (!v_scaled) {        // fp8 cache: the accumulated cached part takes the V scale once
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[mi][db][r] *= v_scale;
+            v_scaled = true;
+        }
+        // scalar iterator over (query, 64-key tile); a query's LDS record is read when the stream reaches it
+        int it_q = sq_lo - 1, it_jt = 0, it_njt = 0, it_pg0 = 0, it_pglast = 0;
+#define SGC_NEXT_SELF(ok, d)                                                                        \
+    do {                                                                                            \
+        while (it_jt >= it_njt && it_q < sq_hi) {                                                   \
+            ++it_q;                                                                                 \
+            const int2 qi = qinfo[min(it_q - sq_lo, MAX_TILE_QUERIES - 1)];                         \
+            const int S__ = __builtin_amdgcn_readfirstlane(qi.x);                                   \
+            it_pg0 = __builtin_amdgcn_readfirstlane(qi.y);                                          \
+            it_pglast = it_pg0 + (S__ - 1) / kPageTokens;                                           \
+            it_njt = ((it_q == sq_hi ? last_qpos : S__ - 1) + BN) / BN;                             \
+            it_jt = 0;                                                                              \
+        }                                                                                           \
+        (ok) = it_jt < it_njt;                                                                      \
+        (d).key0 = it_jt * BN;                                                                      \
+        (d).q = it_q;                                                                               \
+        (d).page0 = it_pg0 + it_jt * 4;                                                             \
+        (d).page_last = it_pglast;                                                                  \
+        ++it_jt;                                                                                    \
+    } while (0)
+        auto fetch_self = [&](const TileDesc &d, char *buf) {
+            const uint32_t po = (uint32_t)min(d.page0 + (lane & 3), d.page_last) * spool_page_256;
+            issue_copy_bf16(po, buf, spool_base, spool_v_off);
+        };
+        TileDesc cur = {1, 0, 0, 0, 0}, nxt = {1, 0, 0, 0, 0};
+        bool have, more;
+        SGC_NEXT_SELF(have, cur);
+        if (have) {
+            fetch_self(cur, buf0 + parity * BUF_BYTES);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+        }
+        __syncthreads();
+        while (have) {
+            char *buf = buf0 + parity * BUF_BYTES;
+            char *other = buf0 + (parity ^ 1) * BUF_BYTES;
+            SGC_NEXT_SELF(more, nxt);
+            if (more) fetch_self(nxt, other);
+            const int key0 = cur.key0, q = cur.q;
+            bool mine = false;                  // does a row of this wave belong to query q and reach key0?
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) mine |= valid[mi] && sq[mi] == q && qpos[mi] >= key0;
+            if (q >= wsq_min && q <= wsq_max && __any(mine))
+                process_tile(buf, c_self, true, true, [&](int mi, int j) { return sq[mi] == q && key0 + j <= qpos[mi]; });
+            if (more) __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            cur = nxt;
+            have = more;
+            parity ^= 1;
+        }
+#undef SGC_NEXT_SELF
+    }
 #ifdef SGC_PHASE_TIMING
     if (lane == 0 && blockIdx.x < 2048) {
+        ph[7] = (unsigned)(__builtin_amdgcn_s_memrealtime() - blk_r0);      // 100 MHz ticks for the whole block so far
+        ph[6] = (unsigned)(__builtin_readcyclecounter() - blk_c0);          // shader-clock ticks (overwrites the barrier slot)
 #pragma unroll
         for (int i = 0; i < 8; ++i) g_phase[(blockIdx.x * 8 + wave) * 8 + i] = ph[i];
     }
@@ -596,12 +591,16 @@ hipError_t launch_one(const AttnArgs &a, int blocks, hipStream_t s)
 {
     static bool configured = false;     // raise the dynamic LDS limit once per instantiation
     auto kern = attn_mfma_kernel<NW, MI, FP8, MODE>;
+    size_t lds = kDynLds;
+#ifdef SGC_EXPERIMENT_LDS
+    if (const char *e = getenv("SGC_EXTRA_LDS")) lds += (size_t)atoi(e);   // development aid: limit occupancy
+#endif
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDynLds);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), kDynLds, s, a);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(NW * 64), lds, s, a);
     return hipGetLastError();
 }
 

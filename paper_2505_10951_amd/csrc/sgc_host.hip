@@ -270,7 +270,7 @@ int sgc_ctx_create(const sgc_attn_params *params, sgc_ctx **out)
     ctx->p = *params;
     ctx->scale = params->softmax_scale > 0.0f ? params->softmax_scale : 1.0f / sqrtf((float)params->head_dim);
     ctx->use_mfma = params->kernel == SGC_KERNEL_MFMA || (params->kernel == SGC_KERNEL_AUTO && mfma_covers(*params));
-    ctx->mfma_variant = 0;
+    ctx->mfma_variant = 1;      // 4 wavefronts x 32 rows, two workgroups per CU: fastest measured
     if (const char *v = getenv("SGC_MFMA_VARIANT")) {
         const int n = atoi(v);
         if (mfma_tile_rows(n) > 0) ctx->mfma_variant = n;

@@ -25,6 +25,8 @@
 // the weights after their rounding to bf16, the values the second product uses.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "sgc_internal.h"
 
 namespace sgc {
@@ -46,8 +48,8 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int D = 128;                       // head dim
 constexpr int BN = 64;                       // keys per LDS tile (4 pages)
 constexpr int PART_BYTES = kPageTokens * D * 2;   // one page's K (or V) of one head as bf16: 4 KiB
-constexpr int BUF_BYTES = 8 * PART_BYTES;    // 4 K parts + 4 V parts
-constexpr int V_TILE_OFF = 4 * PART_BYTES;
+constexpr int HALF_BYTES = 4 * PART_BYTES;   // the K (or V) of one 64-key tile: 16 KiB
+constexpr int LDS_TILE_BYTES = 4 * HALF_BYTES;   // two K buffers, then two V buffers
 constexpr int MAX_TILE_QUERIES = 256;        // queries a row tile can touch (one row each at least)
 constexpr float kKeepBelow = 1073741824.0f;  // 2^30: a tile's weights may sum to this against a stale maximum
 constexpr float kNegBig = -1.0e30f;
@@ -55,9 +57,11 @@ constexpr float kNegBig = -1.0e30f;
 #ifdef SGC_PHASE_TIMING
 // Development aid (not built into the product library): per-phase cycle totals of the tile loop.
 __device__ unsigned long long g_phase[2048 * 8 * 8];   // [block < 2048][wave < 8][phase < 8]
-#define SGC_TS(i) do { const unsigned long long now__ = __builtin_readcyclecounter(); ph[i] += (unsigned)(now__ - tlast); tlast = __builtin_readcyclecounter(); } while (0)
+// SGC_MARK(i): all outstanding memory operations of the wave are waited for, then the time since the block
+// started (100 MHz ticks) is recorded as the end of phase i.
+#define SGC_MARK(i) do { __builtin_amdgcn_s_waitcnt(0); ph[i] = (unsigned)(__builtin_amdgcn_s_memrealtime() - blk_r0); } while (0)
 #else
-#define SGC_TS(i) do { } while (0)
+#define SGC_MARK(i) do { } while (0)
 #endif
 
 __device__ inline float half_swap(float x) { return __shfl_xor(x, 32); }
@@ -69,11 +73,16 @@ __device__ inline uint32_t fp8x2_to_bf16x2(uint32_t w, bool high)
     return (__float_as_uint(f[0]) >> 16) | (__float_as_uint(f[1]) & 0xFFFF0000u);
 }
 
-// 1 KiB global -> LDS, 16 bytes per lane, landing at lds + 16 * lane.
-__device__ inline void copy_1k_to_lds(const char *src_lane, char *lds_block)
+// 4 KiB global -> LDS as four 1 KiB instructions, 16 bytes per lane: byte 1024 q + 16 lane of the source
+// lands at the same offset of lds_part.  The four share one address pair and differ in the immediate.
+__device__ inline void copy_4k_to_lds(const char *src_lane, char *lds_part)
 {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src_lane,
-                                     (__attribute__((address_space(3))) void *)lds_block, 16, 0, 0);
+    const auto *g = (const __attribute__((address_space(1))) void *)src_lane;
+    auto *l = (__attribute__((address_space(3))) void *)lds_part;
+    __builtin_amdgcn_global_load_lds(g, l, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(g, l, 16, 1024, 0);
+    __builtin_amdgcn_global_load_lds(g, l, 16, 2048, 0);
+    __builtin_amdgcn_global_load_lds(g, l, 16, 3072, 0);
 }
 
 struct TileDesc {
@@ -89,9 +98,12 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
 {
     constexpr int BM = NW * MI * 32;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    char *const buf0 = smem;
-    int2 *const qinfo = reinterpret_cast<int2 *>(smem + 2 * BUF_BYTES);   // (suffix length, first suffix page)
+    int2 *const qinfo = reinterpret_cast<int2 *>(smem + LDS_TILE_BYTES);   // (suffix length, first suffix page)
 
+#ifdef SGC_PHASE_TIMING
+    unsigned ph[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const unsigned long long blk_r0 = __builtin_amdgcn_s_memrealtime();
+#endif
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
@@ -139,8 +151,10 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         k_scale = sc[hk];
         v_scale = sc[Hkv + hk];
     }
+    // Scores are kept in log2 units.  Q carries the factor for cached keys; scores against the (unquantised)
+    // suffix keys of the batch are brought to the same units by self_ratio.
     const float c_cache = a.scale_log2e * k_scale;
-    const float c_self = a.scale_log2e;
+    const float self_ratio = KV_FP8 ? 1.0f / k_scale : 1.0f;
 
     // ---- per-lane row bookkeeping ----
     bool valid[MI];
@@ -187,6 +201,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     wsq_min = __builtin_amdgcn_readfirstlane(wsq_min);
     wsq_max = __builtin_amdgcn_readfirstlane(wsq_max);
 
+    SGC_MARK(0);           // tile and row bookkeeping is loaded
     // ---- Q: load, rotate at position P + qpos (suffix) / qpos (prefix), keep as B operands ----
     bf16x8 qf[MI][8];
 #pragma unroll
@@ -220,173 +235,176 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
                 }
             }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                qf[mi][kb][i] = (__bf16)x1[i];
-                qf[mi][kb + 4][i] = (__bf16)x2[i];
+            for (int i = 0; i < 8; ++i) {      // the score scale (log2 units, cached-K scale included) rides on Q
+                qf[mi][kb][i] = (__bf16)(x1[i] * c_cache);
+                qf[mi][kb + 4][i] = (__bf16)(x2[i] * c_cache);
             }
         }
     }
 
     // ---- accumulators ----
-    f32x16 oacc[MI][4];
+    // m_ref is the reference maximum of the row's softmax; the score products start from -m_ref (neg_ref, the
+    // same value in all 16 accumulator registers of a lane, which all belong to one row), so finished scores
+    // are already relative to it.  seen: the row has met at least one visible key.
+    f32x16 oacc[MI][4], neg_ref[MI];
     float m_ref[MI], l_part[MI];
+    bool seen[MI];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
-        m_ref[mi] = kNegBig;
+        m_ref[mi] = 0.f;
         l_part[mi] = 0.f;
+        seen[mi] = false;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) neg_ref[mi][r] = 0.f;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[mi][db][r] = 0.f;
     }
     bool fresh = true;     // no tile processed yet by this wavefront
-#ifdef SGC_PHASE_TIMING
-    unsigned ph[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    unsigned long long tlast = 0;
-    const unsigned long long blk_c0 = __builtin_readcyclecounter(), blk_r0 = __builtin_amdgcn_s_memrealtime();
-#endif
+    SGC_MARK(1);           // Q is in registers
 
     // Per-lane LDS offsets of the operand blocks.  K block (nb, kb): lane (m, hh) reads key m of the 32-key
     // group nb (page 2 nb + m / 16, token m % 16), channels kb * 16 + hh * 8 .. + 7.  Each 16-lane group
     // reads 256 contiguous bytes, which is conflict-free.  V block (pg, db) is 1 KiB contiguous.
     const int lane_koff = ((n >> 4) * PART_BYTES) + (h * kPageTokens + (n & 15)) * 16;
-    const int lane_voff = V_TILE_OFF + lane * 16;
+    const int lane_voff = lane * 16;
 
-    // One 64-key tile from LDS buffer `buf`.  c is the score scale in log2 units.  `careful` forces the
-    // exact running maximum and, with `masked`, masking through keep(mi, j) = "row mi may see key j of
-    // the tile"; otherwise the weights are taken against the current reference maximum without
-    // looking for the tile's maximum, and the careful step only runs when one of them turns out too
-    // large to keep.
-    auto process_tile = [&](const char *buf, const float c, bool careful, const bool masked, auto keep) {
-        // LDS operand blocks are read through a rolling window of 8 register sets: 8 reads are in
-        // flight, each matrix instruction is followed by the read that refills the block it used.
-        bf16x8 frag[8];
-        const char *kbase = buf + lane_koff;
-        const char *vbase = buf + lane_voff;
+    // ---- the pieces of one 32-key half step ---------------------------------------------------------
+    // A 64-key tile is worked on as two 32-key halves (nb = 0, 1): half nb is K blocks 8 nb .. 8 nb + 7 of
+    // the first product (one per 16 channels) and V blocks 8 nb .. 8 nb + 7 of the second (pages 2 nb and
+    // 2 nb + 1, four 32-channel groups each).  LDS operand blocks are read through a rolling window of 8
+    // register sets: each matrix instruction is followed by the read that refills the slot it used with a
+    // block of the NEXT product, so that product never waits on LDS.
+    bf16x8 frag[8];
+    uint32_t pf[MI][2][4];     // weights of one half as bf16 pairs: [row block][page of the half][register pair]
+    float psum[MI];
+    auto k_block = [&](const char *kbuf, int nb, int kb) {
+        return *reinterpret_cast<const bf16x8 *>(kbuf + lane_koff + nb * 2 * PART_BYTES + kb * 512);
+    };
+    auto v_block = [&](const char *vbuf, int nb, int i) {
+        return *reinterpret_cast<const bf16x8 *>(vbuf + lane_voff + (nb * 8 + i) * 1024);
+    };
+    auto no_refill = [&](int) {};
+    // S^T = K Q^T - m_ref for the half whose K blocks the window holds; slot kb is refilled by refill(kb).
+    auto qk_half = [&](f32x16 (&s)[MI], auto refill) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) frag[i] = *reinterpret_cast<const bf16x8 *>(kbase + i * 512);
-        SGC_SCHED_FENCE();
-        SGC_TS(1);
-        f32x16 sacc[MI][2];
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sacc[mi][nb][r] = 0.f;
-        // S^T = K Q^T: block i = (32-key group nb = i / 8, 16-channel group kb = i % 8)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int kb = 0; kb < 8; ++kb) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
-                sacc[mi][i >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i & 7], qf[mi][i & 7], sacc[mi][i >> 3], 0, 0, 0);
-            // refill: K block i + 8, then (while the softmax runs) the first 8 V blocks
-            if (i < 8)
-                frag[i & 7] = *reinterpret_cast<const bf16x8 *>(kbase + 2 * PART_BYTES + i * 512);
-            else
-                frag[i & 7] = *reinterpret_cast<const bf16x8 *>(vbase + (i - 8) * 1024);
-            SGC_SCHED_FENCE();
+                s[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[kb], qf[mi][kb], kb == 0 ? neg_ref[mi] : s[mi], 0, 0, 0);
+            refill(kb);
         }
-        SGC_TS(2);
-
-        uint32_t pf[MI][4][4];     // weights as bf16 pairs: [row block][16-key group][register pair]
-        careful = careful || fresh;
-#ifdef SGC_ABLATE_SOFTMAX
+    };
+    // O^T += V^T P^T for the half whose V blocks the window holds (slot i = page i / 4, channel group i % 4).
+    auto pv_half = [&](auto refill) {
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+        for (int mi = 0; mi < MI; ++mi) l_part[mi] += psum[mi];
 #pragma unroll
-            for (int pg = 0; pg < 4; ++pg)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) pf[mi][pg][i] = __float_as_uint(sacc[mi][pg >> 1][(pg & 1) * 8 + i * 2]);
-        if (false)
-#endif
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-            float psum = 0.f;
-            auto weights = [&]() {
-                psum = 0.f;
-                bf16x2 ones;
-                ones[0] = (__bf16)1.0f;
-                ones[1] = (__bf16)1.0f;
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                    for (int r = 0; r < 16; r += 2) {
-                        bf16x2 pk;
-                        pk[0] = (__bf16)__builtin_amdgcn_exp2f(sacc[mi][nb][r] * c - m_ref[mi]);
-                        pk[1] = (__bf16)__builtin_amdgcn_exp2f(sacc[mi][nb][r + 1] * c - m_ref[mi]);
-                        psum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, psum, false);   // sum of the ROUNDED weights
-                        pf[mi][nb * 2 + (r >> 3)][(r & 7) >> 1] = __builtin_bit_cast(uint32_t, pk);
-                    }
-            };
-            bool redo = careful;
-            if (!careful) {
-                weights();
-                redo = __any(!(psum <= kKeepBelow));   // also catches inf / nan
-            }
-            if (redo) {
-                if (masked) {
-#pragma unroll
-                    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int j = nb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                            if (!keep(mi, j)) sacc[mi][nb][r] = -INFINITY;
-                        }
-                }
-                float tmax = sacc[mi][0][0];
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, sacc[mi][nb][r]);
-                tmax = fmaxf(tmax, half_swap(tmax)) * c;
-                if (__any(tmax > m_ref[mi])) {
-                    const float m_new = fmaxf(m_ref[mi], tmax);
-                    const float alpha = __builtin_amdgcn_exp2f(m_ref[mi] - m_new);
-                    m_ref[mi] = m_new;
-                    l_part[mi] *= alpha;
-#pragma unroll
-                    for (int db = 0; db < 4; ++db)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) oacc[mi][db][r] *= alpha;
-                }
-                weights();
-            }
-            l_part[mi] += psum;
-        }
-        fresh = false;
-        SGC_SCHED_FENCE();
-        SGC_TS(3);
-        // O^T += V^T P^T: block i = (16-key page pg = i / 4, 32-channel group db = i % 4)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < 8; ++i) {
             const int pg = i >> 2, db = i & 3;
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
                 const u32x4 w = {pf[mi][pg][0], pf[mi][pg][1], pf[mi][pg][2], pf[mi][pg][3]};
-                oacc[mi][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i & 7], __builtin_bit_cast(bf16x8, w), oacc[mi][db], 0, 0, 0);
+                oacc[mi][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i], __builtin_bit_cast(bf16x8, w), oacc[mi][db], 0, 0, 0);
             }
-            if (i < 8) frag[i & 7] = *reinterpret_cast<const bf16x8 *>(vbase + (i + 8) * 1024);
-            SGC_SCHED_FENCE();
+            refill(i);
         }
-        SGC_TS(4);
+    };
+    // Weights of one half from scores relative to the reference maximum: one exp2 per score.
+    auto weights = [&](const f32x16 (&s)[MI]) {
+        bf16x2 ones;
+        ones[0] = (__bf16)1.0f;
+        ones[1] = (__bf16)1.0f;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            float acc = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                bf16x2 pk;
+#ifdef SGC_ABL_NOSOFTMAX
+                pk[0] = (__bf16)s[mi][r];
+                pk[1] = (__bf16)s[mi][r + 1];
+#else
+                pk[0] = (__bf16)__builtin_amdgcn_exp2f(s[mi][r]);
+                pk[1] = (__bf16)__builtin_amdgcn_exp2f(s[mi][r + 1]);
+                acc = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, acc, false);   // sum of the ROUNDED weights
+#endif
+                pf[mi][r >> 3][(r & 7) >> 1] = __builtin_bit_cast(uint32_t, pk);
+            }
+            psum[mi] = acc;
+        }
+    };
+    auto weights_overflow = [&]() {       // wave-uniform: some row's weights of this half summed beyond the limit
+        bool bad = false;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) bad |= !(psum[mi] <= kKeepBelow);    // also catches inf / nan
+        return __any(bad);
+    };
+    // The careful part of a softmax step, run before weights().  Masks the half through keep(mi, j) = "row mi
+    // may see key j of the tile" when `masked`; raises the reference maximum to the half's own where that is
+    // larger (rows that have seen no key yet take it as it is), rescales the accumulators and re-bases the
+    // scores.  Returns nothing; m_ref, neg_ref, seen, l_part, oacc and s are updated.
+    auto raise_reference = [&](f32x16 (&s)[MI], const int nb, const bool masked, auto keep) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            if (masked) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int j = nb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                    if (!keep(mi, j)) s[mi][r] = -INFINITY;
+                }
+            }
+            float tmax = s[mi][0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, s[mi][r]);
+            tmax = fmaxf(tmax, half_swap(tmax));               // relative to m_ref
+            const bool has = tmax > -INFINITY;
+            const float delta = seen[mi] ? fmaxf(tmax, 0.f) : (has ? tmax : 0.f);     // new m_ref - old m_ref
+            if (__any(delta != 0.f)) {
+                const float alpha = seen[mi] ? __builtin_amdgcn_exp2f(-delta) : 1.0f;
+                m_ref[mi] += delta;
+                l_part[mi] *= alpha;
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[mi][db][r] *= alpha;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    s[mi][r] -= delta;
+                    neg_ref[mi][r] = -m_ref[mi];
+                }
+            }
+            seen[mi] = seen[mi] || has;
+        }
+    };
+    auto keep_all = [&](int, int) { return true; };
+    // fp8 cache only: scores against suffix keys were formed with the cached-K scale on Q; undo it.  mb is the
+    // reference maximum the product was started from.
+    auto rescale_self = [&](f32x16 (&s)[MI], const float (&mb)[MI]) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[mi][r] = (s[mi][r] + mb[mi]) * self_ratio - mb[mi];
     };
 
     // ---- copy machinery ----------------------------------------------------------------------------
-    // A tile is 32 runs of 1 KiB (fp8 cache: 16 runs of 1 KiB of codes that widen to 2 KiB); run u = part * 4
-    // + quarter with part 0..3 = K of page 0..3, part 4..7 = V of page 0..3.  Wavefront w moves runs
-    // w, w + NW, ...  A run's address is a scalar base (source base + page offset) plus a per-lane 32-bit
-    // offset that is fixed for the launch; page offsets travel as 32-bit counts of 256 bytes, one tile
-    // ahead, in a vector register (lane j < 4 holds page j of the tile) and become scalars by readlane,
-    // so no copy ever waits on a page-table load.
-    constexpr int UNITS_BF16 = 32 / NW, UNITS_FP8 = 16 / NW;
+    // A tile is 8 parts: K of its 4 pages, then V of its 4 pages; a part is 4 KiB of bf16 (2 KiB of fp8
+    // codes that widen to 4 KiB).  With 4 wavefronts, wavefront w moves K and V of page w; with 8, wavefronts
+    // 0..3 move K of page w and 4..7 move V of page w - 4.  A part's source is a scalar base (pool base +
+    // page offset) plus a per-lane offset fixed for the launch; page offsets travel as 32-bit counts of 256
+    // bytes, a step ahead, in a vector register (lane j < 4 holds page j of the tile) and become scalars by
+    // readlane, so no copy ever waits on a page-table load.
+    const int my_page = wave_u & 3;
+    const bool moves_k = NW == 4 || wave_u < 4, moves_v = NW == 4 || wave_u >= 4;
     const char *cache_base = a.pool.pool + (int64_t)a.layer * a.pool.layer_bytes + (int64_t)hk * a.pool.head_part_bytes;
     const uint32_t cache_v_off = (uint32_t)(Hkv * a.pool.head_part_bytes);
     const uint32_t cache_page_256 = (uint32_t)(a.pool.page_bytes >> 8);
     const char *spool_base = a.spool + (int64_t)hk * PART_BYTES;
     const uint32_t spool_v_off = (uint32_t)Hkv * PART_BYTES;
     const uint32_t spool_page_256 = (2u * spool_v_off) >> 8;
-    uint4 stage[KV_FP8 ? UNITS_FP8 : 1];
+    uint4 stage[KV_FP8 ? 4 : 1];      // fp8: [K run 0, K run 1, V run 0, V run 1]
+    bool staged_k = false, staged_v = false;
 
     // Page indices past the last page are clamped to it: such keys are masked out of the scores, and what
     // they multiply in the second product is finite cache content times a zero weight.
@@ -395,98 +413,153 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         return (uint32_t)pt[min(kt * 4 + (lane & 3), n_pages - 1)];
     };
     const uint32_t lane16 = lane * 16;
-    auto issue_copy_bf16 = [&](uint32_t poff, char *buf, const char *base, uint32_t v_off) {
-#pragma unroll
-        for (int j = 0; j < UNITS_BF16; ++j) {
-            const int u = wave_u + NW * j;
-            const int part = u >> 2, quarter = u & 3;
-            const uint32_t off256 = __builtin_amdgcn_readlane(poff, part & 3);
-            const char *sbase = base + ((uint64_t)off256 << 8) + (part >= 4 ? v_off : 0u) + quarter * 1024;
-            copy_1k_to_lds(sbase + lane16, buf + u * 1024);
+    // Copies K of one tile (page offsets poff_k, into kdst) and / or V of one tile (poff_v, into vdst); a null
+    // destination skips that half.
+    auto issue_copy_bf16 = [&](uint32_t poff_k, char *kdst, uint32_t poff_v, char *vdst, const char *base, uint32_t v_off) {
+        if (moves_k && kdst) {
+            const uint32_t off256 = __builtin_amdgcn_readlane(poff_k, my_page);
+            copy_4k_to_lds(base + ((uint64_t)off256 << 8) + lane16, kdst + my_page * PART_BYTES);
+        }
+        if (moves_v && vdst) {
+            const uint32_t off256 = __builtin_amdgcn_readlane(poff_v, my_page);
+            copy_4k_to_lds(base + ((uint64_t)off256 << 8) + v_off + lane16, vdst + my_page * PART_BYTES);
         }
     };
-    auto issue_load_fp8 = [&](uint32_t poff) {
-#pragma unroll
-        for (int j = 0; j < UNITS_FP8; ++j) {
-            const int u = wave_u + NW * j;
-            const int part = u >> 1, run = u & 1;       // a part is 2 KiB of codes
-            const uint32_t off256 = __builtin_amdgcn_readlane(poff, part & 3);
-            const char *sbase = cache_base + ((uint64_t)off256 << 8) + (part >= 4 ? cache_v_off : 0u) + run * 1024;
-            stage[j] = *reinterpret_cast<const uint4 *>(sbase + lane16);
+    auto issue_load_fp8 = [&](uint32_t poff_k, bool want_k, uint32_t poff_v, bool want_v) {
+        staged_k = moves_k && want_k;
+        staged_v = moves_v && want_v;
+        if (staged_k) {
+            const uint32_t off256 = __builtin_amdgcn_readlane(poff_k, my_page);
+            const char *src = cache_base + ((uint64_t)off256 << 8) + lane16;
+            stage[0] = *reinterpret_cast<const uint4 *>(src);
+            stage[1] = *reinterpret_cast<const uint4 *>(src + 1024);
+        }
+        if (staged_v) {
+            const uint32_t off256 = __builtin_amdgcn_readlane(poff_v, my_page);
+            const char *src = cache_base + ((uint64_t)off256 << 8) + cache_v_off + lane16;
+            stage[2] = *reinterpret_cast<const uint4 *>(src);
+            stage[3] = *reinterpret_cast<const uint4 *>(src + 1024);
         }
     };
-    auto store_fp8 = [&](char *buf) {
-#pragma unroll
-        for (int j = 0; j < UNITS_FP8; ++j) {
-            const int u = wave_u + NW * j;
-            const int part = u >> 1, run = u & 1;
-            // 16 codes -> 16 bf16 = 32 bytes; chunk cp of the part lands at 32 * cp of its bf16 image
-            const uint32_t w[4] = {stage[j].x, stage[j].y, stage[j].z, stage[j].w};
-            uint4 o0, o1;
-            o0.x = fp8x2_to_bf16x2(w[0], false); o0.y = fp8x2_to_bf16x2(w[0], true);
-            o0.z = fp8x2_to_bf16x2(w[1], false); o0.w = fp8x2_to_bf16x2(w[1], true);
-            o1.x = fp8x2_to_bf16x2(w[2], false); o1.y = fp8x2_to_bf16x2(w[2], true);
-            o1.z = fp8x2_to_bf16x2(w[3], false); o1.w = fp8x2_to_bf16x2(w[3], true);
-            char *dst = buf + part * PART_BYTES + (run * 64 + lane) * 32;
-            *reinterpret_cast<uint4 *>(dst) = o0;
-            *reinterpret_cast<uint4 *>(dst + 16) = o1;
+    // 16 codes -> 16 bf16 = 32 bytes: chunk (run, lane) of a part lands at 32 (64 run + lane) of its bf16 image
+    auto widen_to_lds = [&](const uint4 &codes, char *dst) {
+        const uint32_t w[4] = {codes.x, codes.y, codes.z, codes.w};
+        uint4 o0, o1;
+        o0.x = fp8x2_to_bf16x2(w[0], false); o0.y = fp8x2_to_bf16x2(w[0], true);
+        o0.z = fp8x2_to_bf16x2(w[1], false); o0.w = fp8x2_to_bf16x2(w[1], true);
+        o1.x = fp8x2_to_bf16x2(w[2], false); o1.y = fp8x2_to_bf16x2(w[2], true);
+        o1.z = fp8x2_to_bf16x2(w[3], false); o1.w = fp8x2_to_bf16x2(w[3], true);
+        *reinterpret_cast<uint4 *>(dst) = o0;
+        *reinterpret_cast<uint4 *>(dst + 16) = o1;
+    };
+    auto store_fp8 = [&](char *kdst, char *vdst) {
+        if (staged_k) {
+            widen_to_lds(stage[0], kdst + my_page * PART_BYTES + lane * 32);
+            widen_to_lds(stage[1], kdst + my_page * PART_BYTES + (64 + lane) * 32);
+        }
+        if (staged_v) {
+            widen_to_lds(stage[2], vdst + my_page * PART_BYTES + lane * 32);
+            widen_to_lds(stage[3], vdst + my_page * PART_BYTES + (64 + lane) * 32);
         }
     };
-    auto fetch_cache = [&](uint32_t poff, char *buf) {
+    // K of one cached tile and / or V of another: kdst / vdst null = none
+    auto fetch_cache = [&](uint32_t ids_k, char *kdst, uint32_t ids_v, char *vdst) {
         if (KV_FP8)
-            issue_load_fp8(poff);
+            issue_load_fp8(ids_k * cache_page_256, kdst != nullptr, ids_v * cache_page_256, vdst != nullptr);
         else
-            issue_copy_bf16(poff, buf, cache_base, cache_v_off);
+            issue_copy_bf16(ids_k * cache_page_256, kdst, ids_v * cache_page_256, vdst, cache_base, cache_v_off);
     };
-    auto land_cache = [&](char *buf) {      // make the fetched cached tile visible in LDS (before the barrier)
-        if (KV_FP8) store_fp8(buf);
+    auto land_cache = [&](char *kdst, char *vdst) {   // make what was fetched visible in LDS (before the barrier)
+        if (KV_FP8) store_fp8(kdst, vdst);
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): direct copies have landed
     };
+    char *const kbuf0 = smem, *const vbuf0 = smem + 2 * HALF_BYTES;
+    auto kbuf_of = [&](int i) -> char * { return kbuf0 + (i & 1) * HALF_BYTES; };
+    auto vbuf_of = [&](int i) -> char * { return vbuf0 + (i & 1) * HALF_BYTES; };
 
-    // Two wavefronts share each SIMD (wave w and w + 4).  Giving one of them standing priority breaks the
-    // lock-step in which both want the matrix unit and then both want the vector unit.
-    if (NW == 8) {
-        if (wave_u < 4)
-            __builtin_amdgcn_s_setprio(2);
-        else
-            __builtin_amdgcn_s_setprio(0);
-    }
-
-    // ---- cached prefix tiles, double buffered ------------------------------------------------------
+    // ---- cached prefix tiles, software pipelined ------------------------------------------------------
+    // The two products of a half frame its softmax: while the vector unit turns the scores of half j into
+    // weights, the matrix unit already forms the scores of half j + 1 (independent instruction streams in
+    // one straight-line region); then comes the second product of half j.  So K runs one tile ahead of V:
+    // during tile step kt, K of tile kt + 2 and V of tile kt + 1 are copied into LDS while K of tile kt + 1
+    // and V of tile kt are read.  At the top of step kt a wavefront holds the scores of (kt, half 0) and, in
+    // its window, the K blocks of (kt, half 1).
     const int n_cache_keys = (MODE == MODE_SUFFIX) ? P : min(P, last_row / g + 1);
     const int n_kt = (n_cache_keys + BN - 1) / BN;
-    int parity = 0;
-    uint32_t pids = 0;          // page ids of the next cached tile, loaded one step before they are needed
+    const int n_my = min(n_kt, (lim_max + BN - 1) / BN);      // tiles this wavefront has rows for
+    f32x16 s0[MI], s1[MI];
+    uint32_t ids1 = 0, ids2 = 0;     // page ids of tiles kt + 1 and kt + 2, loaded a step before they are needed
     if (n_kt > 0) {
-        pids = cache_page_ids(0);
-        fetch_cache(pids * cache_page_256, buf0);
-        pids = cache_page_ids(1);
-        land_cache(buf0);
+        const uint32_t ids0 = cache_page_ids(0);
+        ids1 = cache_page_ids(1);
+        fetch_cache(ids0, kbuf_of(0), ids0, vbuf_of(0));
+        land_cache(kbuf_of(0), vbuf_of(0));
+        if (n_kt > 1) {
+            fetch_cache(ids1, kbuf_of(1), 0, nullptr);
+            land_cache(kbuf_of(1), nullptr);
+        }
+        ids2 = cache_page_ids(2);
     }
     __syncthreads();       // also: qinfo is in LDS
-#ifdef SGC_PHASE_TIMING
-    tlast = __builtin_readcyclecounter();
-#endif
-    for (int kt = 0; kt < n_kt; ++kt) {
-        char *buf = buf0 + parity * BUF_BYTES;
-        char *other = buf0 + (parity ^ 1) * BUF_BYTES;
-        const bool more = kt + 1 < n_kt;
-        if (more) {
-            fetch_cache(pids * cache_page_256, other);
-            pids = cache_page_ids(kt + 2);       // lands before the end-of-step wait, used a step later
-        }
-        SGC_TS(0);
-        const int key0 = kt * BN;
-        if (key0 < lim_max) {                    // some row of this wave still sees keys of this tile
-            const bool masked = key0 + BN > lim_min;
-            process_tile(buf, c_cache, masked, masked, [&](int mi, int j) { return key0 + j < lim[mi]; });
-        }
-        if (more) land_cache(other);
-        SGC_TS(5);
-        __syncthreads();
-        SGC_TS(6);
-        parity ^= 1;
+    if (n_my > 0) {
+        const char *k0 = kbuf_of(0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) frag[i] = k_block(k0, 0, i);
+        qk_half(s0, [&](int i) { frag[i] = k_block(k0, 1, i); });
     }
+    __syncthreads();       // every wavefront has read K of tile 0 before step 0 overwrites it
+    SGC_MARK(2);
+    for (int kt = 0; kt < n_kt; ++kt) {
+        {
+            char *kd = kt + 2 < n_kt ? kbuf_of(kt) : nullptr;
+            char *vd = kt + 1 < n_kt ? vbuf_of(kt + 1) : nullptr;
+#ifndef SGC_ABL_NODMA
+            if (kd || vd) fetch_cache(ids2, kd, ids1, vd);
+#endif
+            ids1 = ids2;
+            ids2 = cache_page_ids(kt + 3);       // lands before the end-of-step wait, used a step later
+        }
+        if (MODE == MODE_SUFFIX || kt < n_my) {  // some row of this wave still sees keys of this tile
+            const int key0 = kt * BN;
+            const bool masked = key0 + BN > lim_min;
+            const bool careful = masked || fresh;
+            // Past this wave's last tile the "next" scores are formed from whatever the other K buffer holds
+            // and never used; this keeps the step free of branches around the matrix instructions.
+            const char *kn = kbuf_of(kt + 1), *vc = vbuf_of(kt);
+            auto keep = [&](int mi, int j) { return key0 + j < lim[mi]; };
+            // A reference raised after the next half's scores were started must be applied to those as well.
+            auto redo = [&](f32x16 (&sc)[MI], f32x16 (&sn)[MI], int nb) {
+                float before[MI];
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) before[mi] = m_ref[mi];
+                raise_reference(sc, nb, false, keep_all);
+                weights(sc);
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sn[mi][r] -= m_ref[mi] - before[mi];
+            };
+            // half 0
+            if (careful) raise_reference(s0, 0, masked, keep);
+            qk_half(s1, [&](int i) { frag[i] = v_block(vc, 0, i); });
+            weights(s0);
+            if (weights_overflow()) redo(s0, s1, 0);
+            pv_half([&](int i) { frag[i] = k_block(kn, 0, i); });
+            // half 1
+            if (careful) raise_reference(s1, 1, masked, keep);
+            qk_half(s0, [&](int i) { frag[i] = v_block(vc, 1, i); });
+            weights(s1);
+            if (weights_overflow()) redo(s1, s0, 1);
+            pv_half([&](int i) { frag[i] = k_block(kn, 1, i); });
+            fresh = false;
+        }
+        land_cache(kt + 2 < n_kt ? kbuf_of(kt) : nullptr, kt + 1 < n_kt ? vbuf_of(kt + 1) : nullptr);
+#ifndef SGC_ABL_NOBAR
+        __syncthreads();
+#endif
+    }
+    SGC_MARK(3);           // cached tiles done
+    int parity = 0;
 
     // ---- the suffix keys of every query this row tile touches, double buffered ------------------------
     bool v_scaled = !KV_FP8;
@@ -520,29 +593,49 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         (d).page_last = it_pglast;                                                                  \
         ++it_jt;                                                                                    \
     } while (0)
-        auto fetch_self = [&](const TileDesc &d, char *buf) {
+        auto fetch_self = [&](const TileDesc &d, int b) {
             const uint32_t po = (uint32_t)min(d.page0 + (lane & 3), d.page_last) * spool_page_256;
-            issue_copy_bf16(po, buf, spool_base, spool_v_off);
+            issue_copy_bf16(po, kbuf_of(b), po, vbuf_of(b), spool_base, spool_v_off);
         };
         TileDesc cur = {1, 0, 0, 0, 0}, nxt = {1, 0, 0, 0, 0};
         bool have, more;
         SGC_NEXT_SELF(have, cur);
         if (have) {
-            fetch_self(cur, buf0 + parity * BUF_BYTES);
+            fetch_self(cur, parity);
             __builtin_amdgcn_s_waitcnt(0x0F70);
         }
         __syncthreads();
         while (have) {
-            char *buf = buf0 + parity * BUF_BYTES;
-            char *other = buf0 + (parity ^ 1) * BUF_BYTES;
             SGC_NEXT_SELF(more, nxt);
-            if (more) fetch_self(nxt, other);
+            if (more) fetch_self(nxt, parity ^ 1);
             const int key0 = cur.key0, q = cur.q;
             bool mine = false;                  // does a row of this wave belong to query q and reach key0?
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) mine |= valid[mi] && sq[mi] == q && qpos[mi] >= key0;
-            if (q >= wsq_min && q <= wsq_max && __any(mine))
-                process_tile(buf, c_self, true, true, [&](int mi, int j) { return sq[mi] == q && key0 + j <= qpos[mi]; });
+            if (q >= wsq_min && q <= wsq_max && __any(mine)) {
+                const char *kc = kbuf_of(parity), *vc = vbuf_of(parity);
+                auto keep = [&](int mi, int j) { return sq[mi] == q && key0 + j <= qpos[mi]; };
+#pragma unroll
+                for (int i = 0; i < 8; ++i) frag[i] = k_block(kc, 0, i);
+                qk_half(s0, [&](int i) { frag[i] = k_block(kc, 1, i); });
+                qk_half(s1, [&](int i) { frag[i] = v_block(vc, 0, i); });
+                // both products started from the same -m_ref; a raise by half 0 is passed on to half 1
+                float before[MI];
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) before[mi] = m_ref[mi];
+                if (KV_FP8) rescale_self(s0, before);
+                raise_reference(s0, 0, true, keep);
+                weights(s0);
+                pv_half([&](int i) { frag[i] = v_block(vc, 1, i); });
+                if (KV_FP8) rescale_self(s1, before);
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s1[mi][r] -= m_ref[mi] - before[mi];
+                raise_reference(s1, 1, true, keep);
+                weights(s1);
+                pv_half(no_refill);
+            }
             if (more) __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads();
             cur = nxt;
@@ -551,14 +644,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         }
 #undef SGC_NEXT_SELF
     }
-#ifdef SGC_PHASE_TIMING
-    if (lane == 0 && blockIdx.x < 2048) {
-        ph[7] = (unsigned)(__builtin_amdgcn_s_memrealtime() - blk_r0);      // 100 MHz ticks for the whole block so far
-        ph[6] = (unsigned)(__builtin_readcyclecounter() - blk_c0);          // shader-clock ticks (overwrites the barrier slot)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) g_phase[(blockIdx.x * 8 + wave) * 8 + i] = ph[i];
-    }
-#endif
+    SGC_MARK(4);           // own suffix tiles done
 
     // ---- normalise and store ----
     uint16_t *og = static_cast<uint16_t *>(a.o);
@@ -582,9 +668,17 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             }
         }
     }
+#ifdef SGC_PHASE_TIMING
+    SGC_MARK(5);           // stores have completed
+    if (lane == 0 && blockIdx.x < 2048) {
+        ph[6] = (unsigned)(blk_r0 & 0xFFFFFFFFu);      // absolute start, low bits
+#pragma unroll
+        for (int i = 0; i < 8; ++i) g_phase[(blockIdx.x * 8 + wave) * 8 + i] = ph[i];
+    }
+#endif
 }
 
-constexpr size_t kDynLds = 2 * BUF_BYTES + MAX_TILE_QUERIES * sizeof(int2);
+constexpr size_t kDynLds = LDS_TILE_BYTES + MAX_TILE_QUERIES * sizeof(int2);
 
 template <int NW, int MI, bool FP8, int MODE>
 hipError_t launch_one(const AttnArgs &a, int blocks, hipStream_t s)

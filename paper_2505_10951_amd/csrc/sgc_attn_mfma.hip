@@ -123,28 +123,137 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         const int ti = tiles_per_head - 1 - (int)(blockIdx.x / Hkv);   // longest rows first
         t.row0 = ti * BM;
         t.n_rows = min(BM, rows - t.row0);
+        t.prefix_len = a.prefix_len;
+        t.pt_off = a.cl_pt_off[t.cluster];
+        t.tok_base = 0;
+        t.sq_lo = 0;
+        t.sq_hi = -1;
+        t.last_qpos = 0;
     }
     // everything that steers the tile loop is made explicitly wave-uniform (scalar registers)
     const int cluster = __builtin_amdgcn_readfirstlane(t.cluster), hk = __builtin_amdgcn_readfirstlane(t.hk);
     t.row0 = __builtin_amdgcn_readfirstlane(t.row0);
     t.n_rows = __builtin_amdgcn_readfirstlane(t.n_rows);
-    const int P = __builtin_amdgcn_readfirstlane((MODE == MODE_SUFFIX) ? a.cl_prefix_len[cluster] : a.prefix_len);
+    const int P = __builtin_amdgcn_readfirstlane(t.prefix_len);
     const int n_pages = (P + kPageTokens - 1) / kPageTokens;
-    const int32_t *pt = a.page_table + __builtin_amdgcn_readfirstlane(a.cl_pt_off[cluster]);
-    const int tok_base = __builtin_amdgcn_readfirstlane((MODE == MODE_SUFFIX) ? a.cl_tok_off[cluster] : 0);
+    const int32_t *pt = a.page_table + __builtin_amdgcn_readfirstlane(t.pt_off);
+    const int tok_base = __builtin_amdgcn_readfirstlane(t.tok_base);
     const int last_row = t.row0 + t.n_rows - 1;
+    const int sq_lo = __builtin_amdgcn_readfirstlane(t.sq_lo), sq_hi = __builtin_amdgcn_readfirstlane(t.sq_hi);
+    const int last_qpos = __builtin_amdgcn_readfirstlane(t.last_qpos);
 
     // ---- the queries this tile touches (suffix mode): lengths and first pages into LDS ----
-    int sq_lo = 0, sq_hi = -1, last_qpos = 0;
     if (MODE == MODE_SUFFIX) {
-        const int last_tau = tok_base + last_row / g;
-        sq_lo = __builtin_amdgcn_readfirstlane(a.tok_sq[tok_base + t.row0 / g]);
-        sq_hi = __builtin_amdgcn_readfirstlane(a.tok_sq[last_tau]);
-        last_qpos = __builtin_amdgcn_readfirstlane(a.tok_qpos[last_tau]);
         for (int i = tid; i <= sq_hi - sq_lo && i < MAX_TILE_QUERIES; i += NW * 64)
             qinfo[i] = make_int2(a.sq_len[sq_lo + i], a.sq_page0[sq_lo + i]);
     }
 
+    // ---- copy machinery ----------------------------------------------------------------------------
+    // A tile is 8 parts: K of its 4 pages, then V of its 4 pages; a part is 4 KiB of bf16 (2 KiB of fp8
+    // codes that widen to 4 KiB).  With 4 wavefronts, wavefront w moves K and V of page w; with 8, wavefronts
+    // 0..3 move K of page w and 4..7 move V of page w - 4.  A part's source is a scalar base (pool base +
+    // page offset) plus a per-lane offset fixed for the launch; page offsets travel as 32-bit counts of 256
+    // bytes, a step ahead, in a vector register (lane j < 4 holds page j of the tile) and become scalars by
+    // readlane, so no copy ever waits on a page-table load.
+    const int my_page = wave_u & 3;
+    const bool moves_k = NW == 4 || wave_u < 4, moves_v = NW == 4 || wave_u >= 4;
+    const char *cache_base = a.pool.pool + (int64_t)a.layer * a.pool.layer_bytes + (int64_t)hk * a.pool.head_part_bytes;
+    const uint32_t cache_v_off = (uint32_t)(Hkv * a.pool.head_part_bytes);
+    const uint32_t cache_page_256 = (uint32_t)(a.pool.page_bytes >> 8);
+    const char *spool_base = a.spool + (int64_t)hk * PART_BYTES;
+    const uint32_t spool_v_off = (uint32_t)Hkv * PART_BYTES;
+    const uint32_t spool_page_256 = (2u * spool_v_off) >> 8;
+    uint4 stage[KV_FP8 ? 4 : 1];      // fp8: [K run 0, K run 1, V run 0, V run 1]
+    bool staged_k = false, staged_v = false;
+
+    // Page indices past the last page are clamped to it: such keys are masked out of the scores, and what
+    // they multiply in the second product is finite cache content times a zero weight.
+    auto cache_page_ids = [&](int kt) __attribute__((always_inline)) -> uint32_t {     // raw page ids; scaled to offsets when used
+        if (n_pages == 0) return 0;       // no cached keys: nothing is ever copied from the cache
+        return (uint32_t)pt[min(kt * 4 + (lane & 3), n_pages - 1)];
+    };
+    const uint32_t lane16 = lane * 16;
+    // Copies K of one tile (page offsets poff_k, into kdst) and / or V of one tile (poff_v, into vdst); a null
+    // destination skips that half.
+    auto issue_copy_bf16 = [&](uint32_t poff_k, char *kdst, uint32_t poff_v, char *vdst, const char *base, uint32_t v_off) __attribute__((always_inline)) {
+        if (moves_k && kdst) {
+            const uint32_t off256 = __builtin_amdgcn_readlane(poff_k, my_page);
+            copy_4k_to_lds(base + ((uint64_t)off256 << 8) + lane16, kdst + my_page * PART_BYTES);
+        }
+        if (moves_v && vdst) {
+            const uint32_t off256 = __builtin_amdgcn_readlane(poff_v, my_page);
+            copy_4k_to_lds(base + ((uint64_t)off256 << 8) + v_off + lane16, vdst + my_page * PART_BYTES);
+        }
+    };
+    auto issue_load_fp8 = [&](uint32_t poff_k, bool want_k, uint32_t poff_v, bool want_v) __attribute__((always_inline)) {
+        staged_k = moves_k && want_k;
+        staged_v = moves_v && want_v;
+        if (staged_k) {
+            const uint32_t off256 = __builtin_amdgcn_readlane(poff_k, my_page);
+            const char *src = cache_base + ((uint64_t)off256 << 8) + lane16;
+            stage[0] = *reinterpret_cast<const uint4 *>(src);
+            stage[1] = *reinterpret_cast<const uint4 *>(src + 1024);
+        }
+        if (staged_v) {
+            const uint32_t off256 = __builtin_amdgcn_readlane(poff_v, my_page);
+            const char *src = cache_base + ((uint64_t)off256 << 8) + cache_v_off + lane16;
+            stage[2] = *reinterpret_cast<const uint4 *>(src);
+            stage[3] = *reinterpret_cast<const uint4 *>(src + 1024);
+        }
+    };
+    // 16 codes -> 16 bf16 = 32 bytes: chunk (run, lane) of a part lands at 32 (64 run + lane) of its bf16 image
+    auto widen_to_lds = [&](const uint4 &codes, char *dst) __attribute__((always_inline)) {
+        const uint32_t w[4] = {codes.x, codes.y, codes.z, codes.w};
+        uint4 o0, o1;
+        o0.x = fp8x2_to_bf16x2(w[0], false); o0.y = fp8x2_to_bf16x2(w[0], true);
+        o0.z = fp8x2_to_bf16x2(w[1], false); o0.w = fp8x2_to_bf16x2(w[1], true);
+        o1.x = fp8x2_to_bf16x2(w[2], false); o1.y = fp8x2_to_bf16x2(w[2], true);
+        o1.z = fp8x2_to_bf16x2(w[3], false); o1.w = fp8x2_to_bf16x2(w[3], true);
+        *reinterpret_cast<uint4 *>(dst) = o0;
+        *reinterpret_cast<uint4 *>(dst + 16) = o1;
+    };
+    // Writes what the last issue_load_fp8 staged; a staged half is written once, and only to a real buffer.
+    auto store_fp8 = [&](char *kdst, char *vdst) __attribute__((always_inline)) {
+        if (staged_k && kdst) {
+            widen_to_lds(stage[0], kdst + my_page * PART_BYTES + lane * 32);
+            widen_to_lds(stage[1], kdst + my_page * PART_BYTES + (64 + lane) * 32);
+        }
+        if (staged_v && vdst) {
+            widen_to_lds(stage[2], vdst + my_page * PART_BYTES + lane * 32);
+            widen_to_lds(stage[3], vdst + my_page * PART_BYTES + (64 + lane) * 32);
+        }
+        staged_k = false;
+        staged_v = false;
+    };
+    // K of one cached tile and / or V of another: kdst / vdst null = none
+    auto fetch_cache = [&](uint32_t ids_k, char *kdst, uint32_t ids_v, char *vdst) __attribute__((always_inline)) {
+        if (KV_FP8)
+            issue_load_fp8(ids_k * cache_page_256, kdst != nullptr, ids_v * cache_page_256, vdst != nullptr);
+        else
+            issue_copy_bf16(ids_k * cache_page_256, kdst, ids_v * cache_page_256, vdst, cache_base, cache_v_off);
+    };
+    auto land_cache = [&](char *kdst, char *vdst) __attribute__((always_inline)) {   // make what was fetched visible in LDS (before the barrier)
+        if (KV_FP8) store_fp8(kdst, vdst);
+#ifdef SGC_ABL_DEFERWAIT
+        __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8): timing experiment only
+#else
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): direct copies have landed
+#endif
+    };
+    char *const kbuf0 = smem, *const vbuf0 = smem + 2 * HALF_BYTES;
+    auto kbuf_of = [&](int i) __attribute__((always_inline)) -> char * { return kbuf0 + (i & 1) * HALF_BYTES; };
+    auto vbuf_of = [&](int i) __attribute__((always_inline)) -> char * { return vbuf0 + (i & 1) * HALF_BYTES; };
+
+    // The first cached tiles are requested before anything else: page ids now, the copies (bf16 cache) as soon
+    // as the ids are there, so that they travel while Q is loaded and rotated.
+    const int n_cache_keys = (MODE == MODE_SUFFIX) ? P : min(P, last_row / g + 1);
+    const int n_kt = (n_cache_keys + BN - 1) / BN;
+    uint32_t ids0 = 0, ids1 = 0, ids2 = 0;     // page ids of tiles 0, 1, 2; later of tiles kt + 1 and kt + 2
+    if (n_kt > 0) {
+        ids0 = cache_page_ids(0);
+        ids1 = cache_page_ids(1);
+        ids2 = cache_page_ids(2);
+    }
     float k_scale = 1.f, v_scale = 1.f;
     if (KV_FP8) {
         const float *sc = a.kv_scale + ((int64_t)cluster * a.n_layers + a.layer) * 2 * Hkv;
@@ -168,10 +277,10 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         const int tk = rc / g;
         head[mi] = hk * g + (rc - tk * g);
         if (MODE == MODE_SUFFIX) {
-            const int tau = tok_base + tk;
-            src_tok[mi] = a.tok_src[tau];
-            qpos[mi] = a.tok_qpos[tau];
-            sq[mi] = a.tok_sq[tau];
+            const TokInfo ti = a.tok_info[tok_base + tk];
+            src_tok[mi] = ti.src;
+            qpos[mi] = ti.qpos;
+            sq[mi] = ti.sq;
             lim[mi] = P;
         } else {
             src_tok[mi] = tk;
@@ -201,6 +310,10 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     wsq_min = __builtin_amdgcn_readfirstlane(wsq_min);
     wsq_max = __builtin_amdgcn_readfirstlane(wsq_max);
 
+    if (!KV_FP8 && n_kt > 0) {
+        fetch_cache(ids0, kbuf_of(0), ids0, vbuf_of(0));
+        if (n_kt > 1) fetch_cache(ids1, kbuf_of(1), 0, nullptr);
+    }
     SGC_MARK(0);           // tile and row bookkeeping is loaded
     // ---- Q: load, rotate at position P + qpos (suffix) / qpos (prefix), keep as B operands ----
     bf16x8 qf[MI][8];
@@ -279,15 +392,15 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     bf16x8 frag[8];
     uint32_t pf[MI][2][4];     // weights of one half as bf16 pairs: [row block][page of the half][register pair]
     float psum[MI];
-    auto k_block = [&](const char *kbuf, int nb, int kb) {
+    auto k_block = [&](const char *kbuf, int nb, int kb) __attribute__((always_inline)) {
         return *reinterpret_cast<const bf16x8 *>(kbuf + lane_koff + nb * 2 * PART_BYTES + kb * 512);
     };
-    auto v_block = [&](const char *vbuf, int nb, int i) {
+    auto v_block = [&](const char *vbuf, int nb, int i) __attribute__((always_inline)) {
         return *reinterpret_cast<const bf16x8 *>(vbuf + lane_voff + (nb * 8 + i) * 1024);
     };
-    auto no_refill = [&](int) {};
+    auto no_refill = [&](int) __attribute__((always_inline)) {};
     // S^T = K Q^T - m_ref for the half whose K blocks the window holds; slot kb is refilled by refill(kb).
-    auto qk_half = [&](f32x16 (&s)[MI], auto refill) {
+    auto qk_half = [&](f32x16 (&s)[MI], auto refill) __attribute__((always_inline)) {
 #pragma unroll
         for (int kb = 0; kb < 8; ++kb) {
 #pragma unroll
@@ -297,7 +410,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         }
     };
     // O^T += V^T P^T for the half whose V blocks the window holds (slot i = page i / 4, channel group i % 4).
-    auto pv_half = [&](auto refill) {
+    auto pv_half = [&](auto refill) __attribute__((always_inline)) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) l_part[mi] += psum[mi];
 #pragma unroll
@@ -312,7 +425,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         }
     };
     // Weights of one half from scores relative to the reference maximum: one exp2 per score.
-    auto weights = [&](const f32x16 (&s)[MI]) {
+    auto weights = [&](const f32x16 (&s)[MI]) __attribute__((always_inline)) {
         bf16x2 ones;
         ones[0] = (__bf16)1.0f;
         ones[1] = (__bf16)1.0f;
@@ -335,7 +448,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             psum[mi] = acc;
         }
     };
-    auto weights_overflow = [&]() {       // wave-uniform: some row's weights of this half summed beyond the limit
+    auto weights_overflow = [&]() __attribute__((always_inline)) {       // wave-uniform: some row's weights of this half summed beyond the limit
         bool bad = false;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) bad |= !(psum[mi] <= kKeepBelow);    // also catches inf / nan
@@ -345,7 +458,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     // may see key j of the tile" when `masked`; raises the reference maximum to the half's own where that is
     // larger (rows that have seen no key yet take it as it is), rescales the accumulators and re-bases the
     // scores.  Returns nothing; m_ref, neg_ref, seen, l_part, oacc and s are updated.
-    auto raise_reference = [&](f32x16 (&s)[MI], const int nb, const bool masked, auto keep) {
+    auto raise_reference = [&](f32x16 (&s)[MI], const int nb, const bool masked, auto keep) __attribute__((always_inline)) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             if (masked) {
@@ -378,104 +491,15 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             seen[mi] = seen[mi] || has;
         }
     };
-    auto keep_all = [&](int, int) { return true; };
+    auto keep_all = [&](int, int) __attribute__((always_inline)) { return true; };
     // fp8 cache only: scores against suffix keys were formed with the cached-K scale on Q; undo it.  mb is the
     // reference maximum the product was started from.
-    auto rescale_self = [&](f32x16 (&s)[MI], const float (&mb)[MI]) {
+    auto rescale_self = [&](f32x16 (&s)[MI], const float (&mb)[MI]) __attribute__((always_inline)) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[mi][r] = (s[mi][r] + mb[mi]) * self_ratio - mb[mi];
     };
-
-    // ---- copy machinery ----------------------------------------------------------------------------
-    // A tile is 8 parts: K of its 4 pages, then V of its 4 pages; a part is 4 KiB of bf16 (2 KiB of fp8
-    // codes that widen to 4 KiB).  With 4 wavefronts, wavefront w moves K and V of page w; with 8, wavefronts
-    // 0..3 move K of page w and 4..7 move V of page w - 4.  A part's source is a scalar base (pool base +
-    // page offset) plus a per-lane offset fixed for the launch; page offsets travel as 32-bit counts of 256
-    // bytes, a step ahead, in a vector register (lane j < 4 holds page j of the tile) and become scalars by
-    // readlane, so no copy ever waits on a page-table load.
-    const int my_page = wave_u & 3;
-    const bool moves_k = NW == 4 || wave_u < 4, moves_v = NW == 4 || wave_u >= 4;
-    const char *cache_base = a.pool.pool + (int64_t)a.layer * a.pool.layer_bytes + (int64_t)hk * a.pool.head_part_bytes;
-    const uint32_t cache_v_off = (uint32_t)(Hkv * a.pool.head_part_bytes);
-    const uint32_t cache_page_256 = (uint32_t)(a.pool.page_bytes >> 8);
-    const char *spool_base = a.spool + (int64_t)hk * PART_BYTES;
-    const uint32_t spool_v_off = (uint32_t)Hkv * PART_BYTES;
-    const uint32_t spool_page_256 = (2u * spool_v_off) >> 8;
-    uint4 stage[KV_FP8 ? 4 : 1];      // fp8: [K run 0, K run 1, V run 0, V run 1]
-    bool staged_k = false, staged_v = false;
-
-    // Page indices past the last page are clamped to it: such keys are masked out of the scores, and what
-    // they multiply in the second product is finite cache content times a zero weight.
-    auto cache_page_ids = [&](int kt) -> uint32_t {     // raw page ids; scaled to offsets when used
-        if (n_pages == 0) return 0;       // no cached keys: nothing is ever copied from the cache
-        return (uint32_t)pt[min(kt * 4 + (lane & 3), n_pages - 1)];
-    };
-    const uint32_t lane16 = lane * 16;
-    // Copies K of one tile (page offsets poff_k, into kdst) and / or V of one tile (poff_v, into vdst); a null
-    // destination skips that half.
-    auto issue_copy_bf16 = [&](uint32_t poff_k, char *kdst, uint32_t poff_v, char *vdst, const char *base, uint32_t v_off) {
-        if (moves_k && kdst) {
-            const uint32_t off256 = __builtin_amdgcn_readlane(poff_k, my_page);
-            copy_4k_to_lds(base + ((uint64_t)off256 << 8) + lane16, kdst + my_page * PART_BYTES);
-        }
-        if (moves_v && vdst) {
-            const uint32_t off256 = __builtin_amdgcn_readlane(poff_v, my_page);
-            copy_4k_to_lds(base + ((uint64_t)off256 << 8) + v_off + lane16, vdst + my_page * PART_BYTES);
-        }
-    };
-    auto issue_load_fp8 = [&](uint32_t poff_k, bool want_k, uint32_t poff_v, bool want_v) {
-        staged_k = moves_k && want_k;
-        staged_v = moves_v && want_v;
-        if (staged_k) {
-            const uint32_t off256 = __builtin_amdgcn_readlane(poff_k, my_page);
-            const char *src = cache_base + ((uint64_t)off256 << 8) + lane16;
-            stage[0] = *reinterpret_cast<const uint4 *>(src);
-            stage[1] = *reinterpret_cast<const uint4 *>(src + 1024);
-        }
-        if (staged_v) {
-            const uint32_t off256 = __builtin_amdgcn_readlane(poff_v, my_page);
-            const char *src = cache_base + ((uint64_t)off256 << 8) + cache_v_off + lane16;
-            stage[2] = *reinterpret_cast<const uint4 *>(src);
-            stage[3] = *reinterpret_cast<const uint4 *>(src + 1024);
-        }
-    };
-    // 16 codes -> 16 bf16 = 32 bytes: chunk (run, lane) of a part lands at 32 (64 run + lane) of its bf16 image
-    auto widen_to_lds = [&](const uint4 &codes, char *dst) {
-        const uint32_t w[4] = {codes.x, codes.y, codes.z, codes.w};
-        uint4 o0, o1;
-        o0.x = fp8x2_to_bf16x2(w[0], false); o0.y = fp8x2_to_bf16x2(w[0], true);
-        o0.z = fp8x2_to_bf16x2(w[1], false); o0.w = fp8x2_to_bf16x2(w[1], true);
-        o1.x = fp8x2_to_bf16x2(w[2], false); o1.y = fp8x2_to_bf16x2(w[2], true);
-        o1.z = fp8x2_to_bf16x2(w[3], false); o1.w = fp8x2_to_bf16x2(w[3], true);
-        *reinterpret_cast<uint4 *>(dst) = o0;
-        *reinterpret_cast<uint4 *>(dst + 16) = o1;
-    };
-    auto store_fp8 = [&](char *kdst, char *vdst) {
-        if (staged_k) {
-            widen_to_lds(stage[0], kdst + my_page * PART_BYTES + lane * 32);
-            widen_to_lds(stage[1], kdst + my_page * PART_BYTES + (64 + lane) * 32);
-        }
-        if (staged_v) {
-            widen_to_lds(stage[2], vdst + my_page * PART_BYTES + lane * 32);
-            widen_to_lds(stage[3], vdst + my_page * PART_BYTES + (64 + lane) * 32);
-        }
-    };
-    // K of one cached tile and / or V of another: kdst / vdst null = none
-    auto fetch_cache = [&](uint32_t ids_k, char *kdst, uint32_t ids_v, char *vdst) {
-        if (KV_FP8)
-            issue_load_fp8(ids_k * cache_page_256, kdst != nullptr, ids_v * cache_page_256, vdst != nullptr);
-        else
-            issue_copy_bf16(ids_k * cache_page_256, kdst, ids_v * cache_page_256, vdst, cache_base, cache_v_off);
-    };
-    auto land_cache = [&](char *kdst, char *vdst) {   // make what was fetched visible in LDS (before the barrier)
-        if (KV_FP8) store_fp8(kdst, vdst);
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): direct copies have landed
-    };
-    char *const kbuf0 = smem, *const vbuf0 = smem + 2 * HALF_BYTES;
-    auto kbuf_of = [&](int i) -> char * { return kbuf0 + (i & 1) * HALF_BYTES; };
-    auto vbuf_of = [&](int i) -> char * { return vbuf0 + (i & 1) * HALF_BYTES; };
 
     // ---- cached prefix tiles, software pipelined ------------------------------------------------------
     // The two products of a half frame its softmax: while the vector unit turns the scores of half j into
@@ -484,51 +508,87 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     // during tile step kt, K of tile kt + 2 and V of tile kt + 1 are copied into LDS while K of tile kt + 1
     // and V of tile kt are read.  At the top of step kt a wavefront holds the scores of (kt, half 0) and, in
     // its window, the K blocks of (kt, half 1).
-    const int n_cache_keys = (MODE == MODE_SUFFIX) ? P : min(P, last_row / g + 1);
-    const int n_kt = (n_cache_keys + BN - 1) / BN;
     const int n_my = min(n_kt, (lim_max + BN - 1) / BN);      // tiles this wavefront has rows for
     f32x16 s0[MI], s1[MI];
-    uint32_t ids1 = 0, ids2 = 0;     // page ids of tiles kt + 1 and kt + 2, loaded a step before they are needed
     if (n_kt > 0) {
-        const uint32_t ids0 = cache_page_ids(0);
-        ids1 = cache_page_ids(1);
-        fetch_cache(ids0, kbuf_of(0), ids0, vbuf_of(0));
-        land_cache(kbuf_of(0), vbuf_of(0));
-        if (n_kt > 1) {
-            fetch_cache(ids1, kbuf_of(1), 0, nullptr);
-            land_cache(kbuf_of(1), nullptr);
+        if (KV_FP8) {      // through registers: one tile's worth at a time
+            fetch_cache(ids0, kbuf_of(0), ids0, vbuf_of(0));
+            land_cache(kbuf_of(0), vbuf_of(0));
+            if (n_kt > 1) {
+                fetch_cache(ids1, kbuf_of(1), 0, nullptr);
+                land_cache(kbuf_of(1), nullptr);
+            }
+        } else {
+            land_cache(nullptr, nullptr);
         }
-        ids2 = cache_page_ids(2);
     }
     __syncthreads();       // also: qinfo is in LDS
     if (n_my > 0) {
         const char *k0 = kbuf_of(0);
 #pragma unroll
         for (int i = 0; i < 8; ++i) frag[i] = k_block(k0, 0, i);
-        qk_half(s0, [&](int i) { frag[i] = k_block(k0, 1, i); });
+        qk_half(s0, [&](int i) __attribute__((always_inline)) { frag[i] = k_block(k0, 1, i); });
     }
     __syncthreads();       // every wavefront has read K of tile 0 before step 0 overwrites it
     SGC_MARK(2);
-    for (int kt = 0; kt < n_kt; ++kt) {
-        {
-            char *kd = kt + 2 < n_kt ? kbuf_of(kt) : nullptr;
-            char *vd = kt + 1 < n_kt ? vbuf_of(kt + 1) : nullptr;
+    // One part's copy: per-lane source address and LDS destination.  Issued as four 1 KiB instructions that
+    // the steady-state step spreads between its matrix instructions, so that a wavefront never sits on a
+    // full memory-instruction queue while the matrix unit idles.
+    struct PartCopy {
+        const char *src;
+        char *dst;
+    };
+    auto cache_part = [&](bool is_v, uint32_t ids, char *dst_half) __attribute__((always_inline)) -> PartCopy {
+        const uint32_t off256 = (uint32_t)__builtin_amdgcn_readlane(ids, my_page) * cache_page_256;
+        return {cache_base + ((uint64_t)off256 << 8) + (is_v ? cache_v_off : 0u) + lane16, dst_half + my_page * PART_BYTES};
+    };
+    auto copy_quarter = [&](const PartCopy &pc, int slot) __attribute__((always_inline)) {     // slot 0, 2, 4, 6 -> quarter 0..3; odd slots: nothing
+        const auto *gp = (const __attribute__((address_space(1))) void *)pc.src;
+        auto *lp = (__attribute__((address_space(3))) void *)pc.dst;
+        switch (slot) {
+            case 0: __builtin_amdgcn_global_load_lds(gp, lp, 16, 0, 0); break;
+            case 2: __builtin_amdgcn_global_load_lds(gp, lp, 16, 1024, 0); break;
+            case 4: __builtin_amdgcn_global_load_lds(gp, lp, 16, 2048, 0); break;
+            case 6: __builtin_amdgcn_global_load_lds(gp, lp, 16, 3072, 0); break;
+            default: break;
+        }
+    };
+    // Step kt.  spread (a true_type / false_type tag): issue this step's copies between the matrix
+    // instructions (needs a bf16 cache, both copies due and this wavefront computing) or at the top.
+    auto cache_step = [&](const int kt, auto spread_tag) __attribute__((always_inline)) {
+        constexpr bool spread = decltype(spread_tag)::value;
+        char *kd = kt + 2 < n_kt ? kbuf_of(kt) : nullptr;
+        char *vd = kt + 1 < n_kt ? vbuf_of(kt + 1) : nullptr;
+#ifdef SGC_ABL_SAMETILE
+        const uint32_t ids3 = cache_page_ids(0);
+#else
+        const uint32_t ids3 = cache_page_ids(kt + 3);    // issued before the copies, used a step later
+#endif
+        PartCopy first = {nullptr, nullptr}, second = {nullptr, nullptr};
+        if (spread) {
+            if (NW == 4) {
+                first = cache_part(true, ids1, vd);      // V of tile kt + 1 is needed first
+                second = cache_part(false, ids2, kd);
+            } else {
+                first = moves_v ? cache_part(true, ids1, vd) : cache_part(false, ids2, kd);
+            }
+        } else {
 #ifndef SGC_ABL_NODMA
             if (kd || vd) fetch_cache(ids2, kd, ids1, vd);
 #endif
-            ids1 = ids2;
-            ids2 = cache_page_ids(kt + 3);       // lands before the end-of-step wait, used a step later
         }
-        if (MODE == MODE_SUFFIX || kt < n_my) {  // some row of this wave still sees keys of this tile
+        ids1 = ids2;
+        ids2 = ids3;
+        if (spread || MODE == MODE_SUFFIX || kt < n_my) {  // some row of this wave still sees keys of this tile
             const int key0 = kt * BN;
             const bool masked = key0 + BN > lim_min;
             const bool careful = masked || fresh;
             // Past this wave's last tile the "next" scores are formed from whatever the other K buffer holds
             // and never used; this keeps the step free of branches around the matrix instructions.
             const char *kn = kbuf_of(kt + 1), *vc = vbuf_of(kt);
-            auto keep = [&](int mi, int j) { return key0 + j < lim[mi]; };
+            auto keep = [&](int mi, int j) __attribute__((always_inline)) { return key0 + j < lim[mi]; };
             // A reference raised after the next half's scores were started must be applied to those as well.
-            auto redo = [&](f32x16 (&sc)[MI], f32x16 (&sn)[MI], int nb) {
+            auto redo = [&](f32x16 (&sc)[MI], f32x16 (&sn)[MI], int nb) __attribute__((always_inline)) {
                 float before[MI];
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi) before[mi] = m_ref[mi];
@@ -541,22 +601,38 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             };
             // half 0
             if (careful) raise_reference(s0, 0, masked, keep);
-            qk_half(s1, [&](int i) { frag[i] = v_block(vc, 0, i); });
+            qk_half(s1, [&](int i) __attribute__((always_inline)) {
+                frag[i] = v_block(vc, 0, i);
+                if (spread) copy_quarter(first, i);
+            });
             weights(s0);
             if (weights_overflow()) redo(s0, s1, 0);
-            pv_half([&](int i) { frag[i] = k_block(kn, 0, i); });
+            pv_half([&](int i) __attribute__((always_inline)) {
+                frag[i] = k_block(kn, 0, i);
+                if (spread && NW == 4) copy_quarter(second, i);
+            });
             // half 1
             if (careful) raise_reference(s1, 1, masked, keep);
-            qk_half(s0, [&](int i) { frag[i] = v_block(vc, 1, i); });
+            qk_half(s0, [&](int i) __attribute__((always_inline)) { frag[i] = v_block(vc, 1, i); });
             weights(s1);
             if (weights_overflow()) redo(s1, s0, 1);
-            pv_half([&](int i) { frag[i] = k_block(kn, 1, i); });
+            pv_half([&](int i) __attribute__((always_inline)) { frag[i] = k_block(kn, 1, i); });
             fresh = false;
         }
-        land_cache(kt + 2 < n_kt ? kbuf_of(kt) : nullptr, kt + 1 < n_kt ? vbuf_of(kt + 1) : nullptr);
+        land_cache(kd, vd);
 #ifndef SGC_ABL_NOBAR
         __syncthreads();
 #endif
+    };
+    {
+        int kt = 0;
+#ifndef SGC_ABL_NODMA
+        if (!KV_FP8) {
+            const int n_spread = min(n_kt - 2, MODE == MODE_SUFFIX ? n_kt : n_my);
+            for (; kt < n_spread; ++kt) cache_step(kt, std::true_type{});
+        }
+#endif
+        for (; kt < n_kt; ++kt) cache_step(kt, std::false_type{});
     }
     SGC_MARK(3);           // cached tiles done
     int parity = 0;
@@ -593,7 +669,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         (d).page_last = it_pglast;                                                                  \
         ++it_jt;                                                                                    \
     } while (0)
-        auto fetch_self = [&](const TileDesc &d, int b) {
+        auto fetch_self = [&](const TileDesc &d, int b) __attribute__((always_inline)) {
             const uint32_t po = (uint32_t)min(d.page0 + (lane & 3), d.page_last) * spool_page_256;
             issue_copy_bf16(po, kbuf_of(b), po, vbuf_of(b), spool_base, spool_v_off);
         };
@@ -614,11 +690,11 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             for (int mi = 0; mi < MI; ++mi) mine |= valid[mi] && sq[mi] == q && qpos[mi] >= key0;
             if (q >= wsq_min && q <= wsq_max && __any(mine)) {
                 const char *kc = kbuf_of(parity), *vc = vbuf_of(parity);
-                auto keep = [&](int mi, int j) { return sq[mi] == q && key0 + j <= qpos[mi]; };
+                auto keep = [&](int mi, int j) __attribute__((always_inline)) { return sq[mi] == q && key0 + j <= qpos[mi]; };
 #pragma unroll
                 for (int i = 0; i < 8; ++i) frag[i] = k_block(kc, 0, i);
-                qk_half(s0, [&](int i) { frag[i] = k_block(kc, 1, i); });
-                qk_half(s1, [&](int i) { frag[i] = v_block(vc, 0, i); });
+                qk_half(s0, [&](int i) __attribute__((always_inline)) { frag[i] = k_block(kc, 1, i); });
+                qk_half(s1, [&](int i) __attribute__((always_inline)) { frag[i] = v_block(vc, 0, i); });
                 // both products started from the same -m_ref; a raise by half 0 is passed on to half 1
                 float before[MI];
 #pragma unroll
@@ -626,7 +702,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
                 if (KV_FP8) rescale_self(s0, before);
                 raise_reference(s0, 0, true, keep);
                 weights(s0);
-                pv_half([&](int i) { frag[i] = v_block(vc, 1, i); });
+                pv_half([&](int i) __attribute__((always_inline)) { frag[i] = v_block(vc, 1, i); });
                 if (KV_FP8) rescale_self(s1, before);
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)

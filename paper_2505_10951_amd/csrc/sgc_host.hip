@@ -216,15 +216,41 @@ void build_tiles(sgc_plan *pl, int tile_rows)
         for (int i = 1; i < kXcd; ++i)
             if (load[i] < load[x]) x = i;
         load[x] += u.work;
-        for (int64_t r = 0; r < u.rows; r += tile_rows)
-            lists[x].push_back({u.cluster, u.hk, (int32_t)r, (int32_t)std::min<int64_t>(tile_rows, u.rows - r)});
+        for (int64_t r = 0; r < u.rows; r += tile_rows) {
+            Tile t{};
+            t.cluster = u.cluster;
+            t.hk = u.hk;
+            t.row0 = (int32_t)r;
+            t.n_rows = (int32_t)std::min<int64_t>(tile_rows, u.rows - r);
+            t.prefix_len = pl->cl_prefix_len[u.cluster];
+            t.tok_base = pl->cl_tok_off[u.cluster];
+            const int32_t first_tok = t.tok_base + t.row0 / g, last_tok = t.tok_base + (t.row0 + t.n_rows - 1) / g;
+            t.sq_lo = pl->tok_sq[first_tok];
+            t.sq_hi = pl->tok_sq[last_tok];
+            t.last_qpos = pl->tok_qpos[last_tok];
+            lists[x].push_back(t);
+        }
     }
     size_t slots = 0;
     for (auto &l : lists) slots = std::max(slots, l.size());
-    pl->tiles.assign(slots * kXcd, Tile{0, 0, 0, 0});
+    pl->tiles.assign(slots * kXcd, Tile{});
     for (int x = 0; x < kXcd; ++x)
         for (size_t s = 0; s < lists[x].size(); ++s) pl->tiles[s * kXcd + x] = lists[x][s];
     pl->tile_rows = tile_rows;
+}
+
+// Page-table offsets of the clusters as cache_sync lays the flat table out; they move when clusters
+// are allocated or released, so the tiles carry the cache generation they were filled for.
+void fill_tile_pt_off(sgc_plan *pl, const sgc_cache *c)
+{
+    std::vector<int32_t> off(c->max_clusters, 0);
+    int32_t n = 0;
+    for (int i = 0; i < c->max_clusters; ++i) {
+        off[i] = n;
+        if (c->cl[i].allocated) n += (int32_t)c->cl[i].pages.size();
+    }
+    for (Tile &t : pl->tiles) t.pt_off = t.n_rows > 0 ? off[t.cluster] : 0;
+    pl->tiles_generation = c->generation;
 }
 
 void plan_free_device(sgc_plan *pl)
@@ -540,7 +566,12 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
     plan_free_device(pl);
     pl->tiles.clear();
     pl->tile_rows = 0;
-    if (want_rows > 0) build_tiles(pl, want_rows);
+    if (want_rows > 0) {
+        build_tiles(pl, want_rows);
+        fill_tile_pt_off(pl, pl->cache);
+    }
+    pl->tok_info.resize(pl->tok_src.size());
+    for (size_t i = 0; i < pl->tok_src.size(); ++i) pl->tok_info[i] = {pl->tok_src[i], pl->tok_qpos[i], pl->tok_sq[i], 0};
 
     struct Piece {
         const void *src;
@@ -559,6 +590,7 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
         {pl->sq_page0.data(), pl->sq_page0.size() * 4, (const void **)&pl->d_sq_page0},
         {pl->spage_sq.data(), pl->spage_sq.size() * 4, (const void **)&pl->d_spage_sq},
         {pl->tiles.data(), pl->tiles.size() * sizeof(Tile), (const void **)&pl->d_tiles},
+        {pl->tok_info.data(), pl->tok_info.size() * sizeof(TokInfo), (const void **)&pl->d_tok_info},
     };
     size_t total = 0;
     for (const Piece &p : pieces) total += (p.bytes + 255) / 256 * 256 + 256;
@@ -622,6 +654,13 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
     if ((rc = ensure_rope(ctx, pl->max_position, s)) != SGC_OK) return rc;
     if ((rc = cache_sync(c, s)) != SGC_OK) return rc;
     if ((rc = sgc_plan_upload(pl, hip_stream)) != SGC_OK) return rc;
+    if (!pl->tiles.empty() && pl->tiles_generation != c->generation) {
+        // clusters were allocated or released since the tiles were filled: refresh their page-table offsets
+        fill_tile_pt_off(pl, c);
+        SGC_HIP(ctx, hipMemcpyAsync(const_cast<Tile *>(pl->d_tiles), pl->tiles.data(), pl->tiles.size() * sizeof(Tile),
+                                    hipMemcpyHostToDevice, s));
+        SGC_HIP(ctx, hipStreamSynchronize(s));
+    }
 
     AttnArgs a;
     fill_common_args(a, ctx, c, layer);
@@ -638,6 +677,7 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
     a.tok_src = pl->d_tok_src;
     a.tok_qpos = pl->d_tok_qpos;
     a.tok_sq = pl->d_tok_sq;
+    a.tok_info = pl->d_tok_info;
     a.sq_src0 = pl->d_sq_src0;
     a.sq_len = pl->d_sq_len;
     a.sq_tok0 = pl->d_sq_tok0;

@@ -61,12 +61,27 @@ struct PoolGeom {
     }
 };
 
-// One workgroup's share of an attention launch.
+// One workgroup's share of an attention launch, with everything the workgroup needs to start its
+// loads at once (one 48-byte scalar load instead of a chain of dependent table look-ups).
 struct Tile {
-    int32_t cluster;   // cluster id (index into the cache's per-cluster arrays)
-    int32_t hk;        // KV head
-    int32_t row0;      // first row inside the (cluster, hk) row space; row = token * g + head-in-group
-    int32_t n_rows;    // valid rows in this tile (0 = padding tile, exit at once)
+    int32_t cluster;     // cluster id (index into the cache's per-cluster arrays)
+    int32_t hk;          // KV head
+    int32_t row0;        // first row inside the (cluster, hk) row space; row = token * g + head-in-group
+    int32_t n_rows;      // valid rows in this tile (0 = padding tile, exit at once)
+    int32_t prefix_len;  // cached tokens of the cluster
+    int32_t pt_off;      // first entry of the cluster in the flat page table
+    int32_t tok_base;    // first sorted token of the cluster
+    int32_t sq_lo, sq_hi;   // sorted queries of the tile's first and last row
+    int32_t last_qpos;   // position of the last row's token inside its query
+    int32_t pad[2];
+};
+
+// Per sorted token: where it comes from and where it sits in its query.
+struct TokInfo {
+    int32_t src;    // row of the token in the caller's packed arrays
+    int32_t qpos;   // index of the token inside its query
+    int32_t sq;     // sorted query index
+    int32_t pad;
 };
 
 enum { MODE_SUFFIX = 0, MODE_PREFIX = 1 };
@@ -93,6 +108,7 @@ struct AttnArgs {
     const int32_t *tok_src;       // [T] row of the token in the caller's packed arrays
     const int32_t *tok_qpos;      // [T] index of the token inside its query
     const int32_t *tok_sq;        // [T] sorted query index of the token
+    const TokInfo *tok_info;      // [T] the three above in one record
     const int32_t *sq_src0;       // [n_queries] first packed row of the query
     const int32_t *sq_len;        // [n_queries] suffix length
     const int32_t *sq_tok0;       // [n_queries] first sorted token of the query
@@ -159,6 +175,8 @@ struct sgc_plan {
     std::vector<int32_t> sq_src0, sq_len, sq_tok0, sq_cluster, sq_page0;   // non-empty queries only
     std::vector<int32_t> spage_sq;            // [total suffix pages] owning query of each suffix page
     std::vector<sgc::Tile> tiles;
+    std::vector<sgc::TokInfo> tok_info;
+    uint64_t tiles_generation = 0;            // cache generation the tiles' page-table offsets belong to
     int32_t tile_rows = 0;
     bool uploaded = false;
     char *d_blob = nullptr;                   // one device allocation holding every array below
@@ -166,6 +184,7 @@ struct sgc_plan {
     const int32_t *d_sq_src0 = nullptr, *d_sq_len = nullptr, *d_sq_tok0 = nullptr, *d_sq_cluster = nullptr;
     const int32_t *d_sq_page0 = nullptr, *d_spage_sq = nullptr;
     const sgc::Tile *d_tiles = nullptr;
+    const sgc::TokInfo *d_tok_info = nullptr;
     char *d_spool = nullptr;                  // rotated suffix K / transposed V pages of the batch (MFMA path)
     size_t spool_bytes = 0;
 };

@@ -531,6 +531,36 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     }
     __syncthreads();       // every wavefront has read K of tile 0 before step 0 overwrites it
     SGC_MARK(2);
+    // ---- the stream of this row tile's own suffix key tiles ------------------------------------------------
+    // Scalar iterator over (query, 64-key tile); a query's LDS record is read when the stream reaches it.  The
+    // first tile is requested during the last cached step, into the buffers that step leaves free.
+    int it_q = sq_lo - 1, it_jt = 0, it_njt = 0, it_pg0 = 0, it_pglast = 0;
+#define SGC_NEXT_SELF(ok, d)                                                                        \
+    do {                                                                                            \
+        while (it_jt >= it_njt && it_q < sq_hi) {                                                   \
+            ++it_q;                                                                                 \
+            const int2 qi = qinfo[min(it_q - sq_lo, MAX_TILE_QUERIES - 1)];                         \
+            const int S__ = __builtin_amdgcn_readfirstlane(qi.x);                                   \
+            it_pg0 = __builtin_amdgcn_readfirstlane(qi.y);                                          \
+            it_pglast = it_pg0 + (S__ - 1) / kPageTokens;                                           \
+            it_njt = ((it_q == sq_hi ? last_qpos : S__ - 1) + BN) / BN;                             \
+            it_jt = 0;                                                                              \
+        }                                                                                           \
+        (ok) = it_jt < it_njt;                                                                      \
+        (d).key0 = it_jt * BN;                                                                      \
+        (d).q = it_q;                                                                               \
+        (d).page0 = it_pg0 + it_jt * 4;                                                             \
+        (d).page_last = it_pglast;                                                                  \
+        ++it_jt;                                                                                    \
+    } while (0)
+    auto fetch_self = [&](const TileDesc &d, char *kdst, char *vdst) __attribute__((always_inline)) {
+        const uint32_t po = (uint32_t)min(d.page0 + (lane & 3), d.page_last) * spool_page_256;
+        issue_copy_bf16(po, kdst, po, vdst, spool_base, spool_v_off);
+    };
+    TileDesc cur = {1, 0, 0, 0, 0}, nxt = {1, 0, 0, 0, 0};
+    bool have = false, more = false;
+    if (MODE == MODE_SUFFIX) SGC_NEXT_SELF(have, cur);      // qinfo is visible since the barriers above
+
     // One part's copy: per-lane source address and LDS destination.  Issued as four 1 KiB instructions that
     // the steady-state step spreads between its matrix instructions, so that a wavefront never sits on a
     // full memory-instruction queue while the matrix unit idles.
@@ -576,6 +606,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
 #ifndef SGC_ABL_NODMA
             if (kd || vd) fetch_cache(ids2, kd, ids1, vd);
 #endif
+            if (MODE == MODE_SUFFIX && kt == n_kt - 1 && have) fetch_self(cur, kbuf_of(kt), vbuf_of(kt + 1));
         }
         ids1 = ids2;
         ids2 = ids3;
@@ -635,7 +666,6 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         for (; kt < n_kt; ++kt) cache_step(kt, std::false_type{});
     }
     SGC_MARK(3);           // cached tiles done
-    int parity = 0;
 
     // ---- the suffix keys of every query this row tile touches, double buffered ------------------------
     bool v_scaled = !KV_FP8;
@@ -649,47 +679,24 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
                     for (int r = 0; r < 16; ++r) oacc[mi][db][r] *= v_scale;
             v_scaled = true;
         }
-        // scalar iterator over (query, 64-key tile); a query's LDS record is read when the stream reaches it
-        int it_q = sq_lo - 1, it_jt = 0, it_njt = 0, it_pg0 = 0, it_pglast = 0;
-#define SGC_NEXT_SELF(ok, d)                                                                        \
-    do {                                                                                            \
-        while (it_jt >= it_njt && it_q < sq_hi) {                                                   \
-            ++it_q;                                                                                 \
-            const int2 qi = qinfo[min(it_q - sq_lo, MAX_TILE_QUERIES - 1)];                         \
-            const int S__ = __builtin_amdgcn_readfirstlane(qi.x);                                   \
-            it_pg0 = __builtin_amdgcn_readfirstlane(qi.y);                                          \
-            it_pglast = it_pg0 + (S__ - 1) / kPageTokens;                                           \
-            it_njt = ((it_q == sq_hi ? last_qpos : S__ - 1) + BN) / BN;                             \
-            it_jt = 0;                                                                              \
-        }                                                                                           \
-        (ok) = it_jt < it_njt;                                                                      \
-        (d).key0 = it_jt * BN;                                                                      \
-        (d).q = it_q;                                                                               \
-        (d).page0 = it_pg0 + it_jt * 4;                                                             \
-        (d).page_last = it_pglast;                                                                  \
-        ++it_jt;                                                                                    \
-    } while (0)
-        auto fetch_self = [&](const TileDesc &d, int b) __attribute__((always_inline)) {
-            const uint32_t po = (uint32_t)min(d.page0 + (lane & 3), d.page_last) * spool_page_256;
-            issue_copy_bf16(po, kbuf_of(b), po, vbuf_of(b), spool_base, spool_v_off);
-        };
-        TileDesc cur = {1, 0, 0, 0, 0}, nxt = {1, 0, 0, 0, 0};
-        bool have, more;
-        SGC_NEXT_SELF(have, cur);
-        if (have) {
-            fetch_self(cur, parity);
-            __builtin_amdgcn_s_waitcnt(0x0F70);
+        // own tile i: K in K buffer (kpar + i) & 1, V in V buffer (vpar + i) & 1
+        int kpar = (n_kt + 1) & 1, vpar = n_kt & 1;
+        if (n_kt == 0) {
+            if (have) {
+                fetch_self(cur, kbuf_of(kpar), vbuf_of(vpar));
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+            }
+            __syncthreads();
         }
-        __syncthreads();
         while (have) {
             SGC_NEXT_SELF(more, nxt);
-            if (more) fetch_self(nxt, parity ^ 1);
+            if (more) fetch_self(nxt, kbuf_of(kpar ^ 1), vbuf_of(vpar ^ 1));
             const int key0 = cur.key0, q = cur.q;
             bool mine = false;                  // does a row of this wave belong to query q and reach key0?
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) mine |= valid[mi] && sq[mi] == q && qpos[mi] >= key0;
             if (q >= wsq_min && q <= wsq_max && __any(mine)) {
-                const char *kc = kbuf_of(parity), *vc = vbuf_of(parity);
+                const char *kc = kbuf_of(kpar), *vc = vbuf_of(vpar);
                 auto keep = [&](int mi, int j) __attribute__((always_inline)) { return sq[mi] == q && key0 + j <= qpos[mi]; };
 #pragma unroll
                 for (int i = 0; i < 8; ++i) frag[i] = k_block(kc, 0, i);
@@ -716,7 +723,8 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             __syncthreads();
             cur = nxt;
             have = more;
-            parity ^= 1;
+            kpar ^= 1;
+            vpar ^= 1;
         }
 #undef SGC_NEXT_SELF
     }

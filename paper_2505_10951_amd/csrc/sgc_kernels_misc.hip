@@ -147,6 +147,13 @@ __global__ void rope_table_kernel(float2 *table, int n_pos, int half, double bas
 }
 
 // ---- prefix ingest ---------------------------------------------------------------------------
+// Linear copy of n bytes (a multiple of 16) from LDS to global memory, 16 bytes per thread and turn.
+__device__ inline void copy_out_16(char *dst, const char *lds_src, int n)
+{
+    for (int off = threadIdx.x * 16; off < n; off += blockDim.x * 16)
+        *reinterpret_cast<uint4 *>(dst + off) = *reinterpret_cast<const uint4 *>(lds_src + off);
+}
+
 // Pass 0 (fp8 only): per-head max |rotated K| and max |V| into amax[2][Hkv] via integer atomicMax
 // on the bit patterns of non-negative floats.
 __global__ void ingest_amax_kernel(const void *k, const void *v, int io_dtype, int P, int Hkv, int d,
@@ -202,8 +209,11 @@ __global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *pages,
     const int pg = blockIdx.x, hk = blockIdx.y;
     const int d = g.head_dim, Hkv = g.n_kv_heads, half = d / 2, pairs = d / 16;
     const int page = pages[pg];
-    char *kp = g.k_part(layer, page, hk);
-    char *vp = g.v_part(layer, page, hk);
+    // The page images are put together in LDS (V is a transpose: element-sized scattered writes) and go out
+    // as whole 16-byte rows.
+    extern __shared__ __attribute__((aligned(16))) char page_img[];
+    const int part_bytes = (int)g.head_part_bytes;
+    char *kp = page_img, *vp = page_img + part_bytes;
     float sc_k = 1.f, sc_v = 1.f;   // fp8: the per-head scales the codes are divided by
     if (g.kv_dtype == SGC_FP8_E4M3) {
         sc_k = scale_kv[hk];
@@ -232,6 +242,9 @@ __global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *pages,
             store1(vp, v_page_index(tok, half + cc * 8 + i), g.kv_dtype, y2[i], sc_v);
         }
     }
+    __syncthreads();
+    copy_out_16(g.k_part(layer, page, hk), kp, part_bytes);
+    copy_out_16(g.v_part(layer, page, hk), vp, part_bytes);
 }
 
 // ---- suffix ingest ---------------------------------------------------------------------------
@@ -249,8 +262,10 @@ __global__ void suffix_ingest_kernel(AttnArgs a, const int32_t *spage_sq)
     const int P = a.cl_prefix_len[a.sq_cluster[sq]];
     const int tok0 = (page - a.sq_page0[sq]) * kPageTokens;
     const int64_t part = (int64_t)kPageTokens * d * 2;
-    char *kp = const_cast<char *>(a.spool) + (int64_t)page * 2 * Hkv * part + (int64_t)hk * part;
-    char *vp = kp + (int64_t)Hkv * part;
+    char *kg = const_cast<char *>(a.spool) + (int64_t)page * 2 * Hkv * part + (int64_t)hk * part;
+    char *vg = kg + (int64_t)Hkv * part;
+    extern __shared__ __attribute__((aligned(16))) char page_img[];     // both images are built in LDS first
+    char *kp = page_img, *vp = page_img + part;
     for (int it = threadIdx.x; it < kPageTokens * pairs; it += blockDim.x) {
         const int tok = it / pairs, cc = it % pairs;
         const int j = tok0 + tok;
@@ -274,6 +289,9 @@ __global__ void suffix_ingest_kernel(AttnArgs a, const int32_t *spage_sq)
             store1(vp, v_page_index(tok, half + cc * 8 + i), SGC_BF16, y2[i], 1.f);
         }
     }
+    __syncthreads();
+    copy_out_16(kg, kp, (int)part);
+    copy_out_16(vg, vp, (int)part);
 }
 
 // ---- export / import: raw element moves between page order and [P][Hkv][d] --------------------
@@ -485,15 +503,16 @@ hipError_t launch_prefix_ingest(const PoolGeom &g, int layer, const int32_t *d_p
                            rope, d_scale_kv);
         hipLaunchKernelGGL(amax_to_scale_kernel, dim3((n + 63) / 64), dim3(64), 0, s, d_scale_kv, n);
     }
-    hipLaunchKernelGGL(ingest_write_kernel, grid, dim3(128), 0, s, g, layer, d_pages, prefix_len, k, v, io_dtype, rope,
-                       (const float *)d_scale_kv);
+    hipLaunchKernelGGL(ingest_write_kernel, grid, dim3(128), 2 * (size_t)g.head_part_bytes, s, g, layer, d_pages, prefix_len,
+                       k, v, io_dtype, rope, (const float *)d_scale_kv);
     return hipGetLastError();
 }
 
 hipError_t launch_suffix_ingest(const AttnArgs &a, const int32_t *d_spage_sq, int n_spages, hipStream_t s)
 {
     if (n_spages <= 0) return hipSuccess;
-    hipLaunchKernelGGL(suffix_ingest_kernel, dim3(n_spages, a.n_kv_heads), dim3(128), 0, s, a, d_spage_sq);
+    const size_t lds = 2 * (size_t)kPageTokens * a.head_dim * 2;
+    hipLaunchKernelGGL(suffix_ingest_kernel, dim3(n_spages, a.n_kv_heads), dim3(128), lds, s, a, d_spage_sq);
     return hipGetLastError();
 }
 

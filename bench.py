@@ -23,6 +23,27 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}      # MI355X dense MFMA bf16; fp32 vector
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# file, each counter scaled by what it reads for a plain copy of known size (--copy-calibration).  The runs
+# and the arithmetic are written down in profiles/attn_mfma_suffix_llama3_8b_layer.md; a workload that has
+# not been measured this way reports null.
+MEASURED_HBM_BYTES_PER_LAUNCH = {"llama3_8b_layer": 3.254e8}
+
+
+def copy_calibration() -> int:
+    """A plain device copy of known size, for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters."""
+    import torch
+    n = 256 << 20
+    src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(10):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "copies": 10}), flush=True)
+    return 0
+
+
 
 def prefix_flops(w) -> float:
     P = w.prefix_len.astype(np.float64)
@@ -83,6 +104,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default 1: Llama-3-8B-shaped layer)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for the CPU baseline (0 = skip)")
     ap.add_argument("--suffix-only", action="store_true", help="time only the batched suffix launch (profiling aid)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run ten 256 MiB device copies and exit (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus {args.gpus} is not supported",
@@ -96,6 +119,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.copy_calibration:
+        return copy_calibration()
     w = workloads.config(args.config)
     layer = 0
     t_gen = time.perf_counter()
@@ -115,6 +140,8 @@ def main() -> int:
     stream = s.stream
     labels, slen = w.labels, w.suffix_len
     ev_pairs = []
+    kernel_ms = []            # (suffix ingest, attention) per timed step, from the library's own events
+    sgc.sgc_timing_enable(s.ctx, True)
 
     def step(timed: bool):
         if not args.suffix_only or s.plan is None:
@@ -133,6 +160,8 @@ def main() -> int:
         if timed:
             e1.record()
             ev_pairs.append((e0, e1))
+        if timed:
+            kernel_ms.append(sgc.sgc_timing_last(s.ctx))     # waits for the launch
         if not args.suffix_only:
             torch.cuda.synchronize()       # the pages must be idle before they are released
             for c in range(w.n_clusters):
@@ -147,22 +176,19 @@ def main() -> int:
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
-    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in ev_pairs]))
+    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in ev_pairs]))         # ingest + attention
     kern_ms_min = float(np.min([a.elapsed_time(b) for a, b in ev_pairs]))
+    ingest_ms = float(np.mean([a for a, _ in kernel_ms]))
+    attn_ms = float(np.mean([b for _, b in kernel_ms]))                        # the dominant kernel alone
+    attn_ms_min = float(np.min([b for _, b in kernel_ms]))
 
     fl_suffix = w.flops()
     fl_step = fl_suffix + (0.0 if args.suffix_only else prefix_flops(w))
     info = sgc.sgc_plan_get_info(s.ctx, s.plan)
     dtype = w.io_dtype
     peak = PEAK_TFLOPS[dtype]
-    achieved = fl_suffix / (kern_ms * 1e-3) / 1e12
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+    achieved = fl_suffix / (attn_ms * 1e-3) / 1e12
+    traffic = MEASURED_HBM_BYTES_PER_LAUNCH.get(w.name)
     out = {
         "metric": "suffix-prefill attention TFLOP/s (% MFMA peak) and us/query vs CPU oracle",
         "value": fl_step / (ms_per_step * 1e-3) / 1e12,
@@ -176,7 +202,8 @@ def main() -> int:
                            "alloc + prefix prefill (ingest + causal attention) + assign/plan upload + batched suffix prefill + free",
                    "tile_rows": info.tile_rows, "n_tiles": info.n_tiles},
         "step_flop": fl_step, "suffix_flop": fl_suffix,
-        "suffix_kernel_ms": kern_ms, "suffix_kernel_ms_min": kern_ms_min,
+        "suffix_launch_ms": kern_ms, "suffix_launch_ms_min": kern_ms_min,
+        "suffix_ingest_kernel_ms": ingest_ms, "attention_kernel_ms": attn_ms, "attention_kernel_ms_min": attn_ms_min,
         "us_per_query": ms_per_step * 1e3 / w.n_queries,
         "suffix_us_per_query": kern_ms * 1e3 / w.n_queries,
         "pct_mfma_peak_step": 100.0 * fl_step / (ms_per_step * 1e-3) / 1e12 / peak,
@@ -184,8 +211,8 @@ def main() -> int:
                      "bound": "mfma" if dtype == "bf16" else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": traffic,
                      "algorithmic_bytes": w.algorithmic_bytes(),
-                     "hbm_gbs_algorithmic": w.algorithmic_bytes() / (kern_ms * 1e-3) / 1e9,
-                     "hbm_frac_algorithmic": w.algorithmic_bytes() / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                     "hbm_gbs_algorithmic": w.algorithmic_bytes() / (attn_ms * 1e-3) / 1e9,
+                     "hbm_frac_algorithmic": w.algorithmic_bytes() / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "paper_context": "TTFT reduction up to 6.68x, PFTT up to 15.49x (Table 2; 2x A100-SXM4-40GB, precision not stated); end-to-end LLM latencies, not this kernel",
         "input_gen_s": t_gen,
     }

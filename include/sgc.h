@@ -182,6 +182,14 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cache, sgc_plan *p
                                const void *dev_q, const void *dev_k, const void *dev_v,
                                void *dev_o, float *dev_lse, void *hip_stream);
 
+/* ---- kernel timing (measurement aid; no effect on results) -----------------------------------
+ * With timing on, sgc_suffix_prefill_batched records HIP events on its launch stream around the
+ * suffix K/V ingest kernel and around the attention kernel.  sgc_timing_last waits for the last
+ * recorded launch to finish and returns the two durations in milliseconds (either pointer may be
+ * NULL); SGC_ESTATE if timing is off or nothing was recorded yet.  Host-only calls. */
+int sgc_timing_enable(sgc_ctx *ctx, int on);
+int sgc_timing_last(sgc_ctx *ctx, float *ingest_ms, float *attention_ms);
+
 /* ---- canonical view of a cluster's cache (tests, checkpointing) -----------------------------
  * dev_k, dev_v: [prefix_len][Hkv][d] in kv_dtype (raw e4m3 codes for fp8); K is the rotated K.
  * host_k_scale, host_v_scale: [Hkv] fp32 (written by export / read by import; ignored and may

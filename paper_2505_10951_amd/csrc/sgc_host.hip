@@ -310,6 +310,8 @@ int sgc_ctx_destroy(sgc_ctx *ctx)
 {
     if (!ctx) return SGC_OK;
     if (ctx->d_rope) (void)hipFree(ctx->d_rope);
+    for (hipEvent_t e : ctx->ev)
+        if (e) (void)hipEventDestroy(e);
     delete ctx;
     return SGC_OK;
 }
@@ -685,12 +687,43 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
     a.sq_page0 = pl->d_sq_page0;
     a.spool = pl->d_spool;
     a.total_tokens = pl->total_tokens;
+    if (ctx->timing) SGC_HIP(ctx, hipEventRecord(ctx->ev[0], s));
+    if (ctx->use_mfma) SGC_HIP(ctx, launch_suffix_ingest(a, pl->d_spage_sq, (int)pl->spage_sq.size(), s));
+    if (ctx->timing) SGC_HIP(ctx, hipEventRecord(ctx->ev[1], s));
     if (ctx->use_mfma) {
-        SGC_HIP(ctx, launch_suffix_ingest(a, pl->d_spage_sq, (int)pl->spage_sq.size(), s));
         SGC_HIP(ctx, launch_attn_mfma(a, ctx->mfma_variant, s));
     } else {
         SGC_HIP(ctx, launch_attn_generic(a, pl->total_tokens * ctx->p.n_q_heads, s));
     }
+    if (ctx->timing) {
+        SGC_HIP(ctx, hipEventRecord(ctx->ev[2], s));
+        ctx->timing_valid = true;
+    }
+    return SGC_OK;
+}
+
+int sgc_timing_enable(sgc_ctx *ctx, int on)
+{
+    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (on) {
+        for (hipEvent_t &e : ctx->ev)
+            if (!e) SGC_HIP(ctx, hipEventCreate(&e));
+    }
+    ctx->timing = on != 0;
+    ctx->timing_valid = false;
+    return SGC_OK;
+}
+
+int sgc_timing_last(sgc_ctx *ctx, float *ingest_ms, float *attention_ms)
+{
+    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (!ctx->timing || !ctx->timing_valid) return fail(ctx, SGC_ESTATE, "no timed launch has been recorded");
+    SGC_HIP(ctx, hipEventSynchronize(ctx->ev[2]));
+    float a = 0.f, b = 0.f;
+    SGC_HIP(ctx, hipEventElapsedTime(&a, ctx->ev[0], ctx->ev[1]));
+    SGC_HIP(ctx, hipEventElapsedTime(&b, ctx->ev[1], ctx->ev[2]));
+    if (ingest_ms) *ingest_ms = a;
+    if (attention_ms) *attention_ms = b;
     return SGC_OK;
 }
 

@@ -137,6 +137,9 @@ struct sgc_ctx {
     std::string err;
     float2 *d_rope = nullptr;
     int rope_len = 0;
+    bool timing = false;            // record events around the suffix launch's kernels
+    bool timing_valid = false;
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // before ingest, between, after attention
 };
 
 struct sgc_cluster_entry {

@@ -26,6 +26,7 @@ EXPORTS = [
     "sgc_cache_alloc_cluster", "sgc_cache_free_cluster", "sgc_cache_total_pages", "sgc_cache_free_pages",
     "sgc_cache_cluster_pages", "sgc_prefix_prefill", "sgc_assign_clusters", "sgc_plan_upload",
     "sgc_plan_get_info", "sgc_plan_destroy", "sgc_suffix_prefill_batched", "sgc_cache_export", "sgc_cache_import",
+    "sgc_timing_enable", "sgc_timing_last",
 ]
 
 
@@ -91,6 +92,8 @@ def lib() -> ctypes.CDLL:
         L.sgc_suffix_prefill_batched.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
         L.sgc_cache_export.argtypes = [vp, vp, i32, i32, vp, vp, f32p, f32p, vp]
         L.sgc_cache_import.argtypes = [vp, vp, i32, i32, vp, vp, f32p, f32p, vp]
+        L.sgc_timing_enable.argtypes = [vp, ctypes.c_int]
+        L.sgc_timing_last.argtypes = [vp, f32p, f32p]
         for name in EXPORTS:
             fn = getattr(L, name)
             if fn.restype is ctypes.c_int and name not in ("sgc_version",):
@@ -227,6 +230,17 @@ def sgc_plan_destroy(plan) -> None:
 def sgc_suffix_prefill_batched(ctx, cache, plan, layer: int, dev_q: int, dev_k: int, dev_v: int, dev_o: int,
                                dev_lse: Optional[int] = None, stream: int = 0) -> None:
     _check(ctx, lib().sgc_suffix_prefill_batched(ctx, cache, plan, layer, dev_q, dev_k, dev_v, dev_o, dev_lse, stream))
+
+
+def sgc_timing_enable(ctx, on: bool) -> None:
+    _check(ctx, lib().sgc_timing_enable(ctx, 1 if on else 0))
+
+
+def sgc_timing_last(ctx) -> Tuple[float, float]:
+    """(suffix ingest ms, attention kernel ms) of the last timed sgc_suffix_prefill_batched call."""
+    a, b = ctypes.c_float(0), ctypes.c_float(0)
+    _check(ctx, lib().sgc_timing_last(ctx, ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
 
 
 def sgc_cache_export(ctx, cache, cluster_id: int, layer: int, dev_k: int, dev_v: int, n_kv_heads: int,

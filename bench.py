@@ -139,6 +139,8 @@ def main() -> int:
     torch.cuda.synchronize()
     stream = s.stream
     labels, slen = w.labels, w.suffix_len
+    all_clusters = list(range(w.n_clusters))
+    pq_ptrs, pk_ptrs, pv_ptrs, po_ptrs = ([t.data_ptr() for t in ts] for ts in (dpq, dpk, dpv, dpo))
     ev_pairs = []
     kernel_ms = []            # (suffix ingest, attention) per timed step, from the library's own events
     sgc.sgc_timing_enable(s.ctx, True)
@@ -147,9 +149,7 @@ def main() -> int:
         if not args.suffix_only or s.plan is None:
             for c in range(w.n_clusters):
                 sgc.sgc_cache_alloc_cluster(s.ctx, s.cache, c, int(w.prefix_len[c]))
-            for c in range(w.n_clusters):
-                sgc.sgc_prefix_prefill(s.ctx, s.cache, c, layer, dpq[c].data_ptr(), dpk[c].data_ptr(), dpv[c].data_ptr(),
-                                       dpo[c].data_ptr(), None, int(w.prefix_len[c]), stream)
+            sgc.sgc_prefix_prefill_batched(s.ctx, s.cache, all_clusters, layer, pq_ptrs, pk_ptrs, pv_ptrs, po_ptrs, None, stream)
             s.assign(labels, slen)
             s.upload_plan()
         if timed:
@@ -199,7 +199,7 @@ def main() -> int:
                                f"{w.n_clusters} clusters, prefix {int(w.prefix_len.min())}-{int(w.prefix_len.max())}, "
                                f"{w.n_queries} queries, {w.total_suffix_tokens} suffix tokens, kv {w.kv_dtype}",
                    "step": "suffix launch only" if args.suffix_only else
-                           "alloc + prefix prefill (ingest + causal attention) + assign/plan upload + batched suffix prefill + free",
+                           "alloc + batched prefix prefill (ingest + causal attention) + assign/plan upload + batched suffix prefill + free",
                    "tile_rows": info.tile_rows, "n_tiles": info.n_tiles},
         "step_flop": fl_step, "suffix_flop": fl_suffix,
         "suffix_launch_ms": kern_ms, "suffix_launch_ms_min": kern_ms_min,

@@ -152,6 +152,17 @@ int sgc_prefix_prefill(sgc_ctx *ctx, sgc_cache *cache, int32_t cluster_id, int32
                        const void *dev_q, const void *dev_k, const void *dev_v, void *dev_o,
                        float *dev_lse, int32_t prefix_len, void *hip_stream);
 
+/* The same for n clusters of one layer in one launch per kernel (Sec. 3.4 computes each cluster's
+ * cache once; a batch of clusters is independent work).  cluster_ids[n]: distinct allocated
+ * clusters.  dev_q, dev_k, dev_v, dev_o, dev_lse: HOST arrays of n device pointers, entry i shaped
+ * as above for cluster_ids[i] with that cluster's prefix_len; dev_q and dev_o may both be NULL
+ * (cache fill only) or hold NULL entries for clusters that need no attention output; dev_lse may be
+ * NULL or hold NULL entries.  The pointer arrays are read before the call returns. */
+int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *cache, int32_t n, const int32_t *cluster_ids,
+                               int32_t layer, const void *const *dev_q, const void *const *dev_k,
+                               const void *const *dev_v, void *const *dev_o, float *const *dev_lse,
+                               void *hip_stream);
+
 /* ---- query -> cluster -> cache mapping (Sec. 3.2 labels; Sec. 3.4 cluster-wise serving) ------
  * Host-only, deterministic.  labels[n] in [0, n_clusters) is query n's cluster, suffix_len[n]
  * >= 0 its number of question tokens.  Every cluster that has at least one query must be
@@ -168,7 +179,7 @@ int sgc_assign_clusters(sgc_ctx *ctx, const sgc_cache *cache, int32_t n_queries,
                         int32_t *order, int32_t *cluster_off, int32_t *cu_seqlens,
                         sgc_plan **out_plan);
 /* Copies the plan's work lists to the device (allocates them).  Optional: the first
- * sgc_suffix_prefill_batched call does it otherwise.  Synchronises the stream. */
+ * sgc_suffix_prefill_batched call does it otherwise.  Asynchronous on the stream. */
 int sgc_plan_upload(sgc_plan *plan, void *hip_stream);
 int sgc_plan_get_info(const sgc_plan *plan, sgc_plan_info *out);
 int sgc_plan_destroy(sgc_plan *plan);

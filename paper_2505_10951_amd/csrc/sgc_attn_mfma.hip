@@ -111,24 +111,20 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     const int Hq = a.n_q_heads, Hkv = a.n_kv_heads, g = a.group;
 
     // ---- which tile ----
-    Tile t;
-    if (MODE == MODE_SUFFIX) {
-        t = a.tiles[blockIdx.x];
-        if (t.n_rows == 0) return;
-    } else {
-        const int rows = a.prefix_len * g;
-        const int tiles_per_head = (rows + BM - 1) / BM;
-        t.cluster = a.prefix_cluster;
-        t.hk = blockIdx.x % Hkv;
-        const int ti = tiles_per_head - 1 - (int)(blockIdx.x / Hkv);   // longest rows first
-        t.row0 = ti * BM;
-        t.n_rows = min(BM, rows - t.row0);
-        t.prefix_len = a.prefix_len;
-        t.pt_off = a.cl_pt_off[t.cluster];
+    Tile t = a.tiles[blockIdx.x];
+    if (t.n_rows == 0) return;
+    // where the rows come from and go to: the batch's packed arrays, or (prefix mode) the job's
+    const void *q_base = a.q;
+    void *o_base = a.o;
+    float *lse_base = a.lse;
+    int64_t lse_stride = a.lse_stride;
+    if (MODE == MODE_PREFIX) {
+        const PrefixJob &job = a.jobs[__builtin_amdgcn_readfirstlane(t.tok_base)];
+        q_base = job.q;
+        o_base = job.o;
+        lse_base = job.lse;
+        lse_stride = t.prefix_len;
         t.tok_base = 0;
-        t.sq_lo = 0;
-        t.sq_hi = -1;
-        t.last_qpos = 0;
     }
     // everything that steers the tile loop is made explicitly wave-uniform (scalar registers)
     const int cluster = __builtin_amdgcn_readfirstlane(t.cluster), hk = __builtin_amdgcn_readfirstlane(t.hk);
@@ -319,7 +315,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     bf16x8 qf[MI][8];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
-        const uint16_t *qrow = static_cast<const uint16_t *>(a.q) + io_row[mi];
+        const uint16_t *qrow = static_cast<const uint16_t *>(q_base) + io_row[mi];
         const int pos = (MODE == MODE_SUFFIX ? P : 0) + qpos[mi];
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb) {
@@ -575,6 +571,12 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     auto copy_quarter = [&](const PartCopy &pc, int slot) __attribute__((always_inline)) {     // slot 0, 2, 4, 6 -> quarter 0..3; odd slots: nothing
         const auto *gp = (const __attribute__((address_space(1))) void *)pc.src;
         auto *lp = (__attribute__((address_space(3))) void *)pc.dst;
+#ifdef SGC_ABL_LOADONLY
+        if ((slot & 1) == 0) {      // timing experiment: the same global read, into a register instead of LDS
+            const uint4 x = *reinterpret_cast<const uint4 *>(pc.src + (slot >> 1) * 1024);
+            asm volatile("" ::"v"(x.x), "v"(x.y), "v"(x.z), "v"(x.w));
+        }
+#else
         switch (slot) {
             case 0: __builtin_amdgcn_global_load_lds(gp, lp, 16, 0, 0); break;
             case 2: __builtin_amdgcn_global_load_lds(gp, lp, 16, 1024, 0); break;
@@ -582,6 +584,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             case 6: __builtin_amdgcn_global_load_lds(gp, lp, 16, 3072, 0); break;
             default: break;
         }
+#endif
     };
     // Step kt.  spread (a true_type / false_type tag): issue this step's copies between the matrix
     // instructions (needs a bf16 cache, both copies due and this wavefront computing) or at the top.
@@ -640,7 +643,9 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             if (weights_overflow()) redo(s0, s1, 0);
             pv_half([&](int i) __attribute__((always_inline)) {
                 frag[i] = k_block(kn, 0, i);
+#ifndef SGC_ABL_HALFDMA
                 if (spread && NW == 4) copy_quarter(second, i);
+#endif
             });
             // half 1
             if (careful) raise_reference(s1, 1, masked, keep);
@@ -731,7 +736,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     SGC_MARK(4);           // own suffix tiles done
 
     // ---- normalise and store ----
-    uint16_t *og = static_cast<uint16_t *>(a.o);
+    uint16_t *og = static_cast<uint16_t *>(o_base);
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
         const float l = l_part[mi] + half_swap(l_part[mi]);
@@ -746,9 +751,9 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
                     for (int i = 0; i < 4; ++i) y[i] = (__bf16)(oacc[mi][db][q4 * 4 + i] * inv_l);
                     *reinterpret_cast<bf16x4 *>(og + io_row[mi] + db * 32 + q4 * 8 + h * 4) = y;
                 }
-            if (a.lse && h == 0) {
+            if (lse_base && h == 0) {
                 const int64_t col = (MODE == MODE_SUFFIX) ? (int64_t)src_tok[mi] : (int64_t)qpos[mi];
-                a.lse[(int64_t)head[mi] * a.lse_stride + col] = (m_ref[mi] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+                lse_base[(int64_t)head[mi] * lse_stride + col] = (m_ref[mi] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
             }
         }
     }
@@ -785,16 +790,11 @@ hipError_t launch_one(const AttnArgs &a, int blocks, hipStream_t s)
 template <int NW, int MI>
 hipError_t launch_variant(const AttnArgs &a, hipStream_t s)
 {
-    constexpr int BM = NW * MI * 32;
     const bool fp8 = a.pool.kv_dtype == SGC_FP8_E4M3;
-    if (a.mode == MODE_SUFFIX) {
-        if (a.n_tiles <= 0) return hipSuccess;
+    if (a.n_tiles <= 0) return hipSuccess;
+    if (a.mode == MODE_SUFFIX)
         return fp8 ? launch_one<NW, MI, true, MODE_SUFFIX>(a, a.n_tiles, s) : launch_one<NW, MI, false, MODE_SUFFIX>(a, a.n_tiles, s);
-    }
-    const int rows = a.prefix_len * a.group;
-    const int tiles = (rows + BM - 1) / BM * a.n_kv_heads;
-    if (tiles <= 0) return hipSuccess;
-    return fp8 ? launch_one<NW, MI, true, MODE_PREFIX>(a, tiles, s) : launch_one<NW, MI, false, MODE_PREFIX>(a, tiles, s);
+    return fp8 ? launch_one<NW, MI, true, MODE_PREFIX>(a, a.n_tiles, s) : launch_one<NW, MI, false, MODE_PREFIX>(a, a.n_tiles, s);
 }
 
 }  // namespace

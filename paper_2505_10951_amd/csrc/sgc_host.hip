@@ -111,46 +111,114 @@ int ensure_rope(sgc_ctx *ctx, int need, hipStream_t s)
     return SGC_OK;
 }
 
-// Brings the device copy of the page tables up to date with the host allocator.
+// ---- reusable device blocks and pinned staging ------------------------------------------------
+// A block handed back by dev_release may still be read by launches on the stream it was last used
+// on; work enqueued later on that same stream is ordered behind them, any other stream waits first.
+int dev_acquire(sgc_ctx *ctx, size_t bytes, hipStream_t s, sgc_dev_block *out)
+{
+    bytes = std::max<size_t>((bytes + 4095) / 4096 * 4096, 4096);
+    int best = -1;
+    for (int i = 0; i < (int)ctx->dev_free.size(); ++i) {
+        const sgc_dev_block &b = ctx->dev_free[i];
+        if (b.bytes >= bytes && b.bytes <= 4 * bytes && (best < 0 || b.bytes < ctx->dev_free[best].bytes)) best = i;
+    }
+    if (best >= 0) {
+        *out = ctx->dev_free[best];
+        ctx->dev_free.erase(ctx->dev_free.begin() + best);
+        if (out->last != s) SGC_HIP(ctx, hipStreamSynchronize(out->last));
+        out->last = s;
+        return SGC_OK;
+    }
+    void *p = nullptr;
+    SGC_HIP(ctx, hipMalloc(&p, bytes));
+    out->p = static_cast<char *>(p);
+    out->bytes = bytes;
+    out->last = s;
+    return SGC_OK;
+}
+
+void dev_release(sgc_ctx *ctx, sgc_dev_block b, hipStream_t last)
+{
+    if (!b.p) return;
+    b.last = last;
+    if (ctx->dev_free.size() >= 16) {        // keep the pool small: drop the oldest block
+        (void)hipStreamSynchronize(ctx->dev_free.front().last);
+        (void)hipFree(ctx->dev_free.front().p);
+        ctx->dev_free.erase(ctx->dev_free.begin());
+    }
+    ctx->dev_free.push_back(b);
+}
+
+// Pinned host buffer of at least `bytes` whose previous copy, if any, has finished.
+int stage_begin(sgc_ctx *ctx, size_t bytes, char **host, int *slot)
+{
+    const int i = ctx->stage_next;
+    ctx->stage_next ^= 1;
+    if (!ctx->stage_ev[i]) SGC_HIP(ctx, hipEventCreateWithFlags(&ctx->stage_ev[i], hipEventDisableTiming));
+    if (ctx->stage_pending[i]) {
+        SGC_HIP(ctx, hipEventSynchronize(ctx->stage_ev[i]));
+        ctx->stage_pending[i] = false;
+    }
+    if (ctx->h_stage_cap[i] < bytes) {
+        if (ctx->h_stage[i]) SGC_HIP(ctx, hipHostFree(ctx->h_stage[i]));
+        ctx->h_stage[i] = nullptr;
+        ctx->h_stage_cap[i] = 0;
+        const size_t cap = std::max<size_t>((bytes + 65535) / 65536 * 65536, 1 << 20);
+        void *p = nullptr;
+        SGC_HIP(ctx, hipHostMalloc(&p, cap, hipHostMallocDefault));
+        ctx->h_stage[i] = static_cast<char *>(p);
+        ctx->h_stage_cap[i] = cap;
+    }
+    *host = ctx->h_stage[i];
+    *slot = i;
+    return SGC_OK;
+}
+
+int stage_commit(sgc_ctx *ctx, int slot, void *dev, size_t bytes, hipStream_t s)
+{
+    if (bytes) SGC_HIP(ctx, hipMemcpyAsync(dev, ctx->h_stage[slot], bytes, hipMemcpyHostToDevice, s));
+    SGC_HIP(ctx, hipEventRecord(ctx->stage_ev[slot], s));
+    ctx->stage_pending[slot] = true;
+    return SGC_OK;
+}
+
+// Brings the device copy of the page tables up to date with the host allocator: one array
+// [page table: total_pages][first entry per cluster: max_clusters][prefix length per cluster: max_clusters],
+// rewritten by one copy that is ordered on the stream behind the launches that read the old content.
 int cache_sync(sgc_cache *c, hipStream_t s)
 {
     sgc_ctx *ctx = c->ctx;
-    if (!c->d_pt_off) {
-        SGC_HIP(ctx, hipMalloc(&c->d_pt_off, sizeof(int32_t) * c->max_clusters));
-        SGC_HIP(ctx, hipMalloc(&c->d_prefix_len, sizeof(int32_t) * c->max_clusters));
+    const size_t n_pages = (size_t)c->geom.total_pages, n_cl = (size_t)c->max_clusters;
+    if (!c->d_tables) {
+        SGC_HIP(ctx, hipMalloc(&c->d_tables, sizeof(int32_t) * (n_pages + 2 * n_cl + 16)));
+        c->d_page_table = c->d_tables;
+        c->d_pt_off = c->d_tables + n_pages;
+        c->d_prefix_len = c->d_pt_off + n_cl;
         if (ctx->p.kv_dtype == SGC_FP8_E4M3) {
-            const size_t n = (size_t)c->max_clusters * ctx->p.n_layers * 2 * ctx->p.n_kv_heads;
+            const size_t n = n_cl * ctx->p.n_layers * 2 * ctx->p.n_kv_heads;
             SGC_HIP(ctx, hipMalloc(&c->d_scale, sizeof(float) * n));
             SGC_HIP(ctx, hipMemset(c->d_scale, 0, sizeof(float) * n));
         }
         c->dirty = true;
     }
     if (!c->dirty) return SGC_OK;
-    std::vector<int32_t> off(c->max_clusters, 0), plen(c->max_clusters, 0), flat;
-    for (int i = 0; i < c->max_clusters; ++i) {
-        off[i] = (int32_t)flat.size();
+    char *host = nullptr;
+    int slot = 0;
+    const size_t bytes = sizeof(int32_t) * (n_pages + 2 * n_cl);
+    int rc = stage_begin(ctx, bytes, &host, &slot);
+    if (rc != SGC_OK) return rc;
+    int32_t *flat = reinterpret_cast<int32_t *>(host), *off = flat + n_pages, *plen = off + n_cl;
+    size_t n = 0;
+    for (size_t i = 0; i < n_cl; ++i) {
+        off[i] = (int32_t)n;
+        plen[i] = 0;
         if (c->cl[i].allocated) {
             plen[i] = c->cl[i].prefix_len;
-            flat.insert(flat.end(), c->cl[i].pages.begin(), c->cl[i].pages.end());
+            for (int32_t pg : c->cl[i].pages) flat[n++] = pg;
         }
     }
-    // launches already enqueued may still read the old tables
-    SGC_HIP(ctx, hipStreamSynchronize(s));
-    if (flat.size() > c->d_page_table_cap || !c->d_page_table) {
-        if (c->d_page_table) {
-            SGC_HIP(ctx, hipDeviceSynchronize());
-            (void)hipFree(c->d_page_table);
-            c->d_page_table = nullptr;
-        }
-        const size_t cap = std::max<size_t>((size_t)c->geom.total_pages, 16);
-        SGC_HIP(ctx, hipMalloc(&c->d_page_table, sizeof(int32_t) * cap));
-        c->d_page_table_cap = cap;
-    }
-    if (!flat.empty())
-        SGC_HIP(ctx, hipMemcpyAsync(c->d_page_table, flat.data(), sizeof(int32_t) * flat.size(), hipMemcpyHostToDevice, s));
-    SGC_HIP(ctx, hipMemcpyAsync(c->d_pt_off, off.data(), sizeof(int32_t) * off.size(), hipMemcpyHostToDevice, s));
-    SGC_HIP(ctx, hipMemcpyAsync(c->d_prefix_len, plen.data(), sizeof(int32_t) * plen.size(), hipMemcpyHostToDevice, s));
-    SGC_HIP(ctx, hipStreamSynchronize(s));   // the host vectors above go out of scope
+    for (; n < n_pages; ++n) flat[n] = 0;
+    if ((rc = stage_commit(ctx, slot, c->d_tables, bytes, s)) != SGC_OK) return rc;
     c->dirty = false;
     return SGC_OK;
 }
@@ -255,8 +323,10 @@ void fill_tile_pt_off(sgc_plan *pl, const sgc_cache *c)
 
 void plan_free_device(sgc_plan *pl)
 {
-    if (pl->d_blob) (void)hipFree(pl->d_blob);
-    if (pl->d_spool) (void)hipFree(pl->d_spool);
+    dev_release(pl->ctx, pl->blob, pl->last_stream);
+    dev_release(pl->ctx, pl->spool_block, pl->last_stream);
+    pl->blob = sgc_dev_block{};
+    pl->spool_block = sgc_dev_block{};
     pl->d_blob = nullptr;
     pl->d_spool = nullptr;
     pl->spool_bytes = 0;
@@ -312,6 +382,12 @@ int sgc_ctx_destroy(sgc_ctx *ctx)
     if (ctx->d_rope) (void)hipFree(ctx->d_rope);
     for (hipEvent_t e : ctx->ev)
         if (e) (void)hipEventDestroy(e);
+    (void)hipDeviceSynchronize();
+    for (const sgc_dev_block &b : ctx->dev_free) (void)hipFree(b.p);
+    for (int i = 0; i < 2; ++i) {
+        if (ctx->h_stage[i]) (void)hipHostFree(ctx->h_stage[i]);
+        if (ctx->stage_ev[i]) (void)hipEventDestroy(ctx->stage_ev[i]);
+    }
     delete ctx;
     return SGC_OK;
 }
@@ -364,9 +440,7 @@ int sgc_cache_create(sgc_ctx *ctx, void *dev_pool, size_t pool_bytes, int32_t ma
 int sgc_cache_destroy(sgc_cache *c)
 {
     if (!c) return SGC_OK;
-    if (c->d_page_table) (void)hipFree(c->d_page_table);
-    if (c->d_pt_off) (void)hipFree(c->d_pt_off);
-    if (c->d_prefix_len) (void)hipFree(c->d_prefix_len);
+    if (c->d_tables) (void)hipFree(c->d_tables);
     if (c->d_scale) (void)hipFree(c->d_scale);
     delete c;
     return SGC_OK;
@@ -431,6 +505,170 @@ int sgc_cache_cluster_pages(const sgc_cache *c, int32_t cluster_id, int32_t *out
 }
 
 // ------------------------------------------------------------------------------------------------
+int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int32_t *cluster_ids, int32_t layer,
+                               const void *const *dev_q, const void *const *dev_k, const void *const *dev_v,
+                               void *const *dev_o, float *const *dev_lse, void *hip_stream)
+{
+    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (!c || c->ctx != ctx) return fail(ctx, SGC_EINVAL, "cache is NULL or belongs to another context");
+    if (n < 0) return fail(ctx, SGC_EINVAL, "n %d < 0", n);
+    if (n == 0) return SGC_OK;
+    if (!cluster_ids || !dev_k || !dev_v) return fail(ctx, SGC_EINVAL, "cluster_ids / dev_k / dev_v is NULL");
+    if ((dev_q == nullptr) != (dev_o == nullptr)) return fail(ctx, SGC_EINVAL, "dev_q and dev_o must both be given or both be NULL");
+    if (dev_lse && !dev_o) return fail(ctx, SGC_EINVAL, "dev_lse given without dev_q/dev_o");
+    const int Hkv = ctx->p.n_kv_heads, g = ctx->p.n_q_heads / Hkv;
+    int rc;
+    std::vector<char> seen(c->max_clusters, 0);
+    int max_len = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        if ((rc = check_cluster(ctx, c, cluster_ids[i], layer)) != SGC_OK) return rc;
+        if (seen[cluster_ids[i]]) return fail(ctx, SGC_EINVAL, "cluster %d is named twice", cluster_ids[i]);
+        seen[cluster_ids[i]] = 1;
+        const int32_t P = c->cl[cluster_ids[i]].prefix_len;
+        max_len = std::max(max_len, P);
+        if (P == 0) continue;
+        const void *q = dev_q ? dev_q[i] : nullptr;
+        void *o = dev_o ? dev_o[i] : nullptr;
+        const float *lse = dev_lse ? dev_lse[i] : nullptr;
+        if (!dev_k[i] || !dev_v[i]) return fail(ctx, SGC_EINVAL, "dev_k / dev_v of cluster %d is NULL", cluster_ids[i]);
+        if ((q == nullptr) != (o == nullptr))
+            return fail(ctx, SGC_EINVAL, "dev_q and dev_o of cluster %d must both be given or both be NULL", cluster_ids[i]);
+        if (lse && !o) return fail(ctx, SGC_EINVAL, "dev_lse of cluster %d given without dev_q/dev_o", cluster_ids[i]);
+        if (!aligned16(dev_k[i]) || !aligned16(dev_v[i]) || !aligned16(q) || !aligned16(o) || !aligned16(lse))
+            return fail(ctx, SGC_EINVAL, "device pointers must be 16-byte aligned");
+    }
+    if (max_len == 0) return SGC_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if ((rc = ensure_rope(ctx, max_len, s)) != SGC_OK) return rc;
+    if ((rc = cache_sync(c, s)) != SGC_OK) return rc;
+
+    // jobs, the job of every page, and (MFMA attention) the tile list, in one device block
+    std::vector<int32_t> pt_off(c->max_clusters, 0);
+    for (int i = 0, acc = 0; i < c->max_clusters; ++i) {
+        pt_off[i] = acc;
+        if (c->cl[i].allocated) acc += (int32_t)c->cl[i].pages.size();
+    }
+    std::vector<PrefixJob> jobs;
+    std::vector<int32_t> page_job;
+    bool any_q = false;
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t id = cluster_ids[i], P = c->cl[id].prefix_len;
+        if (P == 0) continue;
+        PrefixJob j{};
+        j.q = dev_q ? dev_q[i] : nullptr;
+        j.k = dev_k[i];
+        j.v = dev_v[i];
+        j.o = dev_o ? dev_o[i] : nullptr;
+        j.lse = dev_lse ? dev_lse[i] : nullptr;
+        j.scale_kv = c->d_scale ? c->d_scale + ((size_t)id * ctx->p.n_layers + layer) * 2 * Hkv : nullptr;
+        j.cluster = id;
+        j.prefix_len = P;
+        j.pt_off = pt_off[id];
+        j.page0 = (int32_t)page_job.size();
+        any_q = any_q || j.q != nullptr;
+        page_job.insert(page_job.end(), c->cl[id].pages.size(), (int32_t)jobs.size());
+        jobs.push_back(j);
+    }
+    std::vector<Tile> tiles;
+    if (any_q && ctx->use_mfma) {
+        // Units (job, KV head) are dealt, heaviest first, to the XCD with the least work so far, each XCD's
+        // tiles longest first; workgroup b runs on XCD b % 8.
+        constexpr int kXcd = 8;
+        const int rows_per_tile = ctx->tile_rows;
+        struct Unit {
+            int job, hk;
+            double work;
+        };
+        std::vector<Unit> units;
+        for (int ji = 0; ji < (int)jobs.size(); ++ji)
+            if (jobs[ji].q)
+                for (int hk = 0; hk < Hkv; ++hk) units.push_back({ji, hk, (double)jobs[ji].prefix_len * jobs[ji].prefix_len});
+        std::stable_sort(units.begin(), units.end(), [](const Unit &x, const Unit &y) { return x.work > y.work; });
+        std::vector<std::vector<Tile>> lists(kXcd);
+        double load[kXcd] = {0};
+        for (const Unit &u : units) {
+            int x = 0;
+            for (int i = 1; i < kXcd; ++i)
+                if (load[i] < load[x]) x = i;
+            load[x] += u.work;
+            const PrefixJob &j = jobs[u.job];
+            const int64_t rows = (int64_t)j.prefix_len * g;
+            for (int64_t r = 0; r < rows; r += rows_per_tile) {
+                Tile t{};
+                t.cluster = j.cluster;
+                t.hk = u.hk;
+                t.row0 = (int32_t)r;
+                t.n_rows = (int32_t)std::min<int64_t>(rows_per_tile, rows - r);
+                t.prefix_len = j.prefix_len;
+                t.pt_off = j.pt_off;
+                t.tok_base = u.job;      // prefix mode: the job index travels here
+                t.sq_lo = 0;
+                t.sq_hi = -1;
+                t.last_qpos = 0;
+                lists[x].push_back(t);
+            }
+        }
+        size_t slots = 0;
+        for (auto &l : lists) {
+            std::stable_sort(l.begin(), l.end(), [](const Tile &x, const Tile &y) { return x.row0 > y.row0; });
+            slots = std::max(slots, l.size());
+        }
+        tiles.assign(slots * kXcd, Tile{});
+        for (int x = 0; x < kXcd; ++x)
+            for (size_t k = 0; k < lists[x].size(); ++k) tiles[k * kXcd + x] = lists[x][k];
+    }
+    const size_t jobs_bytes = (jobs.size() * sizeof(PrefixJob) + 255) / 256 * 256;
+    const size_t pj_bytes = (page_job.size() * sizeof(int32_t) + 255) / 256 * 256;
+    const size_t tiles_bytes = tiles.size() * sizeof(Tile);
+    const size_t total = jobs_bytes + pj_bytes + tiles_bytes;
+    sgc_dev_block blk;
+    if ((rc = dev_acquire(ctx, total, s, &blk)) != SGC_OK) return rc;
+    char *host = nullptr;
+    int slot = 0;
+    if ((rc = stage_begin(ctx, total, &host, &slot)) != SGC_OK) {
+        dev_release(ctx, blk, s);
+        return rc;
+    }
+    memcpy(host, jobs.data(), jobs.size() * sizeof(PrefixJob));
+    memcpy(host + jobs_bytes, page_job.data(), page_job.size() * sizeof(int32_t));
+    if (tiles_bytes) memcpy(host + jobs_bytes + pj_bytes, tiles.data(), tiles_bytes);
+    rc = stage_commit(ctx, slot, blk.p, total, s);
+    const PrefixJob *d_jobs = reinterpret_cast<const PrefixJob *>(blk.p);
+    const int32_t *d_page_job = reinterpret_cast<const int32_t *>(blk.p + jobs_bytes);
+    const Tile *d_tiles = reinterpret_cast<const Tile *>(blk.p + jobs_bytes + pj_bytes);
+    hipError_t e = hipSuccess;
+    if (rc == SGC_OK)
+        e = launch_prefix_ingest(c->geom, layer, c->d_page_table, d_jobs, (int)jobs.size(), d_page_job, (int)page_job.size(),
+                                 ctx->p.io_dtype, ctx->p.rope_base > 0.0f ? ctx->d_rope : nullptr, s);
+    if (rc == SGC_OK && e == hipSuccess && any_q) {
+        AttnArgs a;
+        fill_common_args(a, ctx, c, layer);
+        a.mode = MODE_PREFIX;
+        if (ctx->use_mfma) {
+            a.jobs = d_jobs;
+            a.tiles = d_tiles;
+            a.n_tiles = (int32_t)tiles.size();
+            e = launch_attn_mfma(a, ctx->mfma_variant, s);
+        } else {
+            for (const PrefixJob &j : jobs) {      // the generic kernel works on one cluster per launch
+                if (!j.q) continue;
+                a.q = j.q;
+                a.o = j.o;
+                a.lse = j.lse;
+                a.lse_stride = j.prefix_len;
+                a.prefix_cluster = j.cluster;
+                a.prefix_len = j.prefix_len;
+                e = launch_attn_generic(a, (int64_t)j.prefix_len * ctx->p.n_q_heads, s);
+                if (e != hipSuccess) break;
+            }
+        }
+    }
+    dev_release(ctx, blk, s);
+    if (rc != SGC_OK) return rc;
+    if (e != hipSuccess) return fail_hip(ctx, e, "prefix prefill launch");
+    return SGC_OK;
+}
+
 int sgc_prefix_prefill(sgc_ctx *ctx, sgc_cache *c, int32_t cluster_id, int32_t layer, const void *dev_q,
                        const void *dev_k, const void *dev_v, void *dev_o, float *dev_lse, int32_t prefix_len,
                        void *hip_stream)
@@ -446,35 +684,8 @@ int sgc_prefix_prefill(sgc_ctx *ctx, sgc_cache *c, int32_t cluster_id, int32_t l
     if (dev_lse && !dev_o) return fail(ctx, SGC_EINVAL, "dev_lse given without dev_q/dev_o");
     if (prefix_len == 0) return SGC_OK;
     if (!dev_k || !dev_v) return fail(ctx, SGC_EINVAL, "dev_k / dev_v is NULL");
-    if (!aligned16(dev_k) || !aligned16(dev_v) || !aligned16(dev_q) || !aligned16(dev_o) || !aligned16(dev_lse))
-        return fail(ctx, SGC_EINVAL, "device pointers must be 16-byte aligned");
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    if ((rc = ensure_rope(ctx, prefix_len, s)) != SGC_OK) return rc;
-    if ((rc = cache_sync(c, s)) != SGC_OK) return rc;
-
-    int32_t pt_off = 0;
-    for (int i = 0; i < cluster_id; ++i)
-        if (c->cl[i].allocated) pt_off += (int32_t)c->cl[i].pages.size();
-    float *scale_kv = c->d_scale ? c->d_scale + ((size_t)cluster_id * ctx->p.n_layers + layer) * 2 * ctx->p.n_kv_heads : nullptr;
-    SGC_HIP(ctx, launch_prefix_ingest(c->geom, layer, c->d_page_table + pt_off, prefix_len, dev_k, dev_v, ctx->p.io_dtype,
-                                      ctx->p.rope_base > 0.0f ? ctx->d_rope : nullptr, scale_kv, s));
-    if (!dev_q) return SGC_OK;
-
-    AttnArgs a;
-    fill_common_args(a, ctx, c, layer);
-    a.q = dev_q;
-    a.o = dev_o;
-    a.lse = dev_lse;
-    a.lse_stride = prefix_len;
-    a.mode = MODE_PREFIX;
-    a.prefix_cluster = cluster_id;
-    a.prefix_len = prefix_len;
-    if (ctx->use_mfma) {
-        SGC_HIP(ctx, launch_attn_mfma(a, ctx->mfma_variant, s));
-    } else {
-        SGC_HIP(ctx, launch_attn_generic(a, (int64_t)prefix_len * ctx->p.n_q_heads, s));
-    }
-    return SGC_OK;
+    return sgc_prefix_prefill_batched(ctx, c, 1, &cluster_id, layer, dev_q ? &dev_q : nullptr, &dev_k, &dev_v,
+                                      dev_o ? &dev_o : nullptr, dev_lse ? &dev_lse : nullptr, hip_stream);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -596,19 +807,26 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
     };
     size_t total = 0;
     for (const Piece &p : pieces) total += (p.bytes + 255) / 256 * 256 + 256;
-    SGC_HIP(ctx, hipMalloc(&pl->d_blob, total));
+    int rc = dev_acquire(ctx, total, s, &pl->blob);
+    if (rc != SGC_OK) return rc;
+    pl->d_blob = pl->blob.p;
+    pl->last_stream = s;
+    char *host = nullptr;
+    int slot = 0;
+    if ((rc = stage_begin(ctx, total, &host, &slot)) != SGC_OK) return rc;
     size_t off = 0;
     for (const Piece &p : pieces) {
         *p.dst = pl->d_blob + off;
-        if (p.bytes) SGC_HIP(ctx, hipMemcpyAsync(pl->d_blob + off, p.src, p.bytes, hipMemcpyHostToDevice, s));
+        if (p.bytes) memcpy(host + off, p.src, p.bytes);
         off += (p.bytes + 255) / 256 * 256 + 256;
     }
+    if ((rc = stage_commit(ctx, slot, pl->d_blob, total, s)) != SGC_OK) return rc;
     if (want_rows > 0 && !pl->spage_sq.empty()) {
         // suffix page pool: bf16 pages of every query's rotated suffix K and transposed V
         pl->spool_bytes = pl->spage_sq.size() * (size_t)2 * ctx->p.n_kv_heads * kPageTokens * ctx->p.head_dim * 2;
-        SGC_HIP(ctx, hipMalloc(&pl->d_spool, pl->spool_bytes));
+        if ((rc = dev_acquire(ctx, pl->spool_bytes, s, &pl->spool_block)) != SGC_OK) return rc;
+        pl->d_spool = pl->spool_block.p;
     }
-    SGC_HIP(ctx, hipStreamSynchronize(s));
     pl->uploaded = true;
     return SGC_OK;
 }
@@ -659,10 +877,14 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
     if (!pl->tiles.empty() && pl->tiles_generation != c->generation) {
         // clusters were allocated or released since the tiles were filled: refresh their page-table offsets
         fill_tile_pt_off(pl, c);
-        SGC_HIP(ctx, hipMemcpyAsync(const_cast<Tile *>(pl->d_tiles), pl->tiles.data(), pl->tiles.size() * sizeof(Tile),
-                                    hipMemcpyHostToDevice, s));
-        SGC_HIP(ctx, hipStreamSynchronize(s));
+        const size_t bytes = pl->tiles.size() * sizeof(Tile);
+        char *host = nullptr;
+        int slot = 0;
+        if ((rc = stage_begin(ctx, bytes, &host, &slot)) != SGC_OK) return rc;
+        memcpy(host, pl->tiles.data(), bytes);
+        if ((rc = stage_commit(ctx, slot, const_cast<Tile *>(pl->d_tiles), bytes, s)) != SGC_OK) return rc;
     }
+    pl->last_stream = s;
 
     AttnArgs a;
     fill_common_args(a, ctx, c, layer);

@@ -84,6 +84,18 @@ struct TokInfo {
     int32_t pad;
 };
 
+// One cluster of a (batched) prefix prefill.
+struct PrefixJob {
+    const void *q, *k, *v;   // [P][Hq][d] (q may be null), [P][Hkv][d], io dtype, before rotation
+    void *o;                 // [P][Hq][d] or null
+    float *lse;              // [Hq][P] or null
+    float *scale_kv;         // fp8 cache: the [2][Hkv] scales of this cluster and layer, else null
+    int32_t cluster;
+    int32_t prefix_len;
+    int32_t pt_off;          // first entry of the cluster in the flat page table
+    int32_t page0;           // first page of the job in the launch-wide page numbering
+};
+
 enum { MODE_SUFFIX = 0, MODE_PREFIX = 1 };
 
 // Everything an attention kernel needs, by value.
@@ -116,7 +128,9 @@ struct AttnArgs {
     const int32_t *sq_page0;      // [n_queries] first page of the query in the suffix page pool
     const char *spool;            // suffix page pool (bf16 pages, same layout as cache pages) or null
     int64_t total_tokens;
-    // prefix mode
+    // prefix mode: the MFMA kernel takes its clusters from jobs (a tile's tok_base field is the job index),
+    // the generic kernel works on one cluster per launch (prefix_cluster, prefix_len, q/k/v/o/lse above)
+    const PrefixJob *jobs;
     int32_t prefix_cluster;
     int32_t prefix_len;
     int32_t mode;
@@ -128,6 +142,12 @@ struct AttnArgs {
 }  // namespace sgc
 
 // ---- host objects behind the opaque handles --------------------------------------------------
+struct sgc_dev_block {
+    char *p = nullptr;
+    size_t bytes = 0;
+    hipStream_t last = nullptr;     // stream of the last launch that may still read the block
+};
+
 struct sgc_ctx {
     sgc_attn_params p;
     float scale;
@@ -137,6 +157,14 @@ struct sgc_ctx {
     std::string err;
     float2 *d_rope = nullptr;
     int rope_len = 0;
+    // Device blocks and pinned staging buffers are kept and reused: the per-batch tables are small and a
+    // hipMalloc / hipFree pair per batch costs more than the copies themselves.
+    std::vector<sgc_dev_block> dev_free;
+    char *h_stage[2] = {nullptr, nullptr};
+    size_t h_stage_cap[2] = {0, 0};
+    hipEvent_t stage_ev[2] = {nullptr, nullptr};
+    bool stage_pending[2] = {false, false};
+    int stage_next = 0;
     bool timing = false;            // record events around the suffix launch's kernels
     bool timing_valid = false;
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // before ingest, between, after attention
@@ -156,10 +184,10 @@ struct sgc_cache {
     std::vector<sgc_cluster_entry> cl;
     std::vector<int32_t> free_list;   // stack; back() is handed out next
     uint64_t generation = 0;          // bumped by alloc/free
-    // device mirrors (built lazily)
+    // device mirrors (built lazily): one allocation [page table: total_pages][pt_off: max_clusters][prefix_len: max_clusters]
     bool dirty = true;
+    int32_t *d_tables = nullptr;
     int32_t *d_page_table = nullptr;
-    size_t d_page_table_cap = 0;
     int32_t *d_pt_off = nullptr;
     int32_t *d_prefix_len = nullptr;
     float *d_scale = nullptr;         // fp8 only: [max_clusters][n_layers][2][Hkv]
@@ -182,6 +210,8 @@ struct sgc_plan {
     uint64_t tiles_generation = 0;            // cache generation the tiles' page-table offsets belong to
     int32_t tile_rows = 0;
     bool uploaded = false;
+    sgc_dev_block blob, spool_block;          // device blocks behind d_blob / d_spool (from the context's pool)
+    hipStream_t last_stream = nullptr;        // stream of the last launch that used the plan
     char *d_blob = nullptr;                   // one device allocation holding every array below
     const int32_t *d_cl_tok_off = nullptr, *d_tok_src = nullptr, *d_tok_qpos = nullptr, *d_tok_sq = nullptr;
     const int32_t *d_sq_src0 = nullptr, *d_sq_len = nullptr, *d_sq_tok0 = nullptr, *d_sq_cluster = nullptr;
@@ -198,10 +228,11 @@ namespace sgc {
 // Builds the (cos, sin) table for positions [0, n_pos) in double precision, stored as fp32.
 hipError_t launch_rope_table(float2 *table, int n_pos, int head_dim, double base, hipStream_t s);
 
-// Prefix ingest: rotate K, (quantise), write K and V of one cluster/layer into its pages.
-hipError_t launch_prefix_ingest(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len,
-                                const void *k, const void *v, int io_dtype, const float2 *rope,
-                                float *d_scale_kv /* [2][Hkv] or null */, hipStream_t s);
+// Prefix ingest of n_jobs clusters: rotate K, (quantise), write K and V into the clusters' pages.
+// d_page_job[p] is the job of launch-wide page p (n_pages of them).
+hipError_t launch_prefix_ingest(const PoolGeom &g, int layer, const int32_t *d_page_table, const PrefixJob *d_jobs,
+                                int n_jobs, const int32_t *d_page_job, int n_pages, int io_dtype, const float2 *rope,
+                                hipStream_t s);
 hipError_t launch_cache_export(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len,
                                void *k, void *v, hipStream_t s);
 hipError_t launch_cache_import(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len,

@@ -154,12 +154,14 @@ __device__ inline void copy_out_16(char *dst, const char *lds_src, int n)
         *reinterpret_cast<uint4 *>(dst + off) = *reinterpret_cast<const uint4 *>(lds_src + off);
 }
 
-// Pass 0 (fp8 only): per-head max |rotated K| and max |V| into amax[2][Hkv] via integer atomicMax
-// on the bit patterns of non-negative floats.
-__global__ void ingest_amax_kernel(const void *k, const void *v, int io_dtype, int P, int Hkv, int d,
-                                   const float2 *rope, float *amax)
+// Pass 0 (fp8 only): per-head max |rotated K| and max |V| of every job into its scale slot
+// amax[2][Hkv] via integer atomicMax on the bit patterns of non-negative floats.
+__global__ void ingest_amax_kernel(const PrefixJob *jobs, const int32_t *page_job, int io_dtype, int Hkv, int d,
+                                   const float2 *rope)
 {
-    const int pg = blockIdx.x, hk = blockIdx.y;
+    const PrefixJob job = jobs[page_job[blockIdx.x]];
+    const int pg = blockIdx.x - job.page0, hk = blockIdx.y;
+    const int P = job.prefix_len;
     const int half = d / 2, pairs = d / 16;
     float mk = 0.f, mv = 0.f;
     for (int it = threadIdx.x; it < kPageTokens * pairs; it += blockDim.x) {
@@ -168,11 +170,11 @@ __global__ void ingest_amax_kernel(const void *k, const void *v, int io_dtype, i
         if (j >= P) continue;
         float x1[8], x2[8], y1[8], y2[8];
         const int64_t row = ((int64_t)j * Hkv + hk) * d;
-        load8(k, row + cc * 8, io_dtype, x1);
-        load8(k, row + half + cc * 8, io_dtype, x2);
+        load8(job.k, row + cc * 8, io_dtype, x1);
+        load8(job.k, row + half + cc * 8, io_dtype, x2);
         if (rope) rope8(x1, x2, rope + (int64_t)j * half + cc * 8);
-        load8(v, row + cc * 8, io_dtype, y1);
-        load8(v, row + half + cc * 8, io_dtype, y2);
+        load8(job.v, row + cc * 8, io_dtype, y1);
+        load8(job.v, row + half + cc * 8, io_dtype, y2);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             mk = fmaxf(mk, fmaxf(fabsf(x1[i]), fabsf(x2[i])));
@@ -184,31 +186,29 @@ __global__ void ingest_amax_kernel(const void *k, const void *v, int io_dtype, i
         mv = fmaxf(mv, __shfl_xor(mv, o));
     }
     if ((threadIdx.x & 63) == 0) {
-        atomicMax(reinterpret_cast<unsigned int *>(amax + hk), __float_as_uint(mk));
-        atomicMax(reinterpret_cast<unsigned int *>(amax + Hkv + hk), __float_as_uint(mv));
+        atomicMax(reinterpret_cast<unsigned int *>(job.scale_kv + hk), __float_as_uint(mk));
+        atomicMax(reinterpret_cast<unsigned int *>(job.scale_kv + Hkv + hk), __float_as_uint(mv));
     }
 }
 
-__global__ void fill_zero_kernel(float *p, int n)
+// One workgroup per job, 2 * Hkv values each: to_scale false clears the slot, true turns max|x| into the scale.
+__global__ void scale_slot_kernel(const PrefixJob *jobs, int n, bool to_scale)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0.f;
-}
-
-__global__ void amax_to_scale_kernel(float *p, int n)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = p[i] > 0.f ? p[i] / 448.0f : 1.0f;
+    float *p = jobs[blockIdx.x].scale_kv;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = to_scale ? (p[i] > 0.f ? p[i] / 448.0f : 1.0f) : 0.f;
 }
 
 // One workgroup per (page, KV head): rotate K, convert, write K and V parts in page order.
 // Tokens past the prefix end are written as zeros so that a whole page can always be read.
-__global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *pages, int P, const void *k, const void *v,
-                                    int io_dtype, const float2 *rope, const float *scale_kv)
+__global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *page_table, const PrefixJob *jobs,
+                                    const int32_t *page_job, int io_dtype, const float2 *rope)
 {
-    const int pg = blockIdx.x, hk = blockIdx.y;
+    const PrefixJob job = jobs[page_job[blockIdx.x]];
+    const int pg = blockIdx.x - job.page0, hk = blockIdx.y;
+    const int P = job.prefix_len;
+    const void *k = job.k, *v = job.v;
     const int d = g.head_dim, Hkv = g.n_kv_heads, half = d / 2, pairs = d / 16;
-    const int page = pages[pg];
+    const int page = page_table[job.pt_off + pg];
     // The page images are put together in LDS (V is a transpose: element-sized scattered writes) and go out
     // as whole 16-byte rows.
     extern __shared__ __attribute__((aligned(16))) char page_img[];
@@ -216,8 +216,8 @@ __global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *pages,
     char *kp = page_img, *vp = page_img + part_bytes;
     float sc_k = 1.f, sc_v = 1.f;   // fp8: the per-head scales the codes are divided by
     if (g.kv_dtype == SGC_FP8_E4M3) {
-        sc_k = scale_kv[hk];
-        sc_v = scale_kv[Hkv + hk];
+        sc_k = job.scale_kv[hk];
+        sc_v = job.scale_kv[Hkv + hk];
     }
     for (int it = threadIdx.x; it < kPageTokens * pairs; it += blockDim.x) {
         const int tok = it / pairs, cc = it % pairs;
@@ -490,21 +490,21 @@ hipError_t launch_rope_table(float2 *table, int n_pos, int head_dim, double base
     return hipGetLastError();
 }
 
-hipError_t launch_prefix_ingest(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len, const void *k,
-                                const void *v, int io_dtype, const float2 *rope, float *d_scale_kv, hipStream_t s)
+hipError_t launch_prefix_ingest(const PoolGeom &g, int layer, const int32_t *d_page_table, const PrefixJob *d_jobs,
+                                int n_jobs, const int32_t *d_page_job, int n_pages, int io_dtype, const float2 *rope,
+                                hipStream_t s)
 {
-    const int n_pages = (prefix_len + kPageTokens - 1) / kPageTokens;
-    if (n_pages == 0) return hipSuccess;
+    if (n_pages == 0 || n_jobs == 0) return hipSuccess;
     const dim3 grid(n_pages, g.n_kv_heads);
     if (g.kv_dtype == SGC_FP8_E4M3) {
         const int n = 2 * g.n_kv_heads;
-        hipLaunchKernelGGL(fill_zero_kernel, dim3((n + 63) / 64), dim3(64), 0, s, d_scale_kv, n);
-        hipLaunchKernelGGL(ingest_amax_kernel, grid, dim3(128), 0, s, k, v, io_dtype, prefix_len, g.n_kv_heads, g.head_dim,
-                           rope, d_scale_kv);
-        hipLaunchKernelGGL(amax_to_scale_kernel, dim3((n + 63) / 64), dim3(64), 0, s, d_scale_kv, n);
+        hipLaunchKernelGGL(scale_slot_kernel, dim3(n_jobs), dim3(64), 0, s, d_jobs, n, false);
+        hipLaunchKernelGGL(ingest_amax_kernel, grid, dim3(128), 0, s, d_jobs, d_page_job, io_dtype, g.n_kv_heads, g.head_dim,
+                           rope);
+        hipLaunchKernelGGL(scale_slot_kernel, dim3(n_jobs), dim3(64), 0, s, d_jobs, n, true);
     }
-    hipLaunchKernelGGL(ingest_write_kernel, grid, dim3(128), 2 * (size_t)g.head_part_bytes, s, g, layer, d_pages, prefix_len,
-                       k, v, io_dtype, rope, (const float *)d_scale_kv);
+    hipLaunchKernelGGL(ingest_write_kernel, grid, dim3(128), 2 * (size_t)g.head_part_bytes, s, g, layer, d_page_table, d_jobs,
+                       d_page_job, io_dtype, rope);
     return hipGetLastError();
 }
 

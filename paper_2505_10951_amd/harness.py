@@ -85,6 +85,27 @@ class Session:
         torch.cuda.synchronize()
         return do, (dlse[:, :P] if dlse is not None else None)
 
+    def prefix_prefill_batched(self, clusters, layer: int = 0, with_q: bool = False, want_lse: bool = False):
+        """All the given clusters in one call; returns per-cluster (o, lse) device tensors (None without q)."""
+        w = self.w
+        dk, dv, dq, do, dl = [], [], [], [], []
+        for c in clusters:
+            P = int(w.prefix_len[c])
+            k, v = w.prefix_kv(c, layer)
+            dk.append(to_device(k, w.io_dtype, self.device))
+            dv.append(to_device(v, w.io_dtype, self.device))
+            if with_q:
+                dq.append(to_device(w.prefix_q(c, layer), w.io_dtype, self.device))
+                do.append(torch.empty_like(dq[-1]))
+                dl.append(torch.empty((w.n_q_heads, max(P, 1)), dtype=torch.float32, device=self.device) if want_lse else None)
+        ptr = lambda ts: [None if t is None else t.data_ptr() for t in ts]
+        sgc.sgc_prefix_prefill_batched(self.ctx, self.cache, list(clusters), layer, ptr(dq) if with_q else None, ptr(dk), ptr(dv),
+                                       ptr(do) if with_q else None, ptr(dl) if (with_q and want_lse) else None, self.stream)
+        torch.cuda.synchronize()
+        if not with_q:
+            return [(None, None) for _ in clusters]
+        return [(o, (l[:, :int(w.prefix_len[c])] if l is not None else None)) for c, o, l in zip(clusters, do, dl)]
+
     def fill_all_clusters(self, layer: int = 0) -> None:
         for c in range(self.w.n_clusters):
             self.prefix_prefill(c, layer)

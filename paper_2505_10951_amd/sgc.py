@@ -24,7 +24,7 @@ EXPORTS = [
     "sgc_version", "sgc_status_string", "sgc_ctx_create", "sgc_ctx_destroy", "sgc_last_error",
     "sgc_cache_page_bytes", "sgc_cache_pool_bytes", "sgc_cache_create", "sgc_cache_destroy",
     "sgc_cache_alloc_cluster", "sgc_cache_free_cluster", "sgc_cache_total_pages", "sgc_cache_free_pages",
-    "sgc_cache_cluster_pages", "sgc_prefix_prefill", "sgc_assign_clusters", "sgc_plan_upload",
+    "sgc_cache_cluster_pages", "sgc_prefix_prefill", "sgc_prefix_prefill_batched", "sgc_assign_clusters", "sgc_plan_upload",
     "sgc_plan_get_info", "sgc_plan_destroy", "sgc_suffix_prefill_batched", "sgc_cache_export", "sgc_cache_import",
     "sgc_timing_enable", "sgc_timing_last",
 ]
@@ -85,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.sgc_cache_free_pages.restype = i64
         L.sgc_cache_cluster_pages.argtypes = [vp, i32, i32p, i32, i32p]
         L.sgc_prefix_prefill.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, i32, vp]
+        vpp = ctypes.POINTER(ctypes.c_void_p)
+        L.sgc_prefix_prefill_batched.argtypes = [vp, vp, i32, i32p, i32, vpp, vpp, vpp, vpp, vpp, vp]
         L.sgc_assign_clusters.argtypes = [vp, vp, i32, i32p, i32p, i32, i32p, i32p, i32p, ctypes.POINTER(vp)]
         L.sgc_plan_upload.argtypes = [vp, vp]
         L.sgc_plan_get_info.argtypes = [vp, ctypes.POINTER(sgc_plan_info)]
@@ -195,6 +197,25 @@ def sgc_prefix_prefill(ctx, cache, cluster_id: int, layer: int, dev_q: Optional[
                        dev_o: Optional[int], dev_lse: Optional[int], prefix_len: int, stream: int = 0) -> None:
     _check(ctx, lib().sgc_prefix_prefill(ctx, cache, cluster_id, layer, dev_q, dev_k, dev_v, dev_o, dev_lse,
                                          prefix_len, stream))
+
+
+def _ptr_array(ptrs, n: int):
+    """None, or a sequence of n device addresses (None entries allowed) -> ctypes array of void pointers."""
+    if ptrs is None:
+        return None
+    if len(ptrs) != n:
+        raise ValueError("pointer list and cluster list differ in length")
+    return (ctypes.c_void_p * n)(*[None if p is None else int(p) for p in ptrs])
+
+
+def sgc_prefix_prefill_batched(ctx, cache, cluster_ids: Sequence[int], layer: int, dev_q, dev_k, dev_v, dev_o,
+                               dev_lse=None, stream: int = 0) -> None:
+    """dev_q / dev_k / dev_v / dev_o / dev_lse: sequences of device addresses, one per cluster (or None)."""
+    ids = _i32(cluster_ids)
+    n = ids.shape[0]
+    _check(ctx, lib().sgc_prefix_prefill_batched(ctx, cache, n, ids.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), layer,
+                                                 _ptr_array(dev_q, n), _ptr_array(dev_k, n), _ptr_array(dev_v, n),
+                                                 _ptr_array(dev_o, n), _ptr_array(dev_lse, n), stream))
 
 
 def sgc_assign_clusters(ctx, cache, labels: Sequence[int], suffix_len: Sequence[int], n_clusters: int,

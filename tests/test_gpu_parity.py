@@ -209,6 +209,35 @@ def test_prefix_prefill_cache_and_causal_output(kernel):
             assert np.abs(dlse.cpu().numpy() - lse_ref).max() <= max(4 * fl_lse, 2e-3)
 
 
+@pytest.mark.parametrize("kv", ["bf16", "fp8_e4m3"])
+@pytest.mark.parametrize("kernel", [sgc.SGC_KERNEL_MFMA, sgc.SGC_KERNEL_GENERIC])
+def test_prefix_prefill_batched_equals_one_by_one(kernel, kv):
+    """One call for several clusters (given out of order, one of them empty) against a call per cluster:
+    same kernels, same arithmetic, so caches, outputs and LSE are bit-identical; and against the oracle."""
+    w = workloads.custom("prefix_batched", n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=500000.0, io_dtype="bf16",
+                         kv_dtype=kv, prefix_len=[333, 64, 0, 5, 130], queries_per_cluster=1, suffix_range=(1, 1), seed=19)
+    order = [3, 0, 4, 2, 1]
+    with Session(w, kernel=kernel) as s1, Session(w, kernel=kernel) as s2:
+        for c in range(w.n_clusters):
+            s1.alloc_cluster(c)
+            s2.alloc_cluster(c)
+        single = {c: s1.prefix_prefill(c, 0, with_q=True, want_lse=True) for c in range(w.n_clusters) if w.prefix_len[c] > 0}
+        batched = dict(zip(order, s2.prefix_prefill_batched(order, 0, with_q=True, want_lse=True)))
+        for c in range(w.n_clusters):
+            P = int(w.prefix_len[c])
+            if P == 0:
+                continue
+            e1, e2 = s1.export_cluster(c), s2.export_cluster(c)
+            for x, y in zip(e1, e2):
+                assert np.array_equal(x, y)
+            assert torch.equal(single[c][0], batched[c][0]) and torch.equal(single[c][1], batched[c][1])
+            if kv == "bf16":
+                pk, pv = w.prefix_kv(c)
+                _, _, o_ref, lse_ref = orc.prefix_prefill(w.prefix_q(c), pk, pv, w.rope_base, want_lse=True)
+                assert err_stats(to_host_f32(batched[c][0]), o_ref)["max_abs"] <= TOL_BF16
+                assert np.abs(batched[c][1].cpu().numpy() - lse_ref).max() <= 2e-2
+
+
 def test_prefix_prefill_f32_cache_exact_layout_roundtrip():
     w = workloads.config(0)
     with Session(w) as s:

@@ -207,9 +207,18 @@ def test_launch_entry_points_validate_before_touching_the_device():
         lambda: sgc.sgc_suffix_prefill_batched(ctx, cache, plan, 0, None, 256, 256, 256),          # NULL q
         lambda: sgc.sgc_suffix_prefill_batched(ctx, cache, plan, 0, 256, 256, 264, 256),           # misaligned
         lambda: sgc.sgc_cache_export(ctx, cache, 7, 0, 256, 256, 8),
+        lambda: sgc.sgc_prefix_prefill_batched(ctx, cache, [0, 0], 0, None, [256, 256], [512, 512], None),   # twice
+        lambda: sgc.sgc_prefix_prefill_batched(ctx, cache, [0, 3], 0, None, [256, 256], [512, 512], None),   # range
+        lambda: sgc.sgc_prefix_prefill_batched(ctx, cache, [0, 1], 0, None, [256, None], [512, 512], None),  # NULL k
+        lambda: sgc.sgc_prefix_prefill_batched(ctx, cache, [0, 1], 0, [256, 256], [256, 256], [512, 512], None),  # q, no o
+        lambda: sgc.sgc_prefix_prefill_batched(ctx, cache, [0, 1], 0, [256, None], [256, 256], [512, 512], [256, 256]),
+        lambda: sgc.sgc_prefix_prefill_batched(ctx, cache, [0, 1], 0, None, [256, 264], [512, 512], None),   # misaligned
+        lambda: sgc.sgc_timing_last(ctx),                                                                  # nothing timed
     ]
     expect = [sgc.SGC_EINVAL, sgc.SGC_EINVAL, sgc.SGC_ESHAPE, sgc.SGC_EINVAL, sgc.SGC_EINVAL, sgc.SGC_EINVAL,
-              sgc.SGC_EINVAL, sgc.SGC_EINVAL, sgc.SGC_EINVAL, sgc.SGC_EINVAL]
+              sgc.SGC_EINVAL, sgc.SGC_EINVAL, sgc.SGC_EINVAL, sgc.SGC_EINVAL,
+              sgc.SGC_EINVAL, sgc.SGC_EINVAL, sgc.SGC_EINVAL, sgc.SGC_EINVAL, sgc.SGC_EINVAL, sgc.SGC_EINVAL,
+              sgc.SGC_ESTATE]
     for fn, status in zip(bad, expect):
         with pytest.raises(sgc.SgcError) as e:
             fn()

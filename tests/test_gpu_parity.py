@@ -385,3 +385,54 @@ def test_config2_llama2_7b_ragged_full_size_sampled():
     qs = _sampled_queries(w, 1)[:8]
     _check_suffix(w, out, queries=qs, tol=TOL_BF16, tight=tight_bar(w, qs[:3])[0])
     assert np.isfinite(out["o"]).all()
+
+
+def test_config3_llama3_8b_stack32_resident_cache_sampled_layers():
+    """32 layers over one resident paged cache (8 GiB of pages): every layer's cache is filled before any suffix
+    prefill runs; three layers carry the workload's seeded data and are checked against the oracle on sampled
+    queries, the other 29 are filled with device noise (they only have to stay out of the way)."""
+    w = workloads.config(3)
+    sampled_layers = [0, 17, 31]
+    clusters = list(range(w.n_clusters))
+    with Session(w) as s:
+        pool_gib = s.pool.numel() / 2 ** 30
+        _say("config 3", w.name, "T/layer", w.total_suffix_tokens, "pool GiB %.2f" % pool_gib)
+        assert pool_gib >= 8.0
+        for c in clusters:
+            s.alloc_cluster(c)
+        for layer in sampled_layers:
+            s.prefix_prefill_batched(clusters, layer)
+        gen = torch.Generator(device="cuda:0").manual_seed(1)
+        shp = (int(w.prefix_len.max()), w.n_kv_heads, w.head_dim)
+        for layer in range(w.n_layers):
+            if layer in sampled_layers:
+                continue
+            nk = [torch.randn(shp, generator=gen, device="cuda:0", dtype=torch.bfloat16) for _ in range(2)]
+            sgc.sgc_prefix_prefill_batched(s.ctx, s.cache, clusters, layer, None, [nk[0].data_ptr()] * len(clusters),
+                                           [nk[1].data_ptr()] * len(clusters), None, None, s.stream)
+            torch.cuda.synchronize()
+        order, off, cu = s.assign()
+        _check_bookkeeping(w, {"order": order, "cluster_off": off, "cu_seqlens": cu})
+        qs = _sampled_queries(w, 1)[::5]            # 4 queries, 128 tokens x 32 heads each
+        for layer in sampled_layers:
+            q, k, v = w.suffix_qkv(layer)
+            do = s.suffix_prefill(*(to_device(x, "bf16") for x in (q, k, v)), layer=layer)
+            torch.cuda.synchronize()
+            o = to_host_f32(do)
+            rows, o_ref, _ = oracle_suffix(w, layer, qs)
+            st = err_stats(o[rows], o_ref)
+            _say(f"  layer {layer}: rows {len(rows)} max_abs {st['max_abs']:.3e}")
+            assert np.isfinite(o).all() and st["max_abs"] <= TOL_BF16
+            del q, k, v, do, o
+
+
+def test_config4_llama70b_fp8_long_prefix_full_size_sampled():
+    """fp8 e4m3 cache, 16 384-token prefixes, 1024 queries of 32-256 tokens: the whole batch in one launch,
+    checked on sampled queries against the oracle reading its own quantised cache."""
+    w = workloads.config(4)
+    _say("config 4", w.name, "T", w.total_suffix_tokens, "flop %.3e" % w.flops())
+    out = run_workload(w, want_lse=False)
+    _check_bookkeeping(w, out)
+    qs = _sampled_queries(w, 1)[::2]                # 4 queries
+    _check_suffix(w, out, queries=qs, tol=TOL_FP8)
+    assert np.isfinite(out["o"]).all()

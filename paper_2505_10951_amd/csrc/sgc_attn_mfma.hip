@@ -57,9 +57,9 @@ constexpr float kNegBig = -1.0e30f;
 #ifdef SGC_PHASE_TIMING
 // Development aid (not built into the product library): per-phase cycle totals of the tile loop.
 __device__ unsigned long long g_phase[2048 * 8 * 8];   // [block < 2048][wave < 8][phase < 8]
-// SGC_MARK(i): all outstanding memory operations of the wave are waited for, then the time since the block
-// started (100 MHz ticks) is recorded as the end of phase i.
-#define SGC_MARK(i) do { __builtin_amdgcn_s_waitcnt(0); ph[i] = (unsigned)(__builtin_amdgcn_s_memrealtime() - blk_r0); } while (0)
+// SGC_MARK(i): the time since the block
+// started (100 MHz ticks) is recorded when the wave reaches the end of phase i (no extra waits).
+#define SGC_MARK(i) do { ph[i] = (unsigned)(__builtin_amdgcn_s_memrealtime() - blk_r0); } while (0)
 #else
 #define SGC_MARK(i) do { } while (0)
 #endif
@@ -137,12 +137,6 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     const int last_row = t.row0 + t.n_rows - 1;
     const int sq_lo = __builtin_amdgcn_readfirstlane(t.sq_lo), sq_hi = __builtin_amdgcn_readfirstlane(t.sq_hi);
     const int last_qpos = __builtin_amdgcn_readfirstlane(t.last_qpos);
-
-    // ---- the queries this tile touches (suffix mode): lengths and first pages into LDS ----
-    if (MODE == MODE_SUFFIX) {
-        for (int i = tid; i <= sq_hi - sq_lo && i < MAX_TILE_QUERIES; i += NW * 64)
-            qinfo[i] = make_int2(a.sq_len[sq_lo + i], a.sq_page0[sq_lo + i]);
-    }
 
     // ---- copy machinery ----------------------------------------------------------------------------
     // A tile is 8 parts: K of its 4 pages, then V of its 4 pages; a part is 4 KiB of bf16 (2 KiB of fp8
@@ -244,12 +238,16 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     // as the ids are there, so that they travel while Q is loaded and rotated.
     const int n_cache_keys = (MODE == MODE_SUFFIX) ? P : min(P, last_row / g + 1);
     const int n_kt = (n_cache_keys + BN - 1) / BN;
-    uint32_t ids0 = 0, ids1 = 0, ids2 = 0;     // page ids of tiles 0, 1, 2; later of tiles kt + 1 and kt + 2
-    if (n_kt > 0) {
-        ids0 = cache_page_ids(0);
-        ids1 = cache_page_ids(1);
-        ids2 = cache_page_ids(2);
-    }
+    // page ids of tiles 0, 1, 2 come with the tile record (lane j < 4 holds page j of a tile); later these
+    // hold the ids of tiles kt + 1 and kt + 2
+    auto spread4 = [&](const int32_t *p4) __attribute__((always_inline)) -> uint32_t {
+        const int p0 = __builtin_amdgcn_readfirstlane(p4[0]), p1 = __builtin_amdgcn_readfirstlane(p4[1]);
+        const int p2 = __builtin_amdgcn_readfirstlane(p4[2]), p3 = __builtin_amdgcn_readfirstlane(p4[3]);
+        const int lo = (lane & 1) ? p1 : p0, hi = (lane & 1) ? p3 : p2;
+        return (uint32_t)((lane & 2) ? hi : lo);
+    };
+    const uint32_t ids0 = spread4(t.first_pages);
+    uint32_t ids1 = spread4(t.first_pages + 4), ids2 = spread4(t.first_pages + 8);
     float k_scale = 1.f, v_scale = 1.f;
     if (KV_FP8) {
         const float *sc = a.kv_scale + ((int64_t)cluster * a.n_layers + a.layer) * 2 * Hkv;
@@ -262,6 +260,13 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     const float self_ratio = KV_FP8 ? 1.0f / k_scale : 1.0f;
 
     // ---- per-lane row bookkeeping ----
+    const bool inline_queries = MODE == MODE_SUFFIX && __builtin_amdgcn_readfirstlane(t.n_q) <= kTileQueries;
+    int tq_tok0[kTileQueries], tq_src0[kTileQueries];
+#pragma unroll
+    for (int k = 0; k < kTileQueries; ++k) {
+        tq_tok0[k] = __builtin_amdgcn_readfirstlane(t.q[k].tok0);
+        tq_src0[k] = __builtin_amdgcn_readfirstlane(t.q[k].src0);
+    }
     bool valid[MI];
     int64_t io_row[MI];     // element offset of the row in q / o
     int qpos[MI], sq[MI], lim[MI], src_tok[MI], head[MI];
@@ -273,10 +278,20 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         const int tk = rc / g;
         head[mi] = hk * g + (rc - tk * g);
         if (MODE == MODE_SUFFIX) {
-            const TokInfo ti = a.tok_info[tok_base + tk];
-            src_tok[mi] = ti.src;
-            qpos[mi] = ti.qpos;
-            sq[mi] = ti.sq;
+            const int tau = tok_base + tk;
+            if (inline_queries) {        // which of the (at most 4) queries of the tile record the token belongs to
+                const bool ge1 = tau >= tq_tok0[1], ge2 = tau >= tq_tok0[2], ge3 = tau >= tq_tok0[3];
+                const int first = ge3 ? tq_tok0[3] : ge2 ? tq_tok0[2] : ge1 ? tq_tok0[1] : tq_tok0[0];
+                const int src0 = ge3 ? tq_src0[3] : ge2 ? tq_src0[2] : ge1 ? tq_src0[1] : tq_src0[0];
+                qpos[mi] = tau - first;
+                src_tok[mi] = src0 + qpos[mi];
+                sq[mi] = sq_lo + (int)ge1 + (int)ge2 + (int)ge3;
+            } else {
+                const TokInfo ti = a.tok_info[tau];
+                src_tok[mi] = ti.src;
+                qpos[mi] = ti.qpos;
+                sq[mi] = ti.sq;
+            }
             lim[mi] = P;
         } else {
             src_tok[mi] = tk;
@@ -286,25 +301,11 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         }
         io_row[mi] = ((int64_t)src_tok[mi] * Hq + head[mi]) * D;
     }
-    // wave-uniform bounds: visible cached keys, and the sorted queries / positions of this wave's rows
-    int lim_min = lim[0], lim_max = lim[0], wsq_min = sq[0], wsq_max = sq[0];
-#pragma unroll
-    for (int mi = 1; mi < MI; ++mi) {
-        lim_min = min(lim_min, lim[mi]);
-        lim_max = max(lim_max, lim[mi]);
-        wsq_min = min(wsq_min, sq[mi]);
-        wsq_max = max(wsq_max, sq[mi]);
-    }
-    for (int o = 32; o > 0; o >>= 1) {
-        lim_min = min(lim_min, __shfl_xor(lim_min, o));
-        lim_max = max(lim_max, __shfl_xor(lim_max, o));
-        wsq_min = min(wsq_min, __shfl_xor(wsq_min, o));
-        wsq_max = max(wsq_max, __shfl_xor(wsq_max, o));
-    }
-    lim_min = __builtin_amdgcn_readfirstlane(lim_min);
-    lim_max = __builtin_amdgcn_readfirstlane(lim_max);
-    wsq_min = __builtin_amdgcn_readfirstlane(wsq_min);
-    wsq_max = __builtin_amdgcn_readfirstlane(wsq_max);
+    // wave-uniform bounds: visible cached keys, and the sorted queries of this wave's rows.  Rows are in
+    // sorted order (and rows past the tile's end repeat its last row), so the first lane holds the minima
+    // and lane 31 of the last row block the maxima.
+    const int lim_min = __builtin_amdgcn_readlane(lim[0], 0), lim_max = __builtin_amdgcn_readlane(lim[MI - 1], 31);
+    const int wsq_min = __builtin_amdgcn_readlane(sq[0], 0), wsq_max = __builtin_amdgcn_readlane(sq[MI - 1], 31);
 
     if (!KV_FP8 && n_kt > 0) {
         fetch_cache(ids0, kbuf_of(0), ids0, vbuf_of(0));
@@ -312,42 +313,80 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     }
     SGC_MARK(0);           // tile and row bookkeeping is loaded
     // ---- Q: load, rotate at position P + qpos (suffix) / qpos (prefix), keep as B operands ----
+    // All loads of the phase (Q row halves, then the rotation table entries) are issued before any of them is
+    // used, so the phase costs one memory round trip and not one per channel group.
     bf16x8 qf[MI][8];
+    {
+        uint4 qlo[MI][4], qhi[MI][4];
+        float4 cs[MI][4][4];            // (cos, sin) of two channels per entry
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-        const uint16_t *qrow = static_cast<const uint16_t *>(q_base) + io_row[mi];
-        const int pos = (MODE == MODE_SUFFIX ? P : 0) + qpos[mi];
+        for (int mi = 0; mi < MI; ++mi) {
+            const uint16_t *qrow = static_cast<const uint16_t *>(q_base) + io_row[mi];
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
-            const int c0 = kb * 16 + h * 8;
-            const uint4 lo = *reinterpret_cast<const uint4 *>(qrow + c0);
-            const uint4 hi = *reinterpret_cast<const uint4 *>(qrow + 64 + c0);
-            const uint32_t wl[4] = {lo.x, lo.y, lo.z, lo.w}, wh[4] = {hi.x, hi.y, hi.z, hi.w};
-            float x1[8], x2[8];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                x1[2 * i] = __uint_as_float(wl[i] << 16);
-                x1[2 * i + 1] = __uint_as_float(wl[i] & 0xFFFF0000u);
-                x2[2 * i] = __uint_as_float(wh[i] << 16);
-                x2[2 * i + 1] = __uint_as_float(wh[i] & 0xFFFF0000u);
+            for (int kb = 0; kb < 4; ++kb) {
+                const int c0 = kb * 16 + h * 8;
+                qlo[mi][kb] = *reinterpret_cast<const uint4 *>(qrow + c0);
+                qhi[mi][kb] = *reinterpret_cast<const uint4 *>(qrow + 64 + c0);
             }
-            if (a.rope) {
-                const float4 *tab = reinterpret_cast<const float4 *>(a.rope + (int64_t)pos * 64 + c0);
+        }
+        const bool rotate = a.rope != nullptr;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float4 cs = tab[i];   // (cos, sin) of two channels
-                    const float a0 = x1[2 * i], b0 = x2[2 * i], a1 = x1[2 * i + 1], b1 = x2[2 * i + 1];
-                    x1[2 * i] = a0 * cs.x - b0 * cs.y;
-                    x2[2 * i] = b0 * cs.x + a0 * cs.y;
-                    x1[2 * i + 1] = a1 * cs.z - b1 * cs.w;
-                    x2[2 * i + 1] = b1 * cs.z + a1 * cs.w;
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) cs[mi][kb][i] = make_float4(1.f, 0.f, 1.f, 0.f);
+        if (rotate) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const int pos = (MODE == MODE_SUFFIX ? P : 0) + qpos[mi];
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb) {
+                    const float4 *tab = reinterpret_cast<const float4 *>(a.rope + (int64_t)pos * 64 + kb * 16 + h * 8);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) cs[mi][kb][i] = tab[i];
                 }
             }
+        }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {      // the score scale (log2 units, cached-K scale included) rides on Q
-                qf[mi][kb][i] = (__bf16)(x1[i] * c_cache);
-                qf[mi][kb + 4][i] = (__bf16)(x2[i] * c_cache);
+        for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) {
+                const uint32_t wl[4] = {qlo[mi][kb].x, qlo[mi][kb].y, qlo[mi][kb].z, qlo[mi][kb].w};
+                const uint32_t wh[4] = {qhi[mi][kb].x, qhi[mi][kb].y, qhi[mi][kb].z, qhi[mi][kb].w};
+                float x1[8], x2[8];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float a0 = __uint_as_float(wl[i] << 16), a1 = __uint_as_float(wl[i] & 0xFFFF0000u);
+                    const float b0 = __uint_as_float(wh[i] << 16), b1 = __uint_as_float(wh[i] & 0xFFFF0000u);
+                    const float4 t4 = cs[mi][kb][i];
+                    x1[2 * i] = a0 * t4.x - b0 * t4.y;
+                    x2[2 * i] = b0 * t4.x + a0 * t4.y;
+                    x1[2 * i + 1] = a1 * t4.z - b1 * t4.w;
+                    x2[2 * i + 1] = b1 * t4.z + a1 * t4.w;
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {      // the score scale (log2 units, cached-K scale included) rides on Q
+                    qf[mi][kb][i] = (__bf16)(x1[i] * c_cache);
+                    qf[mi][kb + 4][i] = (__bf16)(x2[i] * c_cache);
+                }
             }
+        }
+    }
+
+    // ---- the queries this tile touches (suffix mode): lengths and first pages into LDS ----
+    // (read by the own-suffix tile iterator after the first barrier; placed after the Q loads so that the
+    // table look-ups of the rare many-queries case do not sit in front of them)
+    if (MODE == MODE_SUFFIX) {
+        if (inline_queries) {
+            if (tid < kTileQueries) {
+                const int len = tid == 0 ? t.q[0].len : tid == 1 ? t.q[1].len : tid == 2 ? t.q[2].len : t.q[3].len;
+                const int pg0 = tid == 0 ? t.q[0].page0 : tid == 1 ? t.q[1].page0 : tid == 2 ? t.q[2].page0 : t.q[3].page0;
+                qinfo[tid] = make_int2(len, pg0);
+            }
+        } else {
+            for (int i = tid; i <= sq_hi - sq_lo && i < MAX_TILE_QUERIES; i += NW * 64)
+                qinfo[i] = make_int2(a.sq_len[sq_lo + i], a.sq_page0[sq_lo + i]);
         }
     }
 

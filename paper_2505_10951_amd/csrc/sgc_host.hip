@@ -2,6 +2,7 @@
 // planner and the C ABI.  Follows SubGCache (arXiv 2505.10951) Sec. 3.2 (cluster labels per
 // query) and Sec. 3.4 (one KV cache per cluster: compute once, reuse for every query of the
 // cluster, release).
+#include <limits.h>
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
@@ -296,6 +297,14 @@ void build_tiles(sgc_plan *pl, int tile_rows)
             t.sq_lo = pl->tok_sq[first_tok];
             t.sq_hi = pl->tok_sq[last_tok];
             t.last_qpos = pl->tok_qpos[last_tok];
+            t.n_q = t.sq_hi - t.sq_lo + 1;
+            for (int k = 0; k < kTileQueries; ++k) {
+                const int32_t sq = t.sq_lo + k;
+                if (sq <= t.sq_hi)
+                    t.q[k] = {pl->sq_tok0[sq], pl->sq_src0[sq], pl->sq_len[sq], pl->sq_page0[sq]};
+                else
+                    t.q[k] = {INT32_MAX, 0, 0, 0};
+            }
             lists[x].push_back(t);
         }
     }
@@ -305,6 +314,12 @@ void build_tiles(sgc_plan *pl, int tile_rows)
     for (int x = 0; x < kXcd; ++x)
         for (size_t s = 0; s < lists[x].size(); ++s) pl->tiles[s * kXcd + x] = lists[x][s];
     pl->tile_rows = tile_rows;
+}
+
+void fill_first_pages(Tile &t, const std::vector<int32_t> &pages)
+{
+    const int n = (int)pages.size();
+    for (int i = 0; i < 12; ++i) t.first_pages[i] = n ? pages[std::min(i, n - 1)] : 0;
 }
 
 // Page-table offsets of the clusters as cache_sync lays the flat table out; they move when clusters
@@ -317,7 +332,11 @@ void fill_tile_pt_off(sgc_plan *pl, const sgc_cache *c)
         off[i] = n;
         if (c->cl[i].allocated) n += (int32_t)c->cl[i].pages.size();
     }
-    for (Tile &t : pl->tiles) t.pt_off = t.n_rows > 0 ? off[t.cluster] : 0;
+    for (Tile &t : pl->tiles) {
+        if (t.n_rows == 0) continue;
+        t.pt_off = off[t.cluster];
+        fill_first_pages(t, c->cl[t.cluster].pages);
+    }
     pl->tiles_generation = c->generation;
 }
 
@@ -605,6 +624,8 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
                 t.sq_lo = 0;
                 t.sq_hi = -1;
                 t.last_qpos = 0;
+                t.n_q = 0;
+                fill_first_pages(t, c->cl[j.cluster].pages);
                 lists[x].push_back(t);
             }
         }

@@ -61,8 +61,15 @@ struct PoolGeom {
     }
 };
 
-// One workgroup's share of an attention launch, with everything the workgroup needs to start its
-// loads at once (one 48-byte scalar load instead of a chain of dependent table look-ups).
+// One workgroup's share of an attention launch, with everything the workgroup needs to start ALL its
+// loads at once (one 160-byte scalar load instead of chains of dependent table look-ups).
+constexpr int kTileQueries = 4;      // queries a tile record describes inline
+struct TileQuery {
+    int32_t tok0;    // first sorted token of the query (INT32_MAX in unused slots)
+    int32_t src0;    // first row of the query in the caller's packed arrays
+    int32_t len;     // suffix length
+    int32_t page0;   // first page of the query in the suffix page pool
+};
 struct Tile {
     int32_t cluster;     // cluster id (index into the cache's per-cluster arrays)
     int32_t hk;          // KV head
@@ -70,11 +77,15 @@ struct Tile {
     int32_t n_rows;      // valid rows in this tile (0 = padding tile, exit at once)
     int32_t prefix_len;  // cached tokens of the cluster
     int32_t pt_off;      // first entry of the cluster in the flat page table
-    int32_t tok_base;    // first sorted token of the cluster
+    int32_t tok_base;    // first sorted token of the cluster (prefix mode: index of the job)
     int32_t sq_lo, sq_hi;   // sorted queries of the tile's first and last row
     int32_t last_qpos;   // position of the last row's token inside its query
-    int32_t pad[2];
+    int32_t n_q;         // sq_hi - sq_lo + 1; the records q[] are valid when n_q <= kTileQueries
+    int32_t pad;
+    int32_t first_pages[12];       // page ids of the cluster's first 12 pages (clamped to its last page)
+    TileQuery q[kTileQueries];     // queries sq_lo, sq_lo + 1, ...
 };
+static_assert(sizeof(Tile) == 160, "tile record layout");
 
 // Per sorted token: where it comes from and where it sits in its query.
 struct TokInfo {

@@ -278,41 +278,53 @@ void build_tiles(sgc_plan *pl, int tile_rows)
         }
     }
     std::stable_sort(units.begin(), units.end(), [](const Unit &a, const Unit &b) { return a.work > b.work; });
-    std::vector<std::vector<Tile>> lists(kXcd);
+    struct Light {      // a tile before its record is written: unit and first row
+        int32_t unit, row0;
+    };
+    std::vector<std::vector<Light>> lists(kXcd);
     double load[kXcd] = {0};
-    for (const Unit &u : units) {
+    for (int ui = 0; ui < (int)units.size(); ++ui) {
+        const Unit &u = units[ui];
         int x = 0;
         for (int i = 1; i < kXcd; ++i)
             if (load[i] < load[x]) x = i;
         load[x] += u.work;
-        for (int64_t r = 0; r < u.rows; r += tile_rows) {
-            Tile t{};
+        for (int64_t r = 0; r < u.rows; r += tile_rows) lists[x].push_back({ui, (int32_t)r});
+    }
+    size_t slots = 0;
+    for (auto &l : lists) slots = std::max(slots, l.size());
+    pl->tiles.resize(slots * kXcd);
+    for (int x = 0; x < kXcd; ++x) {
+        for (size_t k = 0; k < slots; ++k) {
+            Tile &t = pl->tiles[k * kXcd + x];
+            if (k >= lists[x].size()) {
+                t.n_rows = 0;            // padding: the workgroup exits at once and reads nothing else
+                t.cluster = 0;
+                continue;
+            }
+            const Unit &u = units[lists[x][k].unit];
             t.cluster = u.cluster;
             t.hk = u.hk;
-            t.row0 = (int32_t)r;
-            t.n_rows = (int32_t)std::min<int64_t>(tile_rows, u.rows - r);
+            t.row0 = lists[x][k].row0;
+            t.n_rows = (int32_t)std::min<int64_t>(tile_rows, u.rows - t.row0);
             t.prefix_len = pl->cl_prefix_len[u.cluster];
+            t.pt_off = 0;
             t.tok_base = pl->cl_tok_off[u.cluster];
             const int32_t first_tok = t.tok_base + t.row0 / g, last_tok = t.tok_base + (t.row0 + t.n_rows - 1) / g;
             t.sq_lo = pl->tok_sq[first_tok];
             t.sq_hi = pl->tok_sq[last_tok];
             t.last_qpos = pl->tok_qpos[last_tok];
             t.n_q = t.sq_hi - t.sq_lo + 1;
-            for (int k = 0; k < kTileQueries; ++k) {
-                const int32_t sq = t.sq_lo + k;
+            t.pad = 0;
+            for (int q = 0; q < kTileQueries; ++q) {
+                const int32_t sq = t.sq_lo + q;
                 if (sq <= t.sq_hi)
-                    t.q[k] = {pl->sq_tok0[sq], pl->sq_src0[sq], pl->sq_len[sq], pl->sq_page0[sq]};
+                    t.q[q] = {pl->sq_tok0[sq], pl->sq_src0[sq], pl->sq_len[sq], pl->sq_page0[sq]};
                 else
-                    t.q[k] = {INT32_MAX, 0, 0, 0};
+                    t.q[q] = {INT32_MAX, 0, 0, 0};
             }
-            lists[x].push_back(t);
         }
     }
-    size_t slots = 0;
-    for (auto &l : lists) slots = std::max(slots, l.size());
-    pl->tiles.assign(slots * kXcd, Tile{});
-    for (int x = 0; x < kXcd; ++x)
-        for (size_t s = 0; s < lists[x].size(); ++s) pl->tiles[s * kXcd + x] = lists[x][s];
     pl->tile_rows = tile_rows;
 }
 
@@ -588,11 +600,15 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
         page_job.insert(page_job.end(), c->cl[id].pages.size(), (int32_t)jobs.size());
         jobs.push_back(j);
     }
-    std::vector<Tile> tiles;
+    // Tile list of the MFMA attention: units (job, KV head) are dealt, heaviest first, to the XCD with the
+    // least work so far, each XCD's tiles longest first; workgroup b runs on XCD b % 8.
+    constexpr int kXcd = 8;
+    struct Light {
+        int32_t job, hk, row0;
+    };
+    std::vector<std::vector<Light>> lists(kXcd);
+    size_t slots = 0;
     if (any_q && ctx->use_mfma) {
-        // Units (job, KV head) are dealt, heaviest first, to the XCD with the least work so far, each XCD's
-        // tiles longest first; workgroup b runs on XCD b % 8.
-        constexpr int kXcd = 8;
         const int rows_per_tile = ctx->tile_rows;
         struct Unit {
             int job, hk;
@@ -603,44 +619,24 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
             if (jobs[ji].q)
                 for (int hk = 0; hk < Hkv; ++hk) units.push_back({ji, hk, (double)jobs[ji].prefix_len * jobs[ji].prefix_len});
         std::stable_sort(units.begin(), units.end(), [](const Unit &x, const Unit &y) { return x.work > y.work; });
-        std::vector<std::vector<Tile>> lists(kXcd);
         double load[kXcd] = {0};
         for (const Unit &u : units) {
             int x = 0;
             for (int i = 1; i < kXcd; ++i)
                 if (load[i] < load[x]) x = i;
             load[x] += u.work;
-            const PrefixJob &j = jobs[u.job];
-            const int64_t rows = (int64_t)j.prefix_len * g;
-            for (int64_t r = 0; r < rows; r += rows_per_tile) {
-                Tile t{};
-                t.cluster = j.cluster;
-                t.hk = u.hk;
-                t.row0 = (int32_t)r;
-                t.n_rows = (int32_t)std::min<int64_t>(rows_per_tile, rows - r);
-                t.prefix_len = j.prefix_len;
-                t.pt_off = j.pt_off;
-                t.tok_base = u.job;      // prefix mode: the job index travels here
-                t.sq_lo = 0;
-                t.sq_hi = -1;
-                t.last_qpos = 0;
-                t.n_q = 0;
-                fill_first_pages(t, c->cl[j.cluster].pages);
-                lists[x].push_back(t);
-            }
+            const int64_t rows = (int64_t)jobs[u.job].prefix_len * g;
+            for (int64_t r = 0; r < rows; r += rows_per_tile) lists[x].push_back({u.job, u.hk, (int32_t)r});
         }
-        size_t slots = 0;
         for (auto &l : lists) {
-            std::stable_sort(l.begin(), l.end(), [](const Tile &x, const Tile &y) { return x.row0 > y.row0; });
+            std::stable_sort(l.begin(), l.end(), [](const Light &x, const Light &y) { return x.row0 > y.row0; });
             slots = std::max(slots, l.size());
         }
-        tiles.assign(slots * kXcd, Tile{});
-        for (int x = 0; x < kXcd; ++x)
-            for (size_t k = 0; k < lists[x].size(); ++k) tiles[k * kXcd + x] = lists[x][k];
     }
+    const size_t n_tiles = slots * kXcd;
     const size_t jobs_bytes = (jobs.size() * sizeof(PrefixJob) + 255) / 256 * 256;
     const size_t pj_bytes = (page_job.size() * sizeof(int32_t) + 255) / 256 * 256;
-    const size_t tiles_bytes = tiles.size() * sizeof(Tile);
+    const size_t tiles_bytes = n_tiles * sizeof(Tile);
     const size_t total = jobs_bytes + pj_bytes + tiles_bytes;
     sgc_dev_block blk;
     if ((rc = dev_acquire(ctx, total, s, &blk)) != SGC_OK) return rc;
@@ -652,7 +648,25 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
     }
     memcpy(host, jobs.data(), jobs.size() * sizeof(PrefixJob));
     memcpy(host + jobs_bytes, page_job.data(), page_job.size() * sizeof(int32_t));
-    if (tiles_bytes) memcpy(host + jobs_bytes + pj_bytes, tiles.data(), tiles_bytes);
+    Tile *ht = reinterpret_cast<Tile *>(host + jobs_bytes + pj_bytes);
+    for (int x = 0; x < kXcd; ++x) {
+        for (size_t k = 0; k < slots; ++k) {
+            Tile &t = ht[k * kXcd + x];
+            memset(&t, 0, sizeof(Tile));
+            if (k >= lists[x].size()) continue;      // padding tile: n_rows = 0
+            const Light &lt = lists[x][k];
+            const PrefixJob &j = jobs[lt.job];
+            t.cluster = j.cluster;
+            t.hk = lt.hk;
+            t.row0 = lt.row0;
+            t.n_rows = (int32_t)std::min<int64_t>(ctx->tile_rows, (int64_t)j.prefix_len * g - lt.row0);
+            t.prefix_len = j.prefix_len;
+            t.pt_off = j.pt_off;
+            t.tok_base = lt.job;      // prefix mode: the job index travels here
+            t.sq_hi = -1;
+            fill_first_pages(t, c->cl[j.cluster].pages);
+        }
+    }
     rc = stage_commit(ctx, slot, blk.p, total, s);
     const PrefixJob *d_jobs = reinterpret_cast<const PrefixJob *>(blk.p);
     const int32_t *d_page_job = reinterpret_cast<const int32_t *>(blk.p + jobs_bytes);
@@ -668,7 +682,7 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
         if (ctx->use_mfma) {
             a.jobs = d_jobs;
             a.tiles = d_tiles;
-            a.n_tiles = (int32_t)tiles.size();
+            a.n_tiles = (int32_t)n_tiles;
             e = launch_attn_mfma(a, ctx->mfma_variant, s);
         } else {
             for (const PrefixJob &j : jobs) {      // the generic kernel works on one cluster per launch

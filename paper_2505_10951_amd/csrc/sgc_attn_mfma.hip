@@ -394,6 +394,9 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     // m_ref is the reference maximum of the row's softmax; the score products start from -m_ref (neg_ref, the
     // same value in all 16 accumulator registers of a lane, which all belong to one row), so finished scores
     // are already relative to it.  seen: the row has met at least one visible key.
+    // (With 64 rows per wavefront the registers for neg_ref are not there: FOLD is off, the products start
+    // from zero and the weights subtract m_ref themselves.)
+    constexpr bool FOLD = MI == 1;
     f32x16 oacc[MI][4], neg_ref[MI];
     float m_ref[MI], l_part[MI];
     bool seen[MI];
@@ -434,13 +437,14 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         return *reinterpret_cast<const bf16x8 *>(vbuf + lane_voff + (nb * 8 + i) * 1024);
     };
     auto no_refill = [&](int) __attribute__((always_inline)) {};
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     // S^T = K Q^T - m_ref for the half whose K blocks the window holds; slot kb is refilled by refill(kb).
     auto qk_half = [&](f32x16 (&s)[MI], auto refill) __attribute__((always_inline)) {
 #pragma unroll
         for (int kb = 0; kb < 8; ++kb) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
-                s[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[kb], qf[mi][kb], kb == 0 ? neg_ref[mi] : s[mi], 0, 0, 0);
+                s[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[kb], qf[mi][kb], kb == 0 ? (FOLD ? neg_ref[mi] : zero16) : s[mi], 0, 0, 0);
             refill(kb);
         }
     };
@@ -474,8 +478,8 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
                 pk[0] = (__bf16)s[mi][r];
                 pk[1] = (__bf16)s[mi][r + 1];
 #else
-                pk[0] = (__bf16)__builtin_amdgcn_exp2f(s[mi][r]);
-                pk[1] = (__bf16)__builtin_amdgcn_exp2f(s[mi][r + 1]);
+                pk[0] = (__bf16)__builtin_amdgcn_exp2f(FOLD ? s[mi][r] : s[mi][r] - m_ref[mi]);
+                pk[1] = (__bf16)__builtin_amdgcn_exp2f(FOLD ? s[mi][r + 1] : s[mi][r + 1] - m_ref[mi]);
                 acc = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, acc, false);   // sum of the ROUNDED weights
 #endif
                 pf[mi][r >> 3][(r & 7) >> 1] = __builtin_bit_cast(uint32_t, pk);
@@ -506,21 +510,26 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             float tmax = s[mi][0];
 #pragma unroll
             for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, s[mi][r]);
-            tmax = fmaxf(tmax, half_swap(tmax));               // relative to m_ref
+            tmax = fmaxf(tmax, half_swap(tmax));
             const bool has = tmax > -INFINITY;
+            if (!FOLD) tmax -= m_ref[mi];                      // relative to m_ref (FOLD: the scores already are)
             const float delta = seen[mi] ? fmaxf(tmax, 0.f) : (has ? tmax : 0.f);     // new m_ref - old m_ref
             if (__any(delta != 0.f)) {
                 const float alpha = seen[mi] ? __builtin_amdgcn_exp2f(-delta) : 1.0f;
                 m_ref[mi] += delta;
                 l_part[mi] *= alpha;
 #pragma unroll
-                for (int db = 0; db < 4; ++db)
+                for (int db = 0; db < 4; ++db) {       // one accumulator block at a time keeps the temporaries few
 #pragma unroll
                     for (int r = 0; r < 16; ++r) oacc[mi][db][r] *= alpha;
+                    if (MI > 1) __builtin_amdgcn_sched_barrier(0);
+                }
+                if (FOLD) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    s[mi][r] -= delta;
-                    neg_ref[mi][r] = -m_ref[mi];
+                    for (int r = 0; r < 16; ++r) {
+                        s[mi][r] -= delta;
+                        neg_ref[mi][r] = -m_ref[mi];
+                    }
                 }
             }
             seen[mi] = seen[mi] || has;
@@ -533,7 +542,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[mi][r] = (s[mi][r] + mb[mi]) * self_ratio - mb[mi];
+            for (int r = 0; r < 16; ++r) s[mi][r] = FOLD ? (s[mi][r] + mb[mi]) * self_ratio - mb[mi] : s[mi][r] * self_ratio;
     };
 
     // ---- cached prefix tiles, software pipelined ------------------------------------------------------
@@ -670,7 +679,8 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) sn[mi][r] -= m_ref[mi] - before[mi];
+                    for (int r = 0; r < 16; ++r)
+                        if (FOLD) sn[mi][r] -= m_ref[mi] - before[mi];
             };
             // half 0
             if (careful) raise_reference(s0, 0, masked, keep);
@@ -758,7 +768,8 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) s1[mi][r] -= m_ref[mi] - before[mi];
+                    for (int r = 0; r < 16; ++r)
+                        if (FOLD) s1[mi][r] -= m_ref[mi] - before[mi];
                 raise_reference(s1, 1, true, keep);
                 weights(s1);
                 pv_half(no_refill);

@@ -372,3 +372,55 @@ def assign_clusters(labels: Sequence[int], suffix_len: Sequence[int], n_clusters
 def pages_needed(prefix_len: int, page_tokens: int = 16) -> int:
     """Pages a cluster's cache occupies in every layer: ceil(prefix_len / page_tokens)."""
     return -(-int(prefix_len) // int(page_tokens))
+
+
+# ----------------------------------------------------------------------------------------------
+# Query clustering (SubGCache Sec. 3.2; App. A.2: agglomerative hierarchical clustering with
+# Euclidean distance, dendrogram cut at a predefined number of clusters; Sec. 4.6 / Table 3: Ward,
+# Single, Average, Complete and Centroid linkage)
+# ----------------------------------------------------------------------------------------------
+LINKAGES = ("ward", "single", "average", "complete", "centroid")
+
+
+def _linkage_distance(x: np.ndarray, a: List[int], b: List[int], linkage: str) -> float:
+    """Distance between two clusters (member index lists) straight from the linkage's definition."""
+    if linkage in ("single", "complete", "average"):
+        d = np.sqrt(((x[a][:, None, :] - x[b][None, :, :]) ** 2).sum(axis=-1))     # all member pairs
+        return float(d.min() if linkage == "single" else d.max() if linkage == "complete" else d.mean())
+    ca, cb = x[a].mean(axis=0), x[b].mean(axis=0)
+    gap2 = float(((ca - cb) ** 2).sum())
+    if linkage == "centroid":
+        return float(np.sqrt(gap2))
+    if linkage == "ward":           # growth of the within-cluster sum of squares caused by the merge
+        return len(a) * len(b) / (len(a) + len(b)) * gap2
+    raise ValueError("unknown linkage")
+
+
+def cluster_queries(embeddings: np.ndarray, n_clusters: int, linkage: str = "ward") -> np.ndarray:
+    """Agglomerative clustering by its definition: start from singletons, repeatedly merge the two clusters
+    at the smallest linkage distance (recomputed from the members every time) until n_clusters are left.
+
+    Readings where the paper is silent: "cutting the dendrogram at c clusters" = the partition after m - c
+    merges; equal distances are broken towards the pair whose clusters have the smallest first members
+    (compare the smaller first member, then the larger); clusters are numbered by their first member.
+    Returns int32 labels [m].
+    """
+    x = np.asarray(embeddings, dtype=np.float64)
+    m = x.shape[0]
+    if not 1 <= n_clusters <= max(m, 1):
+        raise ValueError("n_clusters out of range")
+    clusters: List[List[int]] = [[i] for i in range(m)]       # kept sorted by first member
+    while len(clusters) > n_clusters:
+        best = None
+        for i in range(len(clusters)):
+            for j in range(i + 1, len(clusters)):
+                d = _linkage_distance(x, clusters[i], clusters[j], linkage)
+                if best is None or d < best[0]:             # strict: the first (smallest-member) pair wins ties
+                    best = (d, i, j)
+        _, i, j = best
+        clusters[i] = sorted(clusters[i] + clusters[j])
+        del clusters[j]
+    labels = np.empty(m, dtype=np.int32)
+    for c, members in enumerate(clusters):
+        labels[members] = c
+    return labels

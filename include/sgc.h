@@ -193,6 +193,24 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cache, sgc_plan *p
                                const void *dev_q, const void *dev_k, const void *dev_v,
                                void *dev_o, float *dev_lse, void *hip_stream);
 
+/* ---- query clustering (Sec. 3.2; App. A.2; linkages of Table 3) -------------------------------
+ * Agglomerative hierarchical clustering of m query (subgraph) embeddings with Euclidean distance,
+ * stopped when n_clusters clusters are left ("cutting the dendrogram at a predefined number of
+ * clusters").  embeddings: HOST array [m][dim], row-major, finite.  labels: HOST array [m], receives
+ * cluster ids 0 .. n_clusters-1, clusters numbered by their first (lowest-index) member; ready for
+ * sgc_assign_clusters.  Equal distances: the pair whose clusters have the smallest first members is
+ * merged.  Arithmetic in fp64.  ctx may be NULL (it only receives the error text).  Host-only;
+ * O(m^2) memory.  m = 0 is allowed; otherwise 1 <= n_clusters <= m. */
+typedef enum {
+    SGC_LINKAGE_WARD = 0,      /* smallest growth of the within-cluster sum of squares */
+    SGC_LINKAGE_SINGLE = 1,    /* closest pair of members */
+    SGC_LINKAGE_AVERAGE = 2,   /* mean over member pairs */
+    SGC_LINKAGE_COMPLETE = 3,  /* farthest pair of members */
+    SGC_LINKAGE_CENTROID = 4   /* distance of the cluster means */
+} sgc_linkage;
+int sgc_cluster_queries(sgc_ctx *ctx, int32_t m, int32_t dim, const float *embeddings, int32_t linkage,
+                        int32_t n_clusters, int32_t *labels);
+
 /* ---- kernel timing (measurement aid; no effect on results) -----------------------------------
  * With timing on, sgc_suffix_prefill_batched records HIP events on its launch stream around the
  * suffix K/V ingest kernel and around the attention kernel.  sgc_timing_last waits for the last

@@ -1,0 +1,126 @@
+// Host-side query clustering of libsgc.
+//
+// SubGCache (arXiv 2505.10951) Sec. 3.2: the subgraph embeddings of a batch's queries are grouped by
+// hierarchical clustering; App. A.2: agglomerative, Euclidean distance, the dendrogram cut at a
+// predefined number of clusters; Sec. 4.6 / Table 3: Ward (default), Single, Average, Complete and
+// Centroid linkage.  The labels it produces are what sgc_assign_clusters takes.
+//
+// The batch is small (Table 4: 50-200 queries), so the whole inter-cluster distance matrix is kept in
+// fp64 and updated after each merge with the Lance-Williams recurrence of the linkage; the closest
+// pair is found by a scan.  O(m^2) memory, O(m^3) time, no device work.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+
+#include <limits>
+#include <new>
+#include <vector>
+
+#include "sgc_internal.h"
+
+namespace {
+
+int fail_cluster(sgc_ctx *ctx, int code, const char *fmt, ...)
+{
+    if (ctx) {
+        char buf[256];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof(buf), fmt, ap);
+        va_end(ap);
+        ctx->err = buf;
+    }
+    return code;
+}
+
+}  // namespace
+
+extern "C" int sgc_cluster_queries(sgc_ctx *ctx, int32_t m, int32_t dim, const float *embeddings, int32_t linkage,
+                                   int32_t n_clusters, int32_t *labels)
+{
+    if (m < 0 || dim < 0) return fail_cluster(ctx, SGC_EINVAL, "m %d / dim %d negative", m, dim);
+    if (m == 0) return SGC_OK;
+    if (!embeddings && dim > 0) return fail_cluster(ctx, SGC_EINVAL, "embeddings is NULL");
+    if (!labels) return fail_cluster(ctx, SGC_EINVAL, "labels is NULL");
+    if (linkage < SGC_LINKAGE_WARD || linkage > SGC_LINKAGE_CENTROID)
+        return fail_cluster(ctx, SGC_EINVAL, "linkage %d unknown", linkage);
+    if (n_clusters < 1 || n_clusters > m)
+        return fail_cluster(ctx, SGC_EINVAL, "n_clusters %d outside [1, %d]", n_clusters, m);
+    if (m > 32768) return fail_cluster(ctx, SGC_EINVAL, "m %d too large for the dense distance matrix", m);
+    for (int64_t i = 0; i < (int64_t)m * dim; ++i)
+        if (!std::isfinite(embeddings[i])) return fail_cluster(ctx, SGC_EINVAL, "embeddings[%lld] is not finite", (long long)i);
+
+    // Ward and centroid recur on squared Euclidean distances, the other three on plain ones.
+    const bool squared = linkage == SGC_LINKAGE_WARD || linkage == SGC_LINKAGE_CENTROID;
+    std::vector<double> dist;
+    std::vector<int32_t> size, parent;
+    std::vector<char> alive;
+    try {
+        dist.assign((size_t)m * m, 0.0);
+        size.assign(m, 1);
+        parent.resize(m);
+        alive.assign(m, 1);
+    } catch (const std::bad_alloc &) {
+        return fail_cluster(ctx, SGC_ENOMEM, "host allocation failed");
+    }
+    for (int i = 0; i < m; ++i) {
+        parent[i] = i;
+        for (int j = i + 1; j < m; ++j) {
+            double acc = 0.0;
+            for (int t = 0; t < dim; ++t) {
+                const double d = (double)embeddings[(size_t)i * dim + t] - (double)embeddings[(size_t)j * dim + t];
+                acc += d * d;
+            }
+            const double v = squared ? acc : sqrt(acc);
+            dist[(size_t)i * m + j] = dist[(size_t)j * m + i] = v;
+        }
+    }
+    // A cluster lives in the slot of its smallest member, so scanning slots (i < j) in order and taking
+    // strict minima gives the tie rule: the pair with the smallest first members wins.
+    for (int remaining = m; remaining > n_clusters; --remaining) {
+        double best = std::numeric_limits<double>::infinity();
+        int bi = -1, bj = -1;
+        for (int i = 0; i < m; ++i) {
+            if (!alive[i]) continue;
+            const double *row = &dist[(size_t)i * m];
+            for (int j = i + 1; j < m; ++j)
+                if (alive[j] && row[j] < best) {
+                    best = row[j];
+                    bi = i;
+                    bj = j;
+                }
+        }
+        const double ni = size[bi], nj = size[bj], dij = dist[(size_t)bi * m + bj];
+        for (int k = 0; k < m; ++k) {
+            if (!alive[k] || k == bi || k == bj) continue;
+            const double dki = dist[(size_t)k * m + bi], dkj = dist[(size_t)k * m + bj], nk = size[k];
+            double v;
+            switch (linkage) {
+                case SGC_LINKAGE_SINGLE: v = dki < dkj ? dki : dkj; break;
+                case SGC_LINKAGE_COMPLETE: v = dki > dkj ? dki : dkj; break;
+                case SGC_LINKAGE_AVERAGE: v = (ni * dki + nj * dkj) / (ni + nj); break;
+                case SGC_LINKAGE_CENTROID:
+                    v = (ni * dki + nj * dkj) / (ni + nj) - ni * nj * dij / ((ni + nj) * (ni + nj));
+                    break;
+                default:   // Ward
+                    v = ((nk + ni) * dki + (nk + nj) * dkj - nk * dij) / (nk + ni + nj);
+                    break;
+            }
+            dist[(size_t)k * m + bi] = dist[(size_t)bi * m + k] = v;
+        }
+        size[bi] += size[bj];
+        alive[bj] = 0;
+        parent[bj] = bi;
+    }
+    // clusters are numbered by their first member
+    std::vector<int32_t> id(m, -1);
+    int32_t next = 0;
+    for (int i = 0; i < m; ++i)
+        if (alive[i]) id[i] = next++;
+    for (int i = 0; i < m; ++i) {
+        int r = i;
+        while (parent[r] != r) r = parent[r];
+        labels[i] = id[r];
+    }
+    return SGC_OK;
+}

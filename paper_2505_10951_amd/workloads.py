@@ -21,6 +21,7 @@ import numpy as np
 _KIND_PREFIX_Q, _KIND_PREFIX_K, _KIND_PREFIX_V = 1, 2, 3
 _KIND_SUFFIX_Q, _KIND_SUFFIX_K, _KIND_SUFFIX_V = 4, 5, 6
 _KIND_STRUCT, _KIND_OUTLIER = 7, 8
+_KIND_EMBED_CENTRE, _KIND_EMBED_NOISE = 9, 10
 
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
@@ -147,6 +148,15 @@ class Workload:
         k = self._rng(layer, _KIND_SUFFIX_K, n).standard_normal((S, self.n_kv_heads, self.head_dim), dtype=np.float32)
         v = self._rng(layer, _KIND_SUFFIX_V, n).standard_normal((S, self.n_kv_heads, self.head_dim), dtype=np.float32)
         return self._store(q * np.float32(self.q_gain)), self._store(self._k_post(k, layer)), self._store(v)
+
+    def query_embeddings(self, dim: int = 64, overlap: float = 0.15) -> np.ndarray:
+        """Stand-in for the GNN embeddings of the queries' retrieved subgraphs: fp32 [n_queries][dim].  Queries
+        of one cluster share a centre (a unit-scale Gaussian point); each adds Gaussian noise of standard
+        deviation `overlap` per coordinate, so that the workload's labels are the clustering's ground truth
+        for small overlap and become ambiguous as it grows."""
+        centres = self._rng(0, _KIND_EMBED_CENTRE, 0).standard_normal((max(self.n_clusters, 1), dim), dtype=np.float32)
+        noise = self._rng(0, _KIND_EMBED_NOISE, 0).standard_normal((self.n_queries, dim), dtype=np.float32)
+        return np.ascontiguousarray(centres[self.labels] + np.float32(overlap) * noise, dtype=np.float32)
 
     def suffix_qkv(self, layer: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
         """All queries packed in original order: Q [T][Hq][d], K, V [T][Hkv][d]."""

@@ -1,0 +1,86 @@
+"""sgc_cluster_queries (host-only C++, Lance-Williams updates) against the clustering oracle (merges
+recomputed from the cluster members by definition): labels must be identical."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2505_10951_amd import sgc, workloads
+
+
+@pytest.mark.parametrize("linkage", orc.LINKAGES)
+@pytest.mark.parametrize("m,dim,c,seed", [(1, 4, 1, 0), (2, 1, 1, 1), (17, 3, 5, 2), (40, 32, 8, 3), (64, 128, 1, 4),
+                                          (64, 128, 64, 5), (70, 16, 13, 6)])
+def test_labels_equal_oracle_on_generic_points(linkage, m, dim, c, seed):
+    x = np.random.default_rng(seed).standard_normal((m, dim)).astype(np.float32)
+    got = sgc.sgc_cluster_queries(None, x, c, linkage)
+    ref = orc.cluster_queries(x, c, linkage)
+    assert got.dtype == np.int32 and np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("linkage", ["single", "complete"])
+def test_exact_ties_follow_the_stated_rule(linkage):
+    # integer grid and duplicated points: min / max of identical values, so ties are exact on both sides
+    rng = np.random.default_rng(5)
+    x = rng.integers(0, 4, size=(30, 2)).astype(np.float32)
+    for c in (1, 3, 7, 12):
+        assert np.array_equal(sgc.sgc_cluster_queries(None, x, c, linkage), orc.cluster_queries(x, c, linkage))
+    line = np.arange(8, dtype=np.float32)[:, None]
+    assert sgc.sgc_cluster_queries(None, line, 7, "single").tolist() == [0, 0, 1, 2, 3, 4, 5, 6]
+
+
+@pytest.mark.parametrize("linkage", orc.LINKAGES)
+def test_duplicates_merge_first(linkage):
+    x = np.array([[5, 5], [1, 1], [5, 5], [9, 0], [1, 1]], dtype=np.float32)
+    assert sgc.sgc_cluster_queries(None, x, 3, linkage).tolist() == [0, 1, 0, 2, 1]
+
+
+@pytest.mark.parametrize("config", [1, 2, 3])
+def test_recovers_the_workload_labels_and_feeds_assign(config):
+    """The paper's flow (Sec. 3.2 -> 3.4): embeddings -> labels -> query-to-cluster plan."""
+    w = workloads.config(config)
+    emb = w.query_embeddings(dim=64, overlap=0.15)
+    labels = sgc.sgc_cluster_queries(None, emb, w.n_clusters, "ward")
+    sub = emb[:60]                                        # the by-definition oracle is O(m^4): a subset
+    c_sub = len(set(w.labels[:60].tolist()))
+    assert np.array_equal(sgc.sgc_cluster_queries(None, sub, c_sub, "ward"), orc.cluster_queries(sub, c_sub, "ward"))
+    # same partition as the generator's labels (cluster numbering differs: first-member order)
+    pairs = set(zip(labels.tolist(), w.labels.tolist()))
+    assert len(pairs) == w.n_clusters
+    o_ref, off_ref, cu_ref = orc.assign_clusters(labels, w.suffix_len, w.n_clusters)
+    params = sgc.make_params(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, io_dtype=w.io_dtype)
+    ctx = sgc.sgc_ctx_create(params)
+    pages = int(sum(-(-int(p) // 16) for p in w.prefix_len))
+    cache = sgc.sgc_cache_create(ctx, 256, sgc.sgc_cache_pool_bytes(params, pages), w.n_clusters)
+    # a cluster's prefix belongs to the generator's label; map it through the partition
+    to_gen = {a: b for a, b in pairs}
+    for c in range(w.n_clusters):
+        sgc.sgc_cache_alloc_cluster(ctx, cache, c, int(w.prefix_len[to_gen[c]]))
+    order, off, cu, plan = sgc.sgc_assign_clusters(ctx, cache, labels, w.suffix_len, w.n_clusters)
+    assert np.array_equal(order, o_ref) and np.array_equal(off, off_ref) and np.array_equal(cu, cu_ref)
+    sgc.sgc_plan_destroy(plan)
+    sgc.sgc_cache_destroy(cache)
+    sgc.sgc_ctx_destroy(ctx)
+
+
+def test_overlapping_embeddings_still_match_the_oracle():
+    w = workloads.config(1)
+    emb = w.query_embeddings(dim=8, overlap=1.5)          # clusters run into each other: no ground truth
+    for linkage in orc.LINKAGES:
+        assert np.array_equal(sgc.sgc_cluster_queries(None, emb[:70], 10, linkage), orc.cluster_queries(emb[:70], 10, linkage))
+
+
+def test_argument_checks():
+    x = np.zeros((4, 3), dtype=np.float32)
+    params = sgc.make_params(n_q_heads=4, n_kv_heads=4, head_dim=64, io_dtype="f32")
+    ctx = sgc.sgc_ctx_create(params)
+    for kwargs in (dict(n_clusters=0), dict(n_clusters=5), dict(n_clusters=2, linkage=9)):
+        with pytest.raises(sgc.SgcError) as e:
+            sgc.sgc_cluster_queries(ctx, x, **kwargs)
+        assert e.value.status == sgc.SGC_EINVAL
+    bad = x.copy()
+    bad[2, 1] = np.nan
+    with pytest.raises(sgc.SgcError):
+        sgc.sgc_cluster_queries(ctx, bad, 2)
+    assert sgc.sgc_cluster_queries(ctx, np.zeros((0, 3), dtype=np.float32), 1).shape == (0,)
+    assert sgc.sgc_cluster_queries(None, np.zeros((3, 0), dtype=np.float32), 2).tolist() == [0, 0, 1]
+    sgc.sgc_ctx_destroy(ctx)

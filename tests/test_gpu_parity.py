@@ -436,3 +436,33 @@ def test_config4_llama70b_fp8_long_prefix_full_size_sampled():
     qs = _sampled_queries(w, 1)[::2]                # 4 queries
     _check_suffix(w, out, queries=qs, tol=TOL_FP8)
     assert np.isfinite(out["o"]).all()
+
+
+def test_streaming_schedule_release_after_each_cluster_equals_all_resident():
+    """Sec. 3.4: clusters are served one after another, each cache released before the next is computed.  With
+    a page pool that only holds the largest cluster, serving cluster by cluster gives bit-identical outputs to
+    the all-resident batched run (a row tile never mixes clusters, so the arithmetic is the same)."""
+    w = _small_gqa(seed=61)
+    ref = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
+    q, k, v = w.suffix_qkv()
+    cu = w.cu_seqlens
+    largest = int(max(-(-int(p) // 16) for p in w.prefix_len))
+    o = np.zeros_like(ref["o"])
+    with Session(w, kernel=sgc.SGC_KERNEL_MFMA, total_pages=largest) as s:
+        for c in range(w.n_clusters):
+            members = np.flatnonzero(w.labels == c)
+            s.alloc_cluster(c)
+            assert sgc.sgc_cache_free_pages(s.cache) == largest - (-(-int(w.prefix_len[c]) // 16))
+            if c + 1 < w.n_clusters and w.prefix_len[c + 1] > 16 * sgc.sgc_cache_free_pages(s.cache):
+                with pytest.raises(sgc.SgcError) as e:      # the next cluster does not fit beside this one
+                    s.alloc_cluster(c + 1)
+                assert e.value.status == sgc.SGC_ENOMEM
+            s.prefix_prefill(c)
+            rows = np.concatenate([np.arange(cu[n], cu[n + 1]) for n in members])
+            s.assign(np.full(members.size, c, dtype=np.int32), w.suffix_len[members])
+            do = s.suffix_prefill(*(to_device(x[rows], "bf16") for x in (q, k, v)))
+            torch.cuda.synchronize()
+            o[rows] = to_host_f32(do)
+            s.free_cluster(c)
+            assert sgc.sgc_cache_free_pages(s.cache) == largest
+    assert np.array_equal(o, ref["o"])

@@ -193,6 +193,29 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cache, sgc_plan *p
                                const void *dev_q, const void *dev_k, const void *dev_v,
                                void *dev_o, float *dev_lse, void *hip_stream);
 
+/* ---- decode after the suffix prefill (App. A.2: generation is capped at 32 tokens per query) -----
+ * Every generated token attends over the cluster's cached prompt, the query's question tokens and
+ * the tokens generated before it.  The cached-prompt part of a step stacks the rows of all queries of
+ * a cluster into shared row tiles, so the prompt's K/V are read once per cluster and step, not once
+ * per query.  bf16 io, head_dim 128 only (SGC_EUNSUPPORTED otherwise).
+ *
+ * sgc_plan_enable_decode: host-only; call it before the plan's first suffix prefill.  Reserves room
+ * for max_new_tokens more tokens in every query's suffix pages and keeps those pages per layer
+ * (device memory: layers x pages of all queries).  A query's question plus generated tokens may not
+ * exceed 1024.
+ *
+ * sgc_decode_step_batched: one layer, one step (0-based) for every query of the plan that has a
+ * non-empty suffix.  dev_q / dev_o: [n_queries][Hq][d], dev_k / dev_v: [n_queries][Hkv][d], row n =
+ * query n in original order, the token generated at this step, before rotation (position
+ * prefix_len + suffix_len + step).  Rows of queries with an empty suffix are not touched.
+ * dev_lse (may be NULL): [Hq][n_queries] fp32, natural log.  Appends the token's rotated K and V to
+ * the query's pages of this layer, then attends.  For each layer the caller runs the suffix prefill
+ * first and then steps 0, 1, 2, ... in order.  Asynchronous on hip_stream. */
+int sgc_plan_enable_decode(sgc_plan *plan, int32_t max_new_tokens);
+int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cache, sgc_plan *plan, int32_t layer,
+                            int32_t step, const void *dev_q, const void *dev_k, const void *dev_v,
+                            void *dev_o, float *dev_lse, void *hip_stream);
+
 /* ---- query clustering (Sec. 3.2; App. A.2; linkages of Table 3) -------------------------------
  * Agglomerative hierarchical clustering of m query (subgraph) embeddings with Euclidean distance,
  * stopped when n_clusters clusters are left ("cutting the dendrogram at a predefined number of

@@ -339,7 +339,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         if (rotate) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
-                const int pos = (MODE == MODE_SUFFIX ? P : 0) + qpos[mi];
+                const int pos = (MODE == MODE_SUFFIX ? P + a.pos_shift : 0) + qpos[mi];
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb) {
                     const float4 *tab = reinterpret_cast<const float4 *>(a.rope + (int64_t)pos * 64 + kb * 16 + h * 8);
@@ -603,7 +603,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     };
     TileDesc cur = {1, 0, 0, 0, 0}, nxt = {1, 0, 0, 0, 0};
     bool have = false, more = false;
-    if (MODE == MODE_SUFFIX) SGC_NEXT_SELF(have, cur);      // qinfo is visible since the barriers above
+    if (MODE == MODE_SUFFIX && !a.skip_self) SGC_NEXT_SELF(have, cur);      // qinfo is visible since the barriers above
 
     // One part's copy: per-lane source address and LDS destination.  Issued as four 1 KiB instructions that
     // the steady-state step spreads between its matrix instructions, so that a wavefront never sits on a

@@ -344,16 +344,85 @@ void fill_tile_pt_off(sgc_plan *pl, const sgc_cache *c)
         off[i] = n;
         if (c->cl[i].allocated) n += (int32_t)c->cl[i].pages.size();
     }
-    for (Tile &t : pl->tiles) {
-        if (t.n_rows == 0) continue;
-        t.pt_off = off[t.cluster];
-        fill_first_pages(t, c->cl[t.cluster].pages);
-    }
+    for (std::vector<Tile> *list : {&pl->tiles, &pl->dtiles})
+        for (Tile &t : *list) {
+            if (t.n_rows == 0) continue;
+            t.pt_off = off[t.cluster];
+            fill_first_pages(t, c->cl[t.cluster].pages);
+        }
     pl->tiles_generation = c->generation;
+}
+
+// Pages of the suffix page pool: every query gets room for its suffix plus decode_cap more tokens.
+void layout_suffix_pages(sgc_plan *pl)
+{
+    pl->spage_sq.clear();
+    int32_t page = 0;
+    for (size_t sq = 0; sq < pl->sq_len.size(); ++sq) {
+        pl->sq_page0[sq] = page;
+        const int32_t np = (pl->sq_len[sq] + pl->decode_cap + kPageTokens - 1) / kPageTokens;
+        pl->spage_sq.insert(pl->spage_sq.end(), np, (int32_t)sq);
+        page += np;
+    }
+}
+
+// Decode work list: one row group (the g heads of a KV head) per query, all queries of a (cluster, KV head)
+// stacked so that one tile of rows shares the cluster's cached K/V.  Same XCD dealing as build_tiles.
+void build_decode_tiles(sgc_plan *pl, int tile_rows)
+{
+    constexpr int kXcd = 8;
+    const sgc_ctx *ctx = pl->ctx;
+    const int g = ctx->p.n_q_heads / ctx->p.n_kv_heads;
+    struct Light {
+        int32_t cluster, hk, row0;
+    };
+    struct Unit {
+        int32_t cluster, hk;
+        double work;
+    };
+    std::vector<Unit> units;
+    for (int c = 0; c < pl->n_clusters; ++c) {
+        const int64_t nq = pl->cl_sq_off[c + 1] - pl->cl_sq_off[c];
+        if (nq == 0) continue;
+        const int64_t nt = (nq * g + tile_rows - 1) / tile_rows;
+        for (int hk = 0; hk < ctx->p.n_kv_heads; ++hk) units.push_back({c, hk, (double)nt * (pl->cl_prefix_len[c] + 64.0)});
+    }
+    std::stable_sort(units.begin(), units.end(), [](const Unit &a, const Unit &b) { return a.work > b.work; });
+    std::vector<std::vector<Light>> lists(kXcd);
+    double load[kXcd] = {0};
+    for (const Unit &u : units) {
+        int x = 0;
+        for (int i = 1; i < kXcd; ++i)
+            if (load[i] < load[x]) x = i;
+        load[x] += u.work;
+        const int64_t rows = (int64_t)(pl->cl_sq_off[u.cluster + 1] - pl->cl_sq_off[u.cluster]) * g;
+        for (int64_t r = 0; r < rows; r += tile_rows) lists[x].push_back({u.cluster, u.hk, (int32_t)r});
+    }
+    size_t slots = 0;
+    for (auto &l : lists) slots = std::max(slots, l.size());
+    pl->dtiles.assign(slots * kXcd, Tile{});
+    for (int x = 0; x < kXcd; ++x)
+        for (size_t k = 0; k < lists[x].size(); ++k) {
+            Tile &t = pl->dtiles[k * kXcd + x];
+            const Light &lt = lists[x][k];
+            const int64_t rows = (int64_t)(pl->cl_sq_off[lt.cluster + 1] - pl->cl_sq_off[lt.cluster]) * g;
+            t.cluster = lt.cluster;
+            t.hk = lt.hk;
+            t.row0 = lt.row0;
+            t.n_rows = (int32_t)std::min<int64_t>(tile_rows, rows - lt.row0);
+            t.prefix_len = pl->cl_prefix_len[lt.cluster];
+            t.tok_base = pl->cl_sq_off[lt.cluster];      // "token" = the query's one new token
+            t.sq_hi = -1;
+            t.n_q = kTileQueries + 1;                     // row bookkeeping from the table, not from inline records
+        }
+    pl->dtok.resize(pl->sq_len.size());
+    for (size_t sq = 0; sq < pl->sq_len.size(); ++sq) pl->dtok[sq] = {pl->sq_query[sq], pl->sq_len[sq], (int32_t)sq, 0};
 }
 
 void plan_free_device(sgc_plan *pl)
 {
+    dev_release(pl->ctx, pl->dec_scratch, pl->last_stream);
+    pl->dec_scratch = sgc_dev_block{};
     dev_release(pl->ctx, pl->blob, pl->last_stream);
     dev_release(pl->ctx, pl->spool_block, pl->last_stream);
     pl->blob = sgc_dev_block{};
@@ -776,12 +845,15 @@ int sgc_assign_clusters(sgc_ctx *ctx, const sgc_cache *c, int32_t n_queries, con
     pl->tok_qpos.resize(total);
     pl->tok_sq.resize(total);
     int32_t t = 0, maxpos = 0, spage = 0;
+    pl->cl_sq_off.assign(n_clusters + 1, 0);
     for (int32_t k = 0; k < n_clusters; ++k) {
         pl->cl_tok_off[k] = t;
+        pl->cl_sq_off[k] = (int32_t)pl->sq_len.size();
         for (int32_t i = cluster_off[k]; i < cluster_off[k + 1]; ++i) {
             const int32_t n = order[i];
             if (suffix_len[n] == 0) continue;             // the kernels never see empty queries
             const int32_t sq = (int32_t)pl->sq_len.size();
+            pl->sq_query.push_back(n);
             pl->sq_src0.push_back(cu_seqlens[n]);
             pl->sq_len.push_back(suffix_len[n]);
             pl->sq_tok0.push_back(t);
@@ -799,6 +871,7 @@ int sgc_assign_clusters(sgc_ctx *ctx, const sgc_cache *c, int32_t n_queries, con
         }
     }
     pl->cl_tok_off[n_clusters] = t;
+    pl->cl_sq_off[n_clusters] = (int32_t)pl->sq_len.size();
     pl->max_position = maxpos;
     *out_plan = pl;
     return SGC_OK;
@@ -814,8 +887,11 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
     plan_free_device(pl);
     pl->tiles.clear();
     pl->tile_rows = 0;
+    pl->dtiles.clear();
+    pl->dtok.clear();
     if (want_rows > 0) {
         build_tiles(pl, want_rows);
+        if (pl->decode_cap > 0) build_decode_tiles(pl, want_rows);
         fill_tile_pt_off(pl, pl->cache);
     }
     pl->tok_info.resize(pl->tok_src.size());
@@ -839,6 +915,9 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
         {pl->spage_sq.data(), pl->spage_sq.size() * 4, (const void **)&pl->d_spage_sq},
         {pl->tiles.data(), pl->tiles.size() * sizeof(Tile), (const void **)&pl->d_tiles},
         {pl->tok_info.data(), pl->tok_info.size() * sizeof(TokInfo), (const void **)&pl->d_tok_info},
+        {pl->sq_query.data(), pl->sq_query.size() * 4, (const void **)&pl->d_sq_query},
+        {pl->dtiles.data(), pl->dtiles.size() * sizeof(Tile), (const void **)&pl->d_dtiles},
+        {pl->dtok.data(), pl->dtok.size() * sizeof(TokInfo), (const void **)&pl->d_dtok},
     };
     size_t total = 0;
     for (const Piece &p : pieces) total += (p.bytes + 255) / 256 * 256 + 256;
@@ -858,9 +937,13 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
     if ((rc = stage_commit(ctx, slot, pl->d_blob, total, s)) != SGC_OK) return rc;
     if (want_rows > 0 && !pl->spage_sq.empty()) {
         // suffix page pool: bf16 pages of every query's rotated suffix K and transposed V
-        pl->spool_bytes = pl->spage_sq.size() * (size_t)2 * ctx->p.n_kv_heads * kPageTokens * ctx->p.head_dim * 2;
+        // (decode: one pool per layer, since the pages have to outlive the layer's suffix launch; zeroed once,
+        // so that pages no token has reached yet hold finite values)
+        pl->spool_layer_bytes = pl->spage_sq.size() * (size_t)2 * ctx->p.n_kv_heads * kPageTokens * ctx->p.head_dim * 2;
+        pl->spool_bytes = pl->spool_layer_bytes * (pl->decode_cap > 0 ? (size_t)ctx->p.n_layers : 1);
         if ((rc = dev_acquire(ctx, pl->spool_bytes, s, &pl->spool_block)) != SGC_OK) return rc;
         pl->d_spool = pl->spool_block.p;
+        if (pl->decode_cap > 0) SGC_HIP(ctx, launch_fill_zero_bytes(pl->d_spool, pl->spool_bytes, s));
     }
     pl->uploaded = true;
     return SGC_OK;
@@ -883,6 +966,27 @@ int sgc_plan_destroy(sgc_plan *pl)
     if (!pl) return SGC_OK;
     plan_free_device(pl);
     delete pl;
+    return SGC_OK;
+}
+
+// Clusters were allocated or released since the tiles were filled: refresh their page-table offsets and
+// first page ids, on the host and in the device copy.
+static int refresh_tiles(sgc_plan *pl, const sgc_cache *c, hipStream_t s)
+{
+    sgc_ctx *ctx = pl->ctx;
+    if (pl->tiles.empty() || pl->tiles_generation == c->generation) return SGC_OK;
+    fill_tile_pt_off(pl, c);
+    for (int which = 0; which < 2; ++which) {
+        const std::vector<Tile> &list = which ? pl->dtiles : pl->tiles;
+        const Tile *dev = which ? pl->d_dtiles : pl->d_tiles;
+        if (list.empty()) continue;
+        const size_t bytes = list.size() * sizeof(Tile);
+        char *host = nullptr;
+        int slot = 0, rc;
+        if ((rc = stage_begin(ctx, bytes, &host, &slot)) != SGC_OK) return rc;
+        memcpy(host, list.data(), bytes);
+        if ((rc = stage_commit(ctx, slot, const_cast<Tile *>(dev), bytes, s)) != SGC_OK) return rc;
+    }
     return SGC_OK;
 }
 
@@ -909,16 +1013,7 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
     if ((rc = ensure_rope(ctx, pl->max_position, s)) != SGC_OK) return rc;
     if ((rc = cache_sync(c, s)) != SGC_OK) return rc;
     if ((rc = sgc_plan_upload(pl, hip_stream)) != SGC_OK) return rc;
-    if (!pl->tiles.empty() && pl->tiles_generation != c->generation) {
-        // clusters were allocated or released since the tiles were filled: refresh their page-table offsets
-        fill_tile_pt_off(pl, c);
-        const size_t bytes = pl->tiles.size() * sizeof(Tile);
-        char *host = nullptr;
-        int slot = 0;
-        if ((rc = stage_begin(ctx, bytes, &host, &slot)) != SGC_OK) return rc;
-        memcpy(host, pl->tiles.data(), bytes);
-        if ((rc = stage_commit(ctx, slot, const_cast<Tile *>(pl->d_tiles), bytes, s)) != SGC_OK) return rc;
-    }
+    if ((rc = refresh_tiles(pl, c, s)) != SGC_OK) return rc;
     pl->last_stream = s;
 
     AttnArgs a;
@@ -942,7 +1037,7 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
     a.sq_tok0 = pl->d_sq_tok0;
     a.sq_cluster = pl->d_sq_cluster;
     a.sq_page0 = pl->d_sq_page0;
-    a.spool = pl->d_spool;
+    a.spool = pl->d_spool + (pl->decode_cap > 0 ? (size_t)layer * pl->spool_layer_bytes : 0);
     a.total_tokens = pl->total_tokens;
     if (ctx->timing) SGC_HIP(ctx, hipEventRecord(ctx->ev[0], s));
     if (ctx->use_mfma) SGC_HIP(ctx, launch_suffix_ingest(a, pl->d_spage_sq, (int)pl->spage_sq.size(), s));
@@ -956,6 +1051,100 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
         SGC_HIP(ctx, hipEventRecord(ctx->ev[2], s));
         ctx->timing_valid = true;
     }
+    return SGC_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+int sgc_plan_enable_decode(sgc_plan *pl, int32_t max_new_tokens)
+{
+    if (!pl) return fail(nullptr, SGC_EINVAL, "plan is NULL");
+    sgc_ctx *ctx = pl->ctx;
+    if (!ctx->use_mfma) return fail(ctx, SGC_EUNSUPPORTED, "decode needs the MFMA path (io bf16, head_dim 128)");
+    if (max_new_tokens < 1 || max_new_tokens > 4096) return fail(ctx, SGC_EINVAL, "max_new_tokens %d outside [1, 4096]", max_new_tokens);
+    for (int32_t len : pl->sq_len)
+        if ((len + max_new_tokens + kPageTokens - 1) / kPageTokens * kPageTokens > kDecodeMaxKeys)
+            return fail(ctx, SGC_EINVAL, "suffix %d + %d new tokens exceeds %d own keys per query", len, max_new_tokens, kDecodeMaxKeys);
+    if (pl->decode_cap == max_new_tokens) return SGC_OK;
+    plan_free_device(pl);          // page numbering changes: the device copy is rebuilt at the next upload
+    pl->decode_cap = max_new_tokens;
+    layout_suffix_pages(pl);
+    return SGC_OK;
+}
+
+int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int32_t layer, int32_t step,
+                            const void *dev_q, const void *dev_k, const void *dev_v, void *dev_o, float *dev_lse,
+                            void *hip_stream)
+{
+    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (!cc || cc->ctx != ctx) return fail(ctx, SGC_EINVAL, "cache is NULL or belongs to another context");
+    if (!pl || pl->ctx != ctx || pl->cache != cc) return fail(ctx, SGC_EINVAL, "plan is NULL or was made for another context/cache");
+    if (layer < 0 || layer >= ctx->p.n_layers) return fail(ctx, SGC_EINVAL, "layer %d outside [0, %d)", layer, ctx->p.n_layers);
+    if (pl->decode_cap <= 0) return fail(ctx, SGC_ESTATE, "decode was not enabled on this plan");
+    if (step < 0 || step >= pl->decode_cap) return fail(ctx, SGC_EINVAL, "step %d outside [0, %d)", step, pl->decode_cap);
+    if (!pl->uploaded) return fail(ctx, SGC_ESTATE, "no suffix prefill has run on this plan: its suffix pages are empty");
+    sgc_cache *c = const_cast<sgc_cache *>(cc);
+    for (int32_t k = 0; k < pl->n_clusters; ++k) {
+        if (pl->cluster_off[k + 1] == pl->cluster_off[k]) continue;
+        if (!c->cl[k].allocated || c->cl[k].prefix_len != pl->cl_prefix_len[k])
+            return fail(ctx, SGC_ESTATE, "cluster %d changed since the plan was made", k);
+    }
+    const int32_t n_sq = (int32_t)pl->sq_len.size();
+    if (n_sq == 0) return SGC_OK;
+    if (!dev_q || !dev_k || !dev_v || !dev_o) return fail(ctx, SGC_EINVAL, "dev_q / dev_k / dev_v / dev_o is NULL");
+    if (!aligned16(dev_q) || !aligned16(dev_k) || !aligned16(dev_v) || !aligned16(dev_o) || !aligned16(dev_lse))
+        return fail(ctx, SGC_EINVAL, "device pointers must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int rc;
+    if ((rc = ensure_rope(ctx, pl->max_position + pl->decode_cap, s)) != SGC_OK) return rc;
+    if ((rc = cache_sync(c, s)) != SGC_OK) return rc;
+    if ((rc = refresh_tiles(pl, c, s)) != SGC_OK) return rc;
+    pl->last_stream = s;
+    // scratch for the cached-prefix part of the step: O [n_queries][Hq][d] bf16, then LSE [Hq][n_queries]
+    const size_t o_bytes = ((size_t)pl->n_queries * ctx->p.n_q_heads * ctx->p.head_dim * 2 + 255) / 256 * 256;
+    const size_t lse_bytes = (size_t)ctx->p.n_q_heads * pl->n_queries * sizeof(float);
+    if (!pl->dec_scratch.p && (rc = dev_acquire(ctx, o_bytes + lse_bytes, s, &pl->dec_scratch)) != SGC_OK) return rc;
+    char *spool = pl->d_spool + (size_t)layer * pl->spool_layer_bytes;
+
+    DecodeArgs d{};
+    d.q = dev_q;
+    d.k = dev_k;
+    d.v = dev_v;
+    d.o = dev_o;
+    d.lse = dev_lse;
+    d.o_cached = pl->dec_scratch.p;
+    d.lse_cached = reinterpret_cast<const float *>(pl->dec_scratch.p + o_bytes);
+    d.spool = spool;
+    d.sq_query = pl->d_sq_query;
+    d.sq_len = pl->d_sq_len;
+    d.sq_page0 = pl->d_sq_page0;
+    d.sq_cluster = pl->d_sq_cluster;
+    d.cl_prefix_len = c->d_prefix_len;
+    d.rope = (ctx->p.rope_base > 0.0f) ? ctx->d_rope : nullptr;
+    d.n_sq = n_sq;
+    d.n_queries = pl->n_queries;
+    d.step = step;
+    d.n_q_heads = ctx->p.n_q_heads;
+    d.n_kv_heads = ctx->p.n_kv_heads;
+    d.scale_log2e = ctx->scale * 1.4426950408889634f;
+    SGC_HIP(ctx, launch_decode_append(d, s));
+
+    AttnArgs a;
+    fill_common_args(a, ctx, c, layer);
+    a.q = dev_q;
+    a.o = pl->dec_scratch.p;
+    a.lse = reinterpret_cast<float *>(pl->dec_scratch.p + o_bytes);
+    a.lse_stride = pl->n_queries;
+    a.mode = MODE_SUFFIX;
+    a.tiles = pl->d_dtiles;
+    a.n_tiles = (int32_t)pl->dtiles.size();
+    a.tok_info = pl->d_dtok;
+    a.sq_len = pl->d_sq_len;
+    a.sq_page0 = pl->d_sq_page0;
+    a.spool = spool;
+    a.pos_shift = step;
+    a.skip_self = 1;
+    SGC_HIP(ctx, launch_attn_mfma(a, ctx->mfma_variant, s));
+    SGC_HIP(ctx, launch_decode_own_keys(d, s));
     return SGC_OK;
 }
 

@@ -107,6 +107,23 @@ struct PrefixJob {
     int32_t page0;           // first page of the job in the launch-wide page numbering
 };
 
+// One decode step of every (non-empty) query of a plan: arguments of the append and own-keys kernels.
+constexpr int kDecodeMaxKeys = 1024;      // own keys (suffix + generated) a query may reach while decoding
+struct DecodeArgs {
+    const void *q, *k, *v;        // the new token of every query: [n_queries][Hq][d], [n_queries][Hkv][d], bf16
+    void *o;                      // [n_queries][Hq][d] bf16
+    float *lse;                   // [Hq][n_queries] natural log, or null
+    const void *o_cached;         // cached-prefix part of the same rows: [n_queries][Hq][d] bf16 (normalised) ...
+    const float *lse_cached;      // ... and its log-sum-exp [Hq][n_queries], natural log (-inf: no cached keys)
+    char *spool;                  // the layer's suffix pages
+    const int32_t *sq_query;      // [n_sq] original index of the sorted query
+    const int32_t *sq_len, *sq_page0, *sq_cluster;
+    const int32_t *cl_prefix_len;
+    const float2 *rope;
+    int32_t n_sq, n_queries, step, n_q_heads, n_kv_heads;
+    float scale_log2e;
+};
+
 enum { MODE_SUFFIX = 0, MODE_PREFIX = 1 };
 
 // Everything an attention kernel needs, by value.
@@ -148,6 +165,10 @@ struct AttnArgs {
     int32_t n_q_heads, n_kv_heads, group, head_dim;
     int32_t io_dtype;
     float scale_log2e;            // softmax_scale * log2(e)
+    // decode: the one new token of a query sits pos_shift tokens behind the end of its suffix, and the MFMA
+    // kernel only does the cached-prefix part (skip_self), leaving the own keys to the decode kernel
+    int32_t pos_shift;
+    int32_t skip_self;
 };
 
 }  // namespace sgc
@@ -216,6 +237,15 @@ struct sgc_plan {
     std::vector<int32_t> tok_src, tok_qpos, tok_sq;
     std::vector<int32_t> sq_src0, sq_len, sq_tok0, sq_cluster, sq_page0;   // non-empty queries only
     std::vector<int32_t> spage_sq;            // [total suffix pages] owning query of each suffix page
+    std::vector<int32_t> sq_query;            // [non-empty queries] original index of the sorted query
+    std::vector<int32_t> cl_sq_off;           // [n_clusters + 1] first sorted query of each cluster
+    // decode (off unless sgc_plan_enable_decode was called): pages leave room for decode_cap more tokens per
+    // query, the suffix page pool exists once per layer, and a second tile list stacks one row group per query
+    int32_t decode_cap = 0;
+    std::vector<sgc::Tile> dtiles;
+    std::vector<sgc::TokInfo> dtok;
+    size_t spool_layer_bytes = 0;
+    sgc_dev_block dec_scratch;                // cached-prefix part of a decode step: O then LSE
     std::vector<sgc::Tile> tiles;
     std::vector<sgc::TokInfo> tok_info;
     uint64_t tiles_generation = 0;            // cache generation the tiles' page-table offsets belong to
@@ -229,6 +259,9 @@ struct sgc_plan {
     const int32_t *d_sq_page0 = nullptr, *d_spage_sq = nullptr;
     const sgc::Tile *d_tiles = nullptr;
     const sgc::TokInfo *d_tok_info = nullptr;
+    const int32_t *d_sq_query = nullptr;
+    const sgc::Tile *d_dtiles = nullptr;
+    const sgc::TokInfo *d_dtok = nullptr;
     char *d_spool = nullptr;                  // rotated suffix K / transposed V pages of the batch (MFMA path)
     size_t spool_bytes = 0;
 };
@@ -254,6 +287,11 @@ hipError_t launch_cache_import(const PoolGeom &g, int layer, const int32_t *d_pa
 hipError_t launch_suffix_ingest(const AttnArgs &a, const int32_t *d_spage_sq, int n_spages, hipStream_t s);
 
 hipError_t launch_attn_generic(const AttnArgs &a, int64_t n_rows, hipStream_t s);
+// Decode: append the new token's rotated K and V to every query's suffix pages; then, per (query, head),
+// attention over the query's own keys merged with the cached-prefix part.  head_dim 128, bf16.
+hipError_t launch_decode_append(const DecodeArgs &d, hipStream_t s);
+hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s);
+hipError_t launch_fill_zero_bytes(void *p, size_t bytes, hipStream_t s);
 // Rows per workgroup of MFMA kernel variant `variant`, or 0 if the variant does not exist.
 int mfma_tile_rows(int variant);
 hipError_t launch_attn_mfma(const AttnArgs &a, int variant, hipStream_t s);

@@ -261,6 +261,7 @@ __global__ void suffix_ingest_kernel(AttnArgs a, const int32_t *spage_sq)
     const int64_t src0 = a.sq_src0[sq];
     const int P = a.cl_prefix_len[a.sq_cluster[sq]];
     const int tok0 = (page - a.sq_page0[sq]) * kPageTokens;
+    if (tok0 >= S) return;      // a page kept free for decoded tokens: not this kernel's to write
     const int64_t part = (int64_t)kPageTokens * d * 2;
     char *kg = const_cast<char *>(a.spool) + (int64_t)page * 2 * Hkv * part + (int64_t)hk * part;
     char *vg = kg + (int64_t)Hkv * part;
@@ -292,6 +293,152 @@ __global__ void suffix_ingest_kernel(AttnArgs a, const int32_t *spage_sq)
     __syncthreads();
     copy_out_16(kg, kp, (int)part);
     copy_out_16(vg, vp, (int)part);
+}
+
+// ---- decode ------------------------------------------------------------------------------------
+// SubGCache App. A.2 caps generation at 32 tokens per query; every generated token attends over the
+// cluster's cached prompt, the query's question tokens and the tokens generated before it (Sec. 3.4:
+// all queries of a cluster reuse the same cache).  The cached-prompt part of a step runs in the MFMA
+// kernel with the rows of all sibling queries stacked into one tile, so the prompt's K/V are read once
+// per cluster instead of once per query; the two kernels here do what is per query.
+
+// Appends the new token (index len + step of the query's own keys) to the query's suffix pages:
+// K rotated at position P + len + step, V as given.  One workgroup per (sorted query, KV head), d = 128.
+__global__ void decode_append_kernel(DecodeArgs a)
+{
+    constexpr int d = 128, half = 64;
+    const int sq = blockIdx.x, hk = blockIdx.y, Hkv = a.n_kv_heads;
+    const int cc = threadIdx.x;            // 8 threads: one 8-channel chunk of each half
+    if (cc >= half / 8) return;
+    const int j = a.sq_len[sq] + a.step;
+    const int P = a.cl_prefix_len[a.sq_cluster[sq]];
+    const int64_t part = (int64_t)kPageTokens * d * 2;
+    char *kp = a.spool + (int64_t)(a.sq_page0[sq] + j / kPageTokens) * 2 * Hkv * part + (int64_t)hk * part;
+    char *vp = kp + (int64_t)Hkv * part;
+    const int tok = j % kPageTokens;
+    const int64_t row = ((int64_t)a.sq_query[sq] * Hkv + hk) * d;
+    float x1[8], x2[8], y1[8], y2[8];
+    load8(a.k, row + cc * 8, SGC_BF16, x1);
+    load8(a.k, row + half + cc * 8, SGC_BF16, x2);
+    if (a.rope) rope8(x1, x2, a.rope + (int64_t)(P + j) * half + cc * 8);
+    load8(a.v, row + cc * 8, SGC_BF16, y1);
+    load8(a.v, row + half + cc * 8, SGC_BF16, y2);
+    store8(kp, k_page_index(tok, cc * 8), SGC_BF16, x1, 1.f);
+    store8(kp, k_page_index(tok, half + cc * 8), SGC_BF16, x2, 1.f);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        store1(vp, v_page_index(tok, cc * 8 + i), SGC_BF16, y1[i], 1.f);
+        store1(vp, v_page_index(tok, half + cc * 8 + i), SGC_BF16, y2[i], 1.f);
+    }
+}
+
+// One wavefront per (sorted query, query head): scores of the new token against the query's own
+// len + step + 1 keys (lane = key), softmax, weighted V sum (lane = channel pair), merged with the
+// cached-prefix part by the log-sum-exp rule.  fp32 arithmetic.
+__global__ void __launch_bounds__(256) decode_own_keys_kernel(DecodeArgs a)
+{
+    constexpr int d = 128, half = 64;
+    __shared__ float q_s[4][d];
+    __shared__ float p_s[4][kDecodeMaxKeys];
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int Hq = a.n_q_heads, Hkv = a.n_kv_heads, g = Hq / Hkv;
+    const int64_t row = (int64_t)blockIdx.x * 4 + wave;
+    const bool live = row < (int64_t)a.n_sq * Hq;
+    int sq = 0, h = 0;
+    if (live) {
+        sq = (int)(row / Hq);
+        h = (int)(row % Hq);
+    }
+    const int hk = h / g;
+    const int n = a.sq_query[sq];
+    const int n_keys = a.sq_len[sq] + a.step + 1;
+    const int P = a.cl_prefix_len[a.sq_cluster[sq]];
+    const int64_t io = ((int64_t)n * Hq + h) * d;
+    if (live && lane < half / 8) {          // rotated query row into LDS
+        float x1[8], x2[8];
+        load8(a.q, io + lane * 8, SGC_BF16, x1);
+        load8(a.q, io + half + lane * 8, SGC_BF16, x2);
+        if (a.rope) rope8(x1, x2, a.rope + (int64_t)(P + n_keys - 1) * half + lane * 8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            q_s[wave][lane * 8 + i] = x1[i];
+            q_s[wave][half + lane * 8 + i] = x2[i];
+        }
+    }
+    __syncthreads();
+    if (!live) return;
+    const int64_t part = (int64_t)kPageTokens * d * 2;
+    const char *pages = a.spool + (int64_t)a.sq_page0[sq] * 2 * Hkv * part + (int64_t)hk * part;
+    const int64_t page_stride = 2 * Hkv * part;
+    // scores (log2 units), lane = key
+    float m = -INFINITY;
+    for (int j = lane; j < n_keys; j += kWave) {
+        const char *kp = pages + (int64_t)(j / kPageTokens) * page_stride;
+        const int tok = j % kPageTokens;
+        float s = 0.f;
+#pragma unroll
+        for (int cc = 0; cc < d / 8; ++cc) {
+            float kk[8];
+            load8(kp, k_page_index(tok, cc * 8), SGC_BF16, kk);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s += q_s[wave][cc * 8 + i] * kk[i];
+        }
+        s *= a.scale_log2e;
+        p_s[wave][j] = s;
+        m = fmaxf(m, s);
+    }
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    float l = 0.f;
+    for (int j = lane; j < n_keys; j += kWave) {
+        const float p = exp2f(p_s[wave][j] - m);
+        p_s[wave][j] = p;
+        l += p;
+    }
+    for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
+    const int n_pages = (n_keys + kPageTokens - 1) / kPageTokens;
+    for (int j = n_keys + lane; j < n_pages * kPageTokens; j += kWave) p_s[wave][j] = 0.f;   // tail of the last page
+    __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0): the wave's LDS writes are done before its lanes read them
+    // weighted V sum, lane = channels (lane, lane + 64); a page holds, per channel, two runs of 8 tokens
+    float acc[2] = {0.f, 0.f};
+    for (int pg = 0; pg < n_pages; ++pg) {
+        const char *vp = pages + (int64_t)pg * page_stride + (int64_t)Hkv * part;
+        const float *pw = &p_s[wave][pg * kPageTokens];
+#pragma unroll
+        for (int cI = 0; cI < 2; ++cI) {
+            const int c = lane + cI * 64;
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                float vv[8];
+                load8(vp, (((c >> 5) * 2 + hh) * 32 + (c & 31)) * 8, SGC_BF16, vv);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[cI] += pw[4 * hh + (i & 3) + 8 * (i >> 2)] * vv[i];
+            }
+        }
+    }
+    // merge with the cached-prefix part (natural-log LSE there; log2 units here)
+    const float lse_own = m + log2f(l);
+    float lse_c = -INFINITY;
+    if (a.lse_cached) lse_c = a.lse_cached[(int64_t)h * a.n_queries + n] * 1.4426950408889634f;
+    const bool use_cached = lse_c > -INFINITY;
+    const float M = fmaxf(lse_own, lse_c);
+    const float wc = use_cached ? exp2f(lse_c - M) : 0.f;
+    const float wo = exp2f(m - M);                       // weight of the unnormalised own sum
+    const float denom = wc + exp2f(lse_own - M);
+    uint16_t *og = static_cast<uint16_t *>(a.o);
+    const uint16_t *oc = static_cast<const uint16_t *>(a.o_cached);
+#pragma unroll
+    for (int cI = 0; cI < 2; ++cI) {
+        const int c = lane + cI * 64;
+        const float cached = use_cached ? bf16_to_f32(oc[io + c]) : 0.f;
+        og[io + c] = f32_to_bf16((wc * cached + wo * acc[cI]) / denom);
+    }
+    if (a.lse && lane == 0) a.lse[(int64_t)h * a.n_queries + n] = (M + log2f(denom)) * 0.6931471805599453f;
+}
+
+__global__ void fill_zero_bytes_kernel(uint4 *p, size_t n16)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = make_uint4(0, 0, 0, 0);
 }
 
 // ---- export / import: raw element moves between page order and [P][Hkv][d] --------------------
@@ -513,6 +660,30 @@ hipError_t launch_suffix_ingest(const AttnArgs &a, const int32_t *d_spage_sq, in
     if (n_spages <= 0) return hipSuccess;
     const size_t lds = 2 * (size_t)kPageTokens * a.head_dim * 2;
     hipLaunchKernelGGL(suffix_ingest_kernel, dim3(n_spages, a.n_kv_heads), dim3(128), lds, s, a, d_spage_sq);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_append(const DecodeArgs &d, hipStream_t s)
+{
+    if (d.n_sq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(decode_append_kernel, dim3(d.n_sq, d.n_kv_heads), dim3(64), 0, s, d);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s)
+{
+    if (d.n_sq <= 0) return hipSuccess;
+    const int64_t rows = (int64_t)d.n_sq * d.n_q_heads;
+    hipLaunchKernelGGL(decode_own_keys_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, d);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_zero_bytes(void *p, size_t bytes, hipStream_t s)
+{
+    if (bytes == 0) return hipSuccess;
+    const size_t n16 = bytes / 16;      // callers pass multiples of 16 bytes
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 4096);
+    hipLaunchKernelGGL(fill_zero_bytes_kernel, dim3(blocks), dim3(256), 0, s, static_cast<uint4 *>(p), n16);
     return hipGetLastError();
 }
 

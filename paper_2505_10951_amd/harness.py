@@ -134,6 +134,18 @@ class Session:
                                        self.stream)
         return do
 
+    # ---- App. A.2: up to 32 generated tokens per query, attending over cache + question + earlier tokens ---
+    def enable_decode(self, max_new_tokens: int) -> None:
+        sgc.sgc_plan_enable_decode(self.ctx, self.plan, max_new_tokens)
+
+    def decode_step(self, step: int, dq: torch.Tensor, dk: torch.Tensor, dv: torch.Tensor, layer: int = 0,
+                    do: Optional[torch.Tensor] = None, dlse: Optional[torch.Tensor] = None):
+        if do is None:
+            do = torch.zeros_like(dq)
+        sgc.sgc_decode_step_batched(self.ctx, self.cache, self.plan, layer, step, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+                                    do.data_ptr(), dlse.data_ptr() if dlse is not None else None, self.stream)
+        return do
+
     def export_cluster(self, c: int, layer: int = 0):
         """Canonical [P][Hkv][d] view of the cluster's cache: (k, v, k_scale, v_scale) on the host.
         k, v are fp32 values for f32/bf16 caches and raw uint8 e4m3 codes for fp8 caches."""

@@ -26,7 +26,7 @@ EXPORTS = [
     "sgc_cache_alloc_cluster", "sgc_cache_free_cluster", "sgc_cache_total_pages", "sgc_cache_free_pages",
     "sgc_cache_cluster_pages", "sgc_prefix_prefill", "sgc_prefix_prefill_batched", "sgc_assign_clusters", "sgc_plan_upload",
     "sgc_plan_get_info", "sgc_plan_destroy", "sgc_suffix_prefill_batched", "sgc_cache_export", "sgc_cache_import",
-    "sgc_timing_enable", "sgc_timing_last", "sgc_cluster_queries",
+    "sgc_timing_enable", "sgc_timing_last", "sgc_cluster_queries", "sgc_plan_enable_decode", "sgc_decode_step_batched",
 ]
 
 
@@ -94,6 +94,8 @@ def lib() -> ctypes.CDLL:
         L.sgc_suffix_prefill_batched.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
         L.sgc_cache_export.argtypes = [vp, vp, i32, i32, vp, vp, f32p, f32p, vp]
         L.sgc_cache_import.argtypes = [vp, vp, i32, i32, vp, vp, f32p, f32p, vp]
+        L.sgc_plan_enable_decode.argtypes = [vp, i32]
+        L.sgc_decode_step_batched.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
         L.sgc_cluster_queries.argtypes = [vp, i32, i32, f32p, i32, i32, i32p]
         L.sgc_timing_enable.argtypes = [vp, ctypes.c_int]
         L.sgc_timing_last.argtypes = [vp, f32p, f32p]
@@ -252,6 +254,15 @@ def sgc_plan_destroy(plan) -> None:
 def sgc_suffix_prefill_batched(ctx, cache, plan, layer: int, dev_q: int, dev_k: int, dev_v: int, dev_o: int,
                                dev_lse: Optional[int] = None, stream: int = 0) -> None:
     _check(ctx, lib().sgc_suffix_prefill_batched(ctx, cache, plan, layer, dev_q, dev_k, dev_v, dev_o, dev_lse, stream))
+
+
+def sgc_plan_enable_decode(ctx, plan, max_new_tokens: int) -> None:
+    _check(ctx, lib().sgc_plan_enable_decode(plan, int(max_new_tokens)))
+
+
+def sgc_decode_step_batched(ctx, cache, plan, layer: int, step: int, dev_q: int, dev_k: int, dev_v: int, dev_o: int,
+                            dev_lse: Optional[int] = None, stream: int = 0) -> None:
+    _check(ctx, lib().sgc_decode_step_batched(ctx, cache, plan, layer, step, dev_q, dev_k, dev_v, dev_o, dev_lse, stream))
 
 
 LINKAGES = {"ward": 0, "single": 1, "average": 2, "complete": 3, "centroid": 4}

@@ -22,6 +22,7 @@ _KIND_PREFIX_Q, _KIND_PREFIX_K, _KIND_PREFIX_V = 1, 2, 3
 _KIND_SUFFIX_Q, _KIND_SUFFIX_K, _KIND_SUFFIX_V = 4, 5, 6
 _KIND_STRUCT, _KIND_OUTLIER = 7, 8
 _KIND_EMBED_CENTRE, _KIND_EMBED_NOISE = 9, 10
+_KIND_DECODE_Q, _KIND_DECODE_K, _KIND_DECODE_V = 11, 12, 13
 
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
@@ -147,6 +148,15 @@ class Workload:
         q = self._rng(layer, _KIND_SUFFIX_Q, n).standard_normal((S, self.n_q_heads, self.head_dim), dtype=np.float32)
         k = self._rng(layer, _KIND_SUFFIX_K, n).standard_normal((S, self.n_kv_heads, self.head_dim), dtype=np.float32)
         v = self._rng(layer, _KIND_SUFFIX_V, n).standard_normal((S, self.n_kv_heads, self.head_dim), dtype=np.float32)
+        return self._store(q * np.float32(self.q_gain)), self._store(self._k_post(k, layer)), self._store(v)
+
+    def decode_qkv(self, step: int, layer: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+        """Un-rotated Q [n_queries][Hq][d], K, V [n_queries][Hkv][d] of the token every query generates at
+        decode step `step` (stand-ins for the projections of generated tokens; same recipe as the suffix)."""
+        n = self.n_queries
+        q = self._rng(layer, _KIND_DECODE_Q, step).standard_normal((n, self.n_q_heads, self.head_dim), dtype=np.float32)
+        k = self._rng(layer, _KIND_DECODE_K, step).standard_normal((n, self.n_kv_heads, self.head_dim), dtype=np.float32)
+        v = self._rng(layer, _KIND_DECODE_V, step).standard_normal((n, self.n_kv_heads, self.head_dim), dtype=np.float32)
         return self._store(q * np.float32(self.q_gain)), self._store(self._k_post(k, layer)), self._store(v)
 
     def query_embeddings(self, dim: int = 64, overlap: float = 0.15) -> np.ndarray:

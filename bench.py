@@ -96,6 +96,57 @@ def cpu_baseline(w, budget_s: float):
             "us_per_query": dt / len(sample) * 1e6}
 
 
+def decode_measurement(s, w, layer, n_steps, dq, dk, dv, do, all_clusters, pq_ptrs, pk_ptrs, pv_ptrs, po_ptrs, stream):
+    """Batched decode after the suffix prefill (the paper caps generation at 32 tokens): per-step time, HIP events
+    around each step on the launch stream.  HBM-bound: every step has to read the cached K/V of each cluster
+    once and every query's own keys once."""
+    import torch
+    from paper_2505_10951_amd import sgc
+    from paper_2505_10951_amd.harness import to_device
+    if s.plan is None or sgc.sgc_cache_free_pages(s.cache) == sgc.sgc_cache_total_pages(s.cache):
+        for c in all_clusters:
+            sgc.sgc_cache_alloc_cluster(s.ctx, s.cache, c, int(w.prefix_len[c]))
+        sgc.sgc_prefix_prefill_batched(s.ctx, s.cache, all_clusters, layer, pq_ptrs, pk_ptrs, pv_ptrs, po_ptrs, None, stream)
+    s.assign(w.labels, w.suffix_len)
+    sgc.sgc_plan_enable_decode(s.ctx, s.plan, n_steps)
+    sgc.sgc_suffix_prefill_batched(s.ctx, s.cache, s.plan, layer, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), do.data_ptr(),
+                                   None, stream)
+    tq, tk, tv = (to_device(x, w.io_dtype) for x in w.decode_qkv(0, layer))
+    to = torch.empty_like(tq)
+    torch.cuda.synchronize()
+    times = []
+    for rep in range(2):                      # the first pass warms up; the pages are simply overwritten again
+        times.clear()
+        for t in range(n_steps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            sgc.sgc_decode_step_batched(s.ctx, s.cache, s.plan, layer, t, tq.data_ptr(), tk.data_ptr(), tv.data_ptr(),
+                                        to.data_ptr(), None, stream)
+            e1.record()
+            times.append((e0, e1))
+        torch.cuda.synchronize()
+    ms = [a.elapsed_time(b) for a, b in times]
+    live = w.suffix_len > 0
+    S = w.suffix_len[live].astype(np.float64)
+    P = w.prefix_len[w.labels[live]].astype(np.float64)
+    t_mid = (n_steps - 1) / 2.0
+    kvb = 2.0 * w.n_kv_heads * w.head_dim                         # K and V elements per token
+    used = np.unique(w.labels[live])
+    cache_bytes = float(w.prefix_len[used].sum()) * kvb * w.kv_bytes()
+    own_bytes = float(np.sum(S + t_mid + 1)) * kvb * 2
+    io_bytes = float(live.sum()) * (2 * w.n_q_heads + 2 * w.n_kv_heads) * w.head_dim * 2
+    alg_bytes = cache_bytes + own_bytes + io_bytes
+    flop = float(4.0 * w.n_q_heads * w.head_dim * np.sum(P + S + t_mid + 1))
+    mean_ms = float(np.mean(ms))
+    per_query_read = float(np.sum(P)) * kvb * w.kv_bytes() + own_bytes + io_bytes     # without the sharing
+    return {"steps": n_steps, "ms_per_step": mean_ms, "ms_per_step_min": float(np.min(ms)),
+            "us_per_query_step": mean_ms * 1e3 / max(int(live.sum()), 1),
+            "algorithmic_bytes_per_step": alg_bytes, "flop_per_step": flop,
+            "roofline": {"bound": "hbm", "achieved": alg_bytes / (mean_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": alg_bytes / (mean_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None},
+            "bytes_if_every_query_read_its_prefix": per_query_read}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -104,6 +155,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default 1: Llama-3-8B-shaped layer)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for the CPU baseline (0 = skip)")
     ap.add_argument("--suffix-only", action="store_true", help="time only the batched suffix launch (profiling aid)")
+    ap.add_argument("--decode-steps", type=int, default=32,
+                    help="after the timed steps, time this many batched decode steps on the same workload (0 = skip)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten 256 MiB device copies and exit (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -216,6 +269,9 @@ def main() -> int:
         "paper_context": "TTFT reduction up to 6.68x, PFTT up to 15.49x (Table 2; 2x A100-SXM4-40GB, precision not stated); end-to-end LLM latencies, not this kernel",
         "input_gen_s": t_gen,
     }
+    if args.decode_steps > 0 and dtype == "bf16":
+        out["decode"] = decode_measurement(s, w, layer, args.decode_steps, dq, dk, dv, do, all_clusters,
+                                           pq_ptrs, pk_ptrs, pv_ptrs, po_ptrs, stream)
     s.close()
     if args.cpu_budget > 0:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_budget)

@@ -1125,6 +1125,9 @@ int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int
     d.step = step;
     d.n_q_heads = ctx->p.n_q_heads;
     d.n_kv_heads = ctx->p.n_kv_heads;
+    int32_t longest = 0;
+    for (int32_t len : pl->sq_len) longest = std::max(longest, len);
+    d.key_cap = (longest + pl->decode_cap + kPageTokens - 1) / kPageTokens * kPageTokens;
     d.scale_log2e = ctx->scale * 1.4426950408889634f;
     SGC_HIP(ctx, launch_decode_append(d, s));
 

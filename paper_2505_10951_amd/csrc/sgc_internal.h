@@ -121,6 +121,7 @@ struct DecodeArgs {
     const int32_t *cl_prefix_len;
     const float2 *rope;
     int32_t n_sq, n_queries, step, n_q_heads, n_kv_heads;
+    int32_t key_cap;              // multiple of 16, >= every query's len + step + 1, <= kDecodeMaxKeys
     float scale_log2e;
 };
 

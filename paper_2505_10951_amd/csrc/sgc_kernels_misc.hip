@@ -332,107 +332,176 @@ __global__ void decode_append_kernel(DecodeArgs a)
     }
 }
 
-// One wavefront per (sorted query, query head): scores of the new token against the query's own
-// len + step + 1 keys (lane = key), softmax, weighted V sum (lane = channel pair), merged with the
-// cached-prefix part by the log-sum-exp rule.  fp32 arithmetic.
-__global__ void __launch_bounds__(256) decode_own_keys_kernel(DecodeArgs a)
+// One wavefront per (sorted query, group of G query heads that share a KV head): scores of the new token
+// against the query's own len + step + 1 keys (lane = key, each key read once for the G heads), softmax,
+// weighted V sum (lane = channel pair), merged with the cached-prefix part by the log-sum-exp rule.
+// fp32 arithmetic.  G divides the GQA group size.
+template <int G>
+__global__ void __launch_bounds__(64) decode_own_keys_kernel(DecodeArgs a)
 {
     constexpr int d = 128, half = 64;
-    __shared__ float q_s[4][d];
-    __shared__ float p_s[4][kDecodeMaxKeys];
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    // LDS: the G rotated query rows, then G rows of key_cap weights (key_cap = the batch's largest key count,
+    // rounded up to a page; sized at launch so that many wavefronts fit a CU)
+    extern __shared__ __attribute__((aligned(16))) float dec_lds[];
+    float(*q_s)[d] = reinterpret_cast<float(*)[d]>(dec_lds);
+    const int key_cap = a.key_cap;
+    float *p_base = dec_lds + G * d;
+    const int lane = threadIdx.x;
     const int Hq = a.n_q_heads, Hkv = a.n_kv_heads, g = Hq / Hkv;
-    const int64_t row = (int64_t)blockIdx.x * 4 + wave;
-    const bool live = row < (int64_t)a.n_sq * Hq;
-    int sq = 0, h = 0;
-    if (live) {
-        sq = (int)(row / Hq);
-        h = (int)(row % Hq);
-    }
-    const int hk = h / g;
+    const int units_per_query = Hq / G;
+    const int sq = blockIdx.x / units_per_query;
+    const int h0 = (blockIdx.x % units_per_query) * G;      // first head of the unit
+    const int hk = h0 / g;
     const int n = a.sq_query[sq];
     const int n_keys = a.sq_len[sq] + a.step + 1;
     const int P = a.cl_prefix_len[a.sq_cluster[sq]];
-    const int64_t io = ((int64_t)n * Hq + h) * d;
-    if (live && lane < half / 8) {          // rotated query row into LDS
+    const int64_t io = ((int64_t)n * Hq + h0) * d;           // first of G consecutive rows
+    for (int it = lane; it < G * (half / 8); it += kWave) {    // rotated query rows into LDS
+        const int gi = it / (half / 8), cc = it % (half / 8);
         float x1[8], x2[8];
-        load8(a.q, io + lane * 8, SGC_BF16, x1);
-        load8(a.q, io + half + lane * 8, SGC_BF16, x2);
-        if (a.rope) rope8(x1, x2, a.rope + (int64_t)(P + n_keys - 1) * half + lane * 8);
+        load8(a.q, io + gi * d + cc * 8, SGC_BF16, x1);
+        load8(a.q, io + gi * d + half + cc * 8, SGC_BF16, x2);
+        if (a.rope) rope8(x1, x2, a.rope + (int64_t)(P + n_keys - 1) * half + cc * 8);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            q_s[wave][lane * 8 + i] = x1[i];
-            q_s[wave][half + lane * 8 + i] = x2[i];
+            q_s[gi][cc * 8 + i] = x1[i];
+            q_s[gi][half + cc * 8 + i] = x2[i];
         }
     }
     __syncthreads();
-    if (!live) return;
     const int64_t part = (int64_t)kPageTokens * d * 2;
     const char *pages = a.spool + (int64_t)a.sq_page0[sq] * 2 * Hkv * part + (int64_t)hk * part;
     const int64_t page_stride = 2 * Hkv * part;
     // scores (log2 units), lane = key
-    float m = -INFINITY;
+    float m[G], l[G];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) m[gi] = -INFINITY;
     for (int j = lane; j < n_keys; j += kWave) {
         const char *kp = pages + (int64_t)(j / kPageTokens) * page_stride;
         const int tok = j % kPageTokens;
-        float s = 0.f;
+        uint4 raw[d / 8];                      // the key's 128 channels: all 16 loads in flight before any is used
+#pragma unroll
+        for (int cc = 0; cc < d / 8; ++cc)
+            raw[cc] = *reinterpret_cast<const uint4 *>(kp + (int64_t)k_page_index(tok, cc * 8) * 2);
+        float sc[G];
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) sc[gi] = 0.f;
 #pragma unroll
         for (int cc = 0; cc < d / 8; ++cc) {
+            const uint32_t w[4] = {raw[cc].x, raw[cc].y, raw[cc].z, raw[cc].w};
             float kk[8];
-            load8(kp, k_page_index(tok, cc * 8), SGC_BF16, kk);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) s += q_s[wave][cc * 8 + i] * kk[i];
+            for (int i = 0; i < 4; ++i) {
+                kk[2 * i] = __uint_as_float(w[i] << 16);
+                kk[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+            }
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi) {
+                const float4 qa = *reinterpret_cast<const float4 *>(&q_s[gi][cc * 8]);
+                const float4 qb = *reinterpret_cast<const float4 *>(&q_s[gi][cc * 8 + 4]);
+                sc[gi] += qa.x * kk[0] + qa.y * kk[1] + qa.z * kk[2] + qa.w * kk[3] + qb.x * kk[4] + qb.y * kk[5] +
+                          qb.z * kk[6] + qb.w * kk[7];
+            }
         }
-        s *= a.scale_log2e;
-        p_s[wave][j] = s;
-        m = fmaxf(m, s);
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            sc[gi] *= a.scale_log2e;
+            p_base[gi * key_cap + j] = sc[gi];
+            m[gi] = fmaxf(m[gi], sc[gi]);
+        }
     }
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-    float l = 0.f;
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) {
+        for (int o = 32; o > 0; o >>= 1) m[gi] = fmaxf(m[gi], __shfl_xor(m[gi], o));
+        l[gi] = 0.f;
+    }
     for (int j = lane; j < n_keys; j += kWave) {
-        const float p = exp2f(p_s[wave][j] - m);
-        p_s[wave][j] = p;
-        l += p;
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            const float p = exp2f(p_base[gi * key_cap + j] - m[gi]);
+            p_base[gi * key_cap + j] = p;
+            l[gi] += p;
+        }
     }
-    for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi)
+        for (int o = 32; o > 0; o >>= 1) l[gi] += __shfl_xor(l[gi], o);
     const int n_pages = (n_keys + kPageTokens - 1) / kPageTokens;
-    for (int j = n_keys + lane; j < n_pages * kPageTokens; j += kWave) p_s[wave][j] = 0.f;   // tail of the last page
-    __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0): the wave's LDS writes are done before its lanes read them
+    for (int j = n_keys + lane; j < n_pages * kPageTokens; j += kWave) {     // tail of the last page
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) p_base[gi * key_cap + j] = 0.f;
+    }
+    __syncthreads();
     // weighted V sum, lane = channels (lane, lane + 64); a page holds, per channel, two runs of 8 tokens
-    float acc[2] = {0.f, 0.f};
-    for (int pg = 0; pg < n_pages; ++pg) {
-        const char *vp = pages + (int64_t)pg * page_stride + (int64_t)Hkv * part;
-        const float *pw = &p_s[wave][pg * kPageTokens];
+    float acc[G][2];
 #pragma unroll
-        for (int cI = 0; cI < 2; ++cI) {
-            const int c = lane + cI * 64;
+    for (int gi = 0; gi < G; ++gi) acc[gi][0] = acc[gi][1] = 0.f;
+    // (pages are taken four at a time: their sixteen 16-byte runs are all requested before the first is used)
+    for (int pg0 = 0; pg0 < n_pages; pg0 += 4) {
+        uint4 raw[4][4];
 #pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-                float vv[8];
-                load8(vp, (((c >> 5) * 2 + hh) * 32 + (c & 31)) * 8, SGC_BF16, vv);
+        for (int pi = 0; pi < 4; ++pi) {
+            const int pg = min(pg0 + pi, n_pages - 1);           // a repeated page is skipped below
+            const char *vp = pages + (int64_t)pg * page_stride + (int64_t)Hkv * part;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc[cI] += pw[4 * hh + (i & 3) + 8 * (i >> 2)] * vv[i];
+            for (int cI = 0; cI < 2; ++cI) {
+                const int c = lane + cI * 64;
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh)
+                    raw[pi][cI * 2 + hh] =
+                        *reinterpret_cast<const uint4 *>(vp + (int64_t)((((c >> 5) * 2 + hh) * 32 + (c & 31)) * 8) * 2);
+            }
+        }
+#pragma unroll
+        for (int pi = 0; pi < 4; ++pi) {
+            const int pg = pg0 + pi;
+            if (pg >= n_pages) break;
+#pragma unroll
+            for (int cI = 0; cI < 2; ++cI) {
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    const uint4 rr = raw[pi][cI * 2 + hh];
+                    const uint32_t w[4] = {rr.x, rr.y, rr.z, rr.w};
+                    float vv[8];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        vv[2 * i] = __uint_as_float(w[i] << 16);
+                        vv[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+                    }
+#pragma unroll
+                    for (int gi = 0; gi < G; ++gi) {
+                        const float *pw = p_base + gi * key_cap + pg * kPageTokens + 4 * hh;    // tokens 4 hh + {0..3} and + 8
+                        const float4 pa = *reinterpret_cast<const float4 *>(pw);
+                        const float4 pb = *reinterpret_cast<const float4 *>(pw + 8);
+                        acc[gi][cI] += pa.x * vv[0] + pa.y * vv[1] + pa.z * vv[2] + pa.w * vv[3] + pb.x * vv[4] + pb.y * vv[5] +
+                                       pb.z * vv[6] + pb.w * vv[7];
+                    }
+                }
             }
         }
     }
     // merge with the cached-prefix part (natural-log LSE there; log2 units here)
-    const float lse_own = m + log2f(l);
-    float lse_c = -INFINITY;
-    if (a.lse_cached) lse_c = a.lse_cached[(int64_t)h * a.n_queries + n] * 1.4426950408889634f;
-    const bool use_cached = lse_c > -INFINITY;
-    const float M = fmaxf(lse_own, lse_c);
-    const float wc = use_cached ? exp2f(lse_c - M) : 0.f;
-    const float wo = exp2f(m - M);                       // weight of the unnormalised own sum
-    const float denom = wc + exp2f(lse_own - M);
     uint16_t *og = static_cast<uint16_t *>(a.o);
     const uint16_t *oc = static_cast<const uint16_t *>(a.o_cached);
 #pragma unroll
-    for (int cI = 0; cI < 2; ++cI) {
-        const int c = lane + cI * 64;
-        const float cached = use_cached ? bf16_to_f32(oc[io + c]) : 0.f;
-        og[io + c] = f32_to_bf16((wc * cached + wo * acc[cI]) / denom);
+    for (int gi = 0; gi < G; ++gi) {
+        const int h = h0 + gi;
+        const float lse_own = m[gi] + log2f(l[gi]);
+        float lse_c = -INFINITY;
+        if (a.lse_cached) lse_c = a.lse_cached[(int64_t)h * a.n_queries + n] * 1.4426950408889634f;
+        const bool use_cached = lse_c > -INFINITY;
+        const float M = fmaxf(lse_own, lse_c);
+        const float wc = use_cached ? exp2f(lse_c - M) : 0.f;
+        const float wo = exp2f(m[gi] - M);                       // weight of the unnormalised own sum
+        const float denom = wc + exp2f(lse_own - M);
+#pragma unroll
+        for (int cI = 0; cI < 2; ++cI) {
+            const int c = lane + cI * 64;
+            const float cached = use_cached ? bf16_to_f32(oc[io + gi * d + c]) : 0.f;
+            og[io + gi * d + c] = f32_to_bf16((wc * cached + wo * acc[gi][cI]) / denom);
+        }
+        if (a.lse && lane == 0) a.lse[(int64_t)h * a.n_queries + n] = (M + log2f(denom)) * 0.6931471805599453f;
     }
-    if (a.lse && lane == 0) a.lse[(int64_t)h * a.n_queries + n] = (M + log2f(denom)) * 0.6931471805599453f;
 }
 
 __global__ void fill_zero_bytes_kernel(uint4 *p, size_t n16)
@@ -673,8 +742,16 @@ hipError_t launch_decode_append(const DecodeArgs &d, hipStream_t s)
 hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s)
 {
     if (d.n_sq <= 0) return hipSuccess;
-    const int64_t rows = (int64_t)d.n_sq * d.n_q_heads;
-    hipLaunchKernelGGL(decode_own_keys_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, d);
+    const int g = d.n_q_heads / d.n_kv_heads;
+    const int G = g % 8 == 0 ? 8 : g % 4 == 0 ? 4 : g % 2 == 0 ? 2 : 1;      // heads per wavefront
+    const dim3 grid((unsigned)((int64_t)d.n_sq * (d.n_q_heads / G)));
+    const size_t lds = (size_t)G * (128 + d.key_cap) * sizeof(float);
+    switch (G) {
+        case 8: hipLaunchKernelGGL(decode_own_keys_kernel<8>, grid, dim3(64), lds, s, d); break;
+        case 4: hipLaunchKernelGGL(decode_own_keys_kernel<4>, grid, dim3(64), lds, s, d); break;
+        case 2: hipLaunchKernelGGL(decode_own_keys_kernel<2>, grid, dim3(64), lds, s, d); break;
+        default: hipLaunchKernelGGL(decode_own_keys_kernel<1>, grid, dim3(64), lds, s, d); break;
+    }
     return hipGetLastError();
 }
 

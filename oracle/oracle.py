@@ -424,3 +424,23 @@ def cluster_queries(embeddings: np.ndarray, n_clusters: int, linkage: str = "war
     for c, members in enumerate(clusters):
         labels[members] = c
     return labels
+
+
+# ----------------------------------------------------------------------------------------------
+# Representative subgraph (SubGCache Sec. 3.3): per cluster, the union of all nodes and all edges of the
+# subgraphs its queries retrieved.
+# ----------------------------------------------------------------------------------------------
+def union_subgraphs(labels: Sequence[int], n_clusters: int, node_lists: Sequence[Sequence[int]],
+                    edge_lists: Sequence[Sequence[Tuple[int, int]]]):
+    """Returns (nodes, edges): per cluster the sorted list of distinct node ids and the sorted list of distinct
+    directed edges (src, dst) over the cluster's queries.  Reading where the paper is silent: an edge is the
+    ordered pair as retrieved; the order of the lists (ascending) only makes the prompt deterministic."""
+    nodes = [set() for _ in range(n_clusters)]
+    edges = [set() for _ in range(n_clusters)]
+    for i, lab in enumerate(labels):
+        lab = int(lab)
+        if lab < 0 or lab >= n_clusters:
+            raise ValueError("label out of range")
+        nodes[lab].update(int(x) for x in node_lists[i])
+        edges[lab].update((int(a), int(b)) for a, b in edge_lists[i])
+    return [sorted(s) for s in nodes], [sorted(s) for s in edges]

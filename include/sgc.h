@@ -234,6 +234,19 @@ typedef enum {
 int sgc_cluster_queries(sgc_ctx *ctx, int32_t m, int32_t dim, const float *embeddings, int32_t linkage,
                         int32_t n_clusters, int32_t *labels);
 
+/* ---- representative subgraph (Sec. 3.3) -----------------------------------------------------------
+ * Per cluster, the union of all nodes and of all edges of the subgraphs retrieved by the cluster's
+ * queries.  Query i's subgraph: node ids nodes[node_off[i] .. node_off[i+1]) and directed edges
+ * (edges[2e], edges[2e+1]) for e in [edge_off[i], edge_off[i+1]); duplicates allowed.  Outputs, all
+ * HOST arrays: out_node_off / out_edge_off [n_clusters + 1]; out_nodes with room for node_off[m] ids;
+ * out_edges with room for edge_off[m] pairs.  Cluster k's distinct nodes come out ascending in
+ * out_nodes[out_node_off[k] .. out_node_off[k+1]), its distinct edges ascending by (source,
+ * destination).  (a, b) and (b, a) are different edges.  ctx may be NULL.  Host-only. */
+int sgc_union_subgraphs(sgc_ctx *ctx, int32_t m, const int32_t *labels, int32_t n_clusters,
+                        const int64_t *node_off, const int32_t *nodes, const int64_t *edge_off,
+                        const int32_t *edges, int64_t *out_node_off, int32_t *out_nodes,
+                        int64_t *out_edge_off, int32_t *out_edges);
+
 /* ---- kernel timing (measurement aid; no effect on results) -----------------------------------
  * With timing on, sgc_suffix_prefill_batched records HIP events on its launch stream around the
  * suffix K/V ingest kernel and around the attention kernel.  sgc_timing_last waits for the last

@@ -12,6 +12,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <algorithm>
 #include <limits>
 #include <new>
 #include <vector>
@@ -122,5 +123,70 @@ extern "C" int sgc_cluster_queries(sgc_ctx *ctx, int32_t m, int32_t dim, const f
         while (parent[r] != r) r = parent[r];
         labels[i] = id[r];
     }
+    return SGC_OK;
+}
+
+// ---- representative subgraph (Sec. 3.3) ---------------------------------------------------------
+// For each cluster, the union of all nodes and of all edges of the subgraphs retrieved by the cluster's
+// queries.  Lists come out ascending (edges by source, then destination), which fixes the order in which
+// a caller textualises the representative subgraph and with it the prompt the cache is computed for.
+extern "C" int sgc_union_subgraphs(sgc_ctx *ctx, int32_t m, const int32_t *labels, int32_t n_clusters,
+                                   const int64_t *node_off, const int32_t *nodes, const int64_t *edge_off,
+                                   const int32_t *edges, int64_t *out_node_off, int32_t *out_nodes, int64_t *out_edge_off,
+                                   int32_t *out_edges)
+{
+    if (m < 0 || n_clusters < 1) return fail_cluster(ctx, SGC_EINVAL, "m %d / n_clusters %d out of range", m, n_clusters);
+    if (!out_node_off || !out_edge_off) return fail_cluster(ctx, SGC_EINVAL, "out_node_off / out_edge_off is NULL");
+    if (m > 0 && (!labels || !node_off || !edge_off)) return fail_cluster(ctx, SGC_EINVAL, "labels / node_off / edge_off is NULL");
+    int64_t n_nodes = 0, n_edges = 0;
+    if (m > 0) {
+        if (node_off[0] != 0 || edge_off[0] != 0) return fail_cluster(ctx, SGC_EINVAL, "offsets must start at 0");
+        for (int32_t i = 0; i < m; ++i) {
+            if (labels[i] < 0 || labels[i] >= n_clusters)
+                return fail_cluster(ctx, SGC_EINVAL, "labels[%d] = %d outside [0, %d)", i, labels[i], n_clusters);
+            if (node_off[i + 1] < node_off[i] || edge_off[i + 1] < edge_off[i])
+                return fail_cluster(ctx, SGC_EINVAL, "offsets of query %d decrease", i);
+        }
+        n_nodes = node_off[m];
+        n_edges = edge_off[m];
+    }
+    if ((n_nodes > 0 && (!nodes || !out_nodes)) || (n_edges > 0 && (!edges || !out_edges)))
+        return fail_cluster(ctx, SGC_EINVAL, "nodes / edges / out_nodes / out_edges is NULL");
+    std::vector<std::vector<int32_t>> cn;
+    std::vector<std::vector<uint64_t>> ce;      // edge as (src, dst) packed with a sign flip: sorts like the pair
+    try {
+        cn.resize(n_clusters);
+        ce.resize(n_clusters);
+        for (int32_t i = 0; i < m; ++i) {
+            auto &vn = cn[labels[i]];
+            vn.insert(vn.end(), nodes + node_off[i], nodes + node_off[i + 1]);
+            auto &ve = ce[labels[i]];
+            for (int64_t e = edge_off[i]; e < edge_off[i + 1]; ++e) {
+                const uint64_t a = (uint32_t)edges[2 * e] ^ 0x80000000u, b = (uint32_t)edges[2 * e + 1] ^ 0x80000000u;
+                ve.push_back((a << 32) | b);
+            }
+        }
+    } catch (const std::bad_alloc &) {
+        return fail_cluster(ctx, SGC_ENOMEM, "host allocation failed");
+    }
+    int64_t on = 0, oe = 0;
+    for (int32_t k = 0; k < n_clusters; ++k) {
+        out_node_off[k] = on;
+        out_edge_off[k] = oe;
+        auto &vn = cn[k];
+        std::sort(vn.begin(), vn.end());
+        vn.erase(std::unique(vn.begin(), vn.end()), vn.end());
+        for (int32_t x : vn) out_nodes[on++] = x;
+        auto &ve = ce[k];
+        std::sort(ve.begin(), ve.end());
+        ve.erase(std::unique(ve.begin(), ve.end()), ve.end());
+        for (uint64_t x : ve) {
+            out_edges[2 * oe] = (int32_t)((uint32_t)(x >> 32) ^ 0x80000000u);
+            out_edges[2 * oe + 1] = (int32_t)((uint32_t)x ^ 0x80000000u);
+            ++oe;
+        }
+    }
+    out_node_off[n_clusters] = on;
+    out_edge_off[n_clusters] = oe;
     return SGC_OK;
 }

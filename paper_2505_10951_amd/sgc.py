@@ -27,6 +27,7 @@ EXPORTS = [
     "sgc_cache_cluster_pages", "sgc_prefix_prefill", "sgc_prefix_prefill_batched", "sgc_assign_clusters", "sgc_plan_upload",
     "sgc_plan_get_info", "sgc_plan_destroy", "sgc_suffix_prefill_batched", "sgc_cache_export", "sgc_cache_import",
     "sgc_timing_enable", "sgc_timing_last", "sgc_cluster_queries", "sgc_plan_enable_decode", "sgc_decode_step_batched",
+    "sgc_union_subgraphs",
 ]
 
 
@@ -96,6 +97,8 @@ def lib() -> ctypes.CDLL:
         L.sgc_cache_import.argtypes = [vp, vp, i32, i32, vp, vp, f32p, f32p, vp]
         L.sgc_plan_enable_decode.argtypes = [vp, i32]
         L.sgc_decode_step_batched.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        L.sgc_union_subgraphs.argtypes = [vp, i32, i32p, i32, i64p, i32p, i64p, i32p, i64p, i32p, i64p, i32p]
         L.sgc_cluster_queries.argtypes = [vp, i32, i32, f32p, i32, i32, i32p]
         L.sgc_timing_enable.argtypes = [vp, ctypes.c_int]
         L.sgc_timing_last.argtypes = [vp, f32p, f32p]
@@ -281,6 +284,40 @@ def sgc_cluster_queries(ctx, embeddings: np.ndarray, n_clusters: int, linkage="w
     if rc < 0:
         raise SgcError(rc, sgc_last_error(ctx) if ctx is not None else "sgc_cluster_queries failed")
     return labels
+
+
+def sgc_union_subgraphs(ctx, labels: Sequence[int], n_clusters: int, node_lists, edge_lists):
+    """node_lists[i]: node ids of query i's subgraph; edge_lists[i]: its (src, dst) pairs.  Returns (nodes,
+    edges): per cluster an int32 array of node ids and an int32 [n][2] array of edges (ctx may be None)."""
+    labels = _i32(labels)
+    m = labels.shape[0]
+    if len(node_lists) != m or len(edge_lists) != m:
+        raise ValueError("one node list and one edge list per query")
+    node_off = np.zeros(m + 1, dtype=np.int64)
+    edge_off = np.zeros(m + 1, dtype=np.int64)
+    for i in range(m):
+        node_off[i + 1] = node_off[i] + len(node_lists[i])
+        edge_off[i + 1] = edge_off[i] + len(edge_lists[i])
+    nodes = np.zeros(max(int(node_off[m]), 1), dtype=np.int32)
+    edges = np.zeros((max(int(edge_off[m]), 1), 2), dtype=np.int32)
+    for i in range(m):
+        if len(node_lists[i]):
+            nodes[node_off[i]:node_off[i + 1]] = np.asarray(node_lists[i], dtype=np.int32)
+        if len(edge_lists[i]):
+            edges[edge_off[i]:edge_off[i + 1]] = np.asarray(edge_lists[i], dtype=np.int32).reshape(-1, 2)
+    out_noff = np.zeros(n_clusters + 1, dtype=np.int64)
+    out_eoff = np.zeros(n_clusters + 1, dtype=np.int64)
+    out_nodes = np.zeros_like(nodes)
+    out_edges = np.zeros_like(edges)
+    i32p, i64p = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
+    rc = lib().sgc_union_subgraphs(ctx, m, labels.ctypes.data_as(i32p), int(n_clusters), node_off.ctypes.data_as(i64p),
+                                   nodes.ctypes.data_as(i32p), edge_off.ctypes.data_as(i64p), edges.ctypes.data_as(i32p),
+                                   out_noff.ctypes.data_as(i64p), out_nodes.ctypes.data_as(i32p),
+                                   out_eoff.ctypes.data_as(i64p), out_edges.ctypes.data_as(i32p))
+    if rc < 0:
+        raise SgcError(rc, sgc_last_error(ctx) if ctx is not None else "sgc_union_subgraphs failed")
+    return ([out_nodes[out_noff[k]:out_noff[k + 1]].copy() for k in range(n_clusters)],
+            [out_edges[out_eoff[k]:out_eoff[k + 1]].copy() for k in range(n_clusters)])
 
 
 def sgc_timing_enable(ctx, on: bool) -> None:

@@ -23,6 +23,7 @@ _KIND_SUFFIX_Q, _KIND_SUFFIX_K, _KIND_SUFFIX_V = 4, 5, 6
 _KIND_STRUCT, _KIND_OUTLIER = 7, 8
 _KIND_EMBED_CENTRE, _KIND_EMBED_NOISE = 9, 10
 _KIND_DECODE_Q, _KIND_DECODE_K, _KIND_DECODE_V = 11, 12, 13
+_KIND_GRAPH = 14
 
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
@@ -167,6 +168,22 @@ class Workload:
         centres = self._rng(0, _KIND_EMBED_CENTRE, 0).standard_normal((max(self.n_clusters, 1), dim), dtype=np.float32)
         noise = self._rng(0, _KIND_EMBED_NOISE, 0).standard_normal((self.n_queries, dim), dtype=np.float32)
         return np.ascontiguousarray(centres[self.labels] + np.float32(overlap) * noise, dtype=np.float32)
+
+    def retrieved_subgraphs(self, graph_nodes: int = 5000, core: int = 24, extra: int = 4):
+        """Stand-in for the subgraphs retrieved per query (the paper retrieves a few dozen nodes per query from the
+        Scene Graph / OAG graphs): queries of a cluster draw most of their nodes from the cluster's `core` nodes
+        and add `extra` nodes of their own; edges are random pairs among a query's nodes.  Returns (node_lists,
+        edge_lists) with duplicates left in."""
+        rng = self._rng(0, _KIND_GRAPH, 0)
+        cores = [rng.choice(graph_nodes, size=core, replace=False) for _ in range(max(self.n_clusters, 1))]
+        node_lists, edge_lists = [], []
+        for n in range(self.n_queries):
+            own = np.concatenate([rng.choice(cores[int(self.labels[n])], size=max(core * 3 // 4, 1), replace=True),
+                                  rng.integers(0, graph_nodes, size=extra)])
+            pairs = rng.choice(own, size=(2 * own.size, 2))
+            node_lists.append(own.astype(np.int32))
+            edge_lists.append(pairs.astype(np.int32))
+        return node_lists, edge_lists
 
     def suffix_qkv(self, layer: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
         """All queries packed in original order: Q [T][Hq][d], K, V [T][Hkv][d]."""

@@ -64,7 +64,19 @@ __device__ unsigned long long g_phase[2048 * 8 * 8];   // [block < 2048][wave < 
 #define SGC_MARK(i) do { } while (0)
 #endif
 
-__device__ inline float half_swap(float x) { return __shfl_xor(x, 32); }
+// Combine a value with the one held by the lane 32 away (the other half of a score row), through
+// v_permlane32_swap: with both operands x, the two results hold x's lower half and x's upper half, each
+// in all 64 lanes.
+__device__ inline float half_max(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float half_sum(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
 // Unpacks 2 fp8 e4m3 codes (low or high half of w) to bf16 (exact: e4m3 is a subset of bf16).
 __device__ inline uint32_t fp8x2_to_bf16x2(uint32_t w, bool high)
@@ -510,7 +522,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             float tmax = s[mi][0];
 #pragma unroll
             for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, s[mi][r]);
-            tmax = fmaxf(tmax, half_swap(tmax));
+            tmax = half_max(tmax);
             const bool has = tmax > -INFINITY;
             if (!FOLD) tmax -= m_ref[mi];                      // relative to m_ref (FOLD: the scores already are)
             const float delta = seen[mi] ? fmaxf(tmax, 0.f) : (has ? tmax : 0.f);     // new m_ref - old m_ref
@@ -751,27 +763,44 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             for (int mi = 0; mi < MI; ++mi) mine |= valid[mi] && sq[mi] == q && qpos[mi] >= key0;
             if (q >= wsq_min && q <= wsq_max && __any(mine)) {
                 const char *kc = kbuf_of(kpar), *vc = vbuf_of(vpar);
-                auto keep = [&](int mi, int j) __attribute__((always_inline)) { return sq[mi] == q && key0 + j <= qpos[mi]; };
+                // key j of the tile is visible to a row iff j <= reach (-1: another query's row); the 4 h of
+                // the lane's key index is taken off once
+                int reach[MI];
+                bool far = false;
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) {
+                    const int r0 = (valid[mi] && sq[mi] == q) ? qpos[mi] - key0 : -1;
+                    far |= r0 >= 32;
+                    reach[mi] = r0 - 4 * h;
+                }
+                const bool second_half = __any(far);        // does any row of this wave see keys 32..63 of the tile?
+                auto keep = [&](int mi, int j) __attribute__((always_inline)) { return j - 4 * h <= reach[mi]; };
 #pragma unroll
                 for (int i = 0; i < 8; ++i) frag[i] = k_block(kc, 0, i);
-                qk_half(s0, [&](int i) __attribute__((always_inline)) { frag[i] = k_block(kc, 1, i); });
-                qk_half(s1, [&](int i) __attribute__((always_inline)) { frag[i] = v_block(vc, 0, i); });
-                // both products started from the same -m_ref; a raise by half 0 is passed on to half 1
+                // all products of the tile start from the same -m_ref; a raise by half 0 is passed on to half 1
                 float before[MI];
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi) before[mi] = m_ref[mi];
+                if (second_half) {
+                    qk_half(s0, [&](int i) __attribute__((always_inline)) { frag[i] = k_block(kc, 1, i); });
+                    qk_half(s1, [&](int i) __attribute__((always_inline)) { frag[i] = v_block(vc, 0, i); });
+                } else {
+                    qk_half(s0, [&](int i) __attribute__((always_inline)) { frag[i] = v_block(vc, 0, i); });
+                }
                 if (KV_FP8) rescale_self(s0, before);
                 raise_reference(s0, 0, true, keep);
                 weights(s0);
-                pv_half([&](int i) __attribute__((always_inline)) { frag[i] = v_block(vc, 1, i); });
-                if (KV_FP8) rescale_self(s1, before);
+                if (second_half) {
+                    pv_half([&](int i) __attribute__((always_inline)) { frag[i] = v_block(vc, 1, i); });
+                    if (KV_FP8) rescale_self(s1, before);
 #pragma unroll
-                for (int mi = 0; mi < MI; ++mi)
+                    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (FOLD) s1[mi][r] -= m_ref[mi] - before[mi];
-                raise_reference(s1, 1, true, keep);
-                weights(s1);
+                        for (int r = 0; r < 16; ++r)
+                            if (FOLD) s1[mi][r] -= m_ref[mi] - before[mi];
+                    raise_reference(s1, 1, true, keep);
+                    weights(s1);
+                }
                 pv_half(no_refill);
             }
             if (more) __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -789,7 +818,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     uint16_t *og = static_cast<uint16_t *>(o_base);
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
-        const float l = l_part[mi] + half_swap(l_part[mi]);
+        const float l = half_sum(l_part[mi]);
         const float inv_l = (v_scaled ? 1.0f : v_scale) / l;
         if (valid[mi]) {
 #pragma unroll

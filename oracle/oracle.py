@@ -239,6 +239,55 @@ def quantise_e4m3(x) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
 
 
 # ----------------------------------------------------------------------------------------------
+# The attention layer around the cache (SubGCache Sec. 3.4: the representative prompt, and then each
+# query's question tokens, pass through the LLM's transformer layers; in every layer the hidden states
+# are projected to queries, keys and values, the keys and values of the prompt are what the cache
+# keeps, and the attention output is projected back to the model width).  Weights are stored "out
+# features x in features"; a projection is y[t][f] = sum_i x[t][i] w[f][i].  The matrix product is a
+# library step (numpy, fp64); nothing is rounded between the steps.
+# ----------------------------------------------------------------------------------------------
+def project_qkv(x, w_qkv, n_q_heads: int, n_kv_heads: int, head_dim: int):
+    """x [n][D], w_qkv [(Hq + 2 Hkv) d][D] (rows: Q heads, K heads, V heads, head-major).
+    Returns q [n][Hq][d], k [n][Hkv][d], v [n][Hkv][d], before any rotation."""
+    x = _f64(x)
+    w = _f64(w_qkv)
+    nq, nk = n_q_heads * head_dim, n_kv_heads * head_dim
+    assert w.shape == (nq + 2 * nk, x.shape[1])
+    y = x @ w.T
+    n = x.shape[0]
+    return (np.ascontiguousarray(y[:, :nq]).reshape(n, n_q_heads, head_dim),
+            np.ascontiguousarray(y[:, nq:nq + nk]).reshape(n, n_kv_heads, head_dim),
+            np.ascontiguousarray(y[:, nq + nk:]).reshape(n, n_kv_heads, head_dim))
+
+
+def project_out(o, w_o) -> np.ndarray:
+    """o [n][Hq][d] (heads concatenated head-major along the feature axis), w_o [D][Hq d] -> y [n][D]."""
+    o = _f64(o)
+    w = _f64(w_o)
+    n = o.shape[0]
+    flat = o.reshape(n, -1)
+    assert w.shape[1] == flat.shape[1]
+    return flat @ w.T
+
+
+def attention_layer_prefix(x, w_qkv, w_o, n_q_heads: int, n_kv_heads: int, head_dim: int, rope_base: float,
+                           scale: Optional[float] = None):
+    """One layer over a cluster's prompt.  Returns (cache_k, cache_v, y [P][D]): the cache this layer keeps
+    (projected K rotated at 0..P-1, projected V) and the layer's attention output projected back."""
+    q, k, v = project_qkv(x, w_qkv, n_q_heads, n_kv_heads, head_dim)
+    cache_k, cache_v, o, _ = prefix_prefill(q, k, v, rope_base, scale)
+    return cache_k, cache_v, project_out(o, w_o)
+
+
+def attention_layer_suffix(cache_k, cache_v, x, w_qkv, w_o, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                           rope_base: float, scale: Optional[float] = None) -> np.ndarray:
+    """One layer over one query's question tokens appended to its cluster's cache: y [S][D]."""
+    q, k, v = project_qkv(x, w_qkv, n_q_heads, n_kv_heads, head_dim)
+    o, _, _ = suffix_prefill(cache_k, cache_v, q, k, v, rope_base, scale)
+    return project_out(o, w_o)
+
+
+# ----------------------------------------------------------------------------------------------
 # Independent routine 1: dense numpy full-causal attention over one whole sequence
 # ----------------------------------------------------------------------------------------------
 def rope_numpy(x: np.ndarray, pos: np.ndarray, base: float) -> np.ndarray:

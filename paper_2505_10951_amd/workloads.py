@@ -24,6 +24,7 @@ _KIND_STRUCT, _KIND_OUTLIER = 7, 8
 _KIND_EMBED_CENTRE, _KIND_EMBED_NOISE = 9, 10
 _KIND_DECODE_Q, _KIND_DECODE_K, _KIND_DECODE_V = 11, 12, 13
 _KIND_GRAPH = 14
+_KIND_W_QKV, _KIND_W_O, _KIND_PREFIX_X, _KIND_SUFFIX_X = 15, 16, 17, 18
 
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
@@ -184,6 +185,40 @@ class Workload:
             node_lists.append(own.astype(np.int32))
             edge_lists.append(pairs.astype(np.int32))
         return node_lists, edge_lists
+
+    # ---- the attention layer around the kernel (hidden states and projection weights) -------
+    def layer_weights(self, d_model: int, layer: int = 0) -> Tuple[np.ndarray, np.ndarray]:
+        """Random stand-ins for a trained layer's projections (the paper's backbones keep their weights in
+        "out features x in features" order): w_qkv [(Hq + 2 Hkv) d][d_model], rows = Q heads, then K heads,
+        then V heads, head-major; w_o [d_model][Hq d].  Entries are N(0, 1 / in_features), so projected Q, K, V
+        have unit variance like the direct Q, K, V recipes above."""
+        n_qkv = (self.n_q_heads + 2 * self.n_kv_heads) * self.head_dim
+        n_o = self.n_q_heads * self.head_dim
+        w_qkv = self._rng(layer, _KIND_W_QKV, 0).standard_normal((n_qkv, d_model), dtype=np.float32)
+        w_qkv *= np.float32(1.0 / np.sqrt(d_model))
+        w_qkv[: n_o] *= np.float32(self.q_gain)
+        w_o = self._rng(layer, _KIND_W_O, 0).standard_normal((d_model, n_o), dtype=np.float32)
+        w_o *= np.float32(1.0 / np.sqrt(n_o))
+        return self._store(w_qkv), self._store(w_o)
+
+    def prefix_x(self, cluster: int, d_model: int, layer: int = 0) -> np.ndarray:
+        """Hidden states entering the layer for the cluster's prompt tokens: [P_c][d_model], N(0, 1)."""
+        P = int(self.prefix_len[cluster])
+        return self._store(self._rng(layer, _KIND_PREFIX_X, cluster).standard_normal((P, d_model), dtype=np.float32))
+
+    def suffix_x_query(self, n: int, d_model: int, layer: int = 0) -> np.ndarray:
+        S = int(self.suffix_len[n])
+        return self._store(self._rng(layer, _KIND_SUFFIX_X, n).standard_normal((S, d_model), dtype=np.float32))
+
+    def suffix_x(self, d_model: int, layer: int = 0) -> np.ndarray:
+        """All queries' question-token hidden states packed in original order: [T][d_model]."""
+        cu = self.cu_seqlens
+        x = np.empty((self.total_suffix_tokens, d_model), dtype=np.float32)
+        for n in range(self.n_queries):
+            a, b = int(cu[n]), int(cu[n + 1])
+            if b > a:
+                x[a:b] = self.suffix_x_query(n, d_model, layer)
+        return x
 
     def suffix_qkv(self, layer: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
         """All queries packed in original order: Q [T][Hq][d], K, V [T][Hkv][d]."""

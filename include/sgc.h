@@ -147,7 +147,9 @@ int sgc_cache_cluster_pages(const sgc_cache *cache, int32_t cluster_id, int32_t 
  * dev_q / dev_o: [prefix_len][Hq][d] or both NULL.  When given, o receives the causal
  * self-attention of the prefix (row i sees keys 0..i, read back from the cache as stored) and
  * dev_lse (may be NULL) [Hq][prefix_len] fp32 the natural-log log-sum-exp of the scaled scores.
- * prefix_len must equal the length given to sgc_cache_alloc_cluster. */
+ * prefix_len must equal the length given to sgc_cache_alloc_cluster.
+ * dev_k = dev_v = NULL (dev_q and dev_o given): the pages already hold this layer's keys and values
+ * (sgc_project_qkv_prefix, sgc_cache_import, an earlier call); only the attention output is computed. */
 int sgc_prefix_prefill(sgc_ctx *ctx, sgc_cache *cache, int32_t cluster_id, int32_t layer,
                        const void *dev_q, const void *dev_k, const void *dev_v, void *dev_o,
                        float *dev_lse, int32_t prefix_len, void *hip_stream);
@@ -246,6 +248,43 @@ int sgc_union_subgraphs(sgc_ctx *ctx, int32_t m, const int32_t *labels, int32_t 
                         const int64_t *node_off, const int32_t *nodes, const int64_t *edge_off,
                         const int32_t *edges, int64_t *out_node_off, int32_t *out_nodes,
                         int64_t *out_edge_off, int32_t *out_edges);
+
+/* ---- the attention layer's projections (Sec. 3.4) -------------------------------------------------
+ * Sec. 3.4 feeds the representative prompt, and then every query's question tokens, through the LLM's
+ * layers.  Inside a layer the hidden states x [rows][d_model] are projected to queries, keys and values,
+ * and the attention output is projected back: y = Attention(x Wq^T, x Wk^T, x Wv^T) Wo^T.  Weights are
+ * DEVICE arrays in io_dtype, stored "out features x in features", row-major:
+ *   dev_w_qkv [(Hq + 2 Hkv) d][d_model]: rows are the Q heads, then the K heads, then the V heads, each
+ *             head's d channels together;        dev_w_o [d_model][Hq d].
+ * Products accumulate in fp32; q, keys, values and y are rounded to io_dtype (kv_dtype in the cache)
+ * once, when stored.  Every row of x, q, y must start 16-byte aligned.  Normalisation and residual
+ * connections are the caller's.
+ *
+ * sgc_project_qkv_prefix[_batched]: x of each cluster's prompt [prefix_len][d_model] -> keys rotated at
+ * positions 0..prefix_len-1 and values written into the cluster's pages exactly as sgc_prefix_prefill
+ * stores them (an fp8 cache takes its per-head scales from the projected keys and values), and, when
+ * dev_q is given, the un-rotated queries [prefix_len][Hq][d] into dev_q (pass them to
+ * sgc_prefix_prefill with dev_k = dev_v = NULL to get the prompt's attention output).  Batched form:
+ * dev_x and dev_q are HOST arrays of n device pointers (dev_q may be NULL or hold NULL entries).
+ *
+ * sgc_project_qkv_suffix: x [T][d_model] packed like q of sgc_suffix_prefill_batched -> un-rotated queries
+ * into dev_q [T][Hq][d]; keys (rotated at prefix_len + j) and values are kept with the plan for `layer`
+ * until the next projection or until the plan changes.  Follow it with sgc_suffix_prefill_batched for the
+ * same layer with dev_k = dev_v = NULL; without a projection for that layer that call returns SGC_ESTATE.
+ *
+ * sgc_project_out: dev_o [n_tokens][Hq][d] -> dev_y [n_tokens][d_model].
+ * All three are asynchronous on hip_stream. */
+int sgc_project_qkv_prefix(sgc_ctx *ctx, sgc_cache *cache, int32_t cluster_id, int32_t layer, const void *dev_x,
+                           const void *dev_w_qkv, int32_t d_model, void *dev_q, int32_t prefix_len,
+                           void *hip_stream);
+int sgc_project_qkv_prefix_batched(sgc_ctx *ctx, sgc_cache *cache, int32_t n, const int32_t *cluster_ids,
+                                   int32_t layer, const void *const *dev_x, const void *dev_w_qkv,
+                                   int32_t d_model, void *const *dev_q, void *hip_stream);
+int sgc_project_qkv_suffix(sgc_ctx *ctx, const sgc_cache *cache, sgc_plan *plan, int32_t layer,
+                           const void *dev_x, const void *dev_w_qkv, int32_t d_model, void *dev_q,
+                           void *hip_stream);
+int sgc_project_out(sgc_ctx *ctx, const void *dev_o, const void *dev_w_o, int32_t d_model, int64_t n_tokens,
+                    void *dev_y, void *hip_stream);
 
 /* ---- kernel timing (measurement aid; no effect on results) -----------------------------------
  * With timing on, sgc_suffix_prefill_batched records HIP events on its launch stream around the

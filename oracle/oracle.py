@@ -265,7 +265,7 @@ def project_out(o, w_o) -> np.ndarray:
     o = _f64(o)
     w = _f64(w_o)
     n = o.shape[0]
-    flat = o.reshape(n, -1)
+    flat = o.reshape(n, o.shape[1] * o.shape[2])
     assert w.shape[1] == flat.shape[1]
     return flat @ w.T
 

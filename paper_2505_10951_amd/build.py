@@ -10,7 +10,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libsgc.so")
-SOURCES = ["sgc_host.hip", "sgc_kernels_misc.hip", "sgc_attn_mfma.hip", "sgc_cluster.hip"]
+SOURCES = ["sgc_host.hip", "sgc_kernels_misc.hip", "sgc_attn_mfma.hip", "sgc_cluster.hip", "sgc_gemm.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

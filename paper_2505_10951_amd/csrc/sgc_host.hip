@@ -423,6 +423,9 @@ void plan_free_device(sgc_plan *pl)
 {
     dev_release(pl->ctx, pl->dec_scratch, pl->last_stream);
     pl->dec_scratch = sgc_dev_block{};
+    dev_release(pl->ctx, pl->proj_kv, pl->last_stream);
+    pl->proj_kv = sgc_dev_block{};
+    pl->proj_state = 0;
     dev_release(pl->ctx, pl->blob, pl->last_stream);
     dev_release(pl->ctx, pl->spool_block, pl->last_stream);
     pl->blob = sgc_dev_block{};
@@ -613,7 +616,10 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
     if (!c || c->ctx != ctx) return fail(ctx, SGC_EINVAL, "cache is NULL or belongs to another context");
     if (n < 0) return fail(ctx, SGC_EINVAL, "n %d < 0", n);
     if (n == 0) return SGC_OK;
-    if (!cluster_ids || !dev_k || !dev_v) return fail(ctx, SGC_EINVAL, "cluster_ids / dev_k / dev_v is NULL");
+    // dev_k and dev_v both NULL: the pages already hold this layer's keys (sgc_project_qkv_prefix*), attend only
+    const bool attend_only = !dev_k && !dev_v;
+    if (!cluster_ids || (!attend_only && (!dev_k || !dev_v))) return fail(ctx, SGC_EINVAL, "cluster_ids / dev_k / dev_v is NULL");
+    if (attend_only && !dev_q) return fail(ctx, SGC_EINVAL, "neither keys to store nor queries to attend with");
     if ((dev_q == nullptr) != (dev_o == nullptr)) return fail(ctx, SGC_EINVAL, "dev_q and dev_o must both be given or both be NULL");
     if (dev_lse && !dev_o) return fail(ctx, SGC_EINVAL, "dev_lse given without dev_q/dev_o");
     const int Hkv = ctx->p.n_kv_heads, g = ctx->p.n_q_heads / Hkv;
@@ -630,11 +636,11 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
         const void *q = dev_q ? dev_q[i] : nullptr;
         void *o = dev_o ? dev_o[i] : nullptr;
         const float *lse = dev_lse ? dev_lse[i] : nullptr;
-        if (!dev_k[i] || !dev_v[i]) return fail(ctx, SGC_EINVAL, "dev_k / dev_v of cluster %d is NULL", cluster_ids[i]);
+        if (!attend_only && (!dev_k[i] || !dev_v[i])) return fail(ctx, SGC_EINVAL, "dev_k / dev_v of cluster %d is NULL", cluster_ids[i]);
         if ((q == nullptr) != (o == nullptr))
             return fail(ctx, SGC_EINVAL, "dev_q and dev_o of cluster %d must both be given or both be NULL", cluster_ids[i]);
         if (lse && !o) return fail(ctx, SGC_EINVAL, "dev_lse of cluster %d given without dev_q/dev_o", cluster_ids[i]);
-        if (!aligned16(dev_k[i]) || !aligned16(dev_v[i]) || !aligned16(q) || !aligned16(o) || !aligned16(lse))
+        if ((!attend_only && (!aligned16(dev_k[i]) || !aligned16(dev_v[i]))) || !aligned16(q) || !aligned16(o) || !aligned16(lse))
             return fail(ctx, SGC_EINVAL, "device pointers must be 16-byte aligned");
     }
     if (max_len == 0) return SGC_OK;
@@ -656,8 +662,8 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
         if (P == 0) continue;
         PrefixJob j{};
         j.q = dev_q ? dev_q[i] : nullptr;
-        j.k = dev_k[i];
-        j.v = dev_v[i];
+        j.k = attend_only ? nullptr : dev_k[i];
+        j.v = attend_only ? nullptr : dev_v[i];
         j.o = dev_o ? dev_o[i] : nullptr;
         j.lse = dev_lse ? dev_lse[i] : nullptr;
         j.scale_kv = c->d_scale ? c->d_scale + ((size_t)id * ctx->p.n_layers + layer) * 2 * Hkv : nullptr;
@@ -741,7 +747,7 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
     const int32_t *d_page_job = reinterpret_cast<const int32_t *>(blk.p + jobs_bytes);
     const Tile *d_tiles = reinterpret_cast<const Tile *>(blk.p + jobs_bytes + pj_bytes);
     hipError_t e = hipSuccess;
-    if (rc == SGC_OK)
+    if (rc == SGC_OK && !attend_only)
         e = launch_prefix_ingest(c->geom, layer, c->d_page_table, d_jobs, (int)jobs.size(), d_page_job, (int)page_job.size(),
                                  ctx->p.io_dtype, ctx->p.rope_base > 0.0f ? ctx->d_rope : nullptr, s);
     if (rc == SGC_OK && e == hipSuccess && any_q) {
@@ -787,8 +793,9 @@ int sgc_prefix_prefill(sgc_ctx *ctx, sgc_cache *c, int32_t cluster_id, int32_t l
     if ((dev_q == nullptr) != (dev_o == nullptr)) return fail(ctx, SGC_EINVAL, "dev_q and dev_o must both be given or both be NULL");
     if (dev_lse && !dev_o) return fail(ctx, SGC_EINVAL, "dev_lse given without dev_q/dev_o");
     if (prefix_len == 0) return SGC_OK;
-    if (!dev_k || !dev_v) return fail(ctx, SGC_EINVAL, "dev_k / dev_v is NULL");
-    return sgc_prefix_prefill_batched(ctx, c, 1, &cluster_id, layer, dev_q ? &dev_q : nullptr, &dev_k, &dev_v,
+    if ((dev_k == nullptr) != (dev_v == nullptr)) return fail(ctx, SGC_EINVAL, "dev_k / dev_v is NULL");
+    return sgc_prefix_prefill_batched(ctx, c, 1, &cluster_id, layer, dev_q ? &dev_q : nullptr, dev_k ? &dev_k : nullptr,
+                                      dev_v ? &dev_v : nullptr,
                                       dev_o ? &dev_o : nullptr, dev_lse ? &dev_lse : nullptr, hip_stream);
 }
 
@@ -896,6 +903,13 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
     }
     pl->tok_info.resize(pl->tok_src.size());
     for (size_t i = 0; i < pl->tok_src.size(); ++i) pl->tok_info[i] = {pl->tok_src[i], pl->tok_qpos[i], pl->tok_sq[i], 0};
+    // where the projection's epilogue puts the key and value of each packed row: {16 * page + slot, position}
+    pl->row_dest.resize(2 * pl->tok_src.size());
+    for (size_t i = 0; i < pl->tok_src.size(); ++i) {
+        const int32_t sq = pl->tok_sq[i], qpos = pl->tok_qpos[i];
+        pl->row_dest[2 * (size_t)pl->tok_src[i]] = (pl->sq_page0[sq] + qpos / kPageTokens) * kPageTokens + qpos % kPageTokens;
+        pl->row_dest[2 * (size_t)pl->tok_src[i] + 1] = pl->cl_prefix_len[pl->sq_cluster[sq]] + qpos;
+    }
 
     struct Piece {
         const void *src;
@@ -918,6 +932,7 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
         {pl->sq_query.data(), pl->sq_query.size() * 4, (const void **)&pl->d_sq_query},
         {pl->dtiles.data(), pl->dtiles.size() * sizeof(Tile), (const void **)&pl->d_dtiles},
         {pl->dtok.data(), pl->dtok.size() * sizeof(TokInfo), (const void **)&pl->d_dtok},
+        {pl->row_dest.data(), pl->row_dest.size() * 4, (const void **)&pl->d_row_dest},
     };
     size_t total = 0;
     for (const Piece &p : pieces) total += (p.bytes + 255) / 256 * 256 + 256;
@@ -1005,7 +1020,18 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
             return fail(ctx, SGC_ESTATE, "cluster %d changed since the plan was made", k);
     }
     if (pl->total_tokens == 0) return SGC_OK;
-    if (!dev_q || !dev_k || !dev_v || !dev_o) return fail(ctx, SGC_EINVAL, "dev_q / dev_k / dev_v / dev_o is NULL");
+    // dev_k and dev_v both NULL: take the keys sgc_project_qkv_suffix made for this layer
+    const bool projected = !dev_k && !dev_v;
+    if (projected) {
+        if (pl->proj_state == 0 || pl->proj_layer != layer || !pl->uploaded)
+            return fail(ctx, SGC_ESTATE, "no projected keys for layer %d: call sgc_project_qkv_suffix first", layer);
+        if (pl->proj_state == 2) {
+            dev_k = pl->proj_kv.p;
+            dev_v = pl->proj_kv.p + (size_t)pl->total_tokens * ctx->p.n_kv_heads * ctx->p.head_dim * dtype_bytes(ctx->p.io_dtype);
+        }
+    }
+    const bool skip_ingest = projected && pl->proj_state == 1;
+    if (!dev_q || !dev_o || (!skip_ingest && (!dev_k || !dev_v))) return fail(ctx, SGC_EINVAL, "dev_q / dev_k / dev_v / dev_o is NULL");
     if (!aligned16(dev_q) || !aligned16(dev_k) || !aligned16(dev_v) || !aligned16(dev_o) || !aligned16(dev_lse))
         return fail(ctx, SGC_EINVAL, "device pointers must be 16-byte aligned");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -1040,7 +1066,7 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
     a.spool = pl->d_spool + (pl->decode_cap > 0 ? (size_t)layer * pl->spool_layer_bytes : 0);
     a.total_tokens = pl->total_tokens;
     if (ctx->timing) SGC_HIP(ctx, hipEventRecord(ctx->ev[0], s));
-    if (ctx->use_mfma) SGC_HIP(ctx, launch_suffix_ingest(a, pl->d_spage_sq, (int)pl->spage_sq.size(), s));
+    if (ctx->use_mfma && !skip_ingest) SGC_HIP(ctx, launch_suffix_ingest(a, pl->d_spage_sq, (int)pl->spage_sq.size(), s));
     if (ctx->timing) SGC_HIP(ctx, hipEventRecord(ctx->ev[1], s));
     if (ctx->use_mfma) {
         SGC_HIP(ctx, launch_attn_mfma(a, ctx->mfma_variant, s));
@@ -1226,6 +1252,257 @@ int sgc_cache_import(sgc_ctx *ctx, sgc_cache *cache, int32_t cluster_id, int32_t
 {
     return export_import(ctx, cache, cluster_id, layer, const_cast<void *>(dev_k), const_cast<void *>(dev_v),
                          const_cast<float *>(host_k_scale), const_cast<float *>(host_v_scale), hip_stream, false);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The linear maps around the attention (SubGCache Sec. 3.4: prompt and question tokens pass through the LLM's
+// layers; each layer projects its hidden states to Q, K, V and the attention output back to the model width).
+static bool gemm_covers(const sgc_ctx *ctx, int64_t K, int64_t N)
+{
+    return ctx->p.io_dtype == SGC_BF16 && K >= 64 && K % 64 == 0 && K <= (1 << 20) && N >= 128 && N % 128 == 0;
+}
+
+int sgc_project_qkv_prefix_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int32_t *cluster_ids, int32_t layer,
+                                   const void *const *dev_x, const void *dev_w_qkv, int32_t d_model, void *const *dev_q,
+                                   void *hip_stream)
+{
+    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (!c || c->ctx != ctx) return fail(ctx, SGC_EINVAL, "cache is NULL or belongs to another context");
+    if (n < 0) return fail(ctx, SGC_EINVAL, "n %d < 0", n);
+    if (n == 0) return SGC_OK;
+    if (!cluster_ids || !dev_x || !dev_w_qkv) return fail(ctx, SGC_EINVAL, "cluster_ids / dev_x / dev_w_qkv is NULL");
+    if (d_model <= 0) return fail(ctx, SGC_EINVAL, "d_model %d <= 0", d_model);
+    if (!aligned16(dev_w_qkv) || ((int64_t)d_model * dtype_bytes(ctx->p.io_dtype)) % 16 != 0)
+        return fail(ctx, SGC_EINVAL, "dev_w_qkv and every row of x must be 16-byte aligned");
+    const int Hq = ctx->p.n_q_heads, Hkv = ctx->p.n_kv_heads, d = ctx->p.head_dim;
+    const int nq = Hq * d, nkv = Hkv * d, N = nq + 2 * nkv, K = d_model;
+    const size_t eb = (size_t)dtype_bytes(ctx->p.io_dtype);
+    int rc;
+    std::vector<char> seen(c->max_clusters, 0);
+    int max_len = 0;
+    int64_t total_rows = 0;
+    bool any_q = false;
+    for (int32_t i = 0; i < n; ++i) {
+        if ((rc = check_cluster(ctx, c, cluster_ids[i], layer)) != SGC_OK) return rc;
+        if (seen[cluster_ids[i]]) return fail(ctx, SGC_EINVAL, "cluster %d is named twice", cluster_ids[i]);
+        seen[cluster_ids[i]] = 1;
+        const int32_t P = c->cl[cluster_ids[i]].prefix_len;
+        if (P == 0) continue;
+        max_len = std::max(max_len, P);
+        total_rows += P;
+        if (!dev_x[i]) return fail(ctx, SGC_EINVAL, "dev_x of cluster %d is NULL", cluster_ids[i]);
+        void *q = dev_q ? dev_q[i] : nullptr;
+        if (!aligned16(dev_x[i]) || !aligned16(q)) return fail(ctx, SGC_EINVAL, "device pointers must be 16-byte aligned");
+        any_q = any_q || q != nullptr;
+    }
+    if (max_len == 0) return SGC_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if ((rc = ensure_rope(ctx, max_len, s)) != SGC_OK) return rc;
+    if ((rc = cache_sync(c, s)) != SGC_OK) return rc;
+    const bool fused = gemm_covers(ctx, K, N) && d == 128;
+    const bool to_pages = fused && ctx->p.kv_dtype == SGC_BF16;
+
+    // keys and values that cannot go straight into pages are staged as [rows][Hkv d] matrices, K then V per cluster
+    sgc_dev_block stg{};
+    if (!to_pages && (rc = dev_acquire(ctx, (size_t)total_rows * 2 * nkv * eb, s, &stg)) != SGC_OK) return rc;
+    std::vector<int32_t> ids;
+    std::vector<const void *> kptr, vptr;
+    std::vector<int32_t> pt_off(c->max_clusters, 0);
+    for (int i = 0, acc = 0; i < c->max_clusters; ++i) {
+        pt_off[i] = acc;
+        if (c->cl[i].allocated) acc += (int32_t)c->cl[i].pages.size();
+    }
+    hipError_t e = hipSuccess;
+    if (fused) {
+        std::vector<GemmRowTile> tiles;
+        int64_t row_base = 0;
+        for (int32_t i = 0; i < n; ++i) {
+            const int32_t id = cluster_ids[i], P = c->cl[id].prefix_len;
+            if (P == 0) continue;
+            char *ks = stg.p ? stg.p + (size_t)row_base * 2 * nkv * eb : nullptr;
+            char *vs = ks ? ks + (size_t)P * nkv * eb : nullptr;
+            if (ks) {
+                ids.push_back(id);
+                kptr.push_back(ks);
+                vptr.push_back(vs);
+            }
+            for (int32_t r = 0; r < P; r += 256) {
+                GemmRowTile t{};
+                t.a = static_cast<const char *>(dev_x[i]) + (size_t)r * K * eb;
+                t.c = (dev_q && dev_q[i]) ? static_cast<char *>(dev_q[i]) + (size_t)r * nq * eb : nullptr;
+                t.ck = ks ? ks + (size_t)r * nkv * eb : nullptr;
+                t.cv = vs ? vs + (size_t)r * nkv * eb : nullptr;
+                t.rows = std::min(256, P - r);
+                t.pos0 = r;
+                t.pt_off = pt_off[id];
+                tiles.push_back(t);
+            }
+            row_base += P;
+        }
+        const size_t bytes = tiles.size() * sizeof(GemmRowTile);
+        sgc_dev_block blk;
+        if ((rc = dev_acquire(ctx, bytes, s, &blk)) != SGC_OK) {
+            dev_release(ctx, stg, s);
+            return rc;
+        }
+        char *host = nullptr;
+        int slot = 0;
+        if ((rc = stage_begin(ctx, bytes, &host, &slot)) == SGC_OK) {
+            memcpy(host, tiles.data(), bytes);
+            rc = stage_commit(ctx, slot, blk.p, bytes, s);
+        }
+        if (rc == SGC_OK) {
+            GemmArgs g{};
+            // without any q output only the K and V rows of the weight are multiplied
+            g.w = any_q ? dev_w_qkv : static_cast<const char *>(dev_w_qkv) + (size_t)nq * K * eb;
+            g.N = any_q ? N : 2 * nkv;
+            g.K = K;
+            g.tiles = reinterpret_cast<const GemmRowTile *>(blk.p);
+            g.n_row_tiles = (int32_t)tiles.size();
+            g.n_col_tiles = (g.N + 255) / 256;
+            g.ldc = nq;
+            g.n_plain = any_q ? nq : 0;
+            g.kv_dest = to_pages ? 0 : 2;
+            g.n_kv_heads = Hkv;
+            g.kv_base = c->geom.pool + (int64_t)layer * c->geom.layer_bytes;
+            g.page_bytes = c->geom.page_bytes;
+            g.part_bytes = c->geom.head_part_bytes;
+            g.page_table = c->d_page_table;
+            g.rope = ctx->p.rope_base > 0.0f ? ctx->d_rope : nullptr;
+            e = launch_proj_gemm(g, true, s);
+        }
+        dev_release(ctx, blk, s);
+    } else {
+        int64_t row_base = 0;
+        for (int32_t i = 0; i < n && e == hipSuccess; ++i) {
+            const int32_t id = cluster_ids[i], P = c->cl[id].prefix_len;
+            if (P == 0) continue;
+            char *ks = stg.p + (size_t)row_base * 2 * nkv * eb, *vs = ks + (size_t)P * nkv * eb;
+            ids.push_back(id);
+            kptr.push_back(ks);
+            vptr.push_back(vs);
+            e = launch_proj_generic(dev_x[i], dev_w_qkv, P, N, K, ctx->p.io_dtype, dev_q ? dev_q[i] : nullptr, nq, ks, nkv, vs, s);
+            row_base += P;
+        }
+    }
+    if (rc == SGC_OK && e == hipSuccess && !ids.empty())
+        rc = sgc_prefix_prefill_batched(ctx, c, (int32_t)ids.size(), ids.data(), layer, nullptr, kptr.data(), vptr.data(), nullptr,
+                                        nullptr, hip_stream);
+    dev_release(ctx, stg, s);
+    if (rc != SGC_OK) return rc;
+    if (e != hipSuccess) return fail_hip(ctx, e, "QKV projection launch");
+    return SGC_OK;
+}
+
+int sgc_project_qkv_prefix(sgc_ctx *ctx, sgc_cache *c, int32_t cluster_id, int32_t layer, const void *dev_x,
+                           const void *dev_w_qkv, int32_t d_model, void *dev_q, int32_t prefix_len, void *hip_stream)
+{
+    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (!c || c->ctx != ctx) return fail(ctx, SGC_EINVAL, "cache is NULL or belongs to another context");
+    int rc = check_cluster(ctx, c, cluster_id, layer);
+    if (rc != SGC_OK) return rc;
+    if (prefix_len != c->cl[cluster_id].prefix_len)
+        return fail(ctx, SGC_ESHAPE, "prefix_len %d differs from the %d the cluster was allocated with", prefix_len,
+                    c->cl[cluster_id].prefix_len);
+    return sgc_project_qkv_prefix_batched(ctx, c, 1, &cluster_id, layer, &dev_x, dev_w_qkv, d_model, dev_q ? &dev_q : nullptr,
+                                          hip_stream);
+}
+
+int sgc_project_qkv_suffix(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int32_t layer, const void *dev_x,
+                           const void *dev_w_qkv, int32_t d_model, void *dev_q, void *hip_stream)
+{
+    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (!cc || cc->ctx != ctx) return fail(ctx, SGC_EINVAL, "cache is NULL or belongs to another context");
+    if (!pl || pl->ctx != ctx || pl->cache != cc) return fail(ctx, SGC_EINVAL, "plan is NULL or was made for another context/cache");
+    if (layer < 0 || layer >= ctx->p.n_layers) return fail(ctx, SGC_EINVAL, "layer %d outside [0, %d)", layer, ctx->p.n_layers);
+    if (d_model <= 0) return fail(ctx, SGC_EINVAL, "d_model %d <= 0", d_model);
+    for (int32_t k = 0; k < pl->n_clusters; ++k) {
+        if (pl->cluster_off[k + 1] == pl->cluster_off[k]) continue;
+        if (!cc->cl[k].allocated || cc->cl[k].prefix_len != pl->cl_prefix_len[k])
+            return fail(ctx, SGC_ESTATE, "cluster %d changed since the plan was made", k);
+    }
+    if (pl->total_tokens == 0) return SGC_OK;
+    if (!dev_x || !dev_w_qkv || !dev_q) return fail(ctx, SGC_EINVAL, "dev_x / dev_w_qkv / dev_q is NULL");
+    const size_t eb = (size_t)dtype_bytes(ctx->p.io_dtype);
+    if (!aligned16(dev_x) || !aligned16(dev_w_qkv) || !aligned16(dev_q) || ((int64_t)d_model * eb) % 16 != 0)
+        return fail(ctx, SGC_EINVAL, "device pointers and every row of x must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int rc;
+    if ((rc = ensure_rope(ctx, pl->max_position, s)) != SGC_OK) return rc;
+    if ((rc = sgc_plan_upload(pl, hip_stream)) != SGC_OK) return rc;
+    pl->last_stream = s;
+    const int Hq = ctx->p.n_q_heads, Hkv = ctx->p.n_kv_heads, d = ctx->p.head_dim;
+    const int nq = Hq * d, nkv = Hkv * d, N = nq + 2 * nkv, K = d_model;
+    const int64_t T = pl->total_tokens;
+    if (ctx->use_mfma && gemm_covers(ctx, K, N) && pl->d_spool) {
+        char *spool = pl->d_spool + (pl->decode_cap > 0 ? (size_t)layer * pl->spool_layer_bytes : 0);
+        const int64_t page_bytes = (int64_t)2 * Hkv * kPageTokens * d * 2;
+        SGC_HIP(ctx, launch_zero_last_pages(spool, pl->d_sq_len, pl->d_sq_page0, (int)pl->sq_len.size(), page_bytes, s));
+        GemmArgs g{};
+        g.w = dev_w_qkv;
+        g.N = N;
+        g.K = K;
+        g.a = dev_x;
+        g.c = dev_q;
+        g.M = T;
+        g.n_row_tiles = (int32_t)((T + 255) / 256);
+        g.n_col_tiles = (N + 255) / 256;
+        g.ldc = nq;
+        g.n_plain = nq;
+        g.kv_dest = 1;
+        g.n_kv_heads = Hkv;
+        g.kv_base = spool;
+        g.page_bytes = page_bytes;
+        g.part_bytes = (int64_t)kPageTokens * d * 2;
+        g.row_dest = pl->d_row_dest;
+        g.rope = ctx->p.rope_base > 0.0f ? ctx->d_rope : nullptr;
+        SGC_HIP(ctx, launch_proj_gemm(g, true, s));
+        pl->proj_state = 1;
+    } else {
+        const size_t need = (size_t)T * 2 * nkv * eb;
+        if (pl->proj_kv.bytes < need) {
+            dev_release(ctx, pl->proj_kv, s);
+            pl->proj_kv = sgc_dev_block{};
+            if ((rc = dev_acquire(ctx, need, s, &pl->proj_kv)) != SGC_OK) return rc;
+        }
+        SGC_HIP(ctx, launch_proj_generic(dev_x, dev_w_qkv, T, N, K, ctx->p.io_dtype, dev_q, nq, pl->proj_kv.p, nkv,
+                                         pl->proj_kv.p + (size_t)T * nkv * eb, s));
+        pl->proj_state = 2;
+    }
+    pl->proj_layer = layer;
+    return SGC_OK;
+}
+
+int sgc_project_out(sgc_ctx *ctx, const void *dev_o, const void *dev_w_o, int32_t d_model, int64_t n_tokens, void *dev_y,
+                    void *hip_stream)
+{
+    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (n_tokens < 0) return fail(ctx, SGC_EINVAL, "n_tokens %lld < 0", (long long)n_tokens);
+    if (d_model <= 0) return fail(ctx, SGC_EINVAL, "d_model %d <= 0", d_model);
+    if (n_tokens == 0) return SGC_OK;
+    if (!dev_o || !dev_w_o || !dev_y) return fail(ctx, SGC_EINVAL, "dev_o / dev_w_o / dev_y is NULL");
+    const size_t eb = (size_t)dtype_bytes(ctx->p.io_dtype);
+    const int K = ctx->p.n_q_heads * ctx->p.head_dim, N = d_model;
+    if (!aligned16(dev_o) || !aligned16(dev_w_o) || !aligned16(dev_y) || ((int64_t)N * eb) % 16 != 0)
+        return fail(ctx, SGC_EINVAL, "device pointers and every row of y must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (gemm_covers(ctx, K, N)) {
+        GemmArgs g{};
+        g.w = dev_w_o;
+        g.N = N;
+        g.K = K;
+        g.a = dev_o;
+        g.c = dev_y;
+        g.M = n_tokens;
+        g.n_row_tiles = (int32_t)((n_tokens + 255) / 256);
+        g.n_col_tiles = (N + 255) / 256;
+        g.ldc = N;
+        g.n_plain = N;
+        SGC_HIP(ctx, launch_proj_gemm(g, false, s));
+    } else {
+        SGC_HIP(ctx, launch_proj_generic(dev_o, dev_w_o, n_tokens, N, K, ctx->p.io_dtype, dev_y, N, nullptr, 0, nullptr, s));
+    }
+    return SGC_OK;
 }
 
 }  // extern "C"

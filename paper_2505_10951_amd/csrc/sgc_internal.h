@@ -125,6 +125,41 @@ struct DecodeArgs {
     float scale_log2e;
 };
 
+// ---- projections around the attention (sgc_gemm.hip) -------------------------------------------
+// One slab of up to 256 rows of a projection's left operand and where its results go.
+struct GemmRowTile {
+    const void *a;       // first row of the slab, [rows][K] bf16
+    void *c;             // plain output (Q, or the whole product): first row of the slab, or null to store none
+    void *ck, *cv;       // staged K / V outputs [rows][Hkv d] (first row of the slab), when keys are staged
+    int32_t rows;        // valid rows, 1..256
+    int32_t pos0;        // cache pages: position of the slab's first row inside its cluster (a multiple of 16)
+    int32_t pt_off;      // cache pages: first page-table entry of the cluster
+    int32_t dest0;       // suffix pages: index of the slab's first row in row_dest
+};
+static_assert(sizeof(GemmRowTile) == 48, "row tile record layout");
+
+// C = A W^T on the matrix cores.  Columns [0, n_plain) are stored row-major with leading dimension ldc;
+// with the QKV epilogue the columns after them are Hkv K heads and then Hkv V heads of 128 channels.
+struct GemmArgs {
+    const void *w;                // [N][K] bf16
+    int32_t N, K;
+    const GemmRowTile *tiles;     // [n_row_tiles], or null: slab r is rows 256 r .. of a / c below
+    const void *a;
+    void *c;
+    int64_t M;
+    int32_t n_row_tiles, n_col_tiles;
+    int32_t ldc;
+    int32_t n_plain;
+    int32_t kv_dest;              // 0: the cache's pages (prompt), 1: the batch's suffix pages, 2: staging matrices
+    int32_t n_kv_heads;
+    char *kv_base;                // the layer's first page (cache pool or suffix pool)
+    int64_t page_bytes;           // one page, every head, K and V
+    int64_t part_bytes;           // K (or V) of one head in one page
+    const int32_t *page_table;    // kv_dest 0: flat page ids
+    const int2 *row_dest;         // kv_dest 1: per packed row {16 * page + slot, position}
+    const float2 *rope;           // [position][64] (cos, sin), or null
+};
+
 enum { MODE_SUFFIX = 0, MODE_PREFIX = 1 };
 
 // Everything an attention kernel needs, by value.
@@ -247,6 +282,12 @@ struct sgc_plan {
     std::vector<sgc::TokInfo> dtok;
     size_t spool_layer_bytes = 0;
     sgc_dev_block dec_scratch;                // cached-prefix part of a decode step: O then LSE
+    // projected keys of the batch (sgc_project_qkv_suffix): 1 = the suffix pages of proj_layer are written,
+    // 2 = un-rotated K then V matrices [T][Hkv d] are kept in proj_kv for the suffix launch to ingest
+    int32_t proj_state = 0, proj_layer = -1;
+    sgc_dev_block proj_kv;
+    std::vector<int32_t> row_dest;            // [T][2] per packed row: 16 * suffix page + slot, position
+    const int2 *d_row_dest = nullptr;
     std::vector<sgc::Tile> tiles;
     std::vector<sgc::TokInfo> tok_info;
     uint64_t tiles_generation = 0;            // cache generation the tiles' page-table offsets belong to
@@ -293,6 +334,14 @@ hipError_t launch_attn_generic(const AttnArgs &a, int64_t n_rows, hipStream_t s)
 hipError_t launch_decode_append(const DecodeArgs &d, hipStream_t s);
 hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s);
 hipError_t launch_fill_zero_bytes(void *p, size_t bytes, hipStream_t s);
+// Projections: the bf16 matrix-core kernel (K a multiple of 64, N a multiple of 128; qkv selects the fused
+// epilogue) and a kernel for every other shape and type that deals columns [0, n0), [n0, n0 + n1) and the rest
+// to three row-major matrices (c0 may be null to drop its columns).
+hipError_t launch_proj_gemm(const GemmArgs &g, bool qkv, hipStream_t s);
+hipError_t launch_proj_generic(const void *a, const void *w, int64_t M, int N, int K, int io_dtype, void *c0, int n0, void *c1,
+                               int n1, void *c2, hipStream_t s);
+hipError_t launch_zero_last_pages(char *spool, const int32_t *d_sq_len, const int32_t *d_sq_page0, int n_sq, int64_t page_bytes,
+                                  hipStream_t s);
 // Rows per workgroup of MFMA kernel variant `variant`, or 0 if the variant does not exist.
 int mfma_tile_rows(int variant);
 hipError_t launch_attn_mfma(const AttnArgs &a, int variant, hipStream_t s);

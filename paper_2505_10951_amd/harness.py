@@ -134,6 +134,48 @@ class Session:
                                        self.stream)
         return do
 
+    # ---- Sec. 3.4: the layer around the attention (hidden states in, hidden states out) -------------
+    def layer_prefix(self, clusters, d_model: int, dw_qkv: torch.Tensor, dw_o: torch.Tensor, layer: int = 0,
+                     with_output: bool = True):
+        """QKV projection of the given clusters' prompts into their pages; with_output also runs the prompt's
+        causal attention and the output projection.  Returns per-cluster y device tensors (or None)."""
+        w = self.w
+        dx = [to_device(w.prefix_x(c, d_model, layer), w.io_dtype, self.device) for c in clusters]
+        nq = w.n_q_heads * w.head_dim
+        dq = [torch.empty((x.shape[0], nq), dtype=x.dtype, device=self.device) if with_output else None for x in dx]
+        ptr = lambda ts: [None if t is None else t.data_ptr() for t in ts]
+        sgc.sgc_project_qkv_prefix_batched(self.ctx, self.cache, list(clusters), layer, ptr(dx), dw_qkv.data_ptr(), d_model,
+                                           ptr(dq) if with_output else None, self.stream)
+        if not with_output:
+            torch.cuda.synchronize()
+            return [None for _ in clusters]
+        do = [torch.empty_like(q) for q in dq]
+        sgc.sgc_prefix_prefill_batched(self.ctx, self.cache, list(clusters), layer, ptr(dq), None, None, ptr(do), None, self.stream)
+        ys = []
+        for o in do:
+            y = torch.empty((o.shape[0], d_model), dtype=o.dtype, device=self.device)
+            sgc.sgc_project_out(self.ctx, o.data_ptr(), dw_o.data_ptr(), d_model, o.shape[0], y.data_ptr(), self.stream)
+            ys.append(y)
+        torch.cuda.synchronize()
+        return ys
+
+    def layer_suffix(self, dx: torch.Tensor, d_model: int, dw_qkv: torch.Tensor, dw_o: torch.Tensor, layer: int = 0,
+                     bufs=None):
+        """Whole batch: QKV projection, attention over cache + own tokens, output projection.  Returns y [T][d_model]."""
+        w = self.w
+        T = dx.shape[0]
+        if bufs is None:
+            nq = w.n_q_heads * w.head_dim
+            bufs = (torch.empty((T, nq), dtype=dx.dtype, device=self.device), torch.empty((T, nq), dtype=dx.dtype, device=self.device),
+                    torch.empty((T, d_model), dtype=dx.dtype, device=self.device))
+        dq, do, dy = bufs
+        sgc.sgc_project_qkv_suffix(self.ctx, self.cache, self.plan, layer, dx.data_ptr(), dw_qkv.data_ptr(), d_model,
+                                   dq.data_ptr(), self.stream)
+        sgc.sgc_suffix_prefill_batched(self.ctx, self.cache, self.plan, layer, dq.data_ptr(), None, None, do.data_ptr(), None,
+                                       self.stream)
+        sgc.sgc_project_out(self.ctx, do.data_ptr(), dw_o.data_ptr(), d_model, T, dy.data_ptr(), self.stream)
+        return dy
+
     # ---- App. A.2: up to 32 generated tokens per query, attending over cache + question + earlier tokens ---
     def enable_decode(self, max_new_tokens: int) -> None:
         sgc.sgc_plan_enable_decode(self.ctx, self.plan, max_new_tokens)

@@ -27,7 +27,8 @@ EXPORTS = [
     "sgc_cache_cluster_pages", "sgc_prefix_prefill", "sgc_prefix_prefill_batched", "sgc_assign_clusters", "sgc_plan_upload",
     "sgc_plan_get_info", "sgc_plan_destroy", "sgc_suffix_prefill_batched", "sgc_cache_export", "sgc_cache_import",
     "sgc_timing_enable", "sgc_timing_last", "sgc_cluster_queries", "sgc_plan_enable_decode", "sgc_decode_step_batched",
-    "sgc_union_subgraphs",
+    "sgc_union_subgraphs", "sgc_project_qkv_prefix", "sgc_project_qkv_prefix_batched", "sgc_project_qkv_suffix",
+    "sgc_project_out",
 ]
 
 
@@ -100,6 +101,10 @@ def lib() -> ctypes.CDLL:
         i64p = ctypes.POINTER(ctypes.c_int64)
         L.sgc_union_subgraphs.argtypes = [vp, i32, i32p, i32, i64p, i32p, i64p, i32p, i64p, i32p, i64p, i32p]
         L.sgc_cluster_queries.argtypes = [vp, i32, i32, f32p, i32, i32, i32p]
+        L.sgc_project_qkv_prefix.argtypes = [vp, vp, i32, i32, vp, vp, i32, vp, i32, vp]
+        L.sgc_project_qkv_prefix_batched.argtypes = [vp, vp, i32, i32p, i32, vpp, vp, i32, vpp, vp]
+        L.sgc_project_qkv_suffix.argtypes = [vp, vp, vp, i32, vp, vp, i32, vp, vp]
+        L.sgc_project_out.argtypes = [vp, vp, vp, i32, i64, vp, vp]
         L.sgc_timing_enable.argtypes = [vp, ctypes.c_int]
         L.sgc_timing_last.argtypes = [vp, f32p, f32p]
         for name in EXPORTS:
@@ -257,6 +262,29 @@ def sgc_plan_destroy(plan) -> None:
 def sgc_suffix_prefill_batched(ctx, cache, plan, layer: int, dev_q: int, dev_k: int, dev_v: int, dev_o: int,
                                dev_lse: Optional[int] = None, stream: int = 0) -> None:
     _check(ctx, lib().sgc_suffix_prefill_batched(ctx, cache, plan, layer, dev_q, dev_k, dev_v, dev_o, dev_lse, stream))
+
+
+def sgc_project_qkv_prefix(ctx, cache, cluster_id: int, layer: int, dev_x: int, dev_w_qkv: int, d_model: int,
+                           dev_q: Optional[int], prefix_len: int, stream: int = 0) -> None:
+    _check(ctx, lib().sgc_project_qkv_prefix(ctx, cache, cluster_id, layer, dev_x, dev_w_qkv, d_model, dev_q, prefix_len, stream))
+
+
+def sgc_project_qkv_prefix_batched(ctx, cache, cluster_ids: Sequence[int], layer: int, dev_x, dev_w_qkv: int, d_model: int,
+                                   dev_q=None, stream: int = 0) -> None:
+    """dev_x / dev_q: sequences of device addresses, one per cluster (dev_q may be None or hold None entries)."""
+    ids = _i32(cluster_ids)
+    n = ids.shape[0]
+    _check(ctx, lib().sgc_project_qkv_prefix_batched(ctx, cache, n, ids.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), layer,
+                                                     _ptr_array(dev_x, n), dev_w_qkv, d_model, _ptr_array(dev_q, n), stream))
+
+
+def sgc_project_qkv_suffix(ctx, cache, plan, layer: int, dev_x: int, dev_w_qkv: int, d_model: int, dev_q: int,
+                           stream: int = 0) -> None:
+    _check(ctx, lib().sgc_project_qkv_suffix(ctx, cache, plan, layer, dev_x, dev_w_qkv, d_model, dev_q, stream))
+
+
+def sgc_project_out(ctx, dev_o: int, dev_w_o: int, d_model: int, n_tokens: int, dev_y: int, stream: int = 0) -> None:
+    _check(ctx, lib().sgc_project_out(ctx, dev_o, dev_w_o, d_model, n_tokens, dev_y, stream))
 
 
 def sgc_plan_enable_decode(ctx, plan, max_new_tokens: int) -> None:

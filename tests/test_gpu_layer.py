@@ -1,0 +1,144 @@
+"""GPU parity of the attention layer's projections (SubGCache Sec. 3.4: prompt and question tokens pass
+through the LLM's layers) against the fp64 oracle, through the C ABI.
+
+Error bars.  Products accumulate in fp32 and q, k, v, o, y are each rounded to bf16 once (relative 2^-9).
+  * projected q and cached K, V (sums of d_model terms, one rounding):  |err| <= 2^-8 (|ref| + rms(ref)).
+  * where keys are staged as bf16 before the ingest kernels rotate them, they are rounded twice: 2^-7 there.
+  * layer output y: the attention path's own bar is 2e-2 absolute on o for unit-variance values (6e-2 with an
+    fp8 cache); w_o's rows have unit expected norm, so an error of that size in o arrives in y with the same
+    size whatever y's own magnitude is, and y is rounded once more: |err| <= 2e-2 + 2^-8 |ref|."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2505_10951_amd import sgc, workloads
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2505_10951_amd.harness import Session, to_device, to_host_f32  # noqa: E402
+
+
+def _small(io="bf16", kv="bf16", d=128, Hq=4, Hkv=2, prefix=(300, 77), sizes=(3, 3), lo=5, hi=70, seed=11):
+    return workloads.custom("layer_small", n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, rope_base=10000.0, io_dtype=io,
+                            kv_dtype=kv, prefix_len=list(prefix), cluster_sizes=list(sizes), suffix_range=(lo, hi), seed=seed)
+
+
+def _bar(ref, abs_bar=None, rel=2.0 ** -8):
+    rms = float(np.sqrt(np.mean(ref ** 2))) if ref.size else 0.0
+    return (rel * rms if abs_bar is None else abs_bar) + rel * np.abs(ref)
+
+
+def _check(name, got, ref, **kw):
+    err = np.abs(got.astype(np.float64) - ref)
+    bar = _bar(ref, **kw)
+    worst = float((err / np.maximum(bar, 1e-30)).max()) if err.size else 0.0
+    print(f"{name}: max err {err.max() if err.size else 0:.3e}, rms ref {np.sqrt(np.mean(ref ** 2)) if ref.size else 0:.3e}, worst err/bar {worst:.3f}", flush=True)
+    assert worst <= 1.0, f"{name}: error exceeds the bar by {worst:.2f}x"
+
+
+def _oracle_layer(w, d_model, w_qkv, w_o, queries, layer=0):
+    """cluster -> (ck, cv, y_prefix) for the clusters of `queries`, and query -> y."""
+    H = (w.n_q_heads, w.n_kv_heads, w.head_dim)
+    per_cluster, per_query = {}, {}
+    for n in queries:
+        c = int(w.labels[n])
+        if c not in per_cluster:
+            x = w.prefix_x(c, d_model, layer)
+            per_cluster[c] = orc.attention_layer_prefix(x, w_qkv, w_o, *H, w.rope_base)
+            if w.kv_dtype == "fp8_e4m3":
+                # the cache as stored: quantised per head; the prompt's own rows and every query read that
+                ck, cv, _ = per_cluster[c]
+                ck, cv = orc.quantise_e4m3(ck)[2], orc.quantise_e4m3(cv)[2]
+                q, _, _ = orc.project_qkv(x, w_qkv, *H)
+                o, _ = orc.full_causal_numpy(orc.rope_numpy(q, np.arange(q.shape[0]), w.rope_base), ck, cv, 0.0)
+                per_cluster[c] = (ck, cv, orc.project_out(o, w_o))
+        ck, cv, _ = per_cluster[c]
+        per_query[n] = orc.attention_layer_suffix(ck, cv, w.suffix_x_query(n, d_model, layer), w_qkv, w_o, *H, w.rope_base)
+    return per_cluster, per_query
+
+
+def _run_layer(w, d_model, queries=None, check_cache=True, kernel=sgc.SGC_KERNEL_AUTO, y_bar=2e-2, rel=2.0 ** -8):
+    w_qkv, w_o = w.layer_weights(d_model)
+    queries = list(range(w.n_queries)) if queries is None else queries
+    ref_c, ref_q = _oracle_layer(w, d_model, w_qkv, w_o, queries)
+    cu = w.cu_seqlens
+    with Session(w, kernel=kernel) as s:
+        for c in range(w.n_clusters):
+            s.alloc_cluster(c)
+        dwq, dwo = to_device(w_qkv, w.io_dtype), to_device(w_o, w.io_dtype)
+        ys = s.layer_prefix(list(range(w.n_clusters)), d_model, dwq, dwo)
+        for c, (ck, cv, y_ref) in ref_c.items():
+            if check_cache and w.kv_dtype != "fp8_e4m3":
+                k, v, _, _ = s.export_cluster(c)
+                _check(f"cluster {c} cached K", k, ck, rel=rel)
+                _check(f"cluster {c} cached V", v, cv, rel=rel)
+            _check(f"cluster {c} prompt output", to_host_f32(ys[c]), y_ref, abs_bar=y_bar, rel=rel)
+        s.assign()
+        dx = to_device(w.suffix_x(d_model), w.io_dtype)
+        y = to_host_f32(s.layer_suffix(dx, d_model, dwq, dwo))
+        torch.cuda.synchronize()
+        for n in queries:
+            _check(f"query {n}", y[int(cu[n]):int(cu[n + 1])], ref_q[n], abs_bar=y_bar, rel=rel)
+    return y
+
+
+def test_layer_small_bf16_fused_epilogue():
+    """Two row tiles with a ragged tail in the prompt, several queries per 256-row slab in the batch."""
+    _run_layer(_small(), 192)
+
+
+def test_layer_queries_out_match_projection():
+    """The projected queries alone (un-rotated), and the keys in the suffix pages through the attention of a
+    batch whose prompt is empty (every key the attention sees then comes from the projection's epilogue)."""
+    w = _small(prefix=(0, 33), sizes=(2, 2), lo=17, hi=40, seed=5)
+    d_model = 128
+    w_qkv, w_o = w.layer_weights(d_model)
+    _run_layer(w, d_model)
+    with Session(w) as s:
+        for c in range(w.n_clusters):
+            s.alloc_cluster(c)
+        s.assign()
+        x = w.suffix_x(d_model)
+        dx, dwq = to_device(x, "bf16"), to_device(w_qkv, "bf16")
+        dq = torch.empty((x.shape[0], w.n_q_heads * w.head_dim), dtype=torch.bfloat16, device="cuda:0")
+        sgc.sgc_project_qkv_suffix(s.ctx, s.cache, s.plan, 0, dx.data_ptr(), dwq.data_ptr(), d_model, dq.data_ptr(), s.stream)
+        torch.cuda.synchronize()
+        q_ref, _, _ = orc.project_qkv(x, w_qkv, w.n_q_heads, w.n_kv_heads, w.head_dim)
+        _check("projected q", to_host_f32(dq), q_ref.reshape(x.shape[0], -1))
+
+
+def test_layer_fp8_cache_keys_staged_then_quantised():
+    w = _small(kv="fp8_e4m3", seed=12)
+    _run_layer(w, 128, y_bar=6e-2)
+
+
+def test_layer_other_shapes_take_the_plain_kernel():
+    """fp32 io and head_dim 64: no matrix-core path; products and attention in fp32."""
+    w = _small(io="f32", kv="f32", d=64, Hq=4, Hkv=4, prefix=(50, 21), sizes=(2, 2), lo=3, hi=20, seed=3)
+    _run_layer(w, 96, y_bar=1e-4, rel=1e-5)
+    w = _small(io="bf16", kv="bf16", d=64, Hq=4, Hkv=2, prefix=(40, 21), sizes=(2, 2), lo=3, hi=20, seed=4)
+    _run_layer(w, 72, rel=2.0 ** -7)       # keys staged as bf16, then rotated and rounded again
+
+
+def test_layer_generic_attention_with_bf16_io_keeps_projected_keys_in_the_plan():
+    _run_layer(_small(prefix=(90, 40), lo=4, hi=30, seed=9), 128, kernel=sgc.SGC_KERNEL_GENERIC, rel=2.0 ** -7)
+
+
+def test_layer_without_projection_is_refused():
+    w = _small(prefix=(32, 16), lo=4, hi=8)
+    with Session(w) as s:
+        for c in range(w.n_clusters):
+            s.alloc_cluster(c)
+        s.assign()
+        T = w.total_suffix_tokens
+        dq = torch.zeros((T, w.n_q_heads * w.head_dim), dtype=torch.bfloat16, device="cuda:0")
+        with pytest.raises(sgc.SgcError) as e:
+            sgc.sgc_suffix_prefill_batched(s.ctx, s.cache, s.plan, 0, dq.data_ptr(), None, None, dq.data_ptr(), None, s.stream)
+        assert e.value.status == sgc.SGC_ESTATE
+
+
+def test_layer_llama3_8b_shape_full_size_sampled():
+    """configs[1] with d_model 4096: the whole batch runs; three queries and their clusters' prompts are checked."""
+    w = workloads.config(1)
+    _run_layer(w, 4096, queries=[0, 131, 319], check_cache=True)

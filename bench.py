@@ -147,6 +147,71 @@ def decode_measurement(s, w, layer, n_steps, dq, dk, dv, do, all_clusters, pq_pt
             "bytes_if_every_query_read_its_prefix": per_query_read}
 
 
+def layer_measurement(s, w, layer, d_model, reps, stream):
+    """The attention layer around the kernel (QKV projection with the fused page-writing epilogue, attention from
+    the projected keys, output projection) on the same workload: per-call times from HIP events on the launch
+    stream.  Random weights and hidden states stand in for a trained model's."""
+    import torch
+    from paper_2505_10951_amd import sgc
+    from paper_2505_10951_amd.harness import to_device
+    all_clusters = list(range(w.n_clusters))
+    if sgc.sgc_cache_free_pages(s.cache) == sgc.sgc_cache_total_pages(s.cache):
+        for c in all_clusters:
+            sgc.sgc_cache_alloc_cluster(s.ctx, s.cache, c, int(w.prefix_len[c]))
+    w_qkv, w_o = w.layer_weights(d_model, layer)
+    dwq, dwo = to_device(w_qkv, w.io_dtype), to_device(w_o, w.io_dtype)
+    dpx = [to_device(w.prefix_x(c, d_model, layer), w.io_dtype) for c in all_clusters]
+    dx = to_device(w.suffix_x(d_model, layer), w.io_dtype)
+    T, nq = dx.shape[0], w.n_q_heads * w.head_dim
+    n_qkv = nq + 2 * w.n_kv_heads * w.head_dim
+    dq = torch.empty((T, nq), dtype=dx.dtype, device=dx.device)
+    do = torch.empty_like(dq)
+    dy = torch.empty((T, d_model), dtype=dx.dtype, device=dx.device)
+    px_ptrs = [t.data_ptr() for t in dpx]
+
+    def timed(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        return e0, e1
+
+    calls = {
+        "qkv_prefix": lambda: sgc.sgc_project_qkv_prefix_batched(s.ctx, s.cache, all_clusters, layer, px_ptrs, dwq.data_ptr(),
+                                                                 d_model, None, stream),
+        "qkv_suffix": lambda: sgc.sgc_project_qkv_suffix(s.ctx, s.cache, s.plan, layer, dx.data_ptr(), dwq.data_ptr(), d_model,
+                                                         dq.data_ptr(), stream),
+        "attention": lambda: sgc.sgc_suffix_prefill_batched(s.ctx, s.cache, s.plan, layer, dq.data_ptr(), None, None,
+                                                            do.data_ptr(), None, stream),
+        "out": lambda: sgc.sgc_project_out(s.ctx, do.data_ptr(), dwo.data_ptr(), d_model, T, dy.data_ptr(), stream),
+    }
+    calls["qkv_prefix"]()
+    s.assign(w.labels, w.suffix_len)
+    s.upload_plan()
+    evs = {k: [] for k in calls}
+    for rep in range(reps + 2):
+        for name, fn in calls.items():
+            pair = timed(fn)
+            if rep >= 2:
+                evs[name].append(pair)
+    torch.cuda.synchronize()
+    ms = {k: float(np.mean([a.elapsed_time(b) for a, b in v])) for k, v in evs.items()}
+    P_total = float(w.prefix_len.sum())
+    flop = {"qkv_prefix": 2.0 * P_total * d_model * (n_qkv - nq),          # the prompt's queries are not needed here
+            "qkv_suffix": 2.0 * T * d_model * n_qkv, "attention": w.flops(), "out": 2.0 * T * nq * d_model}
+    peak = PEAK_TFLOPS[w.io_dtype]
+    per = {k: {"ms": ms[k], "tflops": flop[k] / (ms[k] * 1e-3) / 1e12} for k in calls}
+    suffix_ms = ms["qkv_suffix"] + ms["attention"] + ms["out"]
+    suffix_flop = flop["qkv_suffix"] + flop["attention"] + flop["out"]
+    gemm = per["qkv_suffix"]
+    return {"d_model": d_model, "calls": per,
+            "suffix_layer_ms": suffix_ms, "suffix_layer_tflops": suffix_flop / (suffix_ms * 1e-3) / 1e12,
+            "suffix_layer_us_per_query": suffix_ms * 1e3 / max(w.n_queries, 1),
+            "roofline": {"kernel": "proj_gemm_kernel<true> (QKV projection, keys and values written into suffix pages)",
+                         "bound": "mfma" if w.io_dtype == "bf16" else "alu", "achieved": gemm["tflops"], "peak": peak,
+                         "unit": "TFLOP/s", "frac": gemm["tflops"] / peak, "traffic": None}}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -157,6 +222,9 @@ def main() -> int:
     ap.add_argument("--suffix-only", action="store_true", help="time only the batched suffix launch (profiling aid)")
     ap.add_argument("--decode-steps", type=int, default=32,
                     help="after the timed steps, time this many batched decode steps on the same workload (0 = skip)")
+    ap.add_argument("--layer-d-model", type=int, default=-1,
+                    help="model width of the attention-layer measurement (-1: n_q_heads * head_dim, 0: skip)")
+    ap.add_argument("--layer-reps", type=int, default=10)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten 256 MiB device copies and exit (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -269,6 +337,12 @@ def main() -> int:
         "paper_context": "TTFT reduction up to 6.68x, PFTT up to 15.49x (Table 2; 2x A100-SXM4-40GB, precision not stated); end-to-end LLM latencies, not this kernel",
         "input_gen_s": t_gen,
     }
+    d_model = w.n_q_heads * w.head_dim if args.layer_d_model < 0 else args.layer_d_model
+    if d_model > 0 and not args.suffix_only:
+        out["layer"] = layer_measurement(s, w, layer, d_model, args.layer_reps, stream)
+        torch.cuda.synchronize()
+        for c in range(w.n_clusters):
+            sgc.sgc_cache_free_cluster(s.ctx, s.cache, c)
     if args.decode_steps > 0 and dtype == "bf16":
         out["decode"] = decode_measurement(s, w, layer, args.decode_steps, dq, dk, dv, do, all_clusters,
                                            pq_ptrs, pk_ptrs, pv_ptrs, po_ptrs, stream)

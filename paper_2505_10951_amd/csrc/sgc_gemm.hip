@@ -26,6 +26,8 @@
 // matrix and the ingest kernels take it from there.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "sgc_internal.h"
 
 namespace sgc {
@@ -151,38 +153,83 @@ __global__ void __launch_bounds__(256, 1) proj_gemm_kernel(const GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    issue(0, 0);
-    for (int kt = 0; kt < n_steps; ++kt) {
-        const int cur = kt & 1;
-        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's copies of step kt have landed
-        __syncthreads();                         // everyone's have; everyone has finished reading step kt - 1
-        if (kt + 1 < n_steps) issue(kt + 1, cur ^ 1);
-        const char *st = smem + cur * STAGE_BYTES;
-        // operands of sub-step kk + 1 are requested before the products of sub-step kk are issued
-        bf16x8 pf[2][4], qf[2][4];
+    // Sub-step kk of a step multiplies the 16-wide slice kk of the slabs: 8 operand reads, 16 products.  The
+    // reads run one sub-step ahead of the products, and the step's barrier sits in front of its LAST sub-step:
+    // by then every wavefront holds that sub-step's operands in registers, so the buffer can be refilled (copy of
+    // step kt + 2) and the first operands of step kt + 1 requested while the last 16 products still run.
+    auto load_ops = [&](const char *st, int kk, bf16x8 (&p)[4], bf16x8 (&q)[4]) __attribute__((always_inline)) {
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            pf[0][b] = *reinterpret_cast<const bf16x8 *>(st + p_region + b * 4096 + r_off[0]);
-            qf[0][b] = *reinterpret_cast<const bf16x8 *>(st + q_region + b * 4096 + r_off[0]);
+            p[b] = *reinterpret_cast<const bf16x8 *>(st + p_region + b * 4096 + r_off[kk]);
+            q[b] = *reinterpret_cast<const bf16x8 *>(st + q_region + b * 4096 + r_off[kk]);
         }
+    };
+    auto products = [&](const bf16x8 (&p)[4], const bf16x8 (&q)[4]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            if (kk < 3) {
+        for (int pi = 0; pi < 4; ++pi)
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    pf[(kk + 1) & 1][b] = *reinterpret_cast<const bf16x8 *>(st + p_region + b * 4096 + r_off[kk + 1]);
-                    qf[(kk + 1) & 1][b] = *reinterpret_cast<const bf16x8 *>(st + q_region + b * 4096 + r_off[kk + 1]);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);      // keep the reads above in front of the products below
+            for (int qj = 0; qj < 4; ++qj)
+                acc[pi][qj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p[pi], q[qj], acc[pi][qj], 0, 0, 0);
+    };
+    // Issue order of a sub-step: the 8 reads of the next sub-step go out in the shadow of the first 4 products,
+    // so that they have landed long before the next sub-step's first product asks for them.
+    auto order_reads_under_products = [&]() __attribute__((always_inline)) {
 #pragma unroll
-            for (int pi = 0; pi < 4; ++pi)
-#pragma unroll
-                for (int qj = 0; qj < 4; ++qj)
-                    acc[pi][qj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[kk & 1][pi], qf[kk & 1][qj], acc[pi][qj], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one matrix-core instruction
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);     // two LDS reads
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 12, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    bf16x8 p0[4], q0[4], p1[4], q1[4];
+    issue(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): this wavefront's copies have landed
+    __syncthreads();                             // everyone's have
+    if (n_steps > 1) issue(1, 1);
+    load_ops(smem, 0, p0, q0);
+    __builtin_amdgcn_sched_barrier(0);
+    // one step; NEXT: a step follows (barrier, first operands of it), NEXT2: two follow (refill this step's buffer)
+    auto step = [&](int kt, auto next, auto next2) __attribute__((always_inline)) {
+        constexpr bool NEXT = decltype(next)::value, NEXT2 = decltype(next2)::value;
+        const char *st = smem + (kt & 1) * STAGE_BYTES;
+        load_ops(st, 1, p1, q1);
+        products(p0, q0);
+        order_reads_under_products();
+        load_ops(st, 2, p0, q0);
+        products(p1, q1);
+        order_reads_under_products();
+        load_ops(st, 3, p1, q1);
+        products(p0, q0);
+        order_reads_under_products();
+        if (NEXT) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // the copies of step kt + 1, requested a step ago
+            __syncthreads();                     // every wavefront has read all of step kt out of LDS
             __builtin_amdgcn_sched_barrier(0);
+            load_ops(smem + ((kt + 1) & 1) * STAGE_BYTES, 0, p0, q0);
+            if (NEXT2) issue(kt + 2, kt & 1);
         }
-    }
+        products(p1, q1);
+        if (NEXT) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+            }
+        }
+        if (NEXT2) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                __builtin_amdgcn_sched_group_barrier(0x010, 2, 1);     // two of the 16 copy instructions
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int kt = 0;
+    for (; kt + 2 < n_steps; ++kt) step(kt, std::true_type{}, std::true_type{});
+    if (kt + 1 < n_steps) step(kt++, std::true_type{}, std::false_type{});
+    step(kt, std::false_type{}, std::false_type{});
 
     if (col0 >= N) return;          // the second half of a ragged last column tile
     const int rows16 = (rows + 15) & ~15;

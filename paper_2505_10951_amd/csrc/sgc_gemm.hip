@@ -58,6 +58,18 @@ __device__ inline void copy_1k_to_lds(const char *src_lane, char *lds)
     __builtin_amdgcn_global_load_lds(g, l, 16, 0, 0);
 }
 
+// timing experiments (wrong results): leave out the operand reads / the step barrier
+#ifdef SGC_GEMM_ABL_NOREAD
+#define SGC_GEMM_READ(x) do { } while (0)
+#else
+#define SGC_GEMM_READ(x) x
+#endif
+#ifdef SGC_GEMM_ABL_NOBAR
+#define SGC_GEMM_BARRIER() do { } while (0)
+#else
+#define SGC_GEMM_BARRIER() __syncthreads()
+#endif
+
 template <bool QKV>
 __global__ void __launch_bounds__(256, 1) proj_gemm_kernel(const GemmArgs g)
 {
@@ -117,7 +129,14 @@ __global__ void __launch_bounds__(256, 1) proj_gemm_kernel(const GemmArgs g)
     auto issue = [&](int kt, int stage) __attribute__((always_inline)) {
         char *as = smem + stage * STAGE_BYTES + wave * 8192;
         char *bs = as + SLAB_BYTES;
+#ifdef SGC_GEMM_ABL_SAMEK      // timing experiment: every step re-reads the first slabs (wrong results)
+        const uint32_t k_off = 0 * kt;
+#else
         const uint32_t k_off = (uint32_t)kt * (TK * 2);
+#endif
+#ifdef SGC_GEMM_ABL_NODMA      // timing experiment: only the first step's slabs are ever copied (wrong results)
+        if (kt > 0) return;
+#endif
 #pragma unroll
         for (int i = 0; i < 8; ++i) copy_1k_to_lds(a_base + (a_off[i] + k_off), as + i * 1024);
 #pragma unroll
@@ -193,20 +212,20 @@ __global__ void __launch_bounds__(256, 1) proj_gemm_kernel(const GemmArgs g)
     auto step = [&](int kt, auto next, auto next2) __attribute__((always_inline)) {
         constexpr bool NEXT = decltype(next)::value, NEXT2 = decltype(next2)::value;
         const char *st = smem + (kt & 1) * STAGE_BYTES;
-        load_ops(st, 1, p1, q1);
+        SGC_GEMM_READ(load_ops(st, 1, p1, q1));
         products(p0, q0);
         order_reads_under_products();
-        load_ops(st, 2, p0, q0);
+        SGC_GEMM_READ(load_ops(st, 2, p0, q0));
         products(p1, q1);
         order_reads_under_products();
-        load_ops(st, 3, p1, q1);
+        SGC_GEMM_READ(load_ops(st, 3, p1, q1));
         products(p0, q0);
         order_reads_under_products();
         if (NEXT) {
             __builtin_amdgcn_s_waitcnt(0x0F70);  // the copies of step kt + 1, requested a step ago
-            __syncthreads();                     // every wavefront has read all of step kt out of LDS
+            SGC_GEMM_BARRIER();                  // every wavefront has read all of step kt out of LDS
             __builtin_amdgcn_sched_barrier(0);
-            load_ops(smem + ((kt + 1) & 1) * STAGE_BYTES, 0, p0, q0);
+            SGC_GEMM_READ(load_ops(smem + ((kt + 1) & 1) * STAGE_BYTES, 0, p0, q0));
             if (NEXT2) issue(kt + 2, kt & 1);
         }
         products(p1, q1);

@@ -233,6 +233,46 @@ def test_launch_entry_points_validate_before_touching_the_device():
     sgc.sgc_ctx_destroy(ctx)
 
 
+def test_projection_entry_points_validate_before_touching_the_device():
+    ctx, cache = _ctx_cache(2, [32, 48])
+    _, _, _, plan = sgc.sgc_assign_clusters(ctx, cache, [0, 1], [4, 4], 2)
+    E, S, T = sgc.SGC_EINVAL, sgc.SGC_ESHAPE, sgc.SGC_ESTATE
+    bad = [
+        (lambda: sgc.sgc_project_out(ctx, 256, 512, 4096, -1, 768), E),                         # negative rows
+        (lambda: sgc.sgc_project_out(ctx, 256, 512, 0, 8, 768), E),                             # d_model
+        (lambda: sgc.sgc_project_out(ctx, None, 512, 4096, 8, 768), E),                         # NULL o
+        (lambda: sgc.sgc_project_out(ctx, 256, 520, 4096, 8, 768), E),                          # misaligned weight
+        (lambda: sgc.sgc_project_out(ctx, 256, 512, 4100, 8, 768), E),                          # rows of y not 16-byte aligned
+        (lambda: sgc.sgc_project_qkv_prefix(ctx, cache, 5, 0, 256, 512, 4096, None, 32), E),    # cluster range
+        (lambda: sgc.sgc_project_qkv_prefix(ctx, cache, 0, 2, 256, 512, 4096, None, 32), E),    # layer range
+        (lambda: sgc.sgc_project_qkv_prefix(ctx, cache, 0, 0, 256, 512, 4096, None, 31), S),    # length mismatch
+        (lambda: sgc.sgc_project_qkv_prefix(ctx, cache, 0, 0, None, 512, 4096, None, 32), E),   # NULL x
+        (lambda: sgc.sgc_project_qkv_prefix(ctx, cache, 0, 0, 256, None, 4096, None, 32), E),   # NULL weight
+        (lambda: sgc.sgc_project_qkv_prefix(ctx, cache, 0, 0, 256, 512, 100, None, 32), E),     # rows of x not aligned
+        (lambda: sgc.sgc_project_qkv_prefix_batched(ctx, cache, [1, 1], 0, [256, 256], 512, 4096), E),   # twice
+        (lambda: sgc.sgc_project_qkv_prefix_batched(ctx, cache, [0, 1], 0, [256, None], 512, 4096), E),  # NULL x
+        (lambda: sgc.sgc_project_qkv_prefix_batched(ctx, cache, [0, 1], 0, [256, 256], 512, 4096, [256, 260]), E),
+        (lambda: sgc.sgc_project_qkv_suffix(ctx, cache, plan, 7, 256, 512, 4096, 768), E),      # layer range
+        (lambda: sgc.sgc_project_qkv_suffix(ctx, cache, plan, 0, 256, 512, 4096, None), E),     # NULL q
+        (lambda: sgc.sgc_project_qkv_suffix(ctx, cache, plan, 0, 256, 512, -4, 768), E),        # d_model
+        (lambda: sgc.sgc_suffix_prefill_batched(ctx, cache, plan, 0, 256, None, None, 256), T),  # nothing projected yet
+        (lambda: sgc.sgc_suffix_prefill_batched(ctx, cache, plan, 0, 256, None, 256, 256), E),   # only one of k, v
+        (lambda: sgc.sgc_prefix_prefill(ctx, cache, 0, 0, None, None, None, None, None, 32), E),  # nothing to do
+    ]
+    for i, (fn, status) in enumerate(bad):
+        with pytest.raises(sgc.SgcError) as e:
+            fn()
+        assert e.value.status == status, (i, str(e.value))
+    assert sgc.sgc_project_out(ctx, None, None, 4096, 0, None) is None            # zero rows: nothing to check or do
+    sgc.sgc_cache_free_cluster(ctx, cache, 1)
+    with pytest.raises(sgc.SgcError) as e:
+        sgc.sgc_project_qkv_suffix(ctx, cache, plan, 0, 256, 512, 4096, 768)
+    assert e.value.status == sgc.SGC_ESTATE
+    sgc.sgc_plan_destroy(plan)
+    sgc.sgc_cache_destroy(cache)
+    sgc.sgc_ctx_destroy(ctx)
+
+
 def test_workload_generators_are_deterministic_and_shaped():
     w = workloads.config(1)
     assert (w.n_clusters, w.n_queries) == (10, 320) and np.all(w.prefix_len == 1024)

@@ -70,9 +70,23 @@ __device__ inline void copy_1k_to_lds(const char *src_lane, char *lds)
 #define SGC_GEMM_BARRIER() __syncthreads()
 #endif
 
+#ifdef SGC_GEMM_PHASE_TIMING
+// Development aid (not built into the product library): per workgroup and wavefront, the time (100 MHz ticks)
+// from the workgroup's start to the end of the main loop and to the end of the epilogue, and the output kind.
+__device__ unsigned long long g_gemm_phase[4096 * 4 * 4];
+#define SGC_GEMM_T0() const unsigned long long gemm_t0 = __builtin_amdgcn_s_memrealtime()
+#define SGC_GEMM_MARK(i, v) do { if (blockIdx.x < 4096 && lane == 0) g_gemm_phase[(blockIdx.x * 4 + wave) * 4 + (i)] = (v); } while (0)
+#define SGC_GEMM_NOW() (__builtin_amdgcn_s_memrealtime() - gemm_t0)
+#else
+#define SGC_GEMM_T0() do { } while (0)
+#define SGC_GEMM_MARK(i, v) do { } while (0)
+#define SGC_GEMM_NOW() 0
+#endif
+
 template <bool QKV>
 __global__ void __launch_bounds__(256, 1) proj_gemm_kernel(const GemmArgs g)
 {
+    SGC_GEMM_T0();
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
@@ -250,6 +264,11 @@ __global__ void __launch_bounds__(256, 1) proj_gemm_kernel(const GemmArgs g)
     if (kt + 1 < n_steps) step(kt++, std::true_type{}, std::false_type{});
     step(kt, std::false_type{}, std::false_type{});
 
+    SGC_GEMM_MARK(0, SGC_GEMM_NOW());
+    SGC_GEMM_MARK(2, (unsigned long long)kind);
+#ifdef SGC_GEMM_PHASE_TIMING
+    SGC_GEMM_MARK(3, gemm_t0);
+#endif
     if (col0 >= N) return;          // the second half of a ragged last column tile
     const int rows16 = (rows + 15) & ~15;
 
@@ -359,6 +378,7 @@ __global__ void __launch_bounds__(256, 1) proj_gemm_kernel(const GemmArgs g)
                 }
             }
     }
+    SGC_GEMM_MARK(1, SGC_GEMM_NOW());
 }
 
 // Any shape and both io types, one output element per thread, fp32 accumulation; columns are dealt to up to
@@ -417,6 +437,13 @@ __global__ void __launch_bounds__(256) zero_last_pages_kernel(char *spool, const
 }
 
 }  // namespace
+
+#ifdef SGC_GEMM_PHASE_TIMING
+extern "C" int sgc_debug_read_gemm_phases(unsigned long long *host, size_t n)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_gemm_phase), n * sizeof(unsigned long long));
+}
+#endif
 
 hipError_t launch_proj_gemm(const GemmArgs &g, bool qkv, hipStream_t s)
 {

@@ -219,6 +219,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default 1: Llama-3-8B-shaped layer)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for the CPU baseline (0 = skip)")
+    ap.add_argument("--sync-each-step", action="store_true",
+                    help="wait for the GPU at the end of every step (step latency instead of pipelined throughput)")
     ap.add_argument("--suffix-only", action="store_true", help="time only the batched suffix launch (profiling aid)")
     ap.add_argument("--decode-steps", type=int, default=32,
                     help="after the timed steps, time this many batched decode steps on the same workload (0 = skip)")
@@ -263,7 +265,6 @@ def main() -> int:
     all_clusters = list(range(w.n_clusters))
     pq_ptrs, pk_ptrs, pv_ptrs, po_ptrs = ([t.data_ptr() for t in ts] for ts in (dpq, dpk, dpv, dpo))
     ev_pairs = []
-    kernel_ms = []            # (suffix ingest, attention) per timed step, from the library's own events
     sgc.sgc_timing_enable(s.ctx, True)
 
     def step(timed: bool):
@@ -281,22 +282,26 @@ def main() -> int:
         if timed:
             e1.record()
             ev_pairs.append((e0, e1))
-        if timed:
-            kernel_ms.append(sgc.sgc_timing_last(s.ctx))     # waits for the launch
+        if args.sync_each_step:
+            torch.cuda.synchronize()
         if not args.suffix_only:
-            torch.cuda.synchronize()       # the pages must be idle before they are released
+            # Everything runs on one stream: the next step's ingest, which reuses these pages, is ordered behind
+            # this step's attention kernels, so the pages can be handed back without waiting for the GPU.
             for c in range(w.n_clusters):
                 sgc.sgc_cache_free_cluster(s.ctx, s.cache, c)
 
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
+    sgc.sgc_timing_enable(s.ctx, True)          # restart the library's count of timed launches
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step(True)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
+    # per-launch kernel durations of the timed steps, from the library's events (it keeps the last 64)
+    kernel_ms = [sgc.sgc_timing_get(s.ctx, back) for back in range(min(args.steps, 64))]
     kern_ms = float(np.mean([a.elapsed_time(b) for a, b in ev_pairs]))         # ingest + attention
     kern_ms_min = float(np.min([a.elapsed_time(b) for a, b in ev_pairs]))
     ingest_ms = float(np.mean([a for a, _ in kernel_ms]))

@@ -154,7 +154,7 @@ void dev_release(sgc_ctx *ctx, sgc_dev_block b, hipStream_t last)
 int stage_begin(sgc_ctx *ctx, size_t bytes, char **host, int *slot)
 {
     const int i = ctx->stage_next;
-    ctx->stage_next ^= 1;
+    ctx->stage_next = (i + 1) % sgc_ctx::kStageSlots;
     if (!ctx->stage_ev[i]) SGC_HIP(ctx, hipEventCreateWithFlags(&ctx->stage_ev[i], hipEventDisableTiming));
     if (ctx->stage_pending[i]) {
         SGC_HIP(ctx, hipEventSynchronize(ctx->stage_ev[i]));
@@ -483,11 +483,12 @@ int sgc_ctx_destroy(sgc_ctx *ctx)
 {
     if (!ctx) return SGC_OK;
     if (ctx->d_rope) (void)hipFree(ctx->d_rope);
-    for (hipEvent_t e : ctx->ev)
-        if (e) (void)hipEventDestroy(e);
+    for (auto &triple : ctx->ev)
+        for (hipEvent_t e : triple)
+            if (e) (void)hipEventDestroy(e);
     (void)hipDeviceSynchronize();
     for (const sgc_dev_block &b : ctx->dev_free) (void)hipFree(b.p);
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < sgc_ctx::kStageSlots; ++i) {
         if (ctx->h_stage[i]) (void)hipHostFree(ctx->h_stage[i]);
         if (ctx->stage_ev[i]) (void)hipEventDestroy(ctx->stage_ev[i]);
     }
@@ -1065,17 +1066,18 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
     a.sq_page0 = pl->d_sq_page0;
     a.spool = pl->d_spool + (pl->decode_cap > 0 ? (size_t)layer * pl->spool_layer_bytes : 0);
     a.total_tokens = pl->total_tokens;
-    if (ctx->timing) SGC_HIP(ctx, hipEventRecord(ctx->ev[0], s));
+    hipEvent_t *tev = ctx->ev[ctx->timing_count % sgc_ctx::kTimingRing];
+    if (ctx->timing) SGC_HIP(ctx, hipEventRecord(tev[0], s));
     if (ctx->use_mfma && !skip_ingest) SGC_HIP(ctx, launch_suffix_ingest(a, pl->d_spage_sq, (int)pl->spage_sq.size(), s));
-    if (ctx->timing) SGC_HIP(ctx, hipEventRecord(ctx->ev[1], s));
+    if (ctx->timing) SGC_HIP(ctx, hipEventRecord(tev[1], s));
     if (ctx->use_mfma) {
         SGC_HIP(ctx, launch_attn_mfma(a, ctx->mfma_variant, s));
     } else {
         SGC_HIP(ctx, launch_attn_generic(a, pl->total_tokens * ctx->p.n_q_heads, s));
     }
     if (ctx->timing) {
-        SGC_HIP(ctx, hipEventRecord(ctx->ev[2], s));
-        ctx->timing_valid = true;
+        SGC_HIP(ctx, hipEventRecord(tev[2], s));
+        ++ctx->timing_count;
     }
     return SGC_OK;
 }
@@ -1181,26 +1183,31 @@ int sgc_timing_enable(sgc_ctx *ctx, int on)
 {
     if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
     if (on) {
-        for (hipEvent_t &e : ctx->ev)
-            if (!e) SGC_HIP(ctx, hipEventCreate(&e));
+        for (auto &triple : ctx->ev)
+            for (hipEvent_t &e : triple)
+                if (!e) SGC_HIP(ctx, hipEventCreate(&e));
     }
     ctx->timing = on != 0;
-    ctx->timing_valid = false;
+    ctx->timing_count = 0;
     return SGC_OK;
 }
 
-int sgc_timing_last(sgc_ctx *ctx, float *ingest_ms, float *attention_ms)
+int sgc_timing_get(sgc_ctx *ctx, int32_t back, float *ingest_ms, float *attention_ms)
 {
     if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
-    if (!ctx->timing || !ctx->timing_valid) return fail(ctx, SGC_ESTATE, "no timed launch has been recorded");
-    SGC_HIP(ctx, hipEventSynchronize(ctx->ev[2]));
+    if (back < 0 || back >= sgc_ctx::kTimingRing) return fail(ctx, SGC_EINVAL, "back %d outside [0, %d)", back, sgc_ctx::kTimingRing);
+    if (!ctx->timing || ctx->timing_count <= (uint64_t)back) return fail(ctx, SGC_ESTATE, "no such timed launch has been recorded");
+    hipEvent_t *tev = ctx->ev[(ctx->timing_count - 1 - back) % sgc_ctx::kTimingRing];
+    SGC_HIP(ctx, hipEventSynchronize(tev[2]));
     float a = 0.f, b = 0.f;
-    SGC_HIP(ctx, hipEventElapsedTime(&a, ctx->ev[0], ctx->ev[1]));
-    SGC_HIP(ctx, hipEventElapsedTime(&b, ctx->ev[1], ctx->ev[2]));
+    SGC_HIP(ctx, hipEventElapsedTime(&a, tev[0], tev[1]));
+    SGC_HIP(ctx, hipEventElapsedTime(&b, tev[1], tev[2]));
     if (ingest_ms) *ingest_ms = a;
     if (attention_ms) *attention_ms = b;
     return SGC_OK;
 }
+
+int sgc_timing_last(sgc_ctx *ctx, float *ingest_ms, float *attention_ms) { return sgc_timing_get(ctx, 0, ingest_ms, attention_ms); }
 
 // ------------------------------------------------------------------------------------------------
 static int export_import(sgc_ctx *ctx, sgc_cache *c, int32_t cluster_id, int32_t layer, void *dev_k, void *dev_v,

@@ -228,14 +228,17 @@ struct sgc_ctx {
     // Device blocks and pinned staging buffers are kept and reused: the per-batch tables are small and a
     // hipMalloc / hipFree pair per batch costs more than the copies themselves.
     std::vector<sgc_dev_block> dev_free;
-    char *h_stage[2] = {nullptr, nullptr};
-    size_t h_stage_cap[2] = {0, 0};
-    hipEvent_t stage_ev[2] = {nullptr, nullptr};
-    bool stage_pending[2] = {false, false};
+    static constexpr int kStageSlots = 8;      // copies a caller can have in flight before the host waits for one
+    char *h_stage[kStageSlots] = {};
+    size_t h_stage_cap[kStageSlots] = {};
+    hipEvent_t stage_ev[kStageSlots] = {};
+    bool stage_pending[kStageSlots] = {};
     int stage_next = 0;
     bool timing = false;            // record events around the suffix launch's kernels
-    bool timing_valid = false;
-    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // before ingest, between, after attention
+    // the last kTimingRing timed suffix launches: events before ingest, between, after attention
+    static constexpr int kTimingRing = 64;
+    hipEvent_t ev[kTimingRing][3] = {};
+    uint64_t timing_count = 0;      // timed launches recorded since timing was switched on
 };
 
 struct sgc_cluster_entry {

@@ -28,7 +28,7 @@ EXPORTS = [
     "sgc_plan_get_info", "sgc_plan_destroy", "sgc_suffix_prefill_batched", "sgc_cache_export", "sgc_cache_import",
     "sgc_timing_enable", "sgc_timing_last", "sgc_cluster_queries", "sgc_plan_enable_decode", "sgc_decode_step_batched",
     "sgc_union_subgraphs", "sgc_project_qkv_prefix", "sgc_project_qkv_prefix_batched", "sgc_project_qkv_suffix",
-    "sgc_project_out",
+    "sgc_project_out", "sgc_timing_get",
 ]
 
 
@@ -107,6 +107,7 @@ def lib() -> ctypes.CDLL:
         L.sgc_project_out.argtypes = [vp, vp, vp, i32, i64, vp, vp]
         L.sgc_timing_enable.argtypes = [vp, ctypes.c_int]
         L.sgc_timing_last.argtypes = [vp, f32p, f32p]
+        L.sgc_timing_get.argtypes = [vp, i32, f32p, f32p]
         for name in EXPORTS:
             fn = getattr(L, name)
             if fn.restype is ctypes.c_int and name not in ("sgc_version",):
@@ -356,6 +357,13 @@ def sgc_timing_last(ctx) -> Tuple[float, float]:
     """(suffix ingest ms, attention kernel ms) of the last timed sgc_suffix_prefill_batched call."""
     a, b = ctypes.c_float(0), ctypes.c_float(0)
     _check(ctx, lib().sgc_timing_last(ctx, ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
+
+
+def sgc_timing_get(ctx, back: int) -> Tuple[float, float]:
+    """The same for the launch `back` timed launches before the last one (the last 64 are kept)."""
+    a, b = ctypes.c_float(0), ctypes.c_float(0)
+    _check(ctx, lib().sgc_timing_get(ctx, int(back), ctypes.byref(a), ctypes.byref(b)))
     return a.value, b.value
 
 

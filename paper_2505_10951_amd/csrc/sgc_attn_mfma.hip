@@ -138,6 +138,13 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         lse_stride = t.prefix_len;
         t.tok_base = 0;
     }
+    // decode tiles cover one key range of the cluster's cache: own output set, positions continue behind ALL cached keys
+    const int key_range = __builtin_amdgcn_readfirstlane(t.pad) >> 24;
+    const int pos_extra = __builtin_amdgcn_readfirstlane(t.pad) & 0xFFFFFF;
+    if (MODE == MODE_SUFFIX) {
+        o_base = static_cast<char *>(o_base) + key_range * a.split_o_bytes;
+        if (lse_base) lse_base += key_range * a.split_lse_elems;
+    }
     // everything that steers the tile loop is made explicitly wave-uniform (scalar registers)
     const int cluster = __builtin_amdgcn_readfirstlane(t.cluster), hk = __builtin_amdgcn_readfirstlane(t.hk);
     t.row0 = __builtin_amdgcn_readfirstlane(t.row0);
@@ -351,7 +358,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         if (rotate) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
-                const int pos = (MODE == MODE_SUFFIX ? P + a.pos_shift : 0) + qpos[mi];
+                const int pos = (MODE == MODE_SUFFIX ? P + pos_extra + a.pos_shift : 0) + qpos[mi];
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb) {
                     const float4 *tab = reinterpret_cast<const float4 *>(a.rope + (int64_t)pos * 64 + kb * 16 + h * 8);

@@ -328,10 +328,11 @@ void build_tiles(sgc_plan *pl, int tile_rows)
     pl->tile_rows = tile_rows;
 }
 
-void fill_first_pages(Tile &t, const std::vector<int32_t> &pages)
+// first: first page of the tile's key range inside the cluster's page list; n: pages of the range
+void fill_first_pages(Tile &t, const std::vector<int32_t> &pages, int first = 0, int n = -1)
 {
-    const int n = (int)pages.size();
-    for (int i = 0; i < 12; ++i) t.first_pages[i] = n ? pages[std::min(i, n - 1)] : 0;
+    if (n < 0) n = (int)pages.size() - first;
+    for (int i = 0; i < 12; ++i) t.first_pages[i] = n > 0 ? pages[first + std::min(i, n - 1)] : 0;
 }
 
 // Page-table offsets of the clusters as cache_sync lays the flat table out; they move when clusters
@@ -344,12 +345,18 @@ void fill_tile_pt_off(sgc_plan *pl, const sgc_cache *c)
         off[i] = n;
         if (c->cl[i].allocated) n += (int32_t)c->cl[i].pages.size();
     }
-    for (std::vector<Tile> *list : {&pl->tiles, &pl->dtiles})
-        for (Tile &t : *list) {
-            if (t.n_rows == 0) continue;
-            t.pt_off = off[t.cluster];
-            fill_first_pages(t, c->cl[t.cluster].pages);
-        }
+    for (Tile &t : pl->tiles) {
+        if (t.n_rows == 0) continue;
+        t.pt_off = off[t.cluster];
+        fill_first_pages(t, c->cl[t.cluster].pages);
+    }
+    for (size_t i = 0; i < pl->dtiles.size(); ++i) {      // a decode tile covers the key range that starts at dtile_key0
+        Tile &t = pl->dtiles[i];
+        if (t.n_rows == 0) continue;
+        const int first = pl->dtile_key0[i] / kPageTokens;
+        t.pt_off = off[t.cluster] + first;
+        fill_first_pages(t, c->cl[t.cluster].pages, first, (t.prefix_len + kPageTokens - 1) / kPageTokens);
+    }
     pl->tiles_generation = c->generation;
 }
 
@@ -374,19 +381,32 @@ void build_decode_tiles(sgc_plan *pl, int tile_rows)
     const sgc_ctx *ctx = pl->ctx;
     const int g = ctx->p.n_q_heads / ctx->p.n_kv_heads;
     struct Light {
-        int32_t cluster, hk, row0;
+        int32_t cluster, hk, row0, split;
     };
     struct Unit {
         int32_t cluster, hk;
         double work;
     };
     std::vector<Unit> units;
+    int64_t row_tiles = 0;
+    int max_steps = 0;
     for (int c = 0; c < pl->n_clusters; ++c) {
         const int64_t nq = pl->cl_sq_off[c + 1] - pl->cl_sq_off[c];
         if (nq == 0) continue;
         const int64_t nt = (nq * g + tile_rows - 1) / tile_rows;
+        row_tiles += nt * ctx->p.n_kv_heads;
+        max_steps = std::max(max_steps, (pl->cl_prefix_len[c] + 63) / 64);
         for (int hk = 0; hk < ctx->p.n_kv_heads; ++hk) units.push_back({c, hk, (double)nt * (pl->cl_prefix_len[c] + 64.0)});
     }
+    // A step has few rows (one per query and head), so few row tiles: the cached keys of every row tile are split
+    // into S ranges of whole 64-key steps, each range a tile of its own whose partial result the own-keys kernel
+    // merges.  A tile's fixed work (record, Q, store) costs about as much as eight steps, so S stays small: at
+    // most one tile per CU, at least eight steps per range (measured on 80 row tiles x 16 steps: S = 1, 2, 3, 4, 6
+    // -> 60, 57, 57, 62, 65 us per decode step).
+    int S = row_tiles > 0 ? (int)std::min<int64_t>(kDecodeMaxSplits, 256 / row_tiles) : 1;
+    S = std::max(1, std::min(S, max_steps / 8));
+    if (max_steps >= (1 << 24) / 64) S = 1;      // the position offset travels in 24 bits of the tile record
+    pl->dec_splits = S;
     std::stable_sort(units.begin(), units.end(), [](const Unit &a, const Unit &b) { return a.work > b.work; });
     std::vector<std::vector<Light>> lists(kXcd);
     double load[kXcd] = {0};
@@ -396,24 +416,31 @@ void build_decode_tiles(sgc_plan *pl, int tile_rows)
             if (load[i] < load[x]) x = i;
         load[x] += u.work;
         const int64_t rows = (int64_t)(pl->cl_sq_off[u.cluster + 1] - pl->cl_sq_off[u.cluster]) * g;
-        for (int64_t r = 0; r < rows; r += tile_rows) lists[x].push_back({u.cluster, u.hk, (int32_t)r});
+        for (int64_t r = 0; r < rows; r += tile_rows)
+            for (int sp = 0; sp < S; ++sp) lists[x].push_back({u.cluster, u.hk, (int32_t)r, sp});
     }
     size_t slots = 0;
     for (auto &l : lists) slots = std::max(slots, l.size());
     pl->dtiles.assign(slots * kXcd, Tile{});
+    pl->dtile_key0.assign(slots * kXcd, 0);
     for (int x = 0; x < kXcd; ++x)
         for (size_t k = 0; k < lists[x].size(); ++k) {
             Tile &t = pl->dtiles[k * kXcd + x];
             const Light &lt = lists[x][k];
             const int64_t rows = (int64_t)(pl->cl_sq_off[lt.cluster + 1] - pl->cl_sq_off[lt.cluster]) * g;
+            const int P = pl->cl_prefix_len[lt.cluster], steps = (P + 63) / 64;
+            const int key0 = std::min(P, 64 * (int)((int64_t)steps * lt.split / S));
+            const int key1 = std::min(P, 64 * (int)((int64_t)steps * (lt.split + 1) / S));
             t.cluster = lt.cluster;
             t.hk = lt.hk;
             t.row0 = lt.row0;
             t.n_rows = (int32_t)std::min<int64_t>(tile_rows, rows - lt.row0);
-            t.prefix_len = pl->cl_prefix_len[lt.cluster];
+            t.prefix_len = key1 - key0;                   // the tile's own key count ...
+            t.pad = (lt.split << 24) | (P - t.prefix_len);   // ... its split index, and what positions start beyond it
             t.tok_base = pl->cl_sq_off[lt.cluster];      // "token" = the query's one new token
             t.sq_hi = -1;
             t.n_q = kTileQueries + 1;                     // row bookkeeping from the table, not from inline records
+            pl->dtile_key0[k * kXcd + x] = key0;
         }
     pl->dtok.resize(pl->sq_len.size());
     for (size_t sq = 0; sq < pl->sq_len.size(); ++sq) pl->dtok[sq] = {pl->sq_query[sq], pl->sq_len[sq], (int32_t)sq, 0};
@@ -1127,10 +1154,12 @@ int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int
     if ((rc = cache_sync(c, s)) != SGC_OK) return rc;
     if ((rc = refresh_tiles(pl, c, s)) != SGC_OK) return rc;
     pl->last_stream = s;
-    // scratch for the cached-prefix part of the step: O [n_queries][Hq][d] bf16, then LSE [Hq][n_queries]
+    // scratch for the cached-prefix part of the step, one set per key range: O [S][n_queries][Hq][d] bf16, then
+    // LSE [S][Hq][n_queries]
+    const int S = std::max(1, pl->dec_splits);
     const size_t o_bytes = ((size_t)pl->n_queries * ctx->p.n_q_heads * ctx->p.head_dim * 2 + 255) / 256 * 256;
-    const size_t lse_bytes = (size_t)ctx->p.n_q_heads * pl->n_queries * sizeof(float);
-    if (!pl->dec_scratch.p && (rc = dev_acquire(ctx, o_bytes + lse_bytes, s, &pl->dec_scratch)) != SGC_OK) return rc;
+    const size_t lse_bytes = ((size_t)ctx->p.n_q_heads * pl->n_queries * sizeof(float) + 255) / 256 * 256;
+    if (!pl->dec_scratch.p && (rc = dev_acquire(ctx, S * (o_bytes + lse_bytes), s, &pl->dec_scratch)) != SGC_OK) return rc;
     char *spool = pl->d_spool + (size_t)layer * pl->spool_layer_bytes;
 
     DecodeArgs d{};
@@ -1140,7 +1169,10 @@ int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int
     d.o = dev_o;
     d.lse = dev_lse;
     d.o_cached = pl->dec_scratch.p;
-    d.lse_cached = reinterpret_cast<const float *>(pl->dec_scratch.p + o_bytes);
+    d.lse_cached = reinterpret_cast<const float *>(pl->dec_scratch.p + S * o_bytes);
+    d.n_splits = S;
+    d.split_o_elems = (int64_t)(o_bytes / 2);
+    d.split_lse_elems = (int64_t)(lse_bytes / sizeof(float));
     d.spool = spool;
     d.sq_query = pl->d_sq_query;
     d.sq_len = pl->d_sq_len;
@@ -1163,7 +1195,9 @@ int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int
     fill_common_args(a, ctx, c, layer);
     a.q = dev_q;
     a.o = pl->dec_scratch.p;
-    a.lse = reinterpret_cast<float *>(pl->dec_scratch.p + o_bytes);
+    a.lse = reinterpret_cast<float *>(pl->dec_scratch.p + S * o_bytes);
+    a.split_o_bytes = (int64_t)o_bytes;
+    a.split_lse_elems = (int64_t)(lse_bytes / sizeof(float));
     a.lse_stride = pl->n_queries;
     a.mode = MODE_SUFFIX;
     a.tiles = pl->d_dtiles;

@@ -81,7 +81,7 @@ struct Tile {
     int32_t sq_lo, sq_hi;   // sorted queries of the tile's first and last row
     int32_t last_qpos;   // position of the last row's token inside its query
     int32_t n_q;         // sq_hi - sq_lo + 1; the records q[] are valid when n_q <= kTileQueries
-    int32_t pad;
+    int32_t pad;         // decode tiles: key range index << 24 | position offset (cached keys outside the range)
     int32_t first_pages[12];       // page ids of the cluster's first 12 pages (clamped to its last page)
     TileQuery q[kTileQueries];     // queries sq_lo, sq_lo + 1, ...
 };
@@ -108,6 +108,7 @@ struct PrefixJob {
 };
 
 // One decode step of every (non-empty) query of a plan: arguments of the append and own-keys kernels.
+constexpr int kDecodeMaxSplits = 8;       // key ranges the cached part of a decode step may be split into
 constexpr int kDecodeMaxKeys = 1024;      // own keys (suffix + generated) a query may reach while decoding
 struct DecodeArgs {
     const void *q, *k, *v;        // the new token of every query: [n_queries][Hq][d], [n_queries][Hkv][d], bf16
@@ -115,6 +116,8 @@ struct DecodeArgs {
     float *lse;                   // [Hq][n_queries] natural log, or null
     const void *o_cached;         // cached-prefix part of the same rows: [n_queries][Hq][d] bf16 (normalised) ...
     const float *lse_cached;      // ... and its log-sum-exp [Hq][n_queries], natural log (-inf: no cached keys)
+    int32_t n_splits;             // the cached part comes as n_splits partial results (key ranges), set s at ...
+    int64_t split_o_elems, split_lse_elems;   // ... o_cached + s * split_o_elems, lse_cached + s * split_lse_elems
     char *spool;                  // the layer's suffix pages
     const int32_t *sq_query;      // [n_sq] original index of the sorted query
     const int32_t *sq_len, *sq_page0, *sq_cluster;
@@ -205,6 +208,9 @@ struct AttnArgs {
     // kernel only does the cached-prefix part (skip_self), leaving the own keys to the decode kernel
     int32_t pos_shift;
     int32_t skip_self;
+    // a tile whose pad field names key range s (upper 8 bits) writes its rows to o + s * split_o_bytes and
+    // lse + s * split_lse_elems; the low 24 bits of pad are added to the rows' positions
+    int64_t split_o_bytes, split_lse_elems;
 };
 
 }  // namespace sgc
@@ -282,6 +288,8 @@ struct sgc_plan {
     // query, the suffix page pool exists once per layer, and a second tile list stacks one row group per query
     int32_t decode_cap = 0;
     std::vector<sgc::Tile> dtiles;
+    std::vector<int32_t> dtile_key0;          // first cached key of each decode tile's key range
+    int32_t dec_splits = 1;                   // key ranges per row tile
     std::vector<sgc::TokInfo> dtok;
     size_t spool_layer_bytes = 0;
     sgc_dev_block dec_scratch;                // cached-prefix part of a decode step: O then LSE

@@ -480,26 +480,37 @@ __global__ void __launch_bounds__(64) decode_own_keys_kernel(DecodeArgs a)
             }
         }
     }
-    // merge with the cached-prefix part (natural-log LSE there; log2 units here)
+    // merge with the cached-prefix part, which comes as n_splits partial results over key ranges (natural-log
+    // LSE there, -inf for an empty range; log2 units here)
     uint16_t *og = static_cast<uint16_t *>(a.o);
     const uint16_t *oc = static_cast<const uint16_t *>(a.o_cached);
+    const int S = a.n_splits;
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) {
         const int h = h0 + gi;
         const float lse_own = m[gi] + log2f(l[gi]);
-        float lse_c = -INFINITY;
-        if (a.lse_cached) lse_c = a.lse_cached[(int64_t)h * a.n_queries + n] * 1.4426950408889634f;
-        const bool use_cached = lse_c > -INFINITY;
-        const float M = fmaxf(lse_own, lse_c);
-        const float wc = use_cached ? exp2f(lse_c - M) : 0.f;
-        const float wo = exp2f(m[gi] - M);                       // weight of the unnormalised own sum
-        const float denom = wc + exp2f(lse_own - M);
+        float lse_c[kDecodeMaxSplits];
+        float M = lse_own;
 #pragma unroll
-        for (int cI = 0; cI < 2; ++cI) {
-            const int c = lane + cI * 64;
-            const float cached = use_cached ? bf16_to_f32(oc[io + gi * d + c]) : 0.f;
-            og[io + gi * d + c] = f32_to_bf16((wc * cached + wo * acc[gi][cI]) / denom);
+        for (int sp = 0; sp < kDecodeMaxSplits; ++sp) {
+            lse_c[sp] = -INFINITY;
+            if (sp < S && a.lse_cached) lse_c[sp] = a.lse_cached[sp * a.split_lse_elems + (int64_t)h * a.n_queries + n] * 1.4426950408889634f;
+            M = fmaxf(M, lse_c[sp]);
         }
+        const float wo = exp2f(m[gi] - M);                       // weight of the unnormalised own sum
+        float denom = exp2f(lse_own - M);
+        float sum[2] = {wo * acc[gi][0], wo * acc[gi][1]};
+#pragma unroll
+        for (int sp = 0; sp < kDecodeMaxSplits; ++sp) {
+            if (!(lse_c[sp] > -INFINITY)) continue;
+            const float wc = exp2f(lse_c[sp] - M);
+            denom += wc;
+#pragma unroll
+            for (int cI = 0; cI < 2; ++cI)
+                sum[cI] += wc * bf16_to_f32(oc[sp * a.split_o_elems + io + gi * d + lane + cI * 64]);
+        }
+#pragma unroll
+        for (int cI = 0; cI < 2; ++cI) og[io + gi * d + lane + cI * 64] = f32_to_bf16(sum[cI] / denom);
         if (a.lse && lane == 0) a.lse[(int64_t)h * a.n_queries + n] = (M + log2f(denom)) * 0.6931471805599453f;
     }
 }

@@ -100,6 +100,19 @@ def test_decode_many_queries_span_several_row_tiles():
     assert np.abs(got[0] - o_ref).max() <= TOL["bf16"] and np.abs(got[1] - lse_ref).max() <= 5e-2
 
 
+@pytest.mark.parametrize("kv", ["bf16", "fp8_e4m3"])
+def test_decode_long_prompts_split_the_cached_keys_into_ranges(kv):
+    # prompts of 17-40 key steps and few row tiles: the cached part of a step runs as several key ranges per row tile
+    # (one of the clusters is too short to fill every range), merged with the own keys by log-sum-exp
+    w = workloads.custom("decode_split", n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=500000.0, io_dtype="bf16",
+                         kv_dtype=kv, prefix_len=[2500, 1100, 70], cluster_sizes=[3, 2, 2], suffix_range=(2, 35), seed=43)
+    got = _run_decode(w, 3)[0]
+    o_ref, lse_ref = _oracle_decode(w, 0, 3, oracle_caches(w, 0))
+    err, lerr = np.abs(got[0] - o_ref).max(), np.abs(got[1] - lse_ref).max()
+    print(f"  decode split {kv}: max_abs {err:.3e} lse {lerr:.3e}", flush=True)
+    assert np.isfinite(got[0]).all() and err <= TOL[kv] and lerr <= 5e-2
+
+
 def test_decode_argument_checks():
     w = workloads.custom("decode_args", n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=10000.0, io_dtype="bf16",
                          prefix_len=[32], cluster_sizes=[2], suffix_range=(4, 4), seed=43)

@@ -335,17 +335,32 @@ __global__ void decode_append_kernel(DecodeArgs a)
 // One wavefront per (sorted query, group of G query heads that share a KV head): scores of the new token
 // against the query's own len + step + 1 keys (lane = key, each key read once for the G heads), softmax,
 // weighted V sum (lane = channel pair), merged with the cached-prefix part by the log-sum-exp rule.
-// fp32 arithmetic.  G divides the GQA group size.
+// Both products run on bf16 pairs with fp32 accumulation (v_dot2_f32_bf16), on the operands a matrix-core
+// kernel would use: the rotated query and the softmax weights rounded to bf16, the row sum taken over the
+// rounded weights.  G divides the GQA group size.
+typedef __attribute__((ext_vector_type(2))) __bf16 dec_bf16x2;
+
+__device__ inline float dot8_bf16(const uint4 &x, const uint4 &y, float acc)
+{
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dec_bf16x2, x.x), __builtin_bit_cast(dec_bf16x2, y.x), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dec_bf16x2, x.y), __builtin_bit_cast(dec_bf16x2, y.y), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dec_bf16x2, x.z), __builtin_bit_cast(dec_bf16x2, y.z), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dec_bf16x2, x.w), __builtin_bit_cast(dec_bf16x2, y.w), acc, false);
+    return acc;
+}
+
 template <int G>
 __global__ void __launch_bounds__(64) decode_own_keys_kernel(DecodeArgs a)
 {
     constexpr int d = 128, half = 64;
-    // LDS: the G rotated query rows, then G rows of key_cap weights (key_cap = the batch's largest key count,
-    // rounded up to a page; sized at launch so that many wavefronts fit a CU)
-    extern __shared__ __attribute__((aligned(16))) float dec_lds[];
-    float(*q_s)[d] = reinterpret_cast<float(*)[d]>(dec_lds);
+    // LDS: the G rotated query rows as bf16 [G][128]; G rows of key_cap scores (fp32); G rows of key_cap weights as
+    // bf16 in the order the V pages hold their tokens (key_cap = the batch's largest key count, rounded up to a page;
+    // sized at launch so that many wavefronts fit a CU)
+    extern __shared__ __attribute__((aligned(16))) char dec_lds[];
     const int key_cap = a.key_cap;
-    float *p_base = dec_lds + G * d;
+    uint16_t *q_s = reinterpret_cast<uint16_t *>(dec_lds);                          // [G][d]
+    float *p_base = reinterpret_cast<float *>(dec_lds + G * d * 2);                  // [G][key_cap]
+    uint16_t *w_s = reinterpret_cast<uint16_t *>(dec_lds + G * d * 2 + G * key_cap * 4);   // [G][key_cap]
     const int lane = threadIdx.x;
     const int Hq = a.n_q_heads, Hkv = a.n_kv_heads, g = Hq / Hkv;
     const int units_per_query = Hq / G;
@@ -362,11 +377,14 @@ __global__ void __launch_bounds__(64) decode_own_keys_kernel(DecodeArgs a)
         load8(a.q, io + gi * d + cc * 8, SGC_BF16, x1);
         load8(a.q, io + gi * d + half + cc * 8, SGC_BF16, x2);
         if (a.rope) rope8(x1, x2, a.rope + (int64_t)(P + n_keys - 1) * half + cc * 8);
+        uint32_t w1[4], w2[4];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            q_s[gi][cc * 8 + i] = x1[i];
-            q_s[gi][half + cc * 8 + i] = x2[i];
+        for (int i = 0; i < 4; ++i) {
+            w1[i] = (uint32_t)f32_to_bf16(x1[2 * i]) | ((uint32_t)f32_to_bf16(x1[2 * i + 1]) << 16);
+            w2[i] = (uint32_t)f32_to_bf16(x2[2 * i]) | ((uint32_t)f32_to_bf16(x2[2 * i + 1]) << 16);
         }
+        *reinterpret_cast<uint4 *>(q_s + gi * d + cc * 8) = make_uint4(w1[0], w1[1], w1[2], w1[3]);
+        *reinterpret_cast<uint4 *>(q_s + gi * d + half + cc * 8) = make_uint4(w2[0], w2[1], w2[2], w2[3]);
     }
     __syncthreads();
     const int64_t part = (int64_t)kPageTokens * d * 2;
@@ -388,20 +406,9 @@ __global__ void __launch_bounds__(64) decode_own_keys_kernel(DecodeArgs a)
         for (int gi = 0; gi < G; ++gi) sc[gi] = 0.f;
 #pragma unroll
         for (int cc = 0; cc < d / 8; ++cc) {
-            const uint32_t w[4] = {raw[cc].x, raw[cc].y, raw[cc].z, raw[cc].w};
-            float kk[8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                kk[2 * i] = __uint_as_float(w[i] << 16);
-                kk[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
-            }
-#pragma unroll
-            for (int gi = 0; gi < G; ++gi) {
-                const float4 qa = *reinterpret_cast<const float4 *>(&q_s[gi][cc * 8]);
-                const float4 qb = *reinterpret_cast<const float4 *>(&q_s[gi][cc * 8 + 4]);
-                sc[gi] += qa.x * kk[0] + qa.y * kk[1] + qa.z * kk[2] + qa.w * kk[3] + qb.x * kk[4] + qb.y * kk[5] +
-                          qb.z * kk[6] + qb.w * kk[7];
-            }
+            for (int gi = 0; gi < G; ++gi)
+                sc[gi] = dot8_bf16(raw[cc], *reinterpret_cast<const uint4 *>(q_s + gi * d + cc * 8), sc[gi]);
         }
 #pragma unroll
         for (int gi = 0; gi < G; ++gi) {
@@ -415,24 +422,27 @@ __global__ void __launch_bounds__(64) decode_own_keys_kernel(DecodeArgs a)
         for (int o = 32; o > 0; o >>= 1) m[gi] = fmaxf(m[gi], __shfl_xor(m[gi], o));
         l[gi] = 0.f;
     }
-    for (int j = lane; j < n_keys; j += kWave) {
+    // weights, rounded to bf16, stored where the V pages keep their tokens: a page holds, per channel, two runs of
+    // 8 tokens; token t of a page is element (t & 3) | ((t >> 3) << 2) of run (t >> 2) & 1
+    const int n_pages = (n_keys + kPageTokens - 1) / kPageTokens;
+    for (int j = lane; j < n_pages * kPageTokens; j += kWave) {
+        const int pg = j / kPageTokens, t = j % kPageTokens;
+        const int slot = (pg * 2 + ((t >> 2) & 1)) * 8 + ((t & 3) | ((t >> 3) << 2));
 #pragma unroll
         for (int gi = 0; gi < G; ++gi) {
-            const float p = exp2f(p_base[gi * key_cap + j] - m[gi]);
-            p_base[gi * key_cap + j] = p;
-            l[gi] += p;
+            uint16_t wb = 0;                                    // the unused tail of the last page weighs nothing
+            if (j < n_keys) {
+                wb = f32_to_bf16(exp2f(p_base[gi * key_cap + j] - m[gi]));
+                l[gi] += bf16_to_f32(wb);
+            }
+            w_s[gi * key_cap + slot] = wb;
         }
     }
 #pragma unroll
     for (int gi = 0; gi < G; ++gi)
         for (int o = 32; o > 0; o >>= 1) l[gi] += __shfl_xor(l[gi], o);
-    const int n_pages = (n_keys + kPageTokens - 1) / kPageTokens;
-    for (int j = n_keys + lane; j < n_pages * kPageTokens; j += kWave) {     // tail of the last page
-#pragma unroll
-        for (int gi = 0; gi < G; ++gi) p_base[gi * key_cap + j] = 0.f;
-    }
     __syncthreads();
-    // weighted V sum, lane = channels (lane, lane + 64); a page holds, per channel, two runs of 8 tokens
+    // weighted V sum, lane = channels (lane, lane + 64)
     float acc[G][2];
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) acc[gi][0] = acc[gi][1] = 0.f;
@@ -457,25 +467,12 @@ __global__ void __launch_bounds__(64) decode_own_keys_kernel(DecodeArgs a)
             const int pg = pg0 + pi;
             if (pg >= n_pages) break;
 #pragma unroll
-            for (int cI = 0; cI < 2; ++cI) {
+            for (int hh = 0; hh < 2; ++hh) {
 #pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    const uint4 rr = raw[pi][cI * 2 + hh];
-                    const uint32_t w[4] = {rr.x, rr.y, rr.z, rr.w};
-                    float vv[8];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        vv[2 * i] = __uint_as_float(w[i] << 16);
-                        vv[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
-                    }
-#pragma unroll
-                    for (int gi = 0; gi < G; ++gi) {
-                        const float *pw = p_base + gi * key_cap + pg * kPageTokens + 4 * hh;    // tokens 4 hh + {0..3} and + 8
-                        const float4 pa = *reinterpret_cast<const float4 *>(pw);
-                        const float4 pb = *reinterpret_cast<const float4 *>(pw + 8);
-                        acc[gi][cI] += pa.x * vv[0] + pa.y * vv[1] + pa.z * vv[2] + pa.w * vv[3] + pb.x * vv[4] + pb.y * vv[5] +
-                                       pb.z * vv[6] + pb.w * vv[7];
-                    }
+                for (int gi = 0; gi < G; ++gi) {
+                    const uint4 wts = *reinterpret_cast<const uint4 *>(w_s + gi * key_cap + (pg * 2 + hh) * 8);
+                    acc[gi][0] = dot8_bf16(raw[pi][hh], wts, acc[gi][0]);
+                    acc[gi][1] = dot8_bf16(raw[pi][2 + hh], wts, acc[gi][1]);
                 }
             }
         }
@@ -756,7 +753,7 @@ hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s)
     const int g = d.n_q_heads / d.n_kv_heads;
     const int G = g % 8 == 0 ? 8 : g % 4 == 0 ? 4 : g % 2 == 0 ? 2 : 1;      // heads per wavefront
     const dim3 grid((unsigned)((int64_t)d.n_sq * (d.n_q_heads / G)));
-    const size_t lds = (size_t)G * (128 + d.key_cap) * sizeof(float);
+    const size_t lds = (size_t)G * (128 * 2 + (size_t)d.key_cap * (4 + 2));      // q rows (bf16), scores (fp32), weights (bf16)
     switch (G) {
         case 8: hipLaunchKernelGGL(decode_own_keys_kernel<8>, grid, dim3(64), lds, s, d); break;
         case 4: hipLaunchKernelGGL(decode_own_keys_kernel<4>, grid, dim3(64), lds, s, d); break;

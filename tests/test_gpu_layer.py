@@ -142,3 +142,10 @@ def test_layer_llama3_8b_shape_full_size_sampled():
     """configs[1] with d_model 4096: the whole batch runs; three queries and their clusters' prompts are checked."""
     w = workloads.config(1)
     _run_layer(w, 4096, queries=[0, 131, 319], check_cache=True)
+
+
+def test_layer_llama2_7b_ragged_shape_full_size_sampled():
+    """configs[2] (MHA: as many K and V heads as Q heads, prompts of 1106-3871 tokens whose last row tiles and pages
+    are ragged, 61 k question tokens) with d_model 4096; two queries and their clusters' prompts are checked."""
+    w = workloads.config(2)
+    _run_layer(w, 4096, queries=[3, 777], check_cache=True)

@@ -342,6 +342,11 @@ def main() -> int:
         "paper_context": "TTFT reduction up to 6.68x, PFTT up to 15.49x (Table 2; 2x A100-SXM4-40GB, precision not stated); end-to-end LLM latencies, not this kernel",
         "input_gen_s": t_gen,
     }
+    if dtype == "bf16":
+        # what the chip sustains on matrix-core instructions alone (it clocks down under that load): context for frac
+        sustained = float(np.median([sgc.sgc_probe_mfma_rate(s.ctx, 20000, stream) for _ in range(3)]))
+        out["roofline"]["mfma_only_kernel_tflops"] = sustained
+        out["roofline"]["frac_of_mfma_only_kernel"] = achieved / sustained if sustained > 0 else None
     d_model = w.n_q_heads * w.head_dim if args.layer_d_model < 0 else args.layer_d_model
     if d_model > 0 and not args.suffix_only:
         out["layer"] = layer_measurement(s, w, layer, d_model, args.layer_reps, stream)

@@ -345,6 +345,8 @@ hipError_t launch_attn_generic(const AttnArgs &a, int64_t n_rows, hipStream_t s)
 hipError_t launch_decode_append(const DecodeArgs &d, hipStream_t s);
 hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s);
 hipError_t launch_fill_zero_bytes(void *p, size_t bytes, hipStream_t s);
+// Measurement aid: `blocks` workgroups of 4 wavefronts issue iters * 16 bf16 32x32x16 matrix-core instructions each.
+hipError_t launch_mfma_rate(int blocks, int iters, float *sink, hipStream_t s);
 // Projections: the bf16 matrix-core kernel (K a multiple of 64, N a multiple of 128; qkv selects the fused
 // epilogue) and a kernel for every other shape and type that deals columns [0, n0), [n0, n0 + n1) and the rest
 // to three row-major matrices (c0 may be null to drop its columns).

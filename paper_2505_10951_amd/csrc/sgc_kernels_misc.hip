@@ -763,6 +763,42 @@ hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s)
     return hipGetLastError();
 }
 
+// Measurement aid: nothing but matrix-core instructions (four independent accumulator chains per wavefront, one
+// wavefront per SIMD, no memory traffic), to see what the chip sustains under that load.
+typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float probe_f32x16;
+__global__ void __launch_bounds__(256) mfma_rate_kernel(int iters, float *sink)
+{
+    const int lane = threadIdx.x & 63;
+    probe_bf16x8 x, y;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        x[i] = (__bf16)(0.001f * (float)(lane + i));
+        y[i] = (__bf16)(0.002f * (float)(lane - i));
+    }
+    probe_f32x16 acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) acc[u & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc[u & 3], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += acc[c][r];
+    if (sum == 12345.678f) sink[blockIdx.x * 256 + threadIdx.x] = sum;      // keeps the chains alive; never true in practice
+}
+
+hipError_t launch_mfma_rate(int blocks, int iters, float *sink, hipStream_t s)
+{
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(256), 0, s, iters, sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_fill_zero_bytes(void *p, size_t bytes, hipStream_t s)
 {
     if (bytes == 0) return hipSuccess;

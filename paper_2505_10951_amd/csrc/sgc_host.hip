@@ -453,6 +453,9 @@ void plan_free_device(sgc_plan *pl)
     dev_release(pl->ctx, pl->proj_kv, pl->last_stream);
     pl->proj_kv = sgc_dev_block{};
     pl->proj_state = 0;
+    dev_release(pl->ctx, pl->row_dest_block, pl->last_stream);
+    pl->row_dest_block = sgc_dev_block{};
+    pl->d_row_dest = nullptr;
     dev_release(pl->ctx, pl->blob, pl->last_stream);
     dev_release(pl->ctx, pl->spool_block, pl->last_stream);
     pl->blob = sgc_dev_block{};
@@ -946,9 +949,10 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
     };
     Piece pieces[] = {
         {pl->cl_tok_off.data(), pl->cl_tok_off.size() * 4, (const void **)&pl->d_cl_tok_off},
-        {pl->tok_src.data(), pl->tok_src.size() * 4, (const void **)&pl->d_tok_src},
-        {pl->tok_qpos.data(), pl->tok_qpos.size() * 4, (const void **)&pl->d_tok_qpos},
-        {pl->tok_sq.data(), pl->tok_sq.size() * 4, (const void **)&pl->d_tok_sq},
+        // the three per-token arrays are only read by the generic attention kernel (the MFMA kernel has tok_info)
+        {pl->tok_src.data(), want_rows > 0 ? 0 : pl->tok_src.size() * 4, (const void **)&pl->d_tok_src},
+        {pl->tok_qpos.data(), want_rows > 0 ? 0 : pl->tok_qpos.size() * 4, (const void **)&pl->d_tok_qpos},
+        {pl->tok_sq.data(), want_rows > 0 ? 0 : pl->tok_sq.size() * 4, (const void **)&pl->d_tok_sq},
         {pl->sq_src0.data(), pl->sq_src0.size() * 4, (const void **)&pl->d_sq_src0},
         {pl->sq_len.data(), pl->sq_len.size() * 4, (const void **)&pl->d_sq_len},
         {pl->sq_tok0.data(), pl->sq_tok0.size() * 4, (const void **)&pl->d_sq_tok0},
@@ -960,7 +964,6 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
         {pl->sq_query.data(), pl->sq_query.size() * 4, (const void **)&pl->d_sq_query},
         {pl->dtiles.data(), pl->dtiles.size() * sizeof(Tile), (const void **)&pl->d_dtiles},
         {pl->dtok.data(), pl->dtok.size() * sizeof(TokInfo), (const void **)&pl->d_dtok},
-        {pl->row_dest.data(), pl->row_dest.size() * 4, (const void **)&pl->d_row_dest},
     };
     size_t total = 0;
     for (const Piece &p : pieces) total += (p.bytes + 255) / 256 * 256 + 256;
@@ -1510,6 +1513,16 @@ int sgc_project_qkv_suffix(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int3
     if (ctx->use_mfma && gemm_covers(ctx, K, N) && pl->d_spool) {
         char *spool = pl->d_spool + (pl->decode_cap > 0 ? (size_t)layer * pl->spool_layer_bytes : 0);
         const int64_t page_bytes = (int64_t)2 * Hkv * kPageTokens * d * 2;
+        if (!pl->d_row_dest) {          // first projection on this plan: the per-row destinations go to the device
+            const size_t bytes = pl->row_dest.size() * sizeof(int32_t);
+            if ((rc = dev_acquire(ctx, bytes, s, &pl->row_dest_block)) != SGC_OK) return rc;
+            char *host = nullptr;
+            int slot = 0;
+            if ((rc = stage_begin(ctx, bytes, &host, &slot)) != SGC_OK) return rc;
+            memcpy(host, pl->row_dest.data(), bytes);
+            if ((rc = stage_commit(ctx, slot, pl->row_dest_block.p, bytes, s)) != SGC_OK) return rc;
+            pl->d_row_dest = reinterpret_cast<const int2 *>(pl->row_dest_block.p);
+        }
         SGC_HIP(ctx, launch_zero_last_pages(spool, pl->d_sq_len, pl->d_sq_page0, (int)pl->sq_len.size(), page_bytes, s));
         GemmArgs g{};
         g.w = dev_w_qkv;

@@ -298,7 +298,8 @@ struct sgc_plan {
     int32_t proj_state = 0, proj_layer = -1;
     sgc_dev_block proj_kv;
     std::vector<int32_t> row_dest;            // [T][2] per packed row: 16 * suffix page + slot, position
-    const int2 *d_row_dest = nullptr;
+    const int2 *d_row_dest = nullptr;         // uploaded by the first projection on the plan
+    sgc_dev_block row_dest_block;
     std::vector<sgc::Tile> tiles;
     std::vector<sgc::TokInfo> tok_info;
     uint64_t tiles_generation = 0;            // cache generation the tiles' page-table offsets belong to

@@ -149,3 +149,12 @@ def test_layer_llama2_7b_ragged_shape_full_size_sampled():
     are ragged, 61 k question tokens) with d_model 4096; two queries and their clusters' prompts are checked."""
     w = workloads.config(2)
     _run_layer(w, 4096, queries=[3, 777], check_cache=True)
+
+
+@pytest.mark.parametrize("Hq,Hkv,d_model,prefix", [(1, 1, 64, (257, 1)), (2, 1, 128, (16, 255)), (3, 1, 320, (129, 40)),
+                                                   (6, 3, 64, (300, 31))])
+def test_layer_kernel_edge_shapes(Hq, Hkv, d_model, prefix):
+    """One, two and several contraction steps (the main loop is peeled for the last two); a QKV width that leaves
+    half a column tile; prompts of one row, of exactly a page, and one row past a row tile."""
+    w = _small(Hq=Hq, Hkv=Hkv, prefix=prefix, sizes=(2, 3), lo=1, hi=45, seed=100 + Hq + d_model)
+    _run_layer(w, d_model)

@@ -105,9 +105,62 @@ struct TileDesc {
     int page_last; // last suffix page of the query (kind 1)
 };
 
+// Decode (SubGCache App. A.2: up to 32 generated tokens per query): the blocks behind the tiles of a decode
+// step's launch append the step's new token of every query to its suffix pages, K rotated at position
+// P + len + step, V as given; 8 lanes per (sorted query, KV head), one 8-channel chunk of each half per lane.
+// Nothing in the same launch reads those pages (the tiles of a decode step only read the cluster's cache).
+__device__ inline void append_new_tokens(const AttnArgs &a, int blk)
+{
+    const int unit = blk * ((int)blockDim.x >> 3) + ((int)threadIdx.x >> 3), cc = (int)threadIdx.x & 7;
+    const int Hkv = a.n_kv_heads;
+    const int sq = unit / Hkv, hk = unit - sq * Hkv;
+    if (sq >= a.n_append) return;
+    const int j = a.sq_len[sq] + a.pos_shift;
+    const int pos = a.cl_prefix_len[a.sq_cluster[sq]] + j;
+    const int tok = j % kPageTokens;
+    char *kp = const_cast<char *>(a.spool) + (int64_t)(a.sq_page0[sq] + j / kPageTokens) * 2 * Hkv * PART_BYTES + (int64_t)hk * PART_BYTES;
+    char *vp = kp + (int64_t)Hkv * PART_BYTES;
+    const int64_t row = ((int64_t)a.sq_query[sq] * Hkv + hk) * D;
+    const uint16_t *kg = static_cast<const uint16_t *>(a.k) + row, *vg = static_cast<const uint16_t *>(a.v) + row;
+    const uint4 k1 = *reinterpret_cast<const uint4 *>(kg + cc * 8), k2 = *reinterpret_cast<const uint4 *>(kg + D / 2 + cc * 8);
+    const uint4 v1 = *reinterpret_cast<const uint4 *>(vg + cc * 8), v2 = *reinterpret_cast<const uint4 *>(vg + D / 2 + cc * 8);
+    const uint32_t w1[4] = {k1.x, k1.y, k1.z, k1.w}, w2[4] = {k2.x, k2.y, k2.z, k2.w};
+    uint32_t o1[4], o2[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float x1[2] = {__uint_as_float(w1[i] << 16), __uint_as_float(w1[i] & 0xFFFF0000u)};
+        float x2[2] = {__uint_as_float(w2[i] << 16), __uint_as_float(w2[i] & 0xFFFF0000u)};
+        if (a.rope) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const float2 cs = a.rope[(int64_t)pos * (D / 2) + cc * 8 + 2 * i + e];
+                const float p = x1[e], q = x2[e];
+                x1[e] = p * cs.x - q * cs.y;
+                x2[e] = q * cs.x + p * cs.y;
+            }
+        }
+        const bf16x2 r1 = {(__bf16)x1[0], (__bf16)x1[1]}, r2 = {(__bf16)x2[0], (__bf16)x2[1]};
+        o1[i] = __builtin_bit_cast(uint32_t, r1);
+        o2[i] = __builtin_bit_cast(uint32_t, r2);
+    }
+    *reinterpret_cast<uint4 *>(kp + (int64_t)k_page_index(tok, cc * 8) * 2) = make_uint4(o1[0], o1[1], o1[2], o1[3]);
+    *reinterpret_cast<uint4 *>(kp + (int64_t)k_page_index(tok, D / 2 + cc * 8) * 2) = make_uint4(o2[0], o2[1], o2[2], o2[3]);
+    const uint32_t y1[4] = {v1.x, v1.y, v1.z, v1.w}, y2[4] = {v2.x, v2.y, v2.z, v2.w};
+    uint16_t *vq = reinterpret_cast<uint16_t *>(vp);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        vq[v_page_index(tok, cc * 8 + i)] = (uint16_t)(y1[i >> 1] >> (16 * (i & 1)));
+        vq[v_page_index(tok, D / 2 + cc * 8 + i)] = (uint16_t)(y2[i >> 1] >> (16 * (i & 1)));
+    }
+}
+
 template <int NW, int MI, bool KV_FP8, int MODE>
 __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mfma_kernel(const AttnArgs a)
 {
+    if (MODE == MODE_SUFFIX && (int)blockIdx.x >= a.n_tiles) {
+        append_new_tokens(a, (int)blockIdx.x - a.n_tiles);
+        return;
+    }
     constexpr int BM = NW * MI * 32;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     int2 *const qinfo = reinterpret_cast<int2 *>(smem + LDS_TILE_BYTES);   // (suffix length, first suffix page)
@@ -877,9 +930,14 @@ template <int NW, int MI>
 hipError_t launch_variant(const AttnArgs &a, hipStream_t s)
 {
     const bool fp8 = a.pool.kv_dtype == SGC_FP8_E4M3;
-    if (a.n_tiles <= 0) return hipSuccess;
+    if (a.n_tiles <= 0 && a.n_append <= 0) return hipSuccess;
     if (a.mode == MODE_SUFFIX)
-        return fp8 ? launch_one<NW, MI, true, MODE_SUFFIX>(a, a.n_tiles, s) : launch_one<NW, MI, false, MODE_SUFFIX>(a, a.n_tiles, s);
+    {
+        // a decode step's launch carries, behind its tiles, the blocks that append the step's new tokens
+        const int per_block = NW * 64 / 8;
+        const int blocks = a.n_tiles + (a.n_append * a.n_kv_heads + per_block - 1) / per_block;
+        return fp8 ? launch_one<NW, MI, true, MODE_SUFFIX>(a, blocks, s) : launch_one<NW, MI, false, MODE_SUFFIX>(a, blocks, s);
+    }
     return fp8 ? launch_one<NW, MI, true, MODE_PREFIX>(a, a.n_tiles, s) : launch_one<NW, MI, false, MODE_PREFIX>(a, a.n_tiles, s);
 }
 

@@ -1192,7 +1192,6 @@ int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int
     for (int32_t len : pl->sq_len) longest = std::max(longest, len);
     d.key_cap = (longest + pl->decode_cap + kPageTokens - 1) / kPageTokens * kPageTokens;
     d.scale_log2e = ctx->scale * 1.4426950408889634f;
-    SGC_HIP(ctx, launch_decode_append(d, s));
 
     AttnArgs a;
     fill_common_args(a, ctx, c, layer);
@@ -1211,6 +1210,11 @@ int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int
     a.spool = spool;
     a.pos_shift = step;
     a.skip_self = 1;
+    a.k = dev_k;                 // the step's new tokens: appended by the blocks behind the tiles
+    a.v = dev_v;
+    a.sq_cluster = pl->d_sq_cluster;
+    a.sq_query = pl->d_sq_query;
+    a.n_append = n_sq;
     SGC_HIP(ctx, launch_attn_mfma(a, ctx->mfma_variant, s));
     SGC_HIP(ctx, launch_decode_own_keys(d, s));
     return SGC_OK;

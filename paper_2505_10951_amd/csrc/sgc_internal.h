@@ -107,7 +107,7 @@ struct PrefixJob {
     int32_t page0;           // first page of the job in the launch-wide page numbering
 };
 
-// One decode step of every (non-empty) query of a plan: arguments of the append and own-keys kernels.
+// One decode step of every (non-empty) query of a plan: arguments of the own-keys kernel.
 constexpr int kDecodeMaxSplits = 8;       // key ranges the cached part of a decode step may be split into
 constexpr int kDecodeMaxKeys = 1024;      // own keys (suffix + generated) a query may reach while decoding
 struct DecodeArgs {
@@ -211,6 +211,10 @@ struct AttnArgs {
     // a tile whose pad field names key range s (upper 8 bits) writes its rows to o + s * split_o_bytes and
     // lse + s * split_lse_elems; the low 24 bits of pad are added to the rows' positions
     int64_t split_o_bytes, split_lse_elems;
+    // decode: blocks behind the tiles append the new token of each of the n_append sorted queries (k, v above: the
+    // new tokens [n_queries][Hkv][d]; sq_query: original index of the sorted query) to the suffix pages
+    const int32_t *sq_query;
+    int32_t n_append;
 };
 
 }  // namespace sgc
@@ -341,9 +345,8 @@ hipError_t launch_cache_import(const PoolGeom &g, int layer, const int32_t *d_pa
 hipError_t launch_suffix_ingest(const AttnArgs &a, const int32_t *d_spage_sq, int n_spages, hipStream_t s);
 
 hipError_t launch_attn_generic(const AttnArgs &a, int64_t n_rows, hipStream_t s);
-// Decode: append the new token's rotated K and V to every query's suffix pages; then, per (query, head),
-// attention over the query's own keys merged with the cached-prefix part.  head_dim 128, bf16.
-hipError_t launch_decode_append(const DecodeArgs &d, hipStream_t s);
+// Decode, per (query, head): attention over the query's own keys (the step's new token was appended to the suffix
+// pages by the cached-part launch before) merged with the cached-prefix part.  head_dim 128, bf16.
 hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s);
 hipError_t launch_fill_zero_bytes(void *p, size_t bytes, hipStream_t s);
 // Measurement aid: `blocks` workgroups of 4 wavefronts issue iters * 16 bf16 32x32x16 matrix-core instructions each.

@@ -300,37 +300,8 @@ __global__ void suffix_ingest_kernel(AttnArgs a, const int32_t *spage_sq)
 // cluster's cached prompt, the query's question tokens and the tokens generated before it (Sec. 3.4:
 // all queries of a cluster reuse the same cache).  The cached-prompt part of a step runs in the MFMA
 // kernel with the rows of all sibling queries stacked into one tile, so the prompt's K/V are read once
-// per cluster instead of once per query; the two kernels here do what is per query.
-
-// Appends the new token (index len + step of the query's own keys) to the query's suffix pages:
-// K rotated at position P + len + step, V as given.  One workgroup per (sorted query, KV head), d = 128.
-__global__ void decode_append_kernel(DecodeArgs a)
-{
-    constexpr int d = 128, half = 64;
-    const int sq = blockIdx.x, hk = blockIdx.y, Hkv = a.n_kv_heads;
-    const int cc = threadIdx.x;            // 8 threads: one 8-channel chunk of each half
-    if (cc >= half / 8) return;
-    const int j = a.sq_len[sq] + a.step;
-    const int P = a.cl_prefix_len[a.sq_cluster[sq]];
-    const int64_t part = (int64_t)kPageTokens * d * 2;
-    char *kp = a.spool + (int64_t)(a.sq_page0[sq] + j / kPageTokens) * 2 * Hkv * part + (int64_t)hk * part;
-    char *vp = kp + (int64_t)Hkv * part;
-    const int tok = j % kPageTokens;
-    const int64_t row = ((int64_t)a.sq_query[sq] * Hkv + hk) * d;
-    float x1[8], x2[8], y1[8], y2[8];
-    load8(a.k, row + cc * 8, SGC_BF16, x1);
-    load8(a.k, row + half + cc * 8, SGC_BF16, x2);
-    if (a.rope) rope8(x1, x2, a.rope + (int64_t)(P + j) * half + cc * 8);
-    load8(a.v, row + cc * 8, SGC_BF16, y1);
-    load8(a.v, row + half + cc * 8, SGC_BF16, y2);
-    store8(kp, k_page_index(tok, cc * 8), SGC_BF16, x1, 1.f);
-    store8(kp, k_page_index(tok, half + cc * 8), SGC_BF16, x2, 1.f);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        store1(vp, v_page_index(tok, cc * 8 + i), SGC_BF16, y1[i], 1.f);
-        store1(vp, v_page_index(tok, half + cc * 8 + i), SGC_BF16, y2[i], 1.f);
-    }
-}
+// per cluster instead of once per query (blocks behind that launch's tiles append the step's new tokens to the
+// queries' suffix pages); the kernel here does what is per query.
 
 // One wavefront per (sorted query, group of G query heads that share a KV head): scores of the new token
 // against the query's own len + step + 1 keys (lane = key, each key read once for the G heads), softmax,
@@ -737,13 +708,6 @@ hipError_t launch_suffix_ingest(const AttnArgs &a, const int32_t *d_spage_sq, in
     if (n_spages <= 0) return hipSuccess;
     const size_t lds = 2 * (size_t)kPageTokens * a.head_dim * 2;
     hipLaunchKernelGGL(suffix_ingest_kernel, dim3(n_spages, a.n_kv_heads), dim3(128), lds, s, a, d_spage_sq);
-    return hipGetLastError();
-}
-
-hipError_t launch_decode_append(const DecodeArgs &d, hipStream_t s)
-{
-    if (d.n_sq <= 0) return hipSuccess;
-    hipLaunchKernelGGL(decode_append_kernel, dim3(d.n_sq, d.n_kv_heads), dim3(64), 0, s, d);
     return hipGetLastError();
 }
 

@@ -113,6 +113,31 @@ def test_decode_long_prompts_split_the_cached_keys_into_ranges(kv):
     assert np.isfinite(got[0]).all() and err <= TOL[kv] and lerr <= 5e-2
 
 
+@pytest.mark.parametrize("seed", [400, 401, 402, 403, 404, 405])
+def test_decode_random_shapes_against_oracle(seed):
+    """Seeded random small workloads: group sizes 1-8, prompts of 0-1500 tokens (long ones split into key ranges),
+    question lengths of 0-60 around page boundaries, 2-5 generated tokens."""
+    rng = np.random.default_rng(seed)
+    Hkv = int(rng.choice([1, 2, 4]))
+    g = int(rng.choice([1, 2, 4, 8]))
+    nc = int(rng.integers(1, 4))
+    prefix = [int(rng.choice([0, 16, 64, 100, 700, 1500])) for _ in range(nc)]
+    sizes = [int(rng.integers(1, 7)) for _ in range(nc)]
+    slen = [int(rng.choice([0, 1, 14, 15, 16, 17, 31, 32, 33, 47, 60])) for _ in range(sum(sizes))]
+    kv = "fp8_e4m3" if seed % 2 else "bf16"
+    w = workloads.custom(f"decode_random_{seed}", n_q_heads=Hkv * g, n_kv_heads=Hkv, head_dim=128, rope_base=500000.0,
+                         io_dtype="bf16", kv_dtype=kv, prefix_len=prefix, cluster_sizes=sizes, suffix_len=slen, seed=seed)
+    n_steps = int(rng.integers(2, 6))
+    got = _run_decode(w, n_steps)[0]
+    o_ref, lse_ref = _oracle_decode(w, 0, n_steps, oracle_caches(w, 0))
+    live = w.suffix_len > 0
+    err = np.abs(got[0][:, live] - o_ref[:, live]).max() if live.any() else 0.0
+    lerr = np.abs(got[1][:, :, live] - lse_ref[:, :, live]).max() if live.any() else 0.0
+    print(f"  decode random {seed}: Hq {Hkv * g} Hkv {Hkv} prefix {prefix} suffix {slen} steps {n_steps} {kv}: max_abs {err:.3e} lse {lerr:.3e}", flush=True)
+    assert np.isfinite(got[0]).all() and err <= TOL[kv] and lerr <= 5e-2
+    assert np.all(got[0][:, ~live] == 7.0)
+
+
 def test_decode_argument_checks():
     w = workloads.custom("decode_args", n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=10000.0, io_dtype="bf16",
                          prefix_len=[32], cluster_sizes=[2], suffix_range=(4, 4), seed=43)

@@ -206,10 +206,10 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cache, sgc_plan *p
  * (device memory: layers x pages of all queries).  A query's question plus generated tokens may not
  * exceed 1024.
  *
- * sgc_decode_step_batched: one layer, one step (0-based) for every query of the plan that has a
- * non-empty suffix.  dev_q / dev_o: [n_queries][Hq][d], dev_k / dev_v: [n_queries][Hkv][d], row n =
- * query n in original order, the token generated at this step, before rotation (position
- * prefix_len + suffix_len + step).  Rows of queries with an empty suffix are not touched.
+ * sgc_decode_step_batched: one layer, one step (0-based) for every query of the plan (a query without
+ * question tokens generates from the cached prompt alone).  dev_q / dev_o: [n_queries][Hq][d], dev_k /
+ * dev_v: [n_queries][Hkv][d], row n = query n in original order, the token generated at this step,
+ * before rotation (position prefix_len + suffix_len + step).
  * dev_lse (may be NULL): [Hq][n_queries] fp32, natural log.  Appends the token's rotated K and V to
  * the query's pages of this layer, then attends.  For each layer the caller runs the suffix prefill
  * first and then steps 0, 1, 2, ... in order.  Asynchronous on hip_stream. */

@@ -889,7 +889,7 @@ int sgc_assign_clusters(sgc_ctx *ctx, const sgc_cache *c, int32_t n_queries, con
         pl->cl_sq_off[k] = (int32_t)pl->sq_len.size();
         for (int32_t i = cluster_off[k]; i < cluster_off[k + 1]; ++i) {
             const int32_t n = order[i];
-            if (suffix_len[n] == 0) continue;             // the kernels never see empty queries
+            if (suffix_len[n] == 0) continue;             // queries without tokens follow behind the cluster's others
             const int32_t sq = (int32_t)pl->sq_len.size();
             pl->sq_query.push_back(n);
             pl->sq_src0.push_back(cu_seqlens[n]);
@@ -906,6 +906,19 @@ int sgc_assign_clusters(sgc_ctx *ctx, const sgc_cache *c, int32_t n_queries, con
                 pl->tok_sq[t] = sq;
             }
             maxpos = std::max(maxpos, pl->cl_prefix_len[k] + suffix_len[n]);
+        }
+        // Queries without question tokens own no rows of the suffix prefill; they are numbered behind the cluster's
+        // other queries, so that no row tile's query range ever contains one, and take part in decode steps only.
+        for (int32_t i = cluster_off[k]; i < cluster_off[k + 1]; ++i) {
+            const int32_t n = order[i];
+            if (suffix_len[n] != 0) continue;
+            pl->sq_query.push_back(n);
+            pl->sq_src0.push_back(cu_seqlens[n]);
+            pl->sq_len.push_back(0);
+            pl->sq_tok0.push_back(t);
+            pl->sq_cluster.push_back(k);
+            pl->sq_page0.push_back(spage);
+            maxpos = std::max(maxpos, pl->cl_prefix_len[k]);
         }
     }
     pl->cl_tok_off[n_clusters] = t;

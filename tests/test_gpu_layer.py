@@ -29,11 +29,20 @@ def _bar(ref, abs_bar=None, rel=2.0 ** -8):
     return (rel * rms if abs_bar is None else abs_bar) + rel * np.abs(ref)
 
 
-def _check(name, got, ref, **kw):
+def _check(name, got, ref, code_flips=False, **kw):
     err = np.abs(got.astype(np.float64) - ref)
     bar = _bar(ref, **kw)
-    worst = float((err / np.maximum(bar, 1e-30)).max()) if err.size else 0.0
+    ratio = err / np.maximum(bar, 1e-30)
+    worst = float(ratio.max()) if err.size else 0.0
     print(f"{name}: max err {err.max() if err.size else 0:.3e}, rms ref {np.sqrt(np.mean(ref ** 2)) if ref.size else 0:.3e}, worst err/bar {worst:.3f}", flush=True)
+    if code_flips and err.size:
+        # fp8 cache under the layer: the GPU quantises keys and values it projected itself (fp32 sums rounded to
+        # bf16), the oracle its own fp64 ones; a value within 2^-9 of a code boundary (3 % of them) gets the
+        # neighbouring code, a whole fp8 step (2^-3 of its size) away, and a row that gives such a key most of its
+        # weight shows it.  So: all but half a percent of the outputs inside the bar, none off by more than a step.
+        assert float(np.quantile(ratio, 0.995)) <= 1.0, f"{name}: more than 0.5 % of the outputs outside the bar"
+        assert float(err.max()) <= 0.125 * max(1.0, float(np.abs(ref).max())), f"{name}: an output is off by more than an fp8 step"
+        return
     assert worst <= 1.0, f"{name}: error exceeds the bar by {worst:.2f}x"
 
 
@@ -73,13 +82,13 @@ def _run_layer(w, d_model, queries=None, check_cache=True, kernel=sgc.SGC_KERNEL
                 k, v, _, _ = s.export_cluster(c)
                 _check(f"cluster {c} cached K", k, ck, rel=rel)
                 _check(f"cluster {c} cached V", v, cv, rel=rel)
-            _check(f"cluster {c} prompt output", to_host_f32(ys[c]), y_ref, abs_bar=y_bar, rel=rel)
+            _check(f"cluster {c} prompt output", to_host_f32(ys[c]), y_ref, code_flips=w.kv_dtype == "fp8_e4m3", abs_bar=y_bar, rel=rel)
         s.assign()
         dx = to_device(w.suffix_x(d_model), w.io_dtype)
         y = to_host_f32(s.layer_suffix(dx, d_model, dwq, dwo))
         torch.cuda.synchronize()
         for n in queries:
-            _check(f"query {n}", y[int(cu[n]):int(cu[n + 1])], ref_q[n], abs_bar=y_bar, rel=rel)
+            _check(f"query {n}", y[int(cu[n]):int(cu[n + 1])], ref_q[n], code_flips=w.kv_dtype == "fp8_e4m3", abs_bar=y_bar, rel=rel)
     return y
 
 
@@ -158,3 +167,13 @@ def test_layer_kernel_edge_shapes(Hq, Hkv, d_model, prefix):
     half a column tile; prompts of one row, of exactly a page, and one row past a row tile."""
     w = _small(Hq=Hq, Hkv=Hkv, prefix=prefix, sizes=(2, 3), lo=1, hi=45, seed=100 + Hq + d_model)
     _run_layer(w, d_model)
+
+
+@pytest.mark.parametrize("kv", ["bf16", "fp8_e4m3"])
+def test_layer_long_contraction(kv):
+    """A contraction of 32 steps over few output tiles, all three epilogues, prompt and batch; a prompt one row past
+    two row tiles."""
+    w = _small(kv=kv, seed=21)
+    _run_layer(w, 2048, y_bar=6e-2 if kv == "fp8_e4m3" else 2e-2)
+    w2 = _small(kv=kv, prefix=(40, 513), sizes=(4, 1), lo=30, hi=64, seed=22)
+    _run_layer(w2, 2048, y_bar=6e-2 if kv == "fp8_e4m3" else 2e-2)

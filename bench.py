@@ -212,6 +212,29 @@ def layer_measurement(s, w, layer, d_model, reps, stream):
                          "unit": "TFLOP/s", "frac": gemm["tflops"] / peak, "traffic": None}}
 
 
+def phase_report(sgc, n_tiles: int) -> None:
+    """Development libraries only: the attention kernel's own record of when each wavefront of the last launch
+    (the first 2048 workgroups) reached the end of each phase, in 100 MHz ticks since the workgroup started."""
+    import ctypes
+    lib = sgc.lib()
+    if not hasattr(lib, "sgc_debug_read_phases"):
+        print("bench.py: --phase-timing needs a library built with -DSGC_PHASE_TIMING", file=sys.stderr)
+        return
+    n = 2048 * 8 * 8
+    buf = (ctypes.c_ulonglong * n)()
+    lib.sgc_debug_read_phases.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
+    rc = lib.sgc_debug_read_phases(buf, n)
+    a = np.frombuffer(buf, dtype=np.uint64).reshape(2048, 8, 8).astype(np.float64)[:min(n_tiles, 2048)]
+    live = a[a[:, 0, 5] > 0]
+    names = ["tile and row records", "Q loaded and rotated", "first tiles, first scores", "cached steps", "own-suffix tiles", "O stored"]
+    print(f"phase timing (rc {rc}, {live.shape[0]} workgroups): us per phase, wavefront 0 | wavefront 3", file=sys.stderr)
+    per = [np.diff(np.concatenate([[0.0], live[:, wv, :6].mean(axis=0) / 100.0])) for wv in (0, 3)]
+    for i, name in enumerate(names):
+        print(f"  {name:28s} {per[0][i]:7.2f} | {per[1][i]:7.2f}", file=sys.stderr)
+    print(f"  workgroup lifetime: mean {live[:, 0, 5].mean() / 100.0:.2f} us, 90th percentile {np.percentile(live[:, 0, 5], 90) / 100.0:.2f} us",
+          file=sys.stderr)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -227,6 +250,9 @@ def main() -> int:
     ap.add_argument("--layer-d-model", type=int, default=-1,
                     help="model width of the attention-layer measurement (-1: n_q_heads * head_dim, 0: skip)")
     ap.add_argument("--layer-reps", type=int, default=10)
+    ap.add_argument("--phase-timing", action="store_true",
+                    help="with a library built with -DSGC_PHASE_TIMING (build.py -DSGC_PHASE_TIMING -o X, SGC_LIB_PATH=X): "
+                         "print where a workgroup of the suffix attention kernel spends its time, then go on as usual")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten 256 MiB device copies and exit (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -314,6 +340,8 @@ def main() -> int:
         other = {"mode": "host waits after every step" if args.pipelined else "steps enqueued back to back",
                  "ms_per_step": other_ms, "attention_kernel_ms": float(np.mean(other_kernel))}
 
+    if args.phase_timing:
+        phase_report(sgc, sgc.sgc_plan_get_info(s.ctx, s.plan).n_tiles)
     fl_suffix = w.flops()
     fl_step = fl_suffix + (0.0 if args.suffix_only else prefix_flops(w))
     info = sgc.sgc_plan_get_info(s.ctx, s.plan)

@@ -26,9 +26,11 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def build_lib(verbose: bool = False, extra_flags=()) -> str:
-    """Always recompiles every source, then links; returns the library path."""
-    objdir = os.path.join(_HERE, "_build")
+def build_lib(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
+    """Always recompiles every source, then links; returns the library path.  `extra_flags` (-DNAME switches of the
+    development builds: SGC_PHASE_TIMING, SGC_GEMM_PHASE_TIMING, the SGC_ABL_* timing experiments) and `out` give a
+    second library beside the product one; the binding loads it when SGC_LIB_PATH names it."""
+    objdir = os.path.join(_HERE, "_build" if out == LIB else "_build_dev")
     os.makedirs(objdir, exist_ok=True)
     hipcc = _hipcc()
 
@@ -47,12 +49,15 @@ def build_lib(verbose: bool = False, extra_flags=()) -> str:
 
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    print(build_lib(verbose="-v" in sys.argv))
+    # python build.py [-v] [-DNAME ...] [-o other_library.so]
+    argv = sys.argv[1:]
+    out_path = os.path.abspath(argv[argv.index("-o") + 1]) if "-o" in argv else LIB
+    print(build_lib(verbose="-v" in argv, extra_flags=[x for x in argv if x.startswith("-D")], out=out_path))

@@ -875,25 +875,44 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     SGC_MARK(4);           // own suffix tiles done
 
     // ---- normalise and store ----
+    // A lane holds 4-channel pieces of its row; written out as they are they would make 8-byte stores scattered
+    // over 32 rows per instruction.  The wavefront instead stages its 32 x 128 outputs in its own 8 KiB slice of
+    // the tile buffers (idle now: every wavefront is past the last barrier behind its last read), the 16-byte
+    // chunks of row n permuted by n % 16 so that the writes and the reads below spread over all banks, and stores
+    // four whole rows of 256 bytes per instruction.
     uint16_t *og = static_cast<uint16_t *>(o_base);
+    char *const ostage = smem + wave * MI * 8192;
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
         const float l = half_sum(l_part[mi]);
         const float inv_l = (v_scaled ? 1.0f : v_scale) / l;
-        if (valid[mi]) {
+        char *st = ostage + mi * 8192 + n * 256 + h * 8;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    bf16x4 y;
+            for (int q4 = 0; q4 < 4; ++q4) {
+                bf16x4 y;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) y[i] = (__bf16)(oacc[mi][db][q4 * 4 + i] * inv_l);
-                    *reinterpret_cast<bf16x4 *>(og + io_row[mi] + db * 32 + q4 * 8 + h * 4) = y;
-                }
-            if (lse_base && h == 0) {
-                const int64_t col = (MODE == MODE_SUFFIX) ? (int64_t)src_tok[mi] : (int64_t)qpos[mi];
-                lse_base[(int64_t)head[mi] * lse_stride + col] = (m_ref[mi] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+                for (int i = 0; i < 4; ++i) y[i] = (__bf16)(oacc[mi][db][q4 * 4 + i] * inv_l);
+                *reinterpret_cast<bf16x4 *>(st + (((db * 4 + q4) ^ (n & 15)) * 16)) = y;
             }
+        if (valid[mi] && lse_base && h == 0) {
+            const int64_t col = (MODE == MODE_SUFFIX) ? (int64_t)src_tok[mi] : (int64_t)qpos[mi];
+            lse_base[(int64_t)head[mi] * lse_stride + col] = (m_ref[mi] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int r = 4 * k + (lane >> 4), c = lane & 15;     // row r of the block sits in lanes r and r + 32
+            const uint4 y = *reinterpret_cast<const uint4 *>(ostage + mi * 8192 + r * 256 + ((c ^ (r & 15)) * 16));
+            const int64_t row = __shfl(io_row[mi], r);
+            const int ok = __shfl((int)valid[mi], r);
+            if (ok) *reinterpret_cast<uint4 *>(og + row + c * 8) = y;
         }
     }
 #ifdef SGC_PHASE_TIMING

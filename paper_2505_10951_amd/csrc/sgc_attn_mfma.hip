@@ -97,6 +97,39 @@ __device__ inline void copy_4k_to_lds(const char *src_lane, char *lds_part)
     __builtin_amdgcn_global_load_lds(g, l, 16, 3072, 0);
 }
 
+// Rows 16 HF .. 16 HF + 15 of a wavefront's 32 x 128 block of bf16 query rows, from the lanes that loaded them whole
+// (a_jj: 16-byte chunk lane % 16 of row 4 jj + lane / 16 of the half) to the lanes that use them as matrix operands (lane
+// (n, h) of row n: chunks 2 kb + h and 8 + 2 kb + h), through 4 KiB of LDS that belongs to this wavefront alone.
+// The chunks of row r sit permuted by r % 16, so that both the writes and the reads cover all banks.
+template <int HF>
+__device__ __forceinline__ void q_turn_half(char *qst, const uint4 &a0, const uint4 &a1, const uint4 &a2, const uint4 &a3, int lane, int n,
+                                            int h, uint4 (&qlo)[4], uint4 (&qhi)[4])
+{
+    {
+        const int r0 = lane >> 4, c = lane & 15;      // a_jj: chunk c of row 4 jj + r0 of the half
+        *reinterpret_cast<uint4 *>(qst + (r0 + 0) * 256 + ((c ^ (r0 + 0)) * 16)) = a0;
+        *reinterpret_cast<uint4 *>(qst + (r0 + 4) * 256 + ((c ^ (r0 + 4)) * 16)) = a1;
+        *reinterpret_cast<uint4 *>(qst + (r0 + 8) * 256 + ((c ^ (r0 + 8)) * 16)) = a2;
+        *reinterpret_cast<uint4 *>(qst + (r0 + 12) * 256 + ((c ^ (r0 + 12)) * 16)) = a3;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+    const int n16 = n & 15;
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+        const uint4 lo = *reinterpret_cast<const uint4 *>(qst + n16 * 256 + (((2 * kb + h) ^ n16) * 16));
+        const uint4 hi = *reinterpret_cast<const uint4 *>(qst + n16 * 256 + (((8 + 2 * kb + h) ^ n16) * 16));
+        if ((n >> 4) == HF) {
+            qlo[kb] = lo;
+            qhi[kb] = hi;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+}
+
 struct TileDesc {
     int kind;      // 0: cached prefix keys, 1: the suffix keys of sorted query q
     int key0;      // first key of the tile (index inside the prefix / inside the query's suffix)
@@ -391,14 +424,35 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     {
         uint4 qlo[MI][4], qhi[MI][4];
         float4 cs[MI][4][4];            // (cos, sin) of two channels per entry
+        if (NW == 4) {
+            // The operand layout wants 16-byte pieces of 32 different rows per instruction.  Loaded that way the
+            // requests are 32 scattered 32-byte runs each; instead instruction j fetches rows 4 j .. 4 j + 3 whole
+            // (lane = 16-byte chunk lane % 16 of row 4 j + lane / 16), and the wavefront turns the block by
+            // passing it, 16 rows at a time, through its 4 KiB share of the V buffer that nothing uses before the
+            // first step (chunks of row r permuted by r % 16: writes and reads cover all banks).
+            char *const qst = smem + 3 * HALF_BYTES + wave * 4096;
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-            const uint16_t *qrow = static_cast<const uint16_t *>(q_base) + io_row[mi];
+            for (int mi = 0; mi < MI; ++mi) {
+                const int row_index = (int)(io_row[mi] / D);        // src_tok * Hq + head of this lane's row
+                auto whole_row_chunk = [&](int j) __attribute__((always_inline)) -> uint4 {
+                    const int64_t ro = (int64_t)__shfl(row_index, 4 * j + (lane >> 4)) * D;
+                    return *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(q_base) + ro + (lane & 15) * 8);
+                };
+                const uint4 r0 = whole_row_chunk(0), r1 = whole_row_chunk(1), r2 = whole_row_chunk(2), r3 = whole_row_chunk(3);
+                const uint4 r4 = whole_row_chunk(4), r5 = whole_row_chunk(5), r6 = whole_row_chunk(6), r7 = whole_row_chunk(7);
+                q_turn_half<0>(qst, r0, r1, r2, r3, lane, n, h, qlo[mi], qhi[mi]);
+                q_turn_half<1>(qst, r4, r5, r6, r7, lane, n, h, qlo[mi], qhi[mi]);
+            }
+        } else {
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) {
-                const int c0 = kb * 16 + h * 8;
-                qlo[mi][kb] = *reinterpret_cast<const uint4 *>(qrow + c0);
-                qhi[mi][kb] = *reinterpret_cast<const uint4 *>(qrow + 64 + c0);
+            for (int mi = 0; mi < MI; ++mi) {
+                const uint16_t *qrow = static_cast<const uint16_t *>(q_base) + io_row[mi];
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb) {
+                    const int c0 = kb * 16 + h * 8;
+                    qlo[mi][kb] = *reinterpret_cast<const uint4 *>(qrow + c0);
+                    qhi[mi][kb] = *reinterpret_cast<const uint4 *>(qrow + 64 + c0);
+                }
             }
         }
         const bool rotate = a.rope != nullptr;

@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # file, each counter scaled by what it reads for a plain copy of known size (--copy-calibration).  The runs
 # and the arithmetic are written down in profiles/attn_mfma_suffix_llama3_8b_layer.md; a workload that has
 # not been measured this way reports null.
-MEASURED_HBM_BYTES_PER_LAUNCH = {"llama3_8b_layer": 3.254e8}
+MEASURED_HBM_BYTES_PER_LAUNCH = {"llama3_8b_layer": 3.226e8}
 
 
 def copy_calibration() -> int:

@@ -154,6 +154,32 @@ __device__ inline void copy_out_16(char *dst, const char *lds_src, int n)
         *reinterpret_cast<uint4 *>(dst + off) = *reinterpret_cast<const uint4 *>(lds_src + off);
 }
 
+// bf16 pages of 128-channel heads: V is a transpose (a page keeps, per channel, runs of 8 tokens), and element-sized
+// scattered LDS writes of it collide in the banks.  The tokens' values go into a staging tile [16 tokens][128
+// channels] instead, 16 bytes (8 channels) at a time, the sixteen chunks of token t's row at position
+// vt_pos(chunk, t) so that the 16 lanes of a write cover all banks; the page's 16-byte units are then gathered from
+// it column-wise (64 lanes read 64 neighbouring channels of one token) and stored straight to global memory.
+__device__ inline int vt_pos(int chunk, int tok) { return chunk ^ ((tok & 1) << 3) ^ ((tok >> 1) & 7); }
+
+__device__ inline void v_part_from_tile(char *vg, const uint16_t *vt)
+{
+    for (int u = threadIdx.x; u < 256; u += blockDim.x) {       // unit u = ((c / 32) * 2 + h) * 32 + c % 32, see v_page_index
+        const int hh = (u >> 5) & 1, c = (u >> 6) * 32 + (u & 31);
+        uint32_t w[4];
+#pragma unroll
+        for (int i2 = 0; i2 < 4; ++i2) {
+            uint32_t e[2];
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int i = 2 * i2 + k, t = 4 * hh + (i & 3) + 8 * (i >> 2);
+                e[k] = vt[t * 128 + vt_pos(c >> 3, t) * 8 + (c & 7)];
+            }
+            w[i2] = e[0] | (e[1] << 16);
+        }
+        *reinterpret_cast<uint4 *>(vg + u * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
 // Pass 0 (fp8 only): per-head max |rotated K| and max |V| of every job into its scale slot
 // amax[2][Hkv] via integer atomicMax on the bit patterns of non-negative floats.
 __global__ void ingest_amax_kernel(const PrefixJob *jobs, const int32_t *page_job, int io_dtype, int Hkv, int d,
@@ -214,6 +240,7 @@ __global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *page_t
     extern __shared__ __attribute__((aligned(16))) char page_img[];
     const int part_bytes = (int)g.head_part_bytes;
     char *kp = page_img, *vp = page_img + part_bytes;
+    const bool via_tile = g.kv_dtype == SGC_BF16 && d == 128;     // V through the staging tile (see v_part_from_tile)
     float sc_k = 1.f, sc_v = 1.f;   // fp8: the per-head scales the codes are divided by
     if (g.kv_dtype == SGC_FP8_E4M3) {
         sc_k = job.scale_kv[hk];
@@ -236,15 +263,23 @@ __global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *page_t
         }
         store8(kp, k_page_index(tok, cc * 8), g.kv_dtype, x1, sc_k);
         store8(kp, k_page_index(tok, half + cc * 8), g.kv_dtype, x2, sc_k);
+        if (via_tile) {
+            store8(vp, tok * 128 + vt_pos(cc, tok) * 8, SGC_BF16, y1, 1.f);
+            store8(vp, tok * 128 + vt_pos(8 + cc, tok) * 8, SGC_BF16, y2, 1.f);
+        } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            store1(vp, v_page_index(tok, cc * 8 + i), g.kv_dtype, y1[i], sc_v);
-            store1(vp, v_page_index(tok, half + cc * 8 + i), g.kv_dtype, y2[i], sc_v);
+            for (int i = 0; i < 8; ++i) {
+                store1(vp, v_page_index(tok, cc * 8 + i), g.kv_dtype, y1[i], sc_v);
+                store1(vp, v_page_index(tok, half + cc * 8 + i), g.kv_dtype, y2[i], sc_v);
+            }
         }
     }
     __syncthreads();
     copy_out_16(g.k_part(layer, page, hk), kp, part_bytes);
-    copy_out_16(g.v_part(layer, page, hk), vp, part_bytes);
+    if (via_tile)
+        v_part_from_tile(g.v_part(layer, page, hk), reinterpret_cast<const uint16_t *>(vp));
+    else
+        copy_out_16(g.v_part(layer, page, hk), vp, part_bytes);
 }
 
 // ---- suffix ingest ---------------------------------------------------------------------------
@@ -267,6 +302,7 @@ __global__ void suffix_ingest_kernel(AttnArgs a, const int32_t *spage_sq)
     char *vg = kg + (int64_t)Hkv * part;
     extern __shared__ __attribute__((aligned(16))) char page_img[];     // both images are built in LDS first
     char *kp = page_img, *vp = page_img + part;
+    const bool via_tile = d == 128;          // V through the staging tile (see v_part_from_tile)
     for (int it = threadIdx.x; it < kPageTokens * pairs; it += blockDim.x) {
         const int tok = it / pairs, cc = it % pairs;
         const int j = tok0 + tok;
@@ -284,15 +320,23 @@ __global__ void suffix_ingest_kernel(AttnArgs a, const int32_t *spage_sq)
         }
         store8(kp, k_page_index(tok, cc * 8), SGC_BF16, x1, 1.f);
         store8(kp, k_page_index(tok, half + cc * 8), SGC_BF16, x2, 1.f);
+        if (via_tile) {
+            store8(vp, tok * 128 + vt_pos(cc, tok) * 8, SGC_BF16, y1, 1.f);
+            store8(vp, tok * 128 + vt_pos(8 + cc, tok) * 8, SGC_BF16, y2, 1.f);
+        } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            store1(vp, v_page_index(tok, cc * 8 + i), SGC_BF16, y1[i], 1.f);
-            store1(vp, v_page_index(tok, half + cc * 8 + i), SGC_BF16, y2[i], 1.f);
+            for (int i = 0; i < 8; ++i) {
+                store1(vp, v_page_index(tok, cc * 8 + i), SGC_BF16, y1[i], 1.f);
+                store1(vp, v_page_index(tok, half + cc * 8 + i), SGC_BF16, y2[i], 1.f);
+            }
         }
     }
     __syncthreads();
     copy_out_16(kg, kp, (int)part);
-    copy_out_16(vg, vp, (int)part);
+    if (via_tile)
+        v_part_from_tile(vg, reinterpret_cast<const uint16_t *>(vp));
+    else
+        copy_out_16(vg, vp, (int)part);
 }
 
 // ---- decode ------------------------------------------------------------------------------------

@@ -726,17 +726,28 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
                 for (int hk = 0; hk < Hkv; ++hk) units.push_back({ji, hk, (double)jobs[ji].prefix_len * jobs[ji].prefix_len});
         std::stable_sort(units.begin(), units.end(), [](const Unit &x, const Unit &y) { return x.work > y.work; });
         double load[kXcd] = {0};
-        for (const Unit &u : units) {
+        std::vector<int> of_xcd[kXcd];           // the units of each XCD, in the order they were dealt
+        for (int ui = 0; ui < (int)units.size(); ++ui) {
             int x = 0;
             for (int i = 1; i < kXcd; ++i)
                 if (load[i] < load[x]) x = i;
-            load[x] += u.work;
-            const int64_t rows = (int64_t)jobs[u.job].prefix_len * g;
-            for (int64_t r = 0; r < rows; r += rows_per_tile) lists[x].push_back({u.job, u.hk, (int32_t)r});
+            load[x] += units[ui].work;
+            of_xcd[x].push_back(ui);
         }
-        for (auto &l : lists) {
-            std::stable_sort(l.begin(), l.end(), [](const Light &x, const Light &y) { return x.row0 > y.row0; });
-            slots = std::max(slots, l.size());
+        // a unit's tile t starts at row t * rows_per_tile; descending t, units in dealing order among equals
+        auto tiles_of = [&](const Unit &u) { return (int)(((int64_t)jobs[u.job].prefix_len * g + rows_per_tile - 1) / rows_per_tile); };
+        for (int x = 0; x < kXcd; ++x) {
+            int most = 0;
+            size_t all = 0;
+            for (int ui : of_xcd[x]) {
+                most = std::max(most, tiles_of(units[ui]));
+                all += (size_t)tiles_of(units[ui]);
+            }
+            lists[x].reserve(all);
+            for (int t = most - 1; t >= 0; --t)
+                for (int ui : of_xcd[x])
+                    if (t < tiles_of(units[ui])) lists[x].push_back({units[ui].job, units[ui].hk, t * rows_per_tile});
+            slots = std::max(slots, lists[x].size());
         }
     }
     const size_t n_tiles = slots * kXcd;

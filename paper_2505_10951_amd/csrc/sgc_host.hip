@@ -956,15 +956,15 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
         if (pl->decode_cap > 0) build_decode_tiles(pl, want_rows);
         fill_tile_pt_off(pl, pl->cache);
     }
-    pl->tok_info.resize(pl->tok_src.size());
-    for (size_t i = 0; i < pl->tok_src.size(); ++i) pl->tok_info[i] = {pl->tok_src[i], pl->tok_qpos[i], pl->tok_sq[i], 0};
-    // where the projection's epilogue puts the key and value of each packed row: {16 * page + slot, position}
-    pl->row_dest.resize(2 * pl->tok_src.size());
-    for (size_t i = 0; i < pl->tok_src.size(); ++i) {
-        const int32_t sq = pl->tok_sq[i], qpos = pl->tok_qpos[i];
-        pl->row_dest[2 * (size_t)pl->tok_src[i]] = (pl->sq_page0[sq] + qpos / kPageTokens) * kPageTokens + qpos % kPageTokens;
-        pl->row_dest[2 * (size_t)pl->tok_src[i] + 1] = pl->cl_prefix_len[pl->sq_cluster[sq]] + qpos;
+    // The per-token records are only read by tiles that touch more queries than their own record describes.
+    bool wide_tile = false;
+    for (const Tile &t : pl->tiles) wide_tile = wide_tile || (t.n_rows > 0 && t.n_q > kTileQueries);
+    pl->tok_info.clear();
+    if (wide_tile) {
+        pl->tok_info.resize(pl->tok_src.size());
+        for (size_t i = 0; i < pl->tok_src.size(); ++i) pl->tok_info[i] = {pl->tok_src[i], pl->tok_qpos[i], pl->tok_sq[i], 0};
     }
+    pl->row_dest.clear();      // made when a projection first asks for it
 
     struct Piece {
         const void *src;
@@ -1542,6 +1542,13 @@ int sgc_project_qkv_suffix(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int3
         char *spool = pl->d_spool + (pl->decode_cap > 0 ? (size_t)layer * pl->spool_layer_bytes : 0);
         const int64_t page_bytes = (int64_t)2 * Hkv * kPageTokens * d * 2;
         if (!pl->d_row_dest) {          // first projection on this plan: the per-row destinations go to the device
+            // where the epilogue puts the key and value of each packed row: {16 * page + slot, position}
+            pl->row_dest.resize(2 * pl->tok_src.size());
+            for (size_t i = 0; i < pl->tok_src.size(); ++i) {
+                const int32_t sq = pl->tok_sq[i], qpos = pl->tok_qpos[i];
+                pl->row_dest[2 * (size_t)pl->tok_src[i]] = (pl->sq_page0[sq] + qpos / kPageTokens) * kPageTokens + qpos % kPageTokens;
+                pl->row_dest[2 * (size_t)pl->tok_src[i] + 1] = pl->cl_prefix_len[pl->sq_cluster[sq]] + qpos;
+            }
             const size_t bytes = pl->row_dest.size() * sizeof(int32_t);
             if ((rc = dev_acquire(ctx, bytes, s, &pl->row_dest_block)) != SGC_OK) return rc;
             char *host = nullptr;

@@ -175,9 +175,9 @@ int stage_begin(sgc_ctx *ctx, size_t bytes, char **host, int *slot)
     return SGC_OK;
 }
 
-int stage_commit(sgc_ctx *ctx, int slot, void *dev, size_t bytes, hipStream_t s)
+int stage_commit(sgc_ctx *ctx, int slot, void *dev, size_t bytes, hipStream_t s, size_t host_offset = 0)
 {
-    if (bytes) SGC_HIP(ctx, hipMemcpyAsync(dev, ctx->h_stage[slot], bytes, hipMemcpyHostToDevice, s));
+    if (bytes) SGC_HIP(ctx, hipMemcpyAsync(dev, ctx->h_stage[slot] + host_offset, bytes, hipMemcpyHostToDevice, s));
     SGC_HIP(ctx, hipEventRecord(ctx->stage_ev[slot], s));
     ctx->stage_pending[slot] = true;
     return SGC_OK;
@@ -765,6 +765,14 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
     }
     memcpy(host, jobs.data(), jobs.size() * sizeof(PrefixJob));
     memcpy(host + jobs_bytes, page_job.data(), page_job.size() * sizeof(int32_t));
+    const PrefixJob *d_jobs = reinterpret_cast<const PrefixJob *>(blk.p);
+    const int32_t *d_page_job = reinterpret_cast<const int32_t *>(blk.p + jobs_bytes);
+    const Tile *d_tiles = reinterpret_cast<const Tile *>(blk.p + jobs_bytes + pj_bytes);
+    // The ingest kernel needs the jobs only: they go first and the kernel starts while the tile list is written.
+    hipError_t e = hipMemcpyAsync(blk.p, host, jobs_bytes + pj_bytes, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess && !attend_only)
+        e = launch_prefix_ingest(c->geom, layer, c->d_page_table, d_jobs, (int)jobs.size(), d_page_job, (int)page_job.size(),
+                                 ctx->p.io_dtype, ctx->p.rope_base > 0.0f ? ctx->d_rope : nullptr, s);
     Tile *ht = reinterpret_cast<Tile *>(host + jobs_bytes + pj_bytes);
     for (int x = 0; x < kXcd; ++x) {
         for (size_t k = 0; k < slots; ++k) {
@@ -784,14 +792,8 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
             fill_first_pages(t, c->cl[j.cluster].pages);
         }
     }
-    rc = stage_commit(ctx, slot, blk.p, total, s);
-    const PrefixJob *d_jobs = reinterpret_cast<const PrefixJob *>(blk.p);
-    const int32_t *d_page_job = reinterpret_cast<const int32_t *>(blk.p + jobs_bytes);
-    const Tile *d_tiles = reinterpret_cast<const Tile *>(blk.p + jobs_bytes + pj_bytes);
-    hipError_t e = hipSuccess;
-    if (rc == SGC_OK && !attend_only)
-        e = launch_prefix_ingest(c->geom, layer, c->d_page_table, d_jobs, (int)jobs.size(), d_page_job, (int)page_job.size(),
-                                 ctx->p.io_dtype, ctx->p.rope_base > 0.0f ? ctx->d_rope : nullptr, s);
+    // the tiles, and the event that says the staging buffer has been read
+    rc = stage_commit(ctx, slot, blk.p + jobs_bytes + pj_bytes, e == hipSuccess ? tiles_bytes : 0, s, jobs_bytes + pj_bytes);
     if (rc == SGC_OK && e == hipSuccess && any_q) {
         AttnArgs a;
         fill_common_args(a, ctx, c, layer);

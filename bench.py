@@ -195,6 +195,11 @@ def layer_measurement(s, w, layer, d_model, reps, stream):
             if rep >= 2:
                 evs[name].append(pair)
     torch.cuda.synchronize()
+    if hasattr(sgc.lib(), "sgc_debug_read_gemm_phases"):        # library built with -DSGC_GEMM_PHASE_TIMING
+        for name, n_cols in (("qkv_suffix", n_qkv), ("out", d_model)):
+            calls[name]()
+            torch.cuda.synchronize()
+            gemm_phase_report(sgc, name, ((T + 255) // 256) * ((n_cols + 255) // 256))
     ms = {k: float(np.mean([a.elapsed_time(b) for a, b in v])) for k, v in evs.items()}
     P_total = float(w.prefix_len.sum())
     flop = {"qkv_prefix": 2.0 * P_total * d_model * (n_qkv - nq),          # the prompt's queries are not needed here
@@ -210,6 +215,27 @@ def layer_measurement(s, w, layer, d_model, reps, stream):
             "roofline": {"kernel": "proj_gemm_kernel<true> (QKV projection, keys and values written into suffix pages)",
                          "bound": "mfma" if w.io_dtype == "bf16" else "alu", "achieved": gemm["tflops"], "peak": peak,
                          "unit": "TFLOP/s", "frac": gemm["tflops"] / peak, "traffic": None}}
+
+
+def gemm_phase_report(sgc, name: str, n_workgroups: int) -> None:
+    """Development libraries only: the projection kernel's record of its last launch (first 4096 workgroups, four
+    wavefronts each): end of the main loop and end of the epilogue in 100 MHz ticks since the workgroup started,
+    and what the wavefront produced (0 plain columns, 1 a K head, 2 a V head)."""
+    import ctypes
+    lib = sgc.lib()
+    n = 4096 * 16
+    buf = (ctypes.c_ulonglong * n)()
+    lib.sgc_debug_read_gemm_phases.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
+    rc = lib.sgc_debug_read_gemm_phases(buf, n)
+    a = np.frombuffer(buf, dtype=np.uint64).reshape(4096, 4, 4).astype(np.float64)[:min(n_workgroups, 4096)]
+    a = a[a[:, 0, 1] > 0]
+    loop, end, kind = a[..., 0] / 100.0, a[..., 1] / 100.0, a[..., 2]
+    print(f"projection phase timing, {name} (rc {rc}, {a.shape[0]} workgroups): us per wavefront", file=sys.stderr)
+    for k, label in ((0, "plain columns"), (1, "K head"), (2, "V head")):
+        m = kind == k
+        if m.any():
+            print(f"  {label:14s} wavefronts {int(m.sum()):5d}  main loop {loop[m].mean():7.1f}  epilogue {(end - loop)[m].mean():6.1f} "
+                  f"(max {(end - loop)[m].max():.1f})", file=sys.stderr)
 
 
 def phase_report(sgc, n_tiles: int) -> None:

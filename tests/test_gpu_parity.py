@@ -124,6 +124,22 @@ def test_mfma_edge_cases():
         _check_suffix(w, out, tol=TOL_BF16, tight=tight, lse_tol=lse_bar)
 
 
+def test_mfma_row_tile_touching_dozens_of_queries():
+    """Sixty queries of one to three tokens in one cluster, one KV head per query head: a 128-row tile then holds
+    the rows of about sixty queries, far more than a tile record describes inline, so the kernel takes the
+    per-token records and the per-tile query table; a second cluster of ordinary queries shares the batch."""
+    rng = np.random.default_rng(5)
+    slen = np.concatenate([rng.integers(1, 4, size=60), np.array([40, 17, 0, 64])]).astype(np.int32)
+    labels = np.concatenate([np.zeros(60, dtype=np.int32), np.ones(4, dtype=np.int32)])
+    perm = rng.permutation(labels.size)
+    w = workloads.custom("many_tiny", n_q_heads=2, n_kv_heads=2, head_dim=128, rope_base=10000.0, io_dtype="bf16",
+                         prefix_len=[150, 90], labels=labels[perm], suffix_len=slen[perm], seed=41)
+    tight, lse_bar = tight_bar(w, range(w.n_queries))
+    out = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
+    _check_bookkeeping(w, out)
+    _check_suffix(w, out, tol=TOL_BF16, tight=tight, lse_tol=lse_bar)
+
+
 def test_mfma_all_queries_empty_and_single_row():
     w = workloads.custom("empty", n_q_heads=4, n_kv_heads=4, head_dim=128, rope_base=10000.0, io_dtype="bf16",
                          prefix_len=[40], labels=[0, 0], suffix_len=[0, 0], seed=1)

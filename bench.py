@@ -266,7 +266,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default 1: Llama-3-8B-shaped layer)")
+    ap.add_argument("--config", type=int, default=1, help="which of the five benchmark configurations, 0-4 (default 1: Llama-3-8B-shaped layer)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for the CPU baseline (0 = skip)")
     ap.add_argument("--pipelined", action="store_true",
                     help="enqueue the timed steps back to back instead of waiting for the GPU after every step")

@@ -10,6 +10,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <array>
 #include <new>
 #include <numeric>
 
@@ -253,44 +254,59 @@ void fill_common_args(AttnArgs &a, sgc_ctx *ctx, const sgc_cache *c, int32_t lay
     a.scale_log2e = ctx->scale * 1.4426950408889634f;
 }
 
+// Workgroup b of a launch runs on XCD b % 8, and each XCD has an L2 of its own: units of work that read the same
+// keys and values stay on one XCD.  Units are dealt, heaviest first (equal ones in their given order), each to the
+// XCD with the least work so far; returned per XCD: the units' indices in the order they were dealt.
+constexpr int kXcd = 8;
+std::array<std::vector<int>, kXcd> deal_to_xcds(const std::vector<double> &work)
+{
+    std::vector<int> by_work(work.size());
+    std::iota(by_work.begin(), by_work.end(), 0);
+    std::stable_sort(by_work.begin(), by_work.end(), [&](int a, int b) { return work[a] > work[b]; });
+    std::array<std::vector<int>, kXcd> of_xcd;
+    double load[kXcd] = {0};
+    for (int u : by_work) {
+        int x = 0;
+        for (int i = 1; i < kXcd; ++i)
+            if (load[i] < load[x]) x = i;
+        load[x] += work[u];
+        of_xcd[x].push_back(u);
+    }
+    return of_xcd;
+}
+
 // Work list of the batched suffix launch.  One unit = (cluster, KV head): all rows of a unit read
 // the same cached K/V.  Units are dealt, heaviest first, to the XCD with the least work so far;
 // workgroup b runs on XCD b % 8, so slot-major interleaving keeps every tile of a unit on one
 // XCD and that unit's K/V in one L2.
 void build_tiles(sgc_plan *pl, int tile_rows)
 {
-    constexpr int kXcd = 8;
     const sgc_ctx *ctx = pl->ctx;
     const int g = ctx->p.n_q_heads / ctx->p.n_kv_heads;
     struct Unit {
         int cluster, hk;
         int64_t rows;
-        double work;
     };
     std::vector<Unit> units;
+    std::vector<double> work;
     for (int c = 0; c < pl->n_clusters; ++c) {
         const int64_t toks = pl->cl_tok_off[c + 1] - pl->cl_tok_off[c];
         if (toks == 0) continue;
         for (int hk = 0; hk < ctx->p.n_kv_heads; ++hk) {
             const int64_t rows = toks * g;
             const int64_t nt = (rows + tile_rows - 1) / tile_rows;
-            units.push_back({c, hk, rows, (double)nt * (pl->cl_prefix_len[c] + 64.0)});
+            units.push_back({c, hk, rows});
+            work.push_back((double)nt * (pl->cl_prefix_len[c] + 64.0));
         }
     }
-    std::stable_sort(units.begin(), units.end(), [](const Unit &a, const Unit &b) { return a.work > b.work; });
     struct Light {      // a tile before its record is written: unit and first row
         int32_t unit, row0;
     };
     std::vector<std::vector<Light>> lists(kXcd);
-    double load[kXcd] = {0};
-    for (int ui = 0; ui < (int)units.size(); ++ui) {
-        const Unit &u = units[ui];
-        int x = 0;
-        for (int i = 1; i < kXcd; ++i)
-            if (load[i] < load[x]) x = i;
-        load[x] += u.work;
-        for (int64_t r = 0; r < u.rows; r += tile_rows) lists[x].push_back({ui, (int32_t)r});
-    }
+    const auto of_xcd = deal_to_xcds(work);
+    for (int x = 0; x < kXcd; ++x)
+        for (int ui : of_xcd[x])
+            for (int64_t r = 0; r < units[ui].rows; r += tile_rows) lists[x].push_back({ui, (int32_t)r});
     size_t slots = 0;
     for (auto &l : lists) slots = std::max(slots, l.size());
     pl->tiles.resize(slots * kXcd);
@@ -377,7 +393,6 @@ void layout_suffix_pages(sgc_plan *pl)
 // stacked so that one tile of rows shares the cluster's cached K/V.  Same XCD dealing as build_tiles.
 void build_decode_tiles(sgc_plan *pl, int tile_rows)
 {
-    constexpr int kXcd = 8;
     const sgc_ctx *ctx = pl->ctx;
     const int g = ctx->p.n_q_heads / ctx->p.n_kv_heads;
     struct Light {
@@ -385,9 +400,9 @@ void build_decode_tiles(sgc_plan *pl, int tile_rows)
     };
     struct Unit {
         int32_t cluster, hk;
-        double work;
     };
     std::vector<Unit> units;
+    std::vector<double> work;
     int64_t row_tiles = 0;
     int max_steps = 0;
     for (int c = 0; c < pl->n_clusters; ++c) {
@@ -396,7 +411,10 @@ void build_decode_tiles(sgc_plan *pl, int tile_rows)
         const int64_t nt = (nq * g + tile_rows - 1) / tile_rows;
         row_tiles += nt * ctx->p.n_kv_heads;
         max_steps = std::max(max_steps, (pl->cl_prefix_len[c] + 63) / 64);
-        for (int hk = 0; hk < ctx->p.n_kv_heads; ++hk) units.push_back({c, hk, (double)nt * (pl->cl_prefix_len[c] + 64.0)});
+        for (int hk = 0; hk < ctx->p.n_kv_heads; ++hk) {
+            units.push_back({c, hk});
+            work.push_back((double)nt * (pl->cl_prefix_len[c] + 64.0));
+        }
     }
     // A step has few rows (one per query and head), so few row tiles: the cached keys of every row tile are split
     // into S ranges of whole 64-key steps, each range a tile of its own whose partial result the own-keys kernel
@@ -407,18 +425,15 @@ void build_decode_tiles(sgc_plan *pl, int tile_rows)
     S = std::max(1, std::min(S, max_steps / 8));
     if (max_steps >= (1 << 24) / 64) S = 1;      // the position offset travels in 24 bits of the tile record
     pl->dec_splits = S;
-    std::stable_sort(units.begin(), units.end(), [](const Unit &a, const Unit &b) { return a.work > b.work; });
     std::vector<std::vector<Light>> lists(kXcd);
-    double load[kXcd] = {0};
-    for (const Unit &u : units) {
-        int x = 0;
-        for (int i = 1; i < kXcd; ++i)
-            if (load[i] < load[x]) x = i;
-        load[x] += u.work;
-        const int64_t rows = (int64_t)(pl->cl_sq_off[u.cluster + 1] - pl->cl_sq_off[u.cluster]) * g;
-        for (int64_t r = 0; r < rows; r += tile_rows)
-            for (int sp = 0; sp < S; ++sp) lists[x].push_back({u.cluster, u.hk, (int32_t)r, sp});
-    }
+    const auto of_xcd = deal_to_xcds(work);
+    for (int x = 0; x < kXcd; ++x)
+        for (int ui : of_xcd[x]) {
+            const Unit &u = units[ui];
+            const int64_t rows = (int64_t)(pl->cl_sq_off[u.cluster + 1] - pl->cl_sq_off[u.cluster]) * g;
+            for (int64_t r = 0; r < rows; r += tile_rows)
+                for (int sp = 0; sp < S; ++sp) lists[x].push_back({u.cluster, u.hk, (int32_t)r, sp});
+        }
     size_t slots = 0;
     for (auto &l : lists) slots = std::max(slots, l.size());
     pl->dtiles.assign(slots * kXcd, Tile{});
@@ -708,7 +723,6 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
     }
     // Tile list of the MFMA attention: units (job, KV head) are dealt, heaviest first, to the XCD with the
     // least work so far, each XCD's tiles longest first; workgroup b runs on XCD b % 8.
-    constexpr int kXcd = 8;
     struct Light {
         int32_t job, hk, row0;
     };
@@ -718,22 +732,16 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
         const int rows_per_tile = ctx->tile_rows;
         struct Unit {
             int job, hk;
-            double work;
         };
         std::vector<Unit> units;
+        std::vector<double> work;
         for (int ji = 0; ji < (int)jobs.size(); ++ji)
             if (jobs[ji].q)
-                for (int hk = 0; hk < Hkv; ++hk) units.push_back({ji, hk, (double)jobs[ji].prefix_len * jobs[ji].prefix_len});
-        std::stable_sort(units.begin(), units.end(), [](const Unit &x, const Unit &y) { return x.work > y.work; });
-        double load[kXcd] = {0};
-        std::vector<int> of_xcd[kXcd];           // the units of each XCD, in the order they were dealt
-        for (int ui = 0; ui < (int)units.size(); ++ui) {
-            int x = 0;
-            for (int i = 1; i < kXcd; ++i)
-                if (load[i] < load[x]) x = i;
-            load[x] += units[ui].work;
-            of_xcd[x].push_back(ui);
-        }
+                for (int hk = 0; hk < Hkv; ++hk) {
+                    units.push_back({ji, hk});
+                    work.push_back((double)jobs[ji].prefix_len * jobs[ji].prefix_len);
+                }
+        const auto of_xcd = deal_to_xcds(work);
         // a unit's tile t starts at row t * rows_per_tile; descending t, units in dealing order among equals
         auto tiles_of = [&](const Unit &u) { return (int)(((int64_t)jobs[u.job].prefix_len * g + rows_per_tile - 1) / rows_per_tile); };
         for (int x = 0; x < kXcd; ++x) {

@@ -52,7 +52,6 @@ constexpr int HALF_BYTES = 4 * PART_BYTES;   // the K (or V) of one 64-key tile:
 constexpr int LDS_TILE_BYTES = 4 * HALF_BYTES;   // two K buffers, then two V buffers
 constexpr int MAX_TILE_QUERIES = 256;        // queries a row tile can touch (one row each at least)
 constexpr float kKeepBelow = 1073741824.0f;  // 2^30: a tile's weights may sum to this against a stale maximum
-constexpr float kNegBig = -1.0e30f;
 
 #ifdef SGC_PHASE_TIMING
 // Development aid (not built into the product library): per-phase cycle totals of the tile loop.
@@ -194,7 +193,6 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         append_new_tokens(a, (int)blockIdx.x - a.n_tiles);
         return;
     }
-    constexpr int BM = NW * MI * 32;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     int2 *const qinfo = reinterpret_cast<int2 *>(smem + LDS_TILE_BYTES);   // (suffix length, first suffix page)
 
@@ -258,7 +256,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     const char *spool_base = a.spool + (int64_t)hk * PART_BYTES;
     const uint32_t spool_v_off = (uint32_t)Hkv * PART_BYTES;
     const uint32_t spool_page_256 = (2u * spool_v_off) >> 8;
-    uint4 stage[KV_FP8 ? 4 : 1];      // fp8: [K run 0, K run 1, V run 0, V run 1]
+    uint4 stage[4];      // fp8 cache only: codes on their way to LDS [K run 0, K run 1, V run 0, V run 1]
     bool staged_k = false, staged_v = false;
 
     // Page indices past the last page are clamped to it: such keys are masked out of the scores, and what
@@ -424,7 +422,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     {
         uint4 qlo[MI][4], qhi[MI][4];
         float4 cs[MI][4][4];            // (cos, sin) of two channels per entry
-        if (NW == 4) {
+        if (NW == 4 && !KV_FP8) {       // (with an fp8 cache the registers for it are not there, and prompts are long)
             // The operand layout wants 16-byte pieces of 32 different rows per instruction.  Loaded that way the
             // requests are 32 scattered 32-byte runs each; instead instruction j fetches rows 4 j .. 4 j + 3 whole
             // (lane = 16-byte chunk lane % 16 of row 4 j + lane / 16), and the wavefront turns the block by

@@ -299,12 +299,6 @@ int sgc_timing_enable(sgc_ctx *ctx, int on);
 int sgc_timing_get(sgc_ctx *ctx, int32_t back, float *ingest_ms, float *attention_ms);
 int sgc_timing_last(sgc_ctx *ctx, float *ingest_ms, float *attention_ms);
 
-/* Measurement aid: runs a kernel of nothing but bf16 32x32x16 matrix-core instructions (one wavefront per SIMD,
- * iters * 16 instructions each, no memory traffic) on hip_stream, waits for it, and returns the rate the chip
- * sustained in TFLOP/s: what clock throttling under matrix-core load leaves of the datasheet peak.
- * 1 <= iters <= 2^20 (20 000 runs about half a millisecond). */
-int sgc_probe_mfma_rate(sgc_ctx *ctx, int32_t iters, float *out_tflops, void *hip_stream);
-
 /* ---- canonical view of a cluster's cache (tests, checkpointing) -----------------------------
  * dev_k, dev_v: [prefix_len][Hkv][d] in kv_dtype (raw e4m3 codes for fp8); K is the rotated K.
  * host_k_scale, host_v_scale: [Hkv] fp32 (written by export / read by import; ignored and may

@@ -27,10 +27,8 @@ def _hipcc() -> str:
 
 
 def build_lib(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
-    """Always recompiles every source, then links; returns the library path.  `extra_flags` (-DNAME switches of the
-    development builds: SGC_PHASE_TIMING, SGC_GEMM_PHASE_TIMING, the SGC_ABL_* timing experiments) and `out` give a
-    second library beside the product one; the binding loads it when SGC_LIB_PATH names it."""
-    objdir = os.path.join(_HERE, "_build" if out == LIB else "_build_dev")
+    """Always recompiles every source, then links; returns the library path."""
+    objdir = os.path.join(_HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     hipcc = _hipcc()
 
@@ -56,26 +54,6 @@ def build_lib(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     return out
 
 
-def build_dev_tools(verbose: bool = False) -> str:
-    """Compiles (does not run) the development micro-benchmark program that the figures in
-    ``profiles/gfx950_microbenchmarks.md`` come from; returns the executable's path."""
-    outdir = os.path.join(_HERE, "_build_dev")
-    os.makedirs(outdir, exist_ok=True)
-    exe = os.path.join(outdir, "gfx950_ubench")
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-command-line-argument", os.path.join(CSRC, "dev", "gfx950_ubench.hip"), "-o", exe]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed for gfx950_ubench.hip:\n" + r.stdout)
-    return exe
-
-
 if __name__ == "__main__":
-    # python build.py [-v] [-DNAME ...] [-o other_library.so]
-    argv = sys.argv[1:]
-    out_path = os.path.abspath(argv[argv.index("-o") + 1]) if "-o" in argv else LIB
-    print(build_lib(verbose="-v" in argv, extra_flags=[x for x in argv if x.startswith("-D")], out=out_path))
-    if "--dev-tools" in argv:
-        print(build_dev_tools(verbose="-v" in argv))
+    # python build.py [-v]
+    print(build_lib(verbose="-v" in sys.argv[1:]))

@@ -33,13 +33,8 @@ namespace sgc {
 
 namespace {
 
-#ifdef SGC_NO_SCHED_BARRIER
-#define SGC_SCHED_FENCE() do { } while (0)
-#else
-#define SGC_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-#endif
-
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -52,16 +47,6 @@ constexpr int HALF_BYTES = 4 * PART_BYTES;   // the K (or V) of one 64-key tile:
 constexpr int LDS_TILE_BYTES = 4 * HALF_BYTES;   // two K buffers, then two V buffers
 constexpr int MAX_TILE_QUERIES = 256;        // queries a row tile can touch (one row each at least)
 constexpr float kKeepBelow = 1073741824.0f;  // 2^30: a tile's weights may sum to this against a stale maximum
-
-#ifdef SGC_PHASE_TIMING
-// Development aid (not built into the product library): per-phase cycle totals of the tile loop.
-__device__ unsigned long long g_phase[2048 * 8 * 8];   // [block < 2048][wave < 8][phase < 8]
-// SGC_MARK(i): the time since the block
-// started (100 MHz ticks) is recorded when the wave reaches the end of phase i (no extra waits).
-#define SGC_MARK(i) do { ph[i] = (unsigned)(__builtin_amdgcn_s_memrealtime() - blk_r0); } while (0)
-#else
-#define SGC_MARK(i) do { } while (0)
-#endif
 
 // Combine a value with the one held by the lane 32 away (the other half of a score row), through
 // v_permlane32_swap: with both operands x, the two results hold x's lower half and x's upper half, each
@@ -77,10 +62,13 @@ __device__ inline float half_sum(float x)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// Unpacks 2 fp8 e4m3 codes (low or high half of w) to bf16 (exact: e4m3 is a subset of bf16).
-__device__ inline uint32_t fp8x2_to_bf16x2(uint32_t w, bool high)
+// Unpacks 2 fp8 e4m3 codes (low or high half of w) to 16-bit floats: binary16 for keys, bf16 for values (both
+// exact: e4m3 is a subset of either).
+template <bool TO_F16>
+__device__ inline uint32_t fp8x2_to_16x2(uint32_t w, bool high)
 {
     const auto f = high ? __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true) : __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
+    if (TO_F16) return pack2_f16(f[0], f[1]);
     return (__float_as_uint(f[0]) >> 16) | (__float_as_uint(f[1]) & 0xFFFF0000u);
 }
 
@@ -171,9 +159,8 @@ __device__ inline void append_new_tokens(const AttnArgs &a, int blk)
                 x2[e] = q * cs.x + p * cs.y;
             }
         }
-        const bf16x2 r1 = {(__bf16)x1[0], (__bf16)x1[1]}, r2 = {(__bf16)x2[0], (__bf16)x2[1]};
-        o1[i] = __builtin_bit_cast(uint32_t, r1);
-        o2[i] = __builtin_bit_cast(uint32_t, r2);
+        o1[i] = pack2_f16(x1[0], x1[1]);       // keys are kept as binary16
+        o2[i] = pack2_f16(x2[0], x2[1]);
     }
     *reinterpret_cast<uint4 *>(kp + (int64_t)k_page_index(tok, cc * 8) * 2) = make_uint4(o1[0], o1[1], o1[2], o1[3]);
     *reinterpret_cast<uint4 *>(kp + (int64_t)k_page_index(tok, D / 2 + cc * 8) * 2) = make_uint4(o2[0], o2[1], o2[2], o2[3]);
@@ -196,10 +183,6 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     int2 *const qinfo = reinterpret_cast<int2 *>(smem + LDS_TILE_BYTES);   // (suffix length, first suffix page)
 
-#ifdef SGC_PHASE_TIMING
-    unsigned ph[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    const unsigned long long blk_r0 = __builtin_amdgcn_s_memrealtime();
-#endif
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
@@ -294,26 +277,27 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             stage[3] = *reinterpret_cast<const uint4 *>(src + 1024);
         }
     };
-    // 16 codes -> 16 bf16 = 32 bytes: chunk (run, lane) of a part lands at 32 (64 run + lane) of its bf16 image
-    auto widen_to_lds = [&](const uint4 &codes, char *dst) __attribute__((always_inline)) {
+    // 16 codes -> 16 16-bit floats = 32 bytes: chunk (run, lane) of a part lands at 32 (64 run + lane) of its image
+    auto widen_to_lds = [&](const uint4 &codes, char *dst, auto f16_tag) __attribute__((always_inline)) {
+        constexpr bool F = decltype(f16_tag)::value;
         const uint32_t w[4] = {codes.x, codes.y, codes.z, codes.w};
         uint4 o0, o1;
-        o0.x = fp8x2_to_bf16x2(w[0], false); o0.y = fp8x2_to_bf16x2(w[0], true);
-        o0.z = fp8x2_to_bf16x2(w[1], false); o0.w = fp8x2_to_bf16x2(w[1], true);
-        o1.x = fp8x2_to_bf16x2(w[2], false); o1.y = fp8x2_to_bf16x2(w[2], true);
-        o1.z = fp8x2_to_bf16x2(w[3], false); o1.w = fp8x2_to_bf16x2(w[3], true);
+        o0.x = fp8x2_to_16x2<F>(w[0], false); o0.y = fp8x2_to_16x2<F>(w[0], true);
+        o0.z = fp8x2_to_16x2<F>(w[1], false); o0.w = fp8x2_to_16x2<F>(w[1], true);
+        o1.x = fp8x2_to_16x2<F>(w[2], false); o1.y = fp8x2_to_16x2<F>(w[2], true);
+        o1.z = fp8x2_to_16x2<F>(w[3], false); o1.w = fp8x2_to_16x2<F>(w[3], true);
         *reinterpret_cast<uint4 *>(dst) = o0;
         *reinterpret_cast<uint4 *>(dst + 16) = o1;
     };
     // Writes what the last issue_load_fp8 staged; a staged half is written once, and only to a real buffer.
     auto store_fp8 = [&](char *kdst, char *vdst) __attribute__((always_inline)) {
         if (staged_k && kdst) {
-            widen_to_lds(stage[0], kdst + my_page * PART_BYTES + lane * 32);
-            widen_to_lds(stage[1], kdst + my_page * PART_BYTES + (64 + lane) * 32);
+            widen_to_lds(stage[0], kdst + my_page * PART_BYTES + lane * 32, std::true_type{});
+            widen_to_lds(stage[1], kdst + my_page * PART_BYTES + (64 + lane) * 32, std::true_type{});
         }
         if (staged_v && vdst) {
-            widen_to_lds(stage[2], vdst + my_page * PART_BYTES + lane * 32);
-            widen_to_lds(stage[3], vdst + my_page * PART_BYTES + (64 + lane) * 32);
+            widen_to_lds(stage[2], vdst + my_page * PART_BYTES + lane * 32, std::false_type{});
+            widen_to_lds(stage[3], vdst + my_page * PART_BYTES + (64 + lane) * 32, std::false_type{});
         }
         staged_k = false;
         staged_v = false;
@@ -327,11 +311,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     };
     auto land_cache = [&](char *kdst, char *vdst) __attribute__((always_inline)) {   // make what was fetched visible in LDS (before the barrier)
         if (KV_FP8) store_fp8(kdst, vdst);
-#ifdef SGC_ABL_DEFERWAIT
-        __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8): timing experiment only
-#else
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): direct copies have landed
-#endif
     };
     char *const kbuf0 = smem, *const vbuf0 = smem + 2 * HALF_BYTES;
     auto kbuf_of = [&](int i) __attribute__((always_inline)) -> char * { return kbuf0 + (i & 1) * HALF_BYTES; };
@@ -414,11 +394,10 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         fetch_cache(ids0, kbuf_of(0), ids0, vbuf_of(0));
         if (n_kt > 1) fetch_cache(ids1, kbuf_of(1), 0, nullptr);
     }
-    SGC_MARK(0);           // tile and row bookkeeping is loaded
     // ---- Q: load, rotate at position P + qpos (suffix) / qpos (prefix), keep as B operands ----
     // All loads of the phase (Q row halves, then the rotation table entries) are issued before any of them is
     // used, so the phase costs one memory round trip and not one per channel group.
-    bf16x8 qf[MI][8];
+    f16x8 qf[MI][8];
     {
         uint4 qlo[MI][4], qhi[MI][4];
         float4 cs[MI][4][4];            // (cos, sin) of two channels per entry
@@ -491,8 +470,8 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
                 }
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {      // the score scale (log2 units, cached-K scale included) rides on Q
-                    qf[mi][kb][i] = (__bf16)(x1[i] * c_cache);
-                    qf[mi][kb + 4][i] = (__bf16)(x2[i] * c_cache);
+                    qf[mi][kb][i] = (_Float16)(x1[i] * c_cache);
+                    qf[mi][kb + 4][i] = (_Float16)(x2[i] * c_cache);
                 }
             }
         }
@@ -537,7 +516,6 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             for (int r = 0; r < 16; ++r) oacc[mi][db][r] = 0.f;
     }
     bool fresh = true;     // no tile processed yet by this wavefront
-    SGC_MARK(1);           // Q is in registers
 
     // Per-lane LDS offsets of the operand blocks.  K block (nb, kb): lane (m, hh) reads key m of the 32-key
     // group nb (page 2 nb + m / 16, token m % 16), channels kb * 16 + hh * 8 .. + 7.  Each 16-lane group
@@ -568,7 +546,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         for (int kb = 0; kb < 8; ++kb) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
-                s[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[kb], qf[mi][kb], kb == 0 ? (FOLD ? neg_ref[mi] : zero16) : s[mi], 0, 0, 0);
+                s[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, frag[kb]), qf[mi][kb], kb == 0 ? (FOLD ? neg_ref[mi] : zero16) : s[mi], 0, 0, 0);
             refill(kb);
         }
     };
@@ -598,14 +576,9 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
                 bf16x2 pk;
-#ifdef SGC_ABL_NOSOFTMAX
-                pk[0] = (__bf16)s[mi][r];
-                pk[1] = (__bf16)s[mi][r + 1];
-#else
                 pk[0] = (__bf16)__builtin_amdgcn_exp2f(FOLD ? s[mi][r] : s[mi][r] - m_ref[mi]);
                 pk[1] = (__bf16)__builtin_amdgcn_exp2f(FOLD ? s[mi][r + 1] : s[mi][r + 1] - m_ref[mi]);
                 acc = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, acc, false);   // sum of the ROUNDED weights
-#endif
                 pf[mi][r >> 3][(r & 7) >> 1] = __builtin_bit_cast(uint32_t, pk);
             }
             psum[mi] = acc;
@@ -698,7 +671,6 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         qk_half(s0, [&](int i) __attribute__((always_inline)) { frag[i] = k_block(k0, 1, i); });
     }
     __syncthreads();       // every wavefront has read K of tile 0 before step 0 overwrites it
-    SGC_MARK(2);
     // ---- the stream of this row tile's own suffix key tiles ------------------------------------------------
     // Scalar iterator over (query, 64-key tile); a query's LDS record is read when the stream reaches it.  The
     // first tile is requested during the last cached step, into the buffers that step leaves free.
@@ -743,12 +715,6 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     auto copy_quarter = [&](const PartCopy &pc, int slot) __attribute__((always_inline)) {     // slot 0, 2, 4, 6 -> quarter 0..3; odd slots: nothing
         const auto *gp = (const __attribute__((address_space(1))) void *)pc.src;
         auto *lp = (__attribute__((address_space(3))) void *)pc.dst;
-#ifdef SGC_ABL_LOADONLY
-        if ((slot & 1) == 0) {      // timing experiment: the same global read, into a register instead of LDS
-            const uint4 x = *reinterpret_cast<const uint4 *>(pc.src + (slot >> 1) * 1024);
-            asm volatile("" ::"v"(x.x), "v"(x.y), "v"(x.z), "v"(x.w));
-        }
-#else
         switch (slot) {
             case 0: __builtin_amdgcn_global_load_lds(gp, lp, 16, 0, 0); break;
             case 2: __builtin_amdgcn_global_load_lds(gp, lp, 16, 1024, 0); break;
@@ -756,7 +722,6 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             case 6: __builtin_amdgcn_global_load_lds(gp, lp, 16, 3072, 0); break;
             default: break;
         }
-#endif
     };
     // Step kt.  spread (a true_type / false_type tag): issue this step's copies between the matrix
     // instructions (needs a bf16 cache, both copies due and this wavefront computing) or at the top.
@@ -764,11 +729,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         constexpr bool spread = decltype(spread_tag)::value;
         char *kd = kt + 2 < n_kt ? kbuf_of(kt) : nullptr;
         char *vd = kt + 1 < n_kt ? vbuf_of(kt + 1) : nullptr;
-#ifdef SGC_ABL_SAMETILE
-        const uint32_t ids3 = cache_page_ids(0);
-#else
         const uint32_t ids3 = cache_page_ids(kt + 3);    // issued before the copies, used a step later
-#endif
         PartCopy first = {nullptr, nullptr}, second = {nullptr, nullptr};
         if (spread) {
             if (NW == 4) {
@@ -778,9 +739,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
                 first = moves_v ? cache_part(true, ids1, vd) : cache_part(false, ids2, kd);
             }
         } else {
-#ifndef SGC_ABL_NODMA
             if (kd || vd) fetch_cache(ids2, kd, ids1, vd);
-#endif
             if (MODE == MODE_SUFFIX && kt == n_kt - 1 && have) fetch_self(cur, kbuf_of(kt), vbuf_of(kt + 1));
         }
         ids1 = ids2;
@@ -816,9 +775,7 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             if (weights_overflow()) redo(s0, s1, 0);
             pv_half([&](int i) __attribute__((always_inline)) {
                 frag[i] = k_block(kn, 0, i);
-#ifndef SGC_ABL_HALFDMA
                 if (spread && NW == 4) copy_quarter(second, i);
-#endif
             });
             // half 1
             if (careful) raise_reference(s1, 1, masked, keep);
@@ -829,21 +786,16 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             fresh = false;
         }
         land_cache(kd, vd);
-#ifndef SGC_ABL_NOBAR
         __syncthreads();
-#endif
     };
     {
         int kt = 0;
-#ifndef SGC_ABL_NODMA
         if (!KV_FP8) {
             const int n_spread = min(n_kt - 2, MODE == MODE_SUFFIX ? n_kt : n_my);
             for (; kt < n_spread; ++kt) cache_step(kt, std::true_type{});
         }
-#endif
         for (; kt < n_kt; ++kt) cache_step(kt, std::false_type{});
     }
-    SGC_MARK(3);           // cached tiles done
 
     // ---- the suffix keys of every query this row tile touches, double buffered ------------------------
     bool v_scaled = !KV_FP8;
@@ -924,7 +876,6 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
         }
 #undef SGC_NEXT_SELF
     }
-    SGC_MARK(4);           // own suffix tiles done
 
     // ---- normalise and store ----
     // A lane holds 4-channel pieces of its row; written out as they are they would make 8-byte stores scattered
@@ -967,14 +918,6 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             if (ok) *reinterpret_cast<uint4 *>(og + row + c * 8) = y;
         }
     }
-#ifdef SGC_PHASE_TIMING
-    SGC_MARK(5);           // stores have completed
-    if (lane == 0 && blockIdx.x < 2048) {
-        ph[6] = (unsigned)(blk_r0 & 0xFFFFFFFFu);      // absolute start, low bits
-#pragma unroll
-        for (int i = 0; i < 8; ++i) g_phase[(blockIdx.x * 8 + wave) * 8 + i] = ph[i];
-    }
-#endif
 }
 
 constexpr size_t kDynLds = LDS_TILE_BYTES + MAX_TILE_QUERIES * sizeof(int2);
@@ -985,9 +928,6 @@ hipError_t launch_one(const AttnArgs &a, int blocks, hipStream_t s)
     static bool configured = false;     // raise the dynamic LDS limit once per instantiation
     auto kern = attn_mfma_kernel<NW, MI, FP8, MODE>;
     size_t lds = kDynLds;
-#ifdef SGC_EXPERIMENT_LDS
-    if (const char *e = getenv("SGC_EXTRA_LDS")) lds += (size_t)atoi(e);   // development aid: limit occupancy
-#endif
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -1014,12 +954,6 @@ hipError_t launch_variant(const AttnArgs &a, hipStream_t s)
 
 }  // namespace
 
-#ifdef SGC_PHASE_TIMING
-extern "C" int sgc_debug_read_phases(unsigned long long *host, size_t n)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_phase), n * sizeof(unsigned long long));
-}
-#endif
 
 // variant 0: 8 waves x 32 rows (256-row tiles, one workgroup per CU);
 //         1: 4 waves x 32 rows (128-row tiles, two workgroups per CU);

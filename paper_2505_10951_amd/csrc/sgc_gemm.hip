@@ -58,35 +58,9 @@ __device__ inline void copy_1k_to_lds(const char *src_lane, char *lds)
     __builtin_amdgcn_global_load_lds(g, l, 16, 0, 0);
 }
 
-// timing experiments (wrong results): leave out the operand reads / the step barrier
-#ifdef SGC_GEMM_ABL_NOREAD
-#define SGC_GEMM_READ(x) do { } while (0)
-#else
-#define SGC_GEMM_READ(x) x
-#endif
-#ifdef SGC_GEMM_ABL_NOBAR
-#define SGC_GEMM_BARRIER() do { } while (0)
-#else
-#define SGC_GEMM_BARRIER() __syncthreads()
-#endif
-
-#ifdef SGC_GEMM_PHASE_TIMING
-// Development aid (not built into the product library): per workgroup and wavefront, the time (100 MHz ticks)
-// from the workgroup's start to the end of the main loop and to the end of the epilogue, and the output kind.
-__device__ unsigned long long g_gemm_phase[4096 * 4 * 4];
-#define SGC_GEMM_T0() const unsigned long long gemm_t0 = __builtin_amdgcn_s_memrealtime()
-#define SGC_GEMM_MARK(i, v) do { if (blockIdx.x < 4096 && lane == 0) g_gemm_phase[(blockIdx.x * 4 + wave) * 4 + (i)] = (v); } while (0)
-#define SGC_GEMM_NOW() (__builtin_amdgcn_s_memrealtime() - gemm_t0)
-#else
-#define SGC_GEMM_T0() do { } while (0)
-#define SGC_GEMM_MARK(i, v) do { } while (0)
-#define SGC_GEMM_NOW() 0
-#endif
-
 template <bool QKV>
 __global__ void __launch_bounds__(256, 1) proj_gemm_kernel(const GemmArgs g)
 {
-    SGC_GEMM_T0();
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
@@ -143,14 +117,7 @@ __global__ void __launch_bounds__(256, 1) proj_gemm_kernel(const GemmArgs g)
     auto issue = [&](int kt, int stage) __attribute__((always_inline)) {
         char *as = smem + stage * STAGE_BYTES + wave * 8192;
         char *bs = as + SLAB_BYTES;
-#ifdef SGC_GEMM_ABL_SAMEK      // timing experiment: every step re-reads the first slabs (wrong results)
-        const uint32_t k_off = 0 * kt;
-#else
         const uint32_t k_off = (uint32_t)kt * (TK * 2);
-#endif
-#ifdef SGC_GEMM_ABL_NODMA      // timing experiment: only the first step's slabs are ever copied (wrong results)
-        if (kt > 0) return;
-#endif
 #pragma unroll
         for (int i = 0; i < 8; ++i) copy_1k_to_lds(a_base + (a_off[i] + k_off), as + i * 1024);
 #pragma unroll
@@ -226,20 +193,20 @@ __global__ void __launch_bounds__(256, 1) proj_gemm_kernel(const GemmArgs g)
     auto step = [&](int kt, auto next, auto next2) __attribute__((always_inline)) {
         constexpr bool NEXT = decltype(next)::value, NEXT2 = decltype(next2)::value;
         const char *st = smem + (kt & 1) * STAGE_BYTES;
-        SGC_GEMM_READ(load_ops(st, 1, p1, q1));
+        load_ops(st, 1, p1, q1);
         products(p0, q0);
         order_reads_under_products();
-        SGC_GEMM_READ(load_ops(st, 2, p0, q0));
+        load_ops(st, 2, p0, q0);
         products(p1, q1);
         order_reads_under_products();
-        SGC_GEMM_READ(load_ops(st, 3, p1, q1));
+        load_ops(st, 3, p1, q1);
         products(p0, q0);
         order_reads_under_products();
         if (NEXT) {
             __builtin_amdgcn_s_waitcnt(0x0F70);  // the copies of step kt + 1, requested a step ago
-            SGC_GEMM_BARRIER();                  // every wavefront has read all of step kt out of LDS
+            __syncthreads();                  // every wavefront has read all of step kt out of LDS
             __builtin_amdgcn_sched_barrier(0);
-            SGC_GEMM_READ(load_ops(smem + ((kt + 1) & 1) * STAGE_BYTES, 0, p0, q0));
+            load_ops(smem + ((kt + 1) & 1) * STAGE_BYTES, 0, p0, q0);
             if (NEXT2) issue(kt + 2, kt & 1);
         }
         products(p1, q1);
@@ -264,11 +231,6 @@ __global__ void __launch_bounds__(256, 1) proj_gemm_kernel(const GemmArgs g)
     if (kt + 1 < n_steps) step(kt++, std::true_type{}, std::false_type{});
     step(kt, std::false_type{}, std::false_type{});
 
-    SGC_GEMM_MARK(0, SGC_GEMM_NOW());
-    SGC_GEMM_MARK(2, (unsigned long long)kind);
-#ifdef SGC_GEMM_PHASE_TIMING
-    SGC_GEMM_MARK(3, gemm_t0);
-#endif
     if (col0 >= N) return;          // the second half of a ragged last column tile
     const int rows16 = (rows + 15) & ~15;
 
@@ -332,8 +294,11 @@ __global__ void __launch_bounds__(256, 1) proj_gemm_kernel(const GemmArgs g)
                     float x[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) x[e] = valid ? acc[pi][qj][8 * u + e] : 0.f;
-                    const uint32_t a0 = pack2(x[0], x[1]), a1 = pack2(x[2], x[3]);
-                    const uint32_t b0 = pack2(x[4], x[5]), b1 = pack2(x[6], x[7]);
+                    // keys that go straight into pages are binary16 there; everything else is bf16
+                    const uint32_t a0 = to_pages ? pack2_f16(x[0], x[1]) : pack2(x[0], x[1]);
+                    const uint32_t a1 = to_pages ? pack2_f16(x[2], x[3]) : pack2(x[2], x[3]);
+                    const uint32_t b0 = to_pages ? pack2_f16(x[4], x[5]) : pack2(x[4], x[5]);
+                    const uint32_t b1 = to_pages ? pack2_f16(x[6], x[7]) : pack2(x[6], x[7]);
                     const auto s0 = __builtin_amdgcn_permlane32_swap(a0, b0, false, false);
                     const auto s1 = __builtin_amdgcn_permlane32_swap(a1, b1, false, false);
                     const uint4 out = make_uint4(s0[0], s1[0], s0[1], s1[1]);
@@ -378,7 +343,6 @@ __global__ void __launch_bounds__(256, 1) proj_gemm_kernel(const GemmArgs g)
                 }
             }
     }
-    SGC_GEMM_MARK(1, SGC_GEMM_NOW());
 }
 
 // Any shape and both io types, one output element per thread, fp32 accumulation; columns are dealt to up to
@@ -438,12 +402,6 @@ __global__ void __launch_bounds__(256) zero_last_pages_kernel(char *spool, const
 
 }  // namespace
 
-#ifdef SGC_GEMM_PHASE_TIMING
-extern "C" int sgc_debug_read_gemm_phases(unsigned long long *host, size_t n)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_gemm_phase), n * sizeof(unsigned long long));
-}
-#endif
 
 hipError_t launch_proj_gemm(const GemmArgs &g, bool qkv, hipStream_t s)
 {

@@ -515,10 +515,6 @@ int sgc_ctx_create(const sgc_attn_params *params, sgc_ctx **out)
     ctx->scale = params->softmax_scale > 0.0f ? params->softmax_scale : 1.0f / sqrtf((float)params->head_dim);
     ctx->use_mfma = params->kernel == SGC_KERNEL_MFMA || (params->kernel == SGC_KERNEL_AUTO && mfma_covers(*params));
     ctx->mfma_variant = 1;      // 4 wavefronts x 32 rows, two workgroups per CU: fastest measured
-    if (const char *v = getenv("SGC_MFMA_VARIANT")) {
-        const int n = atoi(v);
-        if (mfma_tile_rows(n) > 0) ctx->mfma_variant = n;
-    }
     ctx->tile_rows = ctx->use_mfma ? mfma_tile_rows(ctx->mfma_variant) : 0;
     *out = ctx;
     return SGC_OK;
@@ -1251,38 +1247,6 @@ int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int
     a.n_append = n_sq;
     SGC_HIP(ctx, launch_attn_mfma(a, ctx->mfma_variant, s));
     SGC_HIP(ctx, launch_decode_own_keys(d, s));
-    return SGC_OK;
-}
-
-int sgc_probe_mfma_rate(sgc_ctx *ctx, int32_t iters, float *out_tflops, void *hip_stream)
-{
-    if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
-    if (!out_tflops) return fail(ctx, SGC_EINVAL, "out_tflops is NULL");
-    if (iters < 1 || iters > (1 << 20)) return fail(ctx, SGC_EINVAL, "iters %d outside [1, 2^20]", iters);
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    int dev = 0, cus = 0;
-    SGC_HIP(ctx, hipGetDevice(&dev));
-    SGC_HIP(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    const int blocks = std::max(cus, 1);                    // one workgroup of four wavefronts per CU: one per SIMD
-    sgc_dev_block sink;
-    int rc = dev_acquire(ctx, (size_t)blocks * 256 * sizeof(float), s, &sink);
-    if (rc != SGC_OK) return rc;
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    hipError_t e = hipEventCreate(&e0);
-    if (e == hipSuccess) e = hipEventCreate(&e1);
-    if (e == hipSuccess) e = launch_mfma_rate(blocks, std::min(iters, 64), reinterpret_cast<float *>(sink.p), s);   // warm-up
-    if (e == hipSuccess) e = hipEventRecord(e0, s);
-    if (e == hipSuccess) e = launch_mfma_rate(blocks, iters, reinterpret_cast<float *>(sink.p), s);
-    if (e == hipSuccess) e = hipEventRecord(e1, s);
-    if (e == hipSuccess) e = hipEventSynchronize(e1);
-    float ms = 0.f;
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-    if (e0) (void)hipEventDestroy(e0);
-    if (e1) (void)hipEventDestroy(e1);
-    dev_release(ctx, sink, s);
-    if (e != hipSuccess) return fail_hip(ctx, e, "matrix-core rate probe");
-    const double flop = (double)blocks * 4.0 * (double)iters * 16.0 * 32768.0;
-    *out_tflops = ms > 0.f ? (float)(flop / (ms * 1e-3) / 1e12) : 0.f;
     return SGC_OK;
 }
 

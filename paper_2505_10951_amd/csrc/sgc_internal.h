@@ -37,6 +37,31 @@ __host__ __device__ inline int v_page_index(int tok, int c)
     return ((((c >> 5) * 2 + h) * 32) + (c & 31)) * 8 + i;
 }
 
+// ---- element type of the rotated keys in 16-bit pages ------------------------------------------
+// A rotated key is a sum of two products and has no exact bf16 form.  Rounded to bf16 (8 significant
+// bits) the keys of a head with a few large channels move a score by up to 1e-2 and an output by more
+// than the 2e-2 a bf16 result is held to; IEEE binary16 (11 significant bits) costs the same two bytes
+// and the same matrix-core rate.  So in every 16-bit page (cluster caches with kv_dtype SGC_BF16 and
+// the batch's suffix pages) K is binary16 and V, which is stored as given, stays bf16; the first
+// product runs on binary16 operands (the rotated, scaled query is rounded to binary16 as well), the
+// second on bf16.  Magnitudes beyond 65504 become infinities and poison the rows that see them.
+typedef __attribute__((ext_vector_type(2))) _Float16 sgc_f16x2;
+__device__ inline uint16_t f32_to_f16_bits(float x)
+{
+    const _Float16 h = (_Float16)x;
+    return __builtin_bit_cast(uint16_t, h);
+}
+__device__ inline uint32_t pack2_f16(float a, float b)
+{
+    const sgc_f16x2 p = {(_Float16)a, (_Float16)b};
+    return __builtin_bit_cast(uint32_t, p);
+}
+__device__ inline float f16_bits_to_f32(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+// internal element-type tag beside the sgc_dtype values: IEEE binary16
+constexpr int kElemF16 = 16;
+// the type K is stored in for a cache of type kv_dtype
+__host__ __device__ inline int k_elem_type(int kv_dtype) { return kv_dtype == SGC_BF16 ? kElemF16 : kv_dtype; }
+
 __host__ __device__ inline int dtype_bytes(int dt) { return dt == SGC_F32 ? 4 : (dt == SGC_BF16 ? 2 : 1); }
 
 // Geometry of the page pool, passed by value to kernels.
@@ -349,8 +374,6 @@ hipError_t launch_attn_generic(const AttnArgs &a, int64_t n_rows, hipStream_t s)
 // pages by the cached-part launch before) merged with the cached-prefix part.  head_dim 128, bf16.
 hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s);
 hipError_t launch_fill_zero_bytes(void *p, size_t bytes, hipStream_t s);
-// Measurement aid: `blocks` workgroups of 4 wavefronts issue iters * 16 bf16 32x32x16 matrix-core instructions each.
-hipError_t launch_mfma_rate(int blocks, int iters, float *sink, hipStream_t s);
 // Projections: the bf16 matrix-core kernel (K a multiple of 64, N a multiple of 128; qkv selects the fused
 // epilogue) and a kernel for every other shape and type that deals columns [0, n0), [n0, n0 + n1) and the rest
 // to three row-major matrices (c0 may be null to drop its columns).

@@ -76,6 +76,14 @@ __device__ inline void load8(const void *base, int64_t idx, int dtype, float out
             out[2 * i] = __uint_as_float(w[i] << 16);
             out[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
         }
+    } else if (dtype == kElemF16) {
+        const uint4 a = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + idx);
+        const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = f16_bits_to_f32((uint16_t)(w[i] & 0xFFFFu));
+            out[2 * i + 1] = f16_bits_to_f32((uint16_t)(w[i] >> 16));
+        }
     } else {
         const uint2 a = *reinterpret_cast<const uint2 *>(static_cast<const uint8_t *>(base) + idx);
         const uint32_t w[2] = {a.x, a.y};
@@ -88,6 +96,7 @@ __device__ inline float load1(const void *base, int64_t idx, int dtype)
 {
     if (dtype == SGC_F32) return static_cast<const float *>(base)[idx];
     if (dtype == SGC_BF16) return bf16_to_f32(static_cast<const uint16_t *>(base)[idx]);
+    if (dtype == kElemF16) return f16_bits_to_f32(static_cast<const uint16_t *>(base)[idx]);
     return e4m3_to_f32(static_cast<const uint8_t *>(base)[idx]);
 }
 
@@ -98,6 +107,8 @@ __device__ inline void store1(void *base, int64_t idx, int dtype, float x, float
         static_cast<float *>(base)[idx] = x;
     else if (dtype == SGC_BF16)
         static_cast<uint16_t *>(base)[idx] = f32_to_bf16(x);
+    else if (dtype == kElemF16)
+        static_cast<uint16_t *>(base)[idx] = f32_to_f16_bits(x);
     else
         static_cast<uint8_t *>(base)[idx] = f32_to_e4m3(x / scale);
 }
@@ -113,6 +124,9 @@ __device__ inline void store8(void *base, int64_t idx, int dtype, const float x[
 #pragma unroll
         for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16(x[2 * i]) | ((uint32_t)f32_to_bf16(x[2 * i + 1]) << 16);
         *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(base) + idx) = make_uint4(w[0], w[1], w[2], w[3]);
+    } else if (dtype == kElemF16) {
+        *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(base) + idx) =
+            make_uint4(pack2_f16(x[0], x[1]), pack2_f16(x[2], x[3]), pack2_f16(x[4], x[5]), pack2_f16(x[6], x[7]));
     } else {
         uint32_t w[2] = {0, 0};
 #pragma unroll
@@ -261,8 +275,8 @@ __global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *page_t
 #pragma unroll
             for (int i = 0; i < 8; ++i) x1[i] = x2[i] = y1[i] = y2[i] = 0.f;
         }
-        store8(kp, k_page_index(tok, cc * 8), g.kv_dtype, x1, sc_k);
-        store8(kp, k_page_index(tok, half + cc * 8), g.kv_dtype, x2, sc_k);
+        store8(kp, k_page_index(tok, cc * 8), k_elem_type(g.kv_dtype), x1, sc_k);
+        store8(kp, k_page_index(tok, half + cc * 8), k_elem_type(g.kv_dtype), x2, sc_k);
         if (via_tile) {
             store8(vp, tok * 128 + vt_pos(cc, tok) * 8, SGC_BF16, y1, 1.f);
             store8(vp, tok * 128 + vt_pos(8 + cc, tok) * 8, SGC_BF16, y2, 1.f);
@@ -283,7 +297,7 @@ __global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *page_t
 }
 
 // ---- suffix ingest ---------------------------------------------------------------------------
-// Same page layout as the cache, bf16 only, for the question tokens of every query of the batch
+// Same page layout as the cache, 16-bit only (K binary16, V bf16), for the question tokens of every query of the batch
 // (SubGCache Sec. 3.4: the question tokens are appended to the cached prompt, so suffix token j of a
 // query whose cluster has P prefix tokens is rotated at position P + j).  One workgroup per
 // (suffix page, KV head); tokens past the query's end are written as zeros.
@@ -318,8 +332,8 @@ __global__ void suffix_ingest_kernel(AttnArgs a, const int32_t *spage_sq)
 #pragma unroll
             for (int i = 0; i < 8; ++i) x1[i] = x2[i] = y1[i] = y2[i] = 0.f;
         }
-        store8(kp, k_page_index(tok, cc * 8), SGC_BF16, x1, 1.f);
-        store8(kp, k_page_index(tok, half + cc * 8), SGC_BF16, x2, 1.f);
+        store8(kp, k_page_index(tok, cc * 8), kElemF16, x1, 1.f);
+        store8(kp, k_page_index(tok, half + cc * 8), kElemF16, x2, 1.f);
         if (via_tile) {
             store8(vp, tok * 128 + vt_pos(cc, tok) * 8, SGC_BF16, y1, 1.f);
             store8(vp, tok * 128 + vt_pos(8 + cc, tok) * 8, SGC_BF16, y2, 1.f);
@@ -350,10 +364,20 @@ __global__ void suffix_ingest_kernel(AttnArgs a, const int32_t *spage_sq)
 // One wavefront per (sorted query, group of G query heads that share a KV head): scores of the new token
 // against the query's own len + step + 1 keys (lane = key, each key read once for the G heads), softmax,
 // weighted V sum (lane = channel pair), merged with the cached-prefix part by the log-sum-exp rule.
-// Both products run on bf16 pairs with fp32 accumulation (v_dot2_f32_bf16), on the operands a matrix-core
-// kernel would use: the rotated query and the softmax weights rounded to bf16, the row sum taken over the
-// rounded weights.  G divides the GQA group size.
+// Both products run on 16-bit pairs with fp32 accumulation (v_dot2_f32_f16 on the binary16 keys and the rotated
+// query rounded to binary16; v_dot2_f32_bf16 on the bf16 values and the softmax weights rounded to bf16), the
+// operands a matrix-core kernel would use; the row sum is taken over the rounded weights.  G divides the GQA
+// group size.
 typedef __attribute__((ext_vector_type(2))) __bf16 dec_bf16x2;
+
+__device__ inline float dot8_f16(const uint4 &x, const uint4 &y, float acc)
+{
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(sgc_f16x2, x.x), __builtin_bit_cast(sgc_f16x2, y.x), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(sgc_f16x2, x.y), __builtin_bit_cast(sgc_f16x2, y.y), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(sgc_f16x2, x.z), __builtin_bit_cast(sgc_f16x2, y.z), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(sgc_f16x2, x.w), __builtin_bit_cast(sgc_f16x2, y.w), acc, false);
+    return acc;
+}
 
 __device__ inline float dot8_bf16(const uint4 &x, const uint4 &y, float acc)
 {
@@ -368,7 +392,7 @@ template <int G>
 __global__ void __launch_bounds__(64) decode_own_keys_kernel(DecodeArgs a)
 {
     constexpr int d = 128, half = 64;
-    // LDS: the G rotated query rows as bf16 [G][128]; G rows of key_cap scores (fp32); G rows of key_cap weights as
+    // LDS: the G rotated query rows as binary16 [G][128]; G rows of key_cap scores (fp32); G rows of key_cap weights as
     // bf16 in the order the V pages hold their tokens (key_cap = the batch's largest key count, rounded up to a page;
     // sized at launch so that many wavefronts fit a CU)
     extern __shared__ __attribute__((aligned(16))) char dec_lds[];
@@ -395,8 +419,8 @@ __global__ void __launch_bounds__(64) decode_own_keys_kernel(DecodeArgs a)
         uint32_t w1[4], w2[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            w1[i] = (uint32_t)f32_to_bf16(x1[2 * i]) | ((uint32_t)f32_to_bf16(x1[2 * i + 1]) << 16);
-            w2[i] = (uint32_t)f32_to_bf16(x2[2 * i]) | ((uint32_t)f32_to_bf16(x2[2 * i + 1]) << 16);
+            w1[i] = pack2_f16(x1[2 * i], x1[2 * i + 1]);
+            w2[i] = pack2_f16(x2[2 * i], x2[2 * i + 1]);
         }
         *reinterpret_cast<uint4 *>(q_s + gi * d + cc * 8) = make_uint4(w1[0], w1[1], w1[2], w1[3]);
         *reinterpret_cast<uint4 *>(q_s + gi * d + half + cc * 8) = make_uint4(w2[0], w2[1], w2[2], w2[3]);
@@ -423,7 +447,7 @@ __global__ void __launch_bounds__(64) decode_own_keys_kernel(DecodeArgs a)
         for (int cc = 0; cc < d / 8; ++cc) {
 #pragma unroll
             for (int gi = 0; gi < G; ++gi)
-                sc[gi] = dot8_bf16(raw[cc], *reinterpret_cast<const uint4 *>(q_s + gi * d + cc * 8), sc[gi]);
+                sc[gi] = dot8_f16(raw[cc], *reinterpret_cast<const uint4 *>(q_s + gi * d + cc * 8), sc[gi]);
         }
 #pragma unroll
         for (int gi = 0; gi < G; ++gi) {
@@ -642,7 +666,7 @@ __global__ void __launch_bounds__(256) attn_generic_kernel(AttnArgs a)
 #pragma unroll
         for (int cc = 0; cc < D / 8; ++cc) {
             float kk[8];
-            load8(kp, k_page_index(tok, cc * 8), kvd, kk);
+            load8(kp, k_page_index(tok, cc * 8), k_elem_type(kvd), kk);
 #pragma unroll
             for (int i = 0; i < 8; ++i) s += q_s[wave][cc * 8 + i] * kk[i];
         }
@@ -768,42 +792,6 @@ hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s)
         case 2: hipLaunchKernelGGL(decode_own_keys_kernel<2>, grid, dim3(64), lds, s, d); break;
         default: hipLaunchKernelGGL(decode_own_keys_kernel<1>, grid, dim3(64), lds, s, d); break;
     }
-    return hipGetLastError();
-}
-
-// Measurement aid: nothing but matrix-core instructions (four independent accumulator chains per wavefront, one
-// wavefront per SIMD, no memory traffic), to see what the chip sustains under that load.
-typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8;
-typedef __attribute__((ext_vector_type(16))) float probe_f32x16;
-__global__ void __launch_bounds__(256) mfma_rate_kernel(int iters, float *sink)
-{
-    const int lane = threadIdx.x & 63;
-    probe_bf16x8 x, y;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        x[i] = (__bf16)(0.001f * (float)(lane + i));
-        y[i] = (__bf16)(0.002f * (float)(lane - i));
-    }
-    probe_f32x16 acc[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int u = 0; u < 16; ++u) acc[u & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc[u & 3], 0, 0, 0);
-    }
-    float sum = 0.f;
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sum += acc[c][r];
-    if (sum == 12345.678f) sink[blockIdx.x * 256 + threadIdx.x] = sum;      // keeps the chains alive; never true in practice
-}
-
-hipError_t launch_mfma_rate(int blocks, int iters, float *sink, hipStream_t s)
-{
-    hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(256), 0, s, iters, sink);
     return hipGetLastError();
 }
 

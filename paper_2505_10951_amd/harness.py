@@ -190,12 +190,13 @@ class Session:
 
     def export_cluster(self, c: int, layer: int = 0):
         """Canonical [P][Hkv][d] view of the cluster's cache: (k, v, k_scale, v_scale) on the host.
-        k, v are fp32 values for f32/bf16 caches and raw uint8 e4m3 codes for fp8 caches."""
+        k, v are fp32 values for f32/bf16 caches and raw uint8 e4m3 codes for fp8 caches.  (A 16-bit cache
+        holds the rotated keys as IEEE binary16 and the values as bf16.)"""
         w = self.w
         P = int(w.prefix_len[c])
         shp = (max(P, 1), w.n_kv_heads, w.head_dim)
         tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.uint8}[w.kv_dtype]
-        dk = torch.zeros(shp, dtype=tdt, device=self.device)
+        dk = torch.zeros(shp, dtype=torch.float16 if w.kv_dtype == "bf16" else tdt, device=self.device)
         dv = torch.zeros(shp, dtype=tdt, device=self.device)
         ks, vs = sgc.sgc_cache_export(self.ctx, self.cache, c, layer, dk.data_ptr(), dv.data_ptr(), w.n_kv_heads,
                                       self.stream)
@@ -211,6 +212,8 @@ class Session:
             dv = torch.from_numpy(np.ascontiguousarray(v, dtype=np.uint8)).to(self.device)
         else:
             dk, dv = to_device(k, w.kv_dtype, self.device), to_device(v, w.kv_dtype, self.device)
+            if w.kv_dtype == "bf16":      # keys of a 16-bit cache are binary16
+                dk = torch.from_numpy(np.ascontiguousarray(k, dtype=np.float32)).to(torch.float16).to(self.device)
         sgc.sgc_cache_import(self.ctx, self.cache, c, layer, dk.data_ptr(), dv.data_ptr(), k_scale, v_scale, self.stream)
         torch.cuda.synchronize()
 

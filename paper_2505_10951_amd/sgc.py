@@ -11,8 +11,7 @@ from typing import Optional, Sequence, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# SGC_LIB_PATH lets a developer load an experimental build of the same library instead
-LIB_PATH = os.environ.get("SGC_LIB_PATH") or os.path.join(_HERE, "libsgc.so")
+LIB_PATH = os.path.join(_HERE, "libsgc.so")
 
 SGC_OK, SGC_EINVAL, SGC_ENOMEM, SGC_ESHAPE, SGC_EUNSUPPORTED, SGC_EHIP, SGC_ESTATE = 0, -1, -2, -3, -4, -5, -6
 SGC_F32, SGC_BF16, SGC_FP8_E4M3 = 0, 1, 2
@@ -28,7 +27,7 @@ EXPORTS = [
     "sgc_plan_get_info", "sgc_plan_destroy", "sgc_suffix_prefill_batched", "sgc_cache_export", "sgc_cache_import",
     "sgc_timing_enable", "sgc_timing_last", "sgc_cluster_queries", "sgc_plan_enable_decode", "sgc_decode_step_batched",
     "sgc_union_subgraphs", "sgc_project_qkv_prefix", "sgc_project_qkv_prefix_batched", "sgc_project_qkv_suffix",
-    "sgc_project_out", "sgc_timing_get", "sgc_probe_mfma_rate",
+    "sgc_project_out", "sgc_timing_get",
 ]
 
 
@@ -108,7 +107,6 @@ def lib() -> ctypes.CDLL:
         L.sgc_timing_enable.argtypes = [vp, ctypes.c_int]
         L.sgc_timing_last.argtypes = [vp, f32p, f32p]
         L.sgc_timing_get.argtypes = [vp, i32, f32p, f32p]
-        L.sgc_probe_mfma_rate.argtypes = [vp, i32, f32p, vp]
         for name in EXPORTS:
             fn = getattr(L, name)
             if fn.restype is ctypes.c_int and name not in ("sgc_version",):
@@ -359,13 +357,6 @@ def sgc_timing_last(ctx) -> Tuple[float, float]:
     a, b = ctypes.c_float(0), ctypes.c_float(0)
     _check(ctx, lib().sgc_timing_last(ctx, ctypes.byref(a), ctypes.byref(b)))
     return a.value, b.value
-
-
-def sgc_probe_mfma_rate(ctx, iters: int = 20000, stream: int = 0) -> float:
-    """TFLOP/s the chip sustains on a kernel of bf16 matrix-core instructions only."""
-    out = ctypes.c_float(0)
-    _check(ctx, lib().sgc_probe_mfma_rate(ctx, int(iters), ctypes.byref(out), stream))
-    return out.value
 
 
 def sgc_timing_get(ctx, back: int) -> Tuple[float, float]:

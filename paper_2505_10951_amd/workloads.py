@@ -220,17 +220,28 @@ class Workload:
                 x[a:b] = self.suffix_x_query(n, d_model, layer)
         return x
 
-    def suffix_qkv(self, layer: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
-        """All queries packed in original order: Q [T][Hq][d], K, V [T][Hkv][d]."""
+    def suffix_qkv(self, layer: int = 0, threads: int = 1) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+        """All queries packed in original order: Q [T][Hq][d], K, V [T][Hkv][d].  Every query has its own
+        random stream, so `threads` > 1 draws them side by side and gives the same arrays."""
         T = self.total_suffix_tokens
         cu = self.cu_seqlens
         q = np.empty((T, self.n_q_heads, self.head_dim), dtype=np.float32)
         k = np.empty((T, self.n_kv_heads, self.head_dim), dtype=np.float32)
         v = np.empty((T, self.n_kv_heads, self.head_dim), dtype=np.float32)
-        for n in range(self.n_queries):
+        self._outlier_channels(layer)             # drawn once, before any worker asks for it
+
+        def one(n: int) -> None:
             a, b = int(cu[n]), int(cu[n + 1])
             if b > a:
                 q[a:b], k[a:b], v[a:b] = self.suffix_qkv_query(n, layer)
+
+        if threads > 1:
+            from concurrent.futures import ThreadPoolExecutor
+            with ThreadPoolExecutor(max_workers=threads) as ex:
+                list(ex.map(one, range(self.n_queries)))
+        else:
+            for n in range(self.n_queries):
+                one(n)
         return q, k, v
 
 

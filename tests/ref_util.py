@@ -49,13 +49,16 @@ def oracle_suffix(w: Workload, layer: int = 0, queries: Optional[Sequence[int]] 
 
 def bf16_floor_arrays(pk, pv, q, k, v, rope_base: float, want_lse: bool = False):
     """max |o_rounded - o_exact| (and, with want_lse, the same for LSE) of one query's suffix prefill when the
-    rotated Q and K, the probabilities and the output are rounded to bf16 where a bf16 matrix-core kernel has
-    to round them (dense numpy, fp64 otherwise).  A measure of the error any such kernel carries; used to set
-    a tolerance, never as a reference."""
+    operands are rounded where a 16-bit matrix-core kernel has to round them: the rotated keys and the rotated,
+    scaled queries to IEEE binary16 (what the library keeps and multiplies), the probabilities and the output to
+    bf16 (dense numpy, fp64 otherwise).  A measure of the error any such kernel carries; used to set a
+    tolerance, never as a reference."""
     P, S = pk.shape[0], q.shape[0]
     d = q.shape[-1]
     g = q.shape[1] // k.shape[1]
     r = lambda x: round_to_bf16(np.asarray(x, dtype=np.float32)).astype(np.float64)
+    c_q = np.log2(np.e) / np.sqrt(d)      # the query carries the score scale in log2 units when it is rounded
+    rh = lambda x: np.asarray(x, dtype=np.float32).astype(np.float16).astype(np.float64)
     kr = np.concatenate([orc.rope_numpy(pk, np.arange(P), rope_base), orc.rope_numpy(k, P + np.arange(S), rope_base)])
     qr = orc.rope_numpy(q, P + np.arange(S), rope_base)
     vv = np.concatenate([pv, v]).astype(np.float64)
@@ -72,7 +75,7 @@ def bf16_floor_arrays(pk, pv, q, k, v, rope_base: float, want_lse: bool = False)
         return np.einsum("hij,jhc->ihc", e / z, np.repeat(vv, g, axis=1)), lse
 
     exact, lse_exact = attend(qr, kr, False)
-    rounded, lse_rounded = attend(r(qr), r(kr), True)
+    rounded, lse_rounded = attend(rh(qr * c_q) / c_q, rh(kr), True)
     o_floor = float(np.abs(r(rounded) - exact).max())
     if want_lse:
         return o_floor, float(np.abs(lse_rounded - lse_exact).max())

@@ -227,7 +227,7 @@ def test_prefix_prefill_cache_and_causal_output(kernel):
             ck, cv, o_ref, lse_ref = orc.prefix_prefill(w.prefix_q(c), pk, pv, w.rope_base, want_lse=True)
             ek, ev, _, _ = s.export_cluster(c)
             assert np.array_equal(ev, pv)                                     # V is stored as given
-            assert np.abs(ek - ck).max() <= np.abs(ck).max() * 2.0 ** -8      # K: one bf16 rounding
+            assert np.all(np.abs(ek - ck) <= np.abs(ck) * 2.0 ** -11 + 1e-5)  # K: one binary16 rounding (+ fp32 rotation)
             st = err_stats(to_host_f32(do), o_ref)
             # the prefix's own attention is a suffix prefill over an empty cache
             e = np.zeros((0, w.n_kv_heads, w.head_dim))
@@ -383,7 +383,9 @@ def test_fp8_imported_oracle_cache_isolates_the_attention():
     assert st["max_abs"] <= 6e-3
 
 
-# ---- configs[1..4] at full size, in the benchmark's launch configuration, on sampled queries -----
+# ---- configs[1..4] at full size, in the benchmark's launch configuration ---------------------------
+# configs[1] and configs[2] are checked on EVERY row against the oracle; configs[3] on a query and head of every
+# (cluster, layer) pair, all rows of the pair; configs[4] on a query of every cluster, all heads and rows.
 def _sampled_queries(w, per_cluster, seed=0):
     rng = np.random.default_rng(seed)
     picks = []
@@ -394,74 +396,92 @@ def _sampled_queries(w, per_cluster, seed=0):
     return sorted(picks)
 
 
-def test_config1_llama3_8b_layer_full_size_sampled():
+def test_config1_llama3_8b_layer_full_size_every_row():
     w = workloads.config(1)
     _say("config 1", w.name, "T", w.total_suffix_tokens, "flop %.3e" % w.flops())
     out = run_workload(w)
     _check_bookkeeping(w, out)
-    qs = _sampled_queries(w, 2)
-    tight, lse_bar = tight_bar(w, qs[:4])
-    _check_suffix(w, out, queries=qs, tol=TOL_BF16, tight=tight, lse_tol=lse_bar)
+    tight, lse_bar = tight_bar(w, _sampled_queries(w, 1)[:4])
+    st = _check_suffix(w, out, queries=None, tol=TOL_BF16, lse_tol=lse_bar)       # all 320 queries, all heads, all rows
+    # Outlier key channels make this the config with the peakiest softmax.  With the rotated keys and queries held
+    # as binary16 the largest deviation an ideal kernel shows over the whole batch is 7.8e-3 (the bf16 rounding of
+    # the output itself); the same emulation with bf16 keys and queries shows 2.6e-2.
+    assert st["max_abs"] <= 1.2e-2
     assert np.isfinite(out["o"]).all() and np.abs(out["o"]).max() < 8
 
 
-def test_config2_llama2_7b_ragged_full_size_sampled():
+def test_config2_llama2_7b_ragged_full_size_every_row():
     w = workloads.config(2)
     _say("config 2", w.name, "T", w.total_suffix_tokens, "flop %.3e" % w.flops())
     out = run_workload(w, want_lse=False)
     _check_bookkeeping(w, out)
-    qs = _sampled_queries(w, 1)[:8]
-    _check_suffix(w, out, queries=qs, tol=TOL_BF16, tight=tight_bar(w, qs[:3])[0])
+    _check_suffix(w, out, queries=None, tol=TOL_BF16, tight=tight_bar(w, _sampled_queries(w, 1)[:3])[0])
     assert np.isfinite(out["o"]).all()
 
 
-def test_config3_llama3_8b_stack32_resident_cache_sampled_layers():
-    """32 layers over one resident paged cache (8 GiB of pages): every layer's cache is filled before any suffix
-    prefill runs; three layers carry the workload's seeded data and are checked against the oracle on sampled
-    queries, the other 29 are filled with device noise (they only have to stay out of the way)."""
+def test_config3_llama3_8b_stack32_every_cluster_and_layer():
+    """32 layers over one resident paged cache (8 GiB of pages), every layer with the workload's own seeded data:
+    all caches are filled before any suffix prefill runs; then each layer's whole batch runs in one launch and, for
+    every (cluster, layer) pair, all rows of one of the cluster's queries under one query head are compared with
+    the oracle (the head changes with the pair, so all 32 heads are visited)."""
+    from concurrent.futures import ThreadPoolExecutor
     w = workloads.config(3)
-    sampled_layers = [0, 17, 31]
     clusters = list(range(w.n_clusters))
-    with Session(w) as s:
+    cu = w.cu_seqlens
+    pick = {c: int(np.flatnonzero(w.labels == c)[c % 16]) for c in clusters}        # one query per cluster
+    with Session(w) as s, ThreadPoolExecutor(max_workers=4) as pool:
         pool_gib = s.pool.numel() / 2 ** 30
         _say("config 3", w.name, "T/layer", w.total_suffix_tokens, "pool GiB %.2f" % pool_gib)
         assert pool_gib >= 8.0
         for c in clusters:
             s.alloc_cluster(c)
-        for layer in sampled_layers:
-            s.prefix_prefill_batched(clusters, layer)
-        gen = torch.Generator(device="cuda:0").manual_seed(1)
-        shp = (int(w.prefix_len.max()), w.n_kv_heads, w.head_dim)
-        for layer in range(w.n_layers):
-            if layer in sampled_layers:
-                continue
-            nk = [torch.randn(shp, generator=gen, device="cuda:0", dtype=torch.bfloat16) for _ in range(2)]
-            sgc.sgc_prefix_prefill_batched(s.ctx, s.cache, clusters, layer, None, [nk[0].data_ptr()] * len(clusters),
-                                           [nk[1].data_ptr()] * len(clusters), None, None, s.stream)
+        ahead = [pool.submit(lambda l=l: [w.prefix_kv(c, l) for c in clusters]) for l in range(min(3, w.n_layers))]
+        for layer in range(w.n_layers):                       # fill every layer of every cluster first
+            kv = ahead.pop(0).result()
+            if layer + 3 < w.n_layers:
+                ahead.append(pool.submit(lambda l=layer + 3: [w.prefix_kv(c, l) for c in clusters]))
+            dk = [to_device(k, "bf16") for k, _ in kv]
+            dv = [to_device(v, "bf16") for _, v in kv]
+            sgc.sgc_prefix_prefill_batched(s.ctx, s.cache, clusters, layer, None, [t.data_ptr() for t in dk],
+                                           [t.data_ptr() for t in dv], None, None, s.stream)
             torch.cuda.synchronize()
-        order, off, cu = s.assign()
-        _check_bookkeeping(w, {"order": order, "cluster_off": off, "cu_seqlens": cu})
-        qs = _sampled_queries(w, 1)[::5]            # 4 queries, 128 tokens x 32 heads each
-        for layer in sampled_layers:
-            q, k, v = w.suffix_qkv(layer)
+            del kv, dk, dv
+        order, off, cu_out = s.assign()
+        _check_bookkeeping(w, {"order": order, "cluster_off": off, "cu_seqlens": cu_out})
+        ahead = [pool.submit(w.suffix_qkv, l) for l in range(min(2, w.n_layers))]
+        worst = 0.0
+        for layer in range(w.n_layers):
+            q, k, v = ahead.pop(0).result()
+            if layer + 2 < w.n_layers:
+                ahead.append(pool.submit(w.suffix_qkv, layer + 2))
             do = s.suffix_prefill(*(to_device(x, "bf16") for x in (q, k, v)), layer=layer)
             torch.cuda.synchronize()
             o = to_host_f32(do)
-            rows, o_ref, _ = oracle_suffix(w, layer, qs)
-            st = err_stats(o[rows], o_ref)
-            _say(f"  layer {layer}: rows {len(rows)} max_abs {st['max_abs']:.3e}")
-            assert np.isfinite(o).all() and st["max_abs"] <= TOL_BF16
+            assert np.isfinite(o).all()
+            layer_worst = 0.0
+            for c in clusters:
+                n, head = pick[c], (5 * layer + 3 * c) % w.n_q_heads
+                ck, cv, _, _ = orc.prefix_prefill(None, *w.prefix_kv(c, layer), w.rope_base)
+                a, b = int(cu[n]), int(cu[n + 1])
+                o_ref, _ = orc.suffix_prefill_head(ck, cv, q[a:b], k[a:b], v[a:b], head, w.rope_base)
+                layer_worst = max(layer_worst, float(np.abs(o[a:b, head] - o_ref).max()))
+            _say(f"  layer {layer}: 16 (cluster, head) pairs x 128 rows, max_abs {layer_worst:.3e}")
+            assert layer_worst <= TOL_BF16
+            worst = max(worst, layer_worst)
             del q, k, v, do, o
+        _say(f"  config 3 worst over 512 (cluster, layer) pairs {worst:.3e}")
 
 
-def test_config4_llama70b_fp8_long_prefix_full_size_sampled():
+def test_config4_llama70b_fp8_long_prefix_full_size_every_cluster():
     """fp8 e4m3 cache, 16 384-token prefixes, 1024 queries of 32-256 tokens: the whole batch in one launch,
-    checked on sampled queries against the oracle reading its own quantised cache."""
+    checked on one query of every cluster (all 64 heads, all rows) against the oracle reading its own quantised
+    cache."""
     w = workloads.config(4)
     _say("config 4", w.name, "T", w.total_suffix_tokens, "flop %.3e" % w.flops())
     out = run_workload(w, want_lse=False)
     _check_bookkeeping(w, out)
-    qs = _sampled_queries(w, 1)[::2]                # 4 queries
+    qs = _sampled_queries(w, 1)                     # 8 queries, one per cluster
+    assert sorted(int(w.labels[n]) for n in qs) == list(range(w.n_clusters))
     _check_suffix(w, out, queries=qs, tol=TOL_FP8)
     assert np.isfinite(out["o"]).all()
 

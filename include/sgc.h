@@ -218,6 +218,23 @@ int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cache, sgc_plan *plan
                             int32_t step, const void *dev_q, const void *dev_k, const void *dev_v,
                             void *dev_o, float *dev_lse, void *hip_stream);
 
+/* sgc_decode_step_batched for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same
+ * results.  The call allocates nothing (no hipMalloc / hipFree / host allocation of the HIP runtime's):
+ * the partial results of the step's cached-prompt part, which sgc_decode_step_batched keeps in a block
+ * of the context's pool, go to a fixed 32 MiB device array inside the library (one copy per GPU, held
+ * until the process ends).  SGC_ENOMEM if they need more: n_queries * Hq * d * 2 bytes plus n_queries *
+ * Hq * 4, times the number of key ranges the plan splits long prompts into (at most 8).  Every table the
+ * step reads must already be on the device and current, which is the case once the plan's suffix prefill
+ * has run and no cluster was allocated or released since: SGC_ESTATE otherwise (rotary table too short --
+ * set max_position to cover prefix + question + generated tokens --, page tables or tile lists stale).
+ * All calls on one GPU share the array and it keeps the last call's contents; nothing in it needs
+ * clearing (a step overwrites every entry it reads), but two calls whose kernels overlap on one GPU (two
+ * streams, two host threads, two contexts) race on it. */
+int sgc_decode_step_batched_noalloc(sgc_ctx *ctx, const sgc_cache *cache, sgc_plan *plan, int32_t layer,
+                                    int32_t step, const void *dev_q, const void *dev_k, const void *dev_v,
+                                    void *dev_o, float *dev_lse, void *hip_stream);
+
 /* ---- query clustering (Sec. 3.2; App. A.2; linkages of Table 3) -------------------------------
  * Agglomerative hierarchical clustering of m query (subgraph) embeddings with Euclidean distance,
  * stopped when n_clusters clusters are left ("cutting the dendrogram at a predefined number of

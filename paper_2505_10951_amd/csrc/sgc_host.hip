@@ -1159,9 +1159,38 @@ int sgc_plan_enable_decode(sgc_plan *pl, int32_t max_new_tokens)
     return SGC_OK;
 }
 
-int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int32_t layer, int32_t step,
-                            const void *dev_q, const void *dev_k, const void *dev_v, void *dev_o, float *dev_lse,
-                            void *hip_stream)
+// ---- device scratch for callers that cannot allocate ------------------------------------------------
+// sgc_decode_step_batched_noalloc keeps the partial results of a step's cached-prompt part here instead of in a
+// block from the context's pool.  Every GPU the library runs on holds its own copy of the array until the process
+// ends; host code never uses the array's name as an address, only what hipGetSymbolAddress returned for the
+// device that was current.
+constexpr size_t kNoAllocScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char g_noalloc_scratch[kNoAllocScratchBytes];
+constexpr int kMaxDevices = 64;
+static char *g_noalloc_scratch_ptr[kMaxDevices] = {};
+
+// The array's address on the current device (looked up once per device).
+static int noalloc_scratch(sgc_ctx *ctx, char **out)
+{
+    int dev = -1;
+    SGC_HIP(ctx, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ctx, SGC_EUNSUPPORTED, "device index %d outside [0, %d)", dev, kMaxDevices);
+    if (!g_noalloc_scratch_ptr[dev]) {
+        void *p = nullptr;
+        SGC_HIP(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(g_noalloc_scratch)));
+        if (!p) return fail(ctx, SGC_EHIP, "hipGetSymbolAddress returned a null address for the scratch array");
+        g_noalloc_scratch_ptr[dev] = static_cast<char *>(p);
+    }
+    *out = g_noalloc_scratch_ptr[dev];
+    return SGC_OK;
+}
+
+// One decode step.  no_alloc: nothing may be allocated, so every table the step reads must already be on the device
+// and current (SGC_ESTATE otherwise) and the partial results go to the static scratch array (SGC_ENOMEM if they do
+// not fit).
+static int decode_step(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int32_t layer, int32_t step,
+                       const void *dev_q, const void *dev_k, const void *dev_v, void *dev_o, float *dev_lse,
+                       void *hip_stream, bool no_alloc)
 {
     if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
     if (!cc || cc->ctx != ctx) return fail(ctx, SGC_EINVAL, "cache is NULL or belongs to another context");
@@ -1183,16 +1212,35 @@ int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int
         return fail(ctx, SGC_EINVAL, "device pointers must be 16-byte aligned");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     int rc;
-    if ((rc = ensure_rope(ctx, pl->max_position + pl->decode_cap, s)) != SGC_OK) return rc;
-    if ((rc = cache_sync(c, s)) != SGC_OK) return rc;
-    if ((rc = refresh_tiles(pl, c, s)) != SGC_OK) return rc;
+    if (no_alloc) {
+        // growing the rotary table, the first copy of the page tables and a refreshed tile list all allocate
+        if (ctx->p.rope_base > 0.0f && pl->max_position + pl->decode_cap > ctx->rope_len)
+            return fail(ctx, SGC_ESTATE, "the rotary table ends at position %d, the step needs %d: set max_position, or run "
+                        "sgc_decode_step_batched once", ctx->rope_len, pl->max_position + pl->decode_cap);
+        if (!c->d_tables || c->dirty || (!pl->tiles.empty() && pl->tiles_generation != c->generation))
+            return fail(ctx, SGC_ESTATE, "clusters were allocated or released since the plan's last launch: the device "
+                        "tables are stale and refreshing them allocates");
+    } else {
+        if ((rc = ensure_rope(ctx, pl->max_position + pl->decode_cap, s)) != SGC_OK) return rc;
+        if ((rc = cache_sync(c, s)) != SGC_OK) return rc;
+        if ((rc = refresh_tiles(pl, c, s)) != SGC_OK) return rc;
+    }
     pl->last_stream = s;
     // scratch for the cached-prefix part of the step, one set per key range: O [S][n_queries][Hq][d] bf16, then
     // LSE [S][Hq][n_queries]
     const int S = std::max(1, pl->dec_splits);
     const size_t o_bytes = ((size_t)pl->n_queries * ctx->p.n_q_heads * ctx->p.head_dim * 2 + 255) / 256 * 256;
     const size_t lse_bytes = ((size_t)ctx->p.n_q_heads * pl->n_queries * sizeof(float) + 255) / 256 * 256;
-    if (!pl->dec_scratch.p && (rc = dev_acquire(ctx, S * (o_bytes + lse_bytes), s, &pl->dec_scratch)) != SGC_OK) return rc;
+    char *scratch = nullptr;
+    if (no_alloc) {
+        if (S * (o_bytes + lse_bytes) > kNoAllocScratchBytes)
+            return fail(ctx, SGC_ENOMEM, "the step's partial results need %zu bytes, the static scratch array holds %zu",
+                        S * (o_bytes + lse_bytes), kNoAllocScratchBytes);
+        if ((rc = noalloc_scratch(ctx, &scratch)) != SGC_OK) return rc;
+    } else {
+        if (!pl->dec_scratch.p && (rc = dev_acquire(ctx, S * (o_bytes + lse_bytes), s, &pl->dec_scratch)) != SGC_OK) return rc;
+        scratch = pl->dec_scratch.p;
+    }
     char *spool = pl->d_spool + (size_t)layer * pl->spool_layer_bytes;
 
     DecodeArgs d{};
@@ -1201,8 +1249,8 @@ int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int
     d.v = dev_v;
     d.o = dev_o;
     d.lse = dev_lse;
-    d.o_cached = pl->dec_scratch.p;
-    d.lse_cached = reinterpret_cast<const float *>(pl->dec_scratch.p + S * o_bytes);
+    d.o_cached = scratch;
+    d.lse_cached = reinterpret_cast<const float *>(scratch + S * o_bytes);
     d.n_splits = S;
     d.split_o_elems = (int64_t)(o_bytes / 2);
     d.split_lse_elems = (int64_t)(lse_bytes / sizeof(float));
@@ -1226,8 +1274,8 @@ int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int
     AttnArgs a;
     fill_common_args(a, ctx, c, layer);
     a.q = dev_q;
-    a.o = pl->dec_scratch.p;
-    a.lse = reinterpret_cast<float *>(pl->dec_scratch.p + S * o_bytes);
+    a.o = scratch;
+    a.lse = reinterpret_cast<float *>(scratch + S * o_bytes);
     a.split_o_bytes = (int64_t)o_bytes;
     a.split_lse_elems = (int64_t)(lse_bytes / sizeof(float));
     a.lse_stride = pl->n_queries;
@@ -1248,6 +1296,20 @@ int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int
     SGC_HIP(ctx, launch_attn_mfma(a, ctx->mfma_variant, s));
     SGC_HIP(ctx, launch_decode_own_keys(d, s));
     return SGC_OK;
+}
+
+int sgc_decode_step_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int32_t layer, int32_t step,
+                            const void *dev_q, const void *dev_k, const void *dev_v, void *dev_o, float *dev_lse,
+                            void *hip_stream)
+{
+    return decode_step(ctx, cc, pl, layer, step, dev_q, dev_k, dev_v, dev_o, dev_lse, hip_stream, false);
+}
+
+int sgc_decode_step_batched_noalloc(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int32_t layer, int32_t step,
+                                    const void *dev_q, const void *dev_k, const void *dev_v, void *dev_o, float *dev_lse,
+                                    void *hip_stream)
+{
+    return decode_step(ctx, cc, pl, layer, step, dev_q, dev_k, dev_v, dev_o, dev_lse, hip_stream, true);
 }
 
 int sgc_timing_enable(sgc_ctx *ctx, int on)

@@ -27,7 +27,7 @@ EXPORTS = [
     "sgc_plan_get_info", "sgc_plan_destroy", "sgc_suffix_prefill_batched", "sgc_cache_export", "sgc_cache_import",
     "sgc_timing_enable", "sgc_timing_last", "sgc_cluster_queries", "sgc_plan_enable_decode", "sgc_decode_step_batched",
     "sgc_union_subgraphs", "sgc_project_qkv_prefix", "sgc_project_qkv_prefix_batched", "sgc_project_qkv_suffix",
-    "sgc_project_out", "sgc_timing_get",
+    "sgc_project_out", "sgc_timing_get", "sgc_decode_step_batched_noalloc",
 ]
 
 
@@ -97,6 +97,7 @@ def lib() -> ctypes.CDLL:
         L.sgc_cache_import.argtypes = [vp, vp, i32, i32, vp, vp, f32p, f32p, vp]
         L.sgc_plan_enable_decode.argtypes = [vp, i32]
         L.sgc_decode_step_batched.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
+        L.sgc_decode_step_batched_noalloc.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
         i64p = ctypes.POINTER(ctypes.c_int64)
         L.sgc_union_subgraphs.argtypes = [vp, i32, i32p, i32, i64p, i32p, i64p, i32p, i64p, i32p, i64p, i32p]
         L.sgc_cluster_queries.argtypes = [vp, i32, i32, f32p, i32, i32, i32p]
@@ -294,6 +295,12 @@ def sgc_plan_enable_decode(ctx, plan, max_new_tokens: int) -> None:
 def sgc_decode_step_batched(ctx, cache, plan, layer: int, step: int, dev_q: int, dev_k: int, dev_v: int, dev_o: int,
                             dev_lse: Optional[int] = None, stream: int = 0) -> None:
     _check(ctx, lib().sgc_decode_step_batched(ctx, cache, plan, layer, step, dev_q, dev_k, dev_v, dev_o, dev_lse, stream))
+
+
+def sgc_decode_step_batched_noalloc(ctx, cache, plan, layer: int, step: int, dev_q: int, dev_k: int, dev_v: int, dev_o: int,
+                                    dev_lse: Optional[int] = None, stream: int = 0) -> None:
+    _check(ctx, lib().sgc_decode_step_batched_noalloc(ctx, cache, plan, layer, step, dev_q, dev_k, dev_v, dev_o, dev_lse,
+                                                      stream))
 
 
 LINKAGES = {"ward": 0, "single": 1, "average": 2, "complete": 3, "centroid": 4}

@@ -30,11 +30,14 @@ def _check_suffix(w, out, queries=None, tol=TOL_BF16, tight=None, lse_tol=None):
     if tight is not None:
         assert st["max_abs"] <= tight
     if out.get("lse") is not None:
-        # LSE carries the bf16 rounding of the rotated Q and K through scores of magnitude |s|:
-        # about |s| * 2^-8; 5e-2 unless the caller calibrated a bound
+        # To first order an LSE error is the weighted mean of the row's score errors, so it is bounded by the largest
+        # of them.  A score is scale * <q, k> on operands rounded to binary16 (relative 2^-11 each):
+        # |ds| <= 2^-10 * scale * |q| |k|, which for unit-variance 128-channel rows (|q| |k| ~ 128, scale 0.088) is
+        # 1.1e-2, plus the fp32 accumulation and exp2/log2 of the kernel (1e-3).  2e-2 unless the caller calibrated a
+        # bound on its own data (workloads with scaled-up channels or queries do)
         lerr = np.abs(out["lse"][:, rows] - lse_ref).max() if len(rows) else 0.0
         _say(f"  lse max_abs {lerr:.3e}")
-        assert lerr <= (lse_tol if lse_tol is not None else 5e-2)
+        assert lerr <= (lse_tol if lse_tol is not None else 2e-2)
     return st
 
 
@@ -358,7 +361,11 @@ def test_fp8_cache_small(kernel):
         do = s.suffix_prefill(*(to_device(x, "bf16") for x in (q, k, v)))
         torch.cuda.synchronize()
         out = {"o": to_host_f32(do), "lse": None}
-    _check_suffix(w, out, tol=TOL_FP8, tight=3e-2)
+    # Against the oracle's own quantised cache the stated 6e-2 is the bar: where the GPU's fp32 rotation puts a key
+    # element on the other side of a code boundary (counted above) a row that gives that key most of its weight moves by
+    # up to p (1 - p) * scale * |q_c| * step * |v - o| ~ 2e-2, which no calibration on the CPU side predicts.  The tight
+    # bound on the attention arithmetic itself is taken where both sides read identical codes (next test).
+    _check_suffix(w, out, tol=TOL_FP8)
 
 
 def test_fp8_imported_oracle_cache_isolates_the_attention():
@@ -380,6 +387,8 @@ def test_fp8_imported_oracle_cache_isolates_the_attention():
     o_ref, _ = orc.suffix_prefill_batched(w.labels, w.cu_seqlens, [kdeq], [vdeq], q, k, v, w.rope_base)
     st = err_stats(o, o_ref)
     _say(f"  fp8 import max_abs {st['max_abs']:.3e}")
+    # identical codes on both sides: what is left is the rounding of the output to bf16 (half an ulp of values up to 2:
+    # 3.9e-3) plus the binary16 query and bf16 weight roundings (about 1e-3 together on unit-variance data)
     assert st["max_abs"] <= 6e-3
 
 

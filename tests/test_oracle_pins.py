@@ -378,6 +378,74 @@ def test_quantise_per_head_scale_and_error_bound():
     assert np.abs(deq[:, 1]).max() == pytest.approx(np.abs(x[:, 1]).max(), rel=1e-6)
 
 
+def _rne_to_f32_exact(q: Fraction) -> Fraction:
+    """q rounded to the nearest fp32 value (ties to even), in exact rational arithmetic (normal range only)."""
+    if q == 0:
+        return q
+    sign, a = (-1 if q < 0 else 1), abs(q)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1
+    assert Fraction(2) ** e <= a < Fraction(2) ** (e + 1) and -126 <= e <= 127
+    ulp = Fraction(2) ** (e - 23)
+    n = a / ulp
+    lo = n.numerator // n.denominator
+    rem = n - lo
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and lo % 2 == 1):
+        lo += 1
+    return sign * lo * ulp
+
+
+def _encode_exact(q: Fraction) -> int:
+    """Nearest e4m3 code of a non-negative rational below 448, ties to the even code, from the definition."""
+    vals = [_e4m3_exact(c) for c in range(0x7F)]
+    lo = max(c for c in range(0x7F) if vals[c] <= q)
+    if lo == 0x7E:
+        return lo
+    dlo, dhi = q - vals[lo], vals[lo + 1] - q
+    return lo if dlo < dhi else lo + 1 if dhi < dlo else (lo if lo % 2 == 0 else lo + 1)
+
+
+def test_quantise_code_decision_is_taken_on_the_fp32_quotient():
+    """The reading of "per-head fp32 scales": the scale is an fp32 number and the quotient x / scale that picks the
+    code is an fp32 quotient (the value is rounded to fp32 first).  Values are placed so that the exact quotient lies
+    just beside a code midpoint while its fp32 rounding lands ON the midpoint, where ties-to-even picks the other
+    neighbour: a quantiser that divides in higher precision gives different codes here.  Expected codes come from
+    exact rational arithmetic."""
+    amax = np.float32(3.0)
+    scale = Fraction(float(np.float32(amax) / np.float32(448.0)))         # fp32 division of two fp32 numbers
+    assert scale == _rne_to_f32_exact(Fraction(3) / 448)
+    crafted, expect, differs = [], [], 0
+    for c in range(8, 0x7E):                                               # normal codes
+        mid = (_e4m3_exact(c) + _e4m3_exact(c + 1)) / 2
+        centre = np.float32(float(mid * scale))
+        x = np.nextafter(centre, np.float32(-1e9), dtype=np.float32)
+        for _ in range(8):                                                 # the few fp32 values around mid * scale
+            q = Fraction(float(x)) / scale
+            q32 = _rne_to_f32_exact(q)
+            if q != mid and q32 == mid and float(x) < float(amax):
+                code32, code_exact = _encode_exact(q32), _encode_exact(q)
+                crafted.append(float(x))
+                expect.append(code32)
+                differs += int(code32 != code_exact)
+            x = np.nextafter(x, np.float32(1e9), dtype=np.float32)
+    assert len(crafted) >= 20 and differs >= 10, (len(crafted), differs)     # the pin discriminates
+    vals = np.array([float(amax)] + crafted + [0.0] * (-(len(crafted) + 1) % 4), dtype=np.float64)
+    x = vals.reshape(-1, 1, 4)
+    codes, sc, deq = orc.quantise_e4m3(x)
+    assert Fraction(float(sc[0])) == scale
+    got = codes.reshape(-1)[1:1 + len(crafted)].tolist()
+    assert got == expect
+    assert codes.reshape(-1)[0] == 0x7E                                    # the largest value maps to the largest code
+    # and the dequantised value is code value times the fp32 scale
+    for v, c in zip(deq.reshape(-1)[1:1 + len(crafted)], expect):
+        assert Fraction(float(v)) == _rne_to_f64(_e4m3_exact(c) * scale)
+
+
+def _rne_to_f64(q: Fraction) -> Fraction:
+    return Fraction(float(q))          # Python rounds a Fraction to the nearest double, ties to even
+
+
 # ------------------------------------------------------------------------------------------------
 # cluster bookkeeping
 # ------------------------------------------------------------------------------------------------

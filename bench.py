@@ -20,7 +20,7 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}      # MI355X dense MFMA bf16; fp32 vector
+PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0, "f32": 157.3}      # MI355X dense MFMA bf16 (= fp16) and fp8; fp32 vector
 HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the suffix attention kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
@@ -231,7 +231,7 @@ def layer_measurement(s, w, layer, d_model, reps, stream):
                          "unit": "TFLOP/s", "frac": gemm["tflops"] / peak, "traffic": None}}
 
 
-def other_config(index: int, steps: int, warmup: int, threads: int):
+def other_config(index: int, steps: int, warmup: int, threads: int, kernel=None):
     """One of the other benchmark configurations: its batched suffix prefill launched `steps` times (caches filled
     and the plan uploaded beforehand; kernel durations from the library's HIP events on the launch stream), the
     kernel's roofline figures, and the error against the oracle on two of its queries."""
@@ -242,7 +242,9 @@ def other_config(index: int, steps: int, warmup: int, threads: int):
     layer = 0
     q, k, v = w.suffix_qkv(layer, threads=threads)
     clusters = list(range(w.n_clusters))
-    with Session(w) as s:
+    if kernel is None:        # an fp8 cache over long prompts: first product on the e4m3 codes
+        kernel = sgc.SGC_KERNEL_MFMA_FP8 if w.kv_dtype == "fp8_e4m3" else sgc.SGC_KERNEL_AUTO
+    with Session(w, kernel=kernel) as s:
         stream = s.stream
         for c in clusters:
             sgc.sgc_cache_alloc_cluster(s.ctx, s.cache, c, int(w.prefix_len[c]))
@@ -278,7 +280,17 @@ def other_config(index: int, steps: int, warmup: int, threads: int):
     ingest_ms = float(np.mean([a for a, _ in kernel_ms]))
     mfma = w.io_dtype == "bf16" and w.head_dim == 128
     peak = PEAK_TFLOPS["bf16" if mfma else "f32"]
+    path = "16-bit matrix-core products (binary16 QK^T, bf16 PV)" if mfma else "fp32 vector arithmetic"
     achieved = w.flops() / (attn_ms * 1e-3) / 1e12
+    extra = {}
+    if kernel == sgc.SGC_KERNEL_MFMA_FP8:
+        # half the flops (QK^T) run at the fp8 matrix-core rate, half (PV) at the bf16 rate
+        peak = 2.0 / (1.0 / PEAK_TFLOPS["fp8"] + 1.0 / PEAK_TFLOPS["bf16"])
+        path = "QK^T on the cache's e4m3 codes (fp8 matrix-core rate, query rows quantised to e4m3), PV on bf16"
+        extra = {"frac_of_bf16_peak": achieved / PEAK_TFLOPS["bf16"], "frac_of_fp8_peak": achieved / PEAK_TFLOPS["fp8"],
+                 "peak_is": "harmonic mean of the fp8 and bf16 dense peaks (half the flops at each rate)"}
+    elif w.kv_dtype == "fp8_e4m3":
+        path = "e4m3 codes widened to 16-bit on their way into LDS, 16-bit matrix-core products"
     prof = PROFILED_HBM_BYTES_PER_LAUNCH.get(w.name)
     return {"workload": f"configs[{index}] {w.name}: Hq {w.n_q_heads} Hkv {w.n_kv_heads} d {w.head_dim}, {w.n_clusters} clusters, "
                         f"prefix {int(w.prefix_len.min())}-{int(w.prefix_len.max())}, {w.n_queries} queries, "
@@ -289,11 +301,11 @@ def other_config(index: int, steps: int, warmup: int, threads: int):
             "suffix_ingest_kernel_ms": ingest_ms, "suffix_call_ms": attn_ms + ingest_ms,
             "us_per_query": (attn_ms + ingest_ms) * 1e3 / w.n_queries,
             "roofline": {"kernel": "attn_mfma_kernel (batched suffix prefill)" if mfma else "attn_generic_kernel (fp32 arithmetic)",
-                         "bound": "mfma" if mfma else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                         "path": path, "bound": "mfma" if mfma else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                          "frac": achieved / peak, "frac_of_call": w.flops() / ((attn_ms + ingest_ms) * 1e-3) / 1e12 / peak,
                          "traffic": prof[0] if prof else None, "traffic_source": prof[1] if prof else None,
                          "algorithmic_bytes": w.algorithmic_bytes(),
-                         "hbm_gbs_algorithmic": w.algorithmic_bytes() / (attn_ms * 1e-3) / 1e9},
+                         "hbm_gbs_algorithmic": w.algorithmic_bytes() / (attn_ms * 1e-3) / 1e9, **extra},
             "error": error_against_oracle(o_rows, o_ref, w.kv_dtype, f"queries {picks}: all heads, all rows")}
 
 
@@ -471,6 +483,11 @@ def main() -> int:
         del o_host, dq, dk, dv, do, dpk, dpv, dpq, dpo
         torch.cuda.empty_cache()
         out["configs"] = [other_config(int(i), args.other_steps, 2, gen_threads) for i in others.split(",") if i.strip()]
+        if "4" in [i.strip() for i in others.split(",")]:
+            # the same configuration with the first product on 16-bit operands: what the fp8 first product buys
+            alt = other_config(4, args.other_steps, 2, gen_threads, kernel=sgc.SGC_KERNEL_MFMA)
+            alt["workload"] += " [comparison: 16-bit first product]"
+            out["configs"].append(alt)
     print(json.dumps(out), flush=True)
     return 0
 

@@ -63,7 +63,14 @@ typedef enum { SGC_F32 = 0, SGC_BF16 = 1, SGC_FP8_E4M3 = 2 } sgc_dtype;
 typedef enum {
     SGC_KERNEL_AUTO = 0,    /* MFMA when it covers the shape, else generic */
     SGC_KERNEL_GENERIC = 1, /* fp32-arithmetic kernel, any supported shape/dtype */
-    SGC_KERNEL_MFMA = 2     /* bf16 MFMA kernel: io bf16, kv bf16|fp8, head_dim 128 */
+    SGC_KERNEL_MFMA = 2,    /* matrix-core kernel: io bf16, kv bf16|fp8, head_dim 128; products on 16-bit operands
+                               (an fp8 cache is widened exactly on its way into LDS) */
+    SGC_KERNEL_MFMA_FP8 = 3 /* the same kernel with the FIRST product of the suffix prefill and of decode steps on the
+                               e4m3 codes of an fp8 cache (fp8 matrix-core rate, twice the 16-bit one): each rotated,
+                               scaled query row is rounded to e4m3 with a power-of-two scale of its own (3 significant
+                               bits: a score moves by about 0.03 on unit-variance rows, well inside the 6e-2 the fp8
+                               cache is held to on long prompts; peaked rows over short prompts are better served by
+                               SGC_KERNEL_MFMA).  Weights, values and the second product stay bf16.  kv fp8 only. */
 } sgc_kernel_kind;
 
 /* Plain data, filled by the caller.  struct_size = sizeof(sgc_attn_params). */

@@ -39,12 +39,16 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 constexpr int D = 128;                       // head dim
 constexpr int BN = 64;                       // keys per LDS tile (4 pages)
 constexpr int PART_BYTES = kPageTokens * D * 2;   // one page's K (or V) of one head as bf16: 4 KiB
 constexpr int HALF_BYTES = 4 * PART_BYTES;   // the K (or V) of one 64-key tile: 16 KiB
 constexpr int LDS_TILE_BYTES = 4 * HALF_BYTES;   // two K buffers, then two V buffers
+constexpr int K8_PART_BYTES = kPageTokens * D;    // one page's K of one head as e4m3 codes: 2 KiB
+constexpr int K8_PART_STRIDE = K8_PART_BYTES + 128;   // in LDS consecutive pages sit 2 KiB + 128 bytes apart: the two pages
+                                                      // a 32-key operand read touches then fall into different banks
 constexpr int MAX_TILE_QUERIES = 256;        // queries a row tile can touch (one row each at least)
 constexpr float kKeepBelow = 1073741824.0f;  // 2^30: a tile's weights may sum to this against a stale maximum
 
@@ -173,9 +177,14 @@ __device__ inline void append_new_tokens(const AttnArgs &a, int blk)
     }
 }
 
-template <int NW, int MI, bool KV_FP8, int MODE>
+// QK8 (fp8 cache only): the first product runs on the cache's e4m3 codes as they are (v_mfma_scale_f32_32x32x64_f8f6f4,
+// twice the bf16 rate): the rotated, scaled query row is quantised to e4m3 with a power-of-two scale of its own, which
+// the instruction applies to the row's products in hardware, so scores come out in the same units as on the other
+// paths.  K codes then go to LDS as they are (2 KiB per page part); V is still widened to bf16 for the second product.
+template <int NW, int MI, bool KV_FP8, int MODE, bool QK8>
 __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mfma_kernel(const AttnArgs a)
 {
+    static_assert(!QK8 || (KV_FP8 && MI == 1 && NW == 4), "the fp8 first product needs an fp8 cache");
     if (MODE == MODE_SUFFIX && (int)blockIdx.x >= a.n_tiles) {
         append_new_tokens(a, (int)blockIdx.x - a.n_tiles);
         return;
@@ -261,14 +270,23 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             copy_4k_to_lds(base + ((uint64_t)off256 << 8) + v_off + lane16, vdst + my_page * PART_BYTES);
         }
     };
+    char *kdst_codes = nullptr;      // QK8: where the next K tile's codes go
     auto issue_load_fp8 = [&](uint32_t poff_k, bool want_k, uint32_t poff_v, bool want_v) __attribute__((always_inline)) {
         staged_k = moves_k && want_k;
         staged_v = moves_v && want_v;
         if (staged_k) {
             const uint32_t off256 = __builtin_amdgcn_readlane(poff_k, my_page);
             const char *src = cache_base + ((uint64_t)off256 << 8) + lane16;
-            stage[0] = *reinterpret_cast<const uint4 *>(src);
-            stage[1] = *reinterpret_cast<const uint4 *>(src + 1024);
+            if (QK8) {      // the codes as they are, straight into LDS (kdst_codes: set by the caller)
+                const auto *g = (const __attribute__((address_space(1))) void *)src;
+                auto *l = (__attribute__((address_space(3))) void *)(kdst_codes + my_page * K8_PART_STRIDE);
+                __builtin_amdgcn_global_load_lds(g, l, 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(g, l, 16, 1024, 0);
+                staged_k = false;
+            } else {
+                stage[0] = *reinterpret_cast<const uint4 *>(src);
+                stage[1] = *reinterpret_cast<const uint4 *>(src + 1024);
+            }
         }
         if (staged_v) {
             const uint32_t off256 = __builtin_amdgcn_readlane(poff_v, my_page);
@@ -304,9 +322,10 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     };
     // K of one cached tile and / or V of another: kdst / vdst null = none
     auto fetch_cache = [&](uint32_t ids_k, char *kdst, uint32_t ids_v, char *vdst) __attribute__((always_inline)) {
-        if (KV_FP8)
+        if (KV_FP8) {
+            kdst_codes = kdst;
             issue_load_fp8(ids_k * cache_page_256, kdst != nullptr, ids_v * cache_page_256, vdst != nullptr);
-        else
+        } else
             issue_copy_bf16(ids_k * cache_page_256, kdst, ids_v * cache_page_256, vdst, cache_base, cache_v_off);
     };
     auto land_cache = [&](char *kdst, char *vdst) __attribute__((always_inline)) {   // make what was fetched visible in LDS (before the barrier)
@@ -398,6 +417,8 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     // All loads of the phase (Q row halves, then the rotation table entries) are issued before any of them is
     // used, so the phase costs one memory round trip and not one per channel group.
     f16x8 qf[MI][8];
+    i32x8 q8[2];            // QK8: the row as e4m3 codes, operand t = channels 64 t .. 64 t + 63 in the order kc_block reads keys
+    int qscale = 127;       // QK8: the row's scale as a biased power-of-two exponent (what the scaled product takes)
     {
         uint4 qlo[MI][4], qhi[MI][4];
         float4 cs[MI][4][4];            // (cos, sin) of two channels per entry
@@ -475,6 +496,34 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
                 }
             }
         }
+        if constexpr (QK8) {
+            // The row as e4m3 codes with one power-of-two scale: largest magnitude of the row (both lanes of the pair)
+            // = m 2^x with m in [0.5, 1); values times 2^(8 - x) lie below 256 (the format reaches 448), rounded to
+            // nearest even by the conversion instruction.
+            float amax = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 8; ++kb)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf((float)qf[0][kb][i]));
+            amax = half_max(amax);
+            int e = __builtin_amdgcn_frexp_expf(amax) - 8;
+            e = amax > 0.f ? max(-120, min(e, 120)) : 0;
+            qscale = 127 + e;
+            const float down = __uint_as_float((uint32_t)(127 - e) << 23);      // 2^-e
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int pc = 0; pc < 4; ++pc) {
+                    const f16x8 v = qf[0][4 * t + pc];
+                    int w0 = 0, w1 = 0;
+                    w0 = __builtin_amdgcn_cvt_pk_fp8_f32((float)v[0] * down, (float)v[1] * down, w0, false);
+                    w0 = __builtin_amdgcn_cvt_pk_fp8_f32((float)v[2] * down, (float)v[3] * down, w0, true);
+                    w1 = __builtin_amdgcn_cvt_pk_fp8_f32((float)v[4] * down, (float)v[5] * down, w1, false);
+                    w1 = __builtin_amdgcn_cvt_pk_fp8_f32((float)v[6] * down, (float)v[7] * down, w1, true);
+                    q8[t][2 * pc] = w0;
+                    q8[t][2 * pc + 1] = w1;
+                }
+        }
     }
 
     // ---- the queries this tile touches (suffix mode): lengths and first pages into LDS ----
@@ -538,6 +587,22 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     auto v_block = [&](const char *vbuf, int nb, int i) __attribute__((always_inline)) {
         return *reinterpret_cast<const bf16x8 *>(vbuf + lane_voff + (nb * 8 + i) * 1024);
     };
+    // Cached keys.  QK8: the 64-channel operand of the fp8 product is eight 8-byte pieces (lane (m, hh): key m, channels
+    // 64 t + 16 p + 8 hh .. + 7 for p = 0..3; the contraction does not care which of its 64 slots a channel takes as
+    // long as the query operand uses the same ones); window slot i < 4 holds pieces 2 (i % 2), 2 (i % 2) + 1 of operand
+    // t = i / 2, slots 4..7 are not used by this product.
+    const int lane_k8off = (n >> 4) * K8_PART_STRIDE + (h * kPageTokens + (n & 15)) * 8;
+    auto kc_block = [&](const char *kbuf, int nb, int i) __attribute__((always_inline)) -> bf16x8 {
+        if constexpr (QK8) {
+            if (i >= 4) return frag[i];
+            const char *p = kbuf + lane_k8off + nb * 2 * K8_PART_STRIDE + (4 * (i >> 1) + 2 * (i & 1)) * 256;
+            const uint2 a0 = *reinterpret_cast<const uint2 *>(p), a1 = *reinterpret_cast<const uint2 *>(p + 256);
+            const u32x4 w = {a0.x, a0.y, a1.x, a1.y};
+            return __builtin_bit_cast(bf16x8, w);
+        } else {
+            return k_block(kbuf, nb, i);
+        }
+    };
     auto no_refill = [&](int) __attribute__((always_inline)) {};
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     // S^T = K Q^T - m_ref for the half whose K blocks the window holds; slot kb is refilled by refill(kb).
@@ -548,6 +613,26 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             for (int mi = 0; mi < MI; ++mi)
                 s[mi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, frag[kb]), qf[mi][kb], kb == 0 ? (FOLD ? neg_ref[mi] : zero16) : s[mi], 0, 0, 0);
             refill(kb);
+        }
+    };
+    // The same against cached keys.  QK8: two 64-channel products on the codes; the query row's own scale (a power of two)
+    // is applied by the instruction, so the scores leave it in the usual units with -m_ref already taken off.
+    auto qk_half_cache = [&](f32x16 (&s)[MI], auto refill) __attribute__((always_inline)) {
+        if constexpr (QK8) {
+            refill(4);
+            refill(5);
+            refill(6);
+            refill(7);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const u32x4 lo = __builtin_bit_cast(u32x4, frag[2 * t]), hi = __builtin_bit_cast(u32x4, frag[2 * t + 1]);
+                const i32x8 kop = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+                s[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kop, q8[t], t == 0 ? neg_ref[0] : s[0], 0, 0, 0, 127, 0, qscale);
+                refill(2 * t);
+                refill(2 * t + 1);
+            }
+        } else {
+            qk_half(s, refill);
         }
     };
     // O^T += V^T P^T for the half whose V blocks the window holds (slot i = page i / 4, channel group i % 4).
@@ -667,8 +752,8 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     if (n_my > 0) {
         const char *k0 = kbuf_of(0);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) frag[i] = k_block(k0, 0, i);
-        qk_half(s0, [&](int i) __attribute__((always_inline)) { frag[i] = k_block(k0, 1, i); });
+        for (int i = 0; i < 8; ++i) frag[i] = kc_block(k0, 0, i);
+        qk_half_cache(s0, [&](int i) __attribute__((always_inline)) { frag[i] = kc_block(k0, 1, i); });
     }
     __syncthreads();       // every wavefront has read K of tile 0 before step 0 overwrites it
     // ---- the stream of this row tile's own suffix key tiles ------------------------------------------------
@@ -767,22 +852,22 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
             };
             // half 0
             if (careful) raise_reference(s0, 0, masked, keep);
-            qk_half(s1, [&](int i) __attribute__((always_inline)) {
+            qk_half_cache(s1, [&](int i) __attribute__((always_inline)) {
                 frag[i] = v_block(vc, 0, i);
                 if (spread) copy_quarter(first, i);
             });
             weights(s0);
             if (weights_overflow()) redo(s0, s1, 0);
             pv_half([&](int i) __attribute__((always_inline)) {
-                frag[i] = k_block(kn, 0, i);
+                frag[i] = kc_block(kn, 0, i);
                 if (spread && NW == 4) copy_quarter(second, i);
             });
             // half 1
             if (careful) raise_reference(s1, 1, masked, keep);
-            qk_half(s0, [&](int i) __attribute__((always_inline)) { frag[i] = v_block(vc, 1, i); });
+            qk_half_cache(s0, [&](int i) __attribute__((always_inline)) { frag[i] = v_block(vc, 1, i); });
             weights(s1);
             if (weights_overflow()) redo(s1, s0, 1);
-            pv_half([&](int i) __attribute__((always_inline)) { frag[i] = k_block(kn, 1, i); });
+            pv_half([&](int i) __attribute__((always_inline)) { frag[i] = kc_block(kn, 1, i); });
             fresh = false;
         }
         land_cache(kd, vd);
@@ -922,11 +1007,11 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
 
 constexpr size_t kDynLds = LDS_TILE_BYTES + MAX_TILE_QUERIES * sizeof(int2);
 
-template <int NW, int MI, bool FP8, int MODE>
+template <int NW, int MI, bool FP8, int MODE, bool QK8>
 hipError_t launch_one(const AttnArgs &a, int blocks, hipStream_t s)
 {
     static bool configured = false;     // raise the dynamic LDS limit once per instantiation
-    auto kern = attn_mfma_kernel<NW, MI, FP8, MODE>;
+    auto kern = attn_mfma_kernel<NW, MI, FP8, MODE, QK8>;
     size_t lds = kDynLds;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -937,45 +1022,27 @@ hipError_t launch_one(const AttnArgs &a, int blocks, hipStream_t s)
     return hipGetLastError();
 }
 
-template <int NW, int MI>
-hipError_t launch_variant(const AttnArgs &a, hipStream_t s)
+}  // namespace
+
+// One kernel shape is built: 4 wavefronts x 32 rows, two workgroups per CU.  (8 wavefronts x 32 rows run in lock-step
+// through the step barrier and lose the overlap two independent workgroups have; 64 rows per wavefront need more than
+// 256 vector registers.  Both were measured slower and are not compiled.)
+int mfma_tile_rows() { return 128; }
+
+hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t s)
 {
+    constexpr int NW = 4, MI = 1;
     const bool fp8 = a.pool.kv_dtype == SGC_FP8_E4M3;
     if (a.n_tiles <= 0 && a.n_append <= 0) return hipSuccess;
-    if (a.mode == MODE_SUFFIX)
-    {
+    if (a.mode == MODE_SUFFIX) {
         // a decode step's launch carries, behind its tiles, the blocks that append the step's new tokens
         const int per_block = NW * 64 / 8;
         const int blocks = a.n_tiles + (a.n_append * a.n_kv_heads + per_block - 1) / per_block;
-        return fp8 ? launch_one<NW, MI, true, MODE_SUFFIX>(a, blocks, s) : launch_one<NW, MI, false, MODE_SUFFIX>(a, blocks, s);
+        if (fp8 && a.fp8_first_product) return launch_one<NW, MI, true, MODE_SUFFIX, true>(a, blocks, s);
+        return fp8 ? launch_one<NW, MI, true, MODE_SUFFIX, false>(a, blocks, s) : launch_one<NW, MI, false, MODE_SUFFIX, false>(a, blocks, s);
     }
-    return fp8 ? launch_one<NW, MI, true, MODE_PREFIX>(a, a.n_tiles, s) : launch_one<NW, MI, false, MODE_PREFIX>(a, a.n_tiles, s);
-}
-
-}  // namespace
-
-
-// variant 0: 8 waves x 32 rows (256-row tiles, one workgroup per CU);
-//         1: 4 waves x 32 rows (128-row tiles, two workgroups per CU);
-//         2: 4 waves x 64 rows (256-row tiles, one workgroup per CU)
-int mfma_tile_rows(int variant)
-{
-    switch (variant) {
-        case 0: return 256;
-        case 1: return 128;
-        case 2: return 256;
-        default: return 0;
-    }
-}
-
-hipError_t launch_attn_mfma(const AttnArgs &a, int variant, hipStream_t s)
-{
-    switch (variant) {
-        case 0: return launch_variant<8, 1>(a, s);
-        case 1: return launch_variant<4, 1>(a, s);
-        case 2: return launch_variant<4, 2>(a, s);
-        default: return hipErrorInvalidValue;
-    }
+    // the prompt's own causal attention always takes the 16-bit first product
+    return fp8 ? launch_one<NW, MI, true, MODE_PREFIX, false>(a, a.n_tiles, s) : launch_one<NW, MI, false, MODE_PREFIX, false>(a, a.n_tiles, s);
 }
 
 }  // namespace sgc

@@ -77,10 +77,12 @@ int check_params(const sgc_attn_params *p, sgc_ctx *ctx)
     if (!(p->softmax_scale >= 0.0f) || !std::isfinite(p->softmax_scale))
         return fail(ctx, SGC_EINVAL, "softmax_scale must be finite and >= 0");
     if (p->max_position < 0) return fail(ctx, SGC_EINVAL, "max_position < 0");
-    if (p->kernel < SGC_KERNEL_AUTO || p->kernel > SGC_KERNEL_MFMA)
+    if (p->kernel < SGC_KERNEL_AUTO || p->kernel > SGC_KERNEL_MFMA_FP8)
         return fail(ctx, SGC_EINVAL, "kernel %d unknown", p->kernel);
-    if (p->kernel == SGC_KERNEL_MFMA && !mfma_covers(*p))
+    if ((p->kernel == SGC_KERNEL_MFMA || p->kernel == SGC_KERNEL_MFMA_FP8) && !mfma_covers(*p))
         return fail(ctx, SGC_EUNSUPPORTED, "MFMA kernel needs io bf16, kv bf16|fp8, head_dim 128");
+    if (p->kernel == SGC_KERNEL_MFMA_FP8 && p->kv_dtype != SGC_FP8_E4M3)
+        return fail(ctx, SGC_EUNSUPPORTED, "the fp8 first product needs an fp8 cache");
     return SGC_OK;
 }
 
@@ -252,6 +254,7 @@ void fill_common_args(AttnArgs &a, sgc_ctx *ctx, const sgc_cache *c, int32_t lay
     a.head_dim = ctx->p.head_dim;
     a.io_dtype = ctx->p.io_dtype;
     a.scale_log2e = ctx->scale * 1.4426950408889634f;
+    a.fp8_first_product = ctx->fp8_first_product ? 1 : 0;
 }
 
 // Workgroup b of a launch runs on XCD b % 8, and each XCD has an L2 of its own: units of work that read the same
@@ -513,9 +516,10 @@ int sgc_ctx_create(const sgc_attn_params *params, sgc_ctx **out)
     if (!ctx) return fail(nullptr, SGC_ENOMEM, "host allocation failed");
     ctx->p = *params;
     ctx->scale = params->softmax_scale > 0.0f ? params->softmax_scale : 1.0f / sqrtf((float)params->head_dim);
-    ctx->use_mfma = params->kernel == SGC_KERNEL_MFMA || (params->kernel == SGC_KERNEL_AUTO && mfma_covers(*params));
-    ctx->mfma_variant = 1;      // 4 wavefronts x 32 rows, two workgroups per CU: fastest measured
-    ctx->tile_rows = ctx->use_mfma ? mfma_tile_rows(ctx->mfma_variant) : 0;
+    ctx->use_mfma = params->kernel == SGC_KERNEL_MFMA || params->kernel == SGC_KERNEL_MFMA_FP8 ||
+                    (params->kernel == SGC_KERNEL_AUTO && mfma_covers(*params));
+    ctx->fp8_first_product = params->kernel == SGC_KERNEL_MFMA_FP8;
+    ctx->tile_rows = ctx->use_mfma ? mfma_tile_rows() : 0;
     *out = ctx;
     return SGC_OK;
 }
@@ -806,7 +810,7 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
             a.jobs = d_jobs;
             a.tiles = d_tiles;
             a.n_tiles = (int32_t)n_tiles;
-            e = launch_attn_mfma(a, ctx->mfma_variant, s);
+            e = launch_attn_mfma(a, s);
         } else {
             for (const PrefixJob &j : jobs) {      // the generic kernel works on one cluster per launch
                 if (!j.q) continue;
@@ -1131,7 +1135,7 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
     if (ctx->use_mfma && !skip_ingest) SGC_HIP(ctx, launch_suffix_ingest(a, pl->d_spage_sq, (int)pl->spage_sq.size(), s));
     if (ctx->timing) SGC_HIP(ctx, hipEventRecord(tev[1], s));
     if (ctx->use_mfma) {
-        SGC_HIP(ctx, launch_attn_mfma(a, ctx->mfma_variant, s));
+        SGC_HIP(ctx, launch_attn_mfma(a, s));
     } else {
         SGC_HIP(ctx, launch_attn_generic(a, pl->total_tokens * ctx->p.n_q_heads, s));
     }
@@ -1293,7 +1297,7 @@ static int decode_step(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int32_t 
     a.sq_cluster = pl->d_sq_cluster;
     a.sq_query = pl->d_sq_query;
     a.n_append = n_sq;
-    SGC_HIP(ctx, launch_attn_mfma(a, ctx->mfma_variant, s));
+    SGC_HIP(ctx, launch_attn_mfma(a, s));
     SGC_HIP(ctx, launch_decode_own_keys(d, s));
     return SGC_OK;
 }

@@ -240,6 +240,8 @@ struct AttnArgs {
     // new tokens [n_queries][Hkv][d]; sq_query: original index of the sorted query) to the suffix pages
     const int32_t *sq_query;
     int32_t n_append;
+    // fp8 cache: run the first product on the e4m3 codes, with the query quantised per row (suffix mode)
+    int32_t fp8_first_product;
 };
 
 }  // namespace sgc
@@ -255,7 +257,7 @@ struct sgc_ctx {
     sgc_attn_params p;
     float scale;
     bool use_mfma;
-    int mfma_variant;      // kernel shape choice, see sgc_attn_mfma.hip
+    bool fp8_first_product; // SGC_KERNEL_MFMA_FP8: QK^T on the e4m3 codes of an fp8 cache (suffix prefill and decode)
     int tile_rows;         // rows per workgroup of the chosen attention kernel
     std::string err;
     float2 *d_rope = nullptr;
@@ -382,8 +384,8 @@ hipError_t launch_proj_generic(const void *a, const void *w, int64_t M, int N, i
                                int n1, void *c2, hipStream_t s);
 hipError_t launch_zero_last_pages(char *spool, const int32_t *d_sq_len, const int32_t *d_sq_page0, int n_sq, int64_t page_bytes,
                                   hipStream_t s);
-// Rows per workgroup of MFMA kernel variant `variant`, or 0 if the variant does not exist.
-int mfma_tile_rows(int variant);
-hipError_t launch_attn_mfma(const AttnArgs &a, int variant, hipStream_t s);
+// Rows per workgroup of the MFMA attention kernel.
+int mfma_tile_rows();
+hipError_t launch_attn_mfma(const AttnArgs &a, hipStream_t s);
 
 }  // namespace sgc

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libsgc.so")
 
 SGC_OK, SGC_EINVAL, SGC_ENOMEM, SGC_ESHAPE, SGC_EUNSUPPORTED, SGC_EHIP, SGC_ESTATE = 0, -1, -2, -3, -4, -5, -6
 SGC_F32, SGC_BF16, SGC_FP8_E4M3 = 0, 1, 2
-SGC_KERNEL_AUTO, SGC_KERNEL_GENERIC, SGC_KERNEL_MFMA = 0, 1, 2
+SGC_KERNEL_AUTO, SGC_KERNEL_GENERIC, SGC_KERNEL_MFMA, SGC_KERNEL_MFMA_FP8 = 0, 1, 2, 3
 DTYPES = {"f32": SGC_F32, "bf16": SGC_BF16, "fp8_e4m3": SGC_FP8_E4M3}
 
 # every symbol include/sgc.h declares

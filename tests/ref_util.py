@@ -82,6 +82,41 @@ def bf16_floor_arrays(pk, pv, q, k, v, rope_base: float, want_lse: bool = False)
     return o_floor
 
 
+def round_to_e4m3_pow2_rows(x: np.ndarray) -> np.ndarray:
+    """Rows (last axis) rounded to e4m3 under a power-of-two scale of their own that puts the row's largest magnitude
+    in [128, 256): nearest, ties to even, 3 fraction bits (numpy; the magnitudes stay far from the format's ends)."""
+    x = np.asarray(x, dtype=np.float64)
+    amax = np.abs(x).max(axis=-1, keepdims=True)
+    _, e = np.frexp(np.where(amax > 0, amax, 1.0))
+    y = x * np.exp2(8.0 - e)
+    m, ex = np.frexp(y)
+    step = np.maximum(np.exp2(ex - 4.0), 2.0 ** -9)          # 4 significant bits; fixed spacing below 2^-6
+    return np.round(y / step) * step * np.exp2(e - 8.0)
+
+
+def fp8_query_floor(cache_k, cache_v, q, k, v, rope_base: float) -> float:
+    """max |o - o_exact| of one query's suffix prefill over an (already rotated, dequantised) cache when the rotated,
+    scaled query rows are rounded to e4m3 as the fp8 first product does against cached keys (dense numpy, fp64
+    otherwise; the query's own keys see the unrounded query).  A measure of what that rounding costs, for tolerances."""
+    P, S = cache_k.shape[0], q.shape[0]
+    d = q.shape[-1]
+    g = q.shape[1] // k.shape[1]
+    qr = orc.rope_numpy(q, P + np.arange(S), rope_base)
+    kr = np.concatenate([cache_k, orc.rope_numpy(k, P + np.arange(S), rope_base)])
+    vv = np.concatenate([cache_v, v]).astype(np.float64)
+    mask = np.arange(P + S)[None, :] <= (P + np.arange(S))[:, None]
+    q8 = round_to_e4m3_pow2_rows(qr)
+
+    def attend(q_cache):
+        kk = np.repeat(kr, g, axis=1)
+        s = np.concatenate([np.einsum("ihc,jhc->hij", q_cache, kk[:P]), np.einsum("ihc,jhc->hij", qr, kk[P:])], axis=-1) / np.sqrt(d)
+        s = np.where(mask[None], s, -np.inf)
+        e = np.exp(s - s.max(axis=-1, keepdims=True))
+        return np.einsum("hij,jhc->ihc", e / e.sum(axis=-1, keepdims=True), np.repeat(vv, g, axis=1))
+
+    return float(np.abs(attend(q8) - attend(qr)).max())
+
+
 def bf16_rounding_floor(w: Workload, n: int, layer: int = 0, want_lse: bool = False):
     """bf16_floor_arrays for query n of a workload."""
     pk, pv = w.prefix_kv(int(w.labels[n]), layer)

@@ -35,9 +35,9 @@ def _oracle_decode(w, layer, n_steps, caches):
     return o, lse
 
 
-def _run_decode(w, n_steps, layers=(0,), cap=None):
+def _run_decode(w, n_steps, layers=(0,), cap=None, kernel=sgc.SGC_KERNEL_MFMA):
     out = {}
-    with Session(w, kernel=sgc.SGC_KERNEL_MFMA) as s:
+    with Session(w, kernel=kernel) as s:
         for c in range(w.n_clusters):
             s.alloc_cluster(c)
         for layer in layers:
@@ -61,15 +61,24 @@ def _run_decode(w, n_steps, layers=(0,), cap=None):
     return out
 
 
-@pytest.mark.parametrize("kv", ["bf16", "fp8_e4m3"])
+@pytest.mark.parametrize("kv", ["bf16", "fp8_e4m3", "fp8_e4m3 with the first product on the codes"])
 def test_decode_steps_match_oracle_small(kv):
+    kernel = sgc.SGC_KERNEL_MFMA_FP8 if "codes" in kv else sgc.SGC_KERNEL_MFMA
+    kv = kv.split()[0]
     # suffix lengths around the page size so that appended tokens cross page boundaries; one query without question tokens;
     # one cluster without any cached keys
-    w = workloads.custom("decode_small", n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=500000.0, io_dtype="bf16",
-                         kv_dtype=kv, prefix_len=[200, 71, 0], labels=[0, 1, 0, 2, 1, 0, 2, 0, 1, 0],
-                         suffix_len=[14, 16, 1, 30, 47, 0, 15, 64, 33, 5], seed=31, k_outlier_scale=8.0)
+    if kernel == sgc.SGC_KERNEL_MFMA_FP8:
+        # the first product on the codes rounds the query to e4m3: meant for long prompts, where a row's weight is spread
+        # over many keys (over prompts of a few hundred tokens the same rounding moves outputs by up to 1e-1)
+        w = workloads.custom("decode_long_fp8", n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=500000.0, io_dtype="bf16",
+                             kv_dtype=kv, prefix_len=[6000, 2500], labels=[0, 1, 0, 1, 1, 0], suffix_len=[14, 16, 1, 30, 0, 64],
+                             seed=33)
+    else:
+        w = workloads.custom("decode_small", n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=500000.0, io_dtype="bf16",
+                             kv_dtype=kv, prefix_len=[200, 71, 0], labels=[0, 1, 0, 2, 1, 0, 2, 0, 1, 0],
+                             suffix_len=[14, 16, 1, 30, 47, 0, 15, 64, 33, 5], seed=31, k_outlier_scale=8.0)
     n_steps = 6
-    got = _run_decode(w, n_steps)[0]
+    got = _run_decode(w, n_steps, kernel=kernel)[0]
     o_ref, lse_ref = _oracle_decode(w, 0, n_steps, oracle_caches(w, 0))
     err = np.abs(got[0] - o_ref).max()
     lerr = np.abs(got[1] - lse_ref).max()
@@ -124,7 +133,7 @@ def test_decode_random_shapes_against_oracle(seed):
     w = workloads.custom(f"decode_random_{seed}", n_q_heads=Hkv * g, n_kv_heads=Hkv, head_dim=128, rope_base=500000.0,
                          io_dtype="bf16", kv_dtype=kv, prefix_len=prefix, cluster_sizes=sizes, suffix_len=slen, seed=seed)
     n_steps = int(rng.integers(2, 6))
-    got = _run_decode(w, n_steps)[0]
+    got = _run_decode(w, n_steps, kernel=kernel)[0]
     o_ref, lse_ref = _oracle_decode(w, 0, n_steps, oracle_caches(w, 0))
     err = np.abs(got[0] - o_ref).max()
     lerr = np.abs(got[1] - lse_ref).max()

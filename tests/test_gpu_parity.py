@@ -10,7 +10,8 @@ from oracle import oracle as orc
 from paper_2505_10951_amd import sgc, workloads
 from paper_2505_10951_amd.harness import Session, run_workload, to_device, to_host_f32
 
-from ref_util import bf16_floor_arrays, bf16_rounding_floor, err_stats, oracle_caches, oracle_suffix, tight_bar
+from ref_util import (bf16_floor_arrays, bf16_rounding_floor, err_stats, fp8_query_floor, oracle_caches, oracle_suffix,
+                      tight_bar)
 
 pytestmark = pytest.mark.gpu
 
@@ -333,7 +334,7 @@ def test_fp8_codec_and_quantised_cache_match_oracle():
     assert np.array_equal(ev, codes[::-1])
 
 
-@pytest.mark.parametrize("kernel", [sgc.SGC_KERNEL_MFMA, sgc.SGC_KERNEL_GENERIC])
+@pytest.mark.parametrize("kernel", [sgc.SGC_KERNEL_MFMA, sgc.SGC_KERNEL_GENERIC, sgc.SGC_KERNEL_MFMA_FP8])
 def test_fp8_cache_small(kernel):
     w = workloads.custom("fp8_small", n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=500000.0, io_dtype="bf16",
                          kv_dtype="fp8_e4m3", prefix_len=[260, 64, 31], cluster_sizes=[4, 2, 3], suffix_range=(1, 80),
@@ -365,10 +366,21 @@ def test_fp8_cache_small(kernel):
     # element on the other side of a code boundary (counted above) a row that gives that key most of its weight moves by
     # up to p (1 - p) * scale * |q_c| * step * |v - o| ~ 2e-2, which no calibration on the CPU side predicts.  The tight
     # bound on the attention arithmetic itself is taken where both sides read identical codes (next test).
-    _check_suffix(w, out, tol=TOL_FP8)
+    tol = TOL_FP8
+    if kernel == sgc.SGC_KERNEL_MFMA_FP8:
+        # The fp8 first product rounds every rotated query row to e4m3 (3 significant bits).  Over prompts this short a
+        # row's weight sits on few keys and that rounding alone moves outputs by several 1e-2 (emulated below on the
+        # oracle's side); the stated 6e-2 is what this path is held to at the long prompts it is meant for (configs[4]).
+        caches = oracle_caches(w)
+        floor = max(fp8_query_floor(*caches[int(w.labels[n])], *w.suffix_qkv_query(n), w.rope_base)
+                    for n in range(w.n_queries) if w.suffix_len[n] > 0)
+        _say(f"  fp8 first product: e4m3 query floor {floor:.3e}")
+        tol = 4 * floor + 6e-3
+    _check_suffix(w, out, tol=tol)
 
 
-def test_fp8_imported_oracle_cache_isolates_the_attention():
+@pytest.mark.parametrize("kernel", [sgc.SGC_KERNEL_MFMA, sgc.SGC_KERNEL_MFMA_FP8])
+def test_fp8_imported_oracle_cache_isolates_the_attention(kernel):
     # load the ORACLE's quantised cache into the pages, so both sides read identical codes
     w = workloads.custom("fp8_import", n_q_heads=8, n_kv_heads=1, head_dim=128, rope_base=500000.0, io_dtype="bf16",
                          kv_dtype="fp8_e4m3", prefix_len=[150], cluster_sizes=[3], suffix_range=(5, 40), seed=29)
@@ -376,7 +388,7 @@ def test_fp8_imported_oracle_cache_isolates_the_attention():
     ck, cv, _, _ = orc.prefix_prefill(None, pk, pv, w.rope_base)
     kc, ksc, kdeq = orc.quantise_e4m3(ck)
     vc, vsc, vdeq = orc.quantise_e4m3(cv)
-    with Session(w, kernel=sgc.SGC_KERNEL_MFMA) as s:
+    with Session(w, kernel=kernel) as s:
         s.alloc_cluster(0)
         s.import_cluster(0, 0, kc, vc, ksc, vsc)
         s.assign()
@@ -389,7 +401,14 @@ def test_fp8_imported_oracle_cache_isolates_the_attention():
     _say(f"  fp8 import max_abs {st['max_abs']:.3e}")
     # identical codes on both sides: what is left is the rounding of the output to bf16 (half an ulp of values up to 2:
     # 3.9e-3) plus the binary16 query and bf16 weight roundings (about 1e-3 together on unit-variance data)
-    assert st["max_abs"] <= 6e-3
+    if kernel == sgc.SGC_KERNEL_MFMA:
+        assert st["max_abs"] <= 6e-3
+    else:
+        # the fp8 first product rounds the rotated query to e4m3 (3 significant bits) under a power-of-two row scale:
+        # four times what that rounding alone costs on this very input (numpy emulation on the oracle's side)
+        floor = max(fp8_query_floor(kdeq, vdeq, *w.suffix_qkv_query(n), w.rope_base) for n in range(w.n_queries))
+        _say(f"  fp8 first product: e4m3 query floor {floor:.3e}")
+        assert st["max_abs"] <= min(TOL_FP8, 4 * floor + 6e-3)
 
 
 # ---- configs[1..4] at full size, in the benchmark's launch configuration ---------------------------
@@ -481,13 +500,15 @@ def test_config3_llama3_8b_stack32_every_cluster_and_layer():
         _say(f"  config 3 worst over 512 (cluster, layer) pairs {worst:.3e}")
 
 
-def test_config4_llama70b_fp8_long_prefix_full_size_every_cluster():
+@pytest.mark.parametrize("kernel", [sgc.SGC_KERNEL_MFMA_FP8, sgc.SGC_KERNEL_MFMA])
+def test_config4_llama70b_fp8_long_prefix_full_size_every_cluster(kernel):
     """fp8 e4m3 cache, 16 384-token prefixes, 1024 queries of 32-256 tokens: the whole batch in one launch,
     checked on one query of every cluster (all 64 heads, all rows) against the oracle reading its own quantised
-    cache."""
+    cache.  Both first products: on the e4m3 codes (the path bench.py times for this configuration) and on 16-bit
+    operands."""
     w = workloads.config(4)
-    _say("config 4", w.name, "T", w.total_suffix_tokens, "flop %.3e" % w.flops())
-    out = run_workload(w, want_lse=False)
+    _say("config 4", w.name, "T", w.total_suffix_tokens, "flop %.3e" % w.flops(), "kernel", kernel)
+    out = run_workload(w, want_lse=False, kernel=kernel)
     _check_bookkeeping(w, out)
     qs = _sampled_queries(w, 1)                     # 8 queries, one per cluster
     assert sorted(int(w.labels[n]) for n in qs) == list(range(w.n_clusters))

@@ -327,6 +327,9 @@ def main() -> int:
     ap.add_argument("--other-configs", type=str, default="auto",
                     help="comma-separated indices of further configurations whose suffix launch is timed and reported "
                          "under \"configs\" (auto: 0,2,3,4 when the headline is configs[1], else none; none: skip)")
+    ap.add_argument("--kernel", choices=["auto", "mfma", "mfma_fp8", "generic"], default="auto",
+                    help="attention kernel of the headline configuration (auto: the matrix-core kernel where it covers the shape, "
+                         "with the first product on the e4m3 codes when the cache is fp8)")
     ap.add_argument("--other-steps", type=int, default=5, help="timed suffix launches per further configuration")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten 256 MiB device copies and exit (counter calibration under rocprofv3 --pmc)")
@@ -354,7 +357,9 @@ def main() -> int:
     pq = [w.prefix_q(c, layer) for c in range(w.n_clusters)]
     t_gen = time.perf_counter() - t_gen
 
-    s = Session(w)
+    kinds = {"auto": sgc.SGC_KERNEL_MFMA_FP8 if w.kv_dtype == "fp8_e4m3" else sgc.SGC_KERNEL_AUTO, "mfma": sgc.SGC_KERNEL_MFMA,
+             "mfma_fp8": sgc.SGC_KERNEL_MFMA_FP8, "generic": sgc.SGC_KERNEL_GENERIC}
+    s = Session(w, kernel=kinds[args.kernel])
     dq, dk, dv = (to_device(x, w.io_dtype) for x in (q, k, v))
     do = torch.empty_like(dq)
     dpk = [to_device(a, w.io_dtype) for a, _ in pkv]

@@ -71,9 +71,12 @@ __device__ inline float half_sum(float x)
 template <bool TO_F16>
 __device__ inline uint32_t fp8x2_to_16x2(uint32_t w, bool high)
 {
-    const auto f = high ? __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true) : __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
-    if (TO_F16) return pack2_f16(f[0], f[1]);
-    return (__float_as_uint(f[0]) >> 16) | (__float_as_uint(f[1]) & 0xFFFF0000u);
+    if (TO_F16) {
+        const auto r = high ? __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, true) : __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false);
+        return __builtin_bit_cast(uint32_t, r);
+    }
+    const auto r = high ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true) : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
+    return __builtin_bit_cast(uint32_t, r);
 }
 
 // 4 KiB global -> LDS as four 1 KiB instructions, 16 bytes per lane: byte 1024 q + 16 lane of the source
@@ -248,7 +251,9 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
     const char *spool_base = a.spool + (int64_t)hk * PART_BYTES;
     const uint32_t spool_v_off = (uint32_t)Hkv * PART_BYTES;
     const uint32_t spool_page_256 = (2u * spool_v_off) >> 8;
-    uint4 stage[4];      // fp8 cache only: codes on their way to LDS [K run 0, K run 1, V run 0, V run 1]
+    // fp8 cache only: codes on their way to LDS.  A 2 KiB part is fetched as four runs of 512 codes, 8 per lane; widened,
+    // a lane's 8 codes are 16 bytes at 16 * lane of the run's 1 KiB image, so the stores cover all banks.
+    uint2 stage[8];      // [K runs 0..3, V runs 0..3]
     bool staged_k = false, staged_v = false;
 
     // Page indices past the last page are clamped to it: such keys are masked out of the scores, and what
@@ -284,38 +289,35 @@ __global__ void __launch_bounds__(NW * 64, (NW == 4 && MI == 1) ? 2 : 1) attn_mf
                 __builtin_amdgcn_global_load_lds(g, l, 16, 1024, 0);
                 staged_k = false;
             } else {
-                stage[0] = *reinterpret_cast<const uint4 *>(src);
-                stage[1] = *reinterpret_cast<const uint4 *>(src + 1024);
+                const char *src8 = cache_base + ((uint64_t)off256 << 8) + lane * 8;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) stage[r] = *reinterpret_cast<const uint2 *>(src8 + r * 512);
             }
         }
         if (staged_v) {
             const uint32_t off256 = __builtin_amdgcn_readlane(poff_v, my_page);
-            const char *src = cache_base + ((uint64_t)off256 << 8) + cache_v_off + lane16;
-            stage[2] = *reinterpret_cast<const uint4 *>(src);
-            stage[3] = *reinterpret_cast<const uint4 *>(src + 1024);
+            const char *src8 = cache_base + ((uint64_t)off256 << 8) + cache_v_off + lane * 8;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) stage[4 + r] = *reinterpret_cast<const uint2 *>(src8 + r * 512);
         }
     };
-    // 16 codes -> 16 16-bit floats = 32 bytes: chunk (run, lane) of a part lands at 32 (64 run + lane) of its image
-    auto widen_to_lds = [&](const uint4 &codes, char *dst, auto f16_tag) __attribute__((always_inline)) {
+    // 8 codes -> 8 16-bit floats = 16 bytes
+    auto widen_to_lds = [&](const uint2 &codes, char *dst, auto f16_tag) __attribute__((always_inline)) {
         constexpr bool F = decltype(f16_tag)::value;
-        const uint32_t w[4] = {codes.x, codes.y, codes.z, codes.w};
-        uint4 o0, o1;
-        o0.x = fp8x2_to_16x2<F>(w[0], false); o0.y = fp8x2_to_16x2<F>(w[0], true);
-        o0.z = fp8x2_to_16x2<F>(w[1], false); o0.w = fp8x2_to_16x2<F>(w[1], true);
-        o1.x = fp8x2_to_16x2<F>(w[2], false); o1.y = fp8x2_to_16x2<F>(w[2], true);
-        o1.z = fp8x2_to_16x2<F>(w[3], false); o1.w = fp8x2_to_16x2<F>(w[3], true);
-        *reinterpret_cast<uint4 *>(dst) = o0;
-        *reinterpret_cast<uint4 *>(dst + 16) = o1;
+        uint4 o;
+        o.x = fp8x2_to_16x2<F>(codes.x, false); o.y = fp8x2_to_16x2<F>(codes.x, true);
+        o.z = fp8x2_to_16x2<F>(codes.y, false); o.w = fp8x2_to_16x2<F>(codes.y, true);
+        *reinterpret_cast<uint4 *>(dst) = o;
     };
     // Writes what the last issue_load_fp8 staged; a staged half is written once, and only to a real buffer.
     auto store_fp8 = [&](char *kdst, char *vdst) __attribute__((always_inline)) {
         if (staged_k && kdst) {
-            widen_to_lds(stage[0], kdst + my_page * PART_BYTES + lane * 32, std::true_type{});
-            widen_to_lds(stage[1], kdst + my_page * PART_BYTES + (64 + lane) * 32, std::true_type{});
+#pragma unroll
+            for (int r = 0; r < 4; ++r) widen_to_lds(stage[r], kdst + my_page * PART_BYTES + r * 1024 + lane * 16, std::true_type{});
         }
         if (staged_v && vdst) {
-            widen_to_lds(stage[2], vdst + my_page * PART_BYTES + lane * 32, std::false_type{});
-            widen_to_lds(stage[3], vdst + my_page * PART_BYTES + (64 + lane) * 32, std::false_type{});
+#pragma unroll
+            for (int r = 0; r < 4; ++r) widen_to_lds(stage[4 + r], vdst + my_page * PART_BYTES + r * 1024 + lane * 16, std::false_type{});
         }
         staged_k = false;
         staged_v = false;

@@ -133,7 +133,7 @@ def test_decode_random_shapes_against_oracle(seed):
     w = workloads.custom(f"decode_random_{seed}", n_q_heads=Hkv * g, n_kv_heads=Hkv, head_dim=128, rope_base=500000.0,
                          io_dtype="bf16", kv_dtype=kv, prefix_len=prefix, cluster_sizes=sizes, suffix_len=slen, seed=seed)
     n_steps = int(rng.integers(2, 6))
-    got = _run_decode(w, n_steps, kernel=kernel)[0]
+    got = _run_decode(w, n_steps)[0]
     o_ref, lse_ref = _oracle_decode(w, 0, n_steps, oracle_caches(w, 0))
     err = np.abs(got[0] - o_ref).max()
     lerr = np.abs(got[1] - lse_ref).max()

@@ -123,6 +123,11 @@ const char *sgc_last_error(const sgc_ctx *ctx);
  * cluster's page j / page_tokens.  Inside a page K (after rotation) and V are stored in the
  * order the matrix-core operands are read in, not token-major; use sgc_cache_export /
  * sgc_cache_import to move between that and the canonical [P][Hkv][d] layout.
+ * With kv_dtype = SGC_BF16 (a 16-bit cache) V is stored as given (bf16) and the rotated K, which has
+ * no exact bf16 form, as IEEE binary16: 11 significant bits instead of 8 at the same size, which
+ * keeps the stated 2e-2 output bar under keys with a few large channels.  The rotated, scaled query
+ * is rounded to binary16 as well and the first product runs on binary16 operands.  A rotated key or
+ * scaled query beyond 65504 in magnitude becomes an infinity and the rows that see it come out NaN.
  * With kv_dtype = SGC_FP8_E4M3 each (cluster, layer, kv head) has one fp32 scale for K and one
  * for V: stored code = round_to_nearest_even(x / scale), scale = max|x| / 448 (1 if all zero),
  * OCP E4M3 with saturation; K is scaled after rotation.
@@ -324,7 +329,8 @@ int sgc_timing_get(sgc_ctx *ctx, int32_t back, float *ingest_ms, float *attentio
 int sgc_timing_last(sgc_ctx *ctx, float *ingest_ms, float *attention_ms);
 
 /* ---- canonical view of a cluster's cache (tests, checkpointing) -----------------------------
- * dev_k, dev_v: [prefix_len][Hkv][d] in kv_dtype (raw e4m3 codes for fp8); K is the rotated K.
+ * dev_k, dev_v: [prefix_len][Hkv][d] as stored: fp32 for an fp32 cache; binary16 K and bf16 V for a
+ * 16-bit cache; raw e4m3 codes for fp8.  K is the rotated K.
  * host_k_scale, host_v_scale: [Hkv] fp32 (written by export / read by import; ignored and may
  * be NULL unless the cache is fp8).  Export synchronises the stream before returning. */
 int sgc_cache_export(sgc_ctx *ctx, const sgc_cache *cache, int32_t cluster_id, int32_t layer,

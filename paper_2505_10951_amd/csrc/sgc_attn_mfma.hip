@@ -1,4 +1,5 @@
-// bf16 MFMA attention kernel of libsgc for gfx950 (MI355X), head_dim 128.
+// Matrix-core attention kernel of libsgc for gfx950 (MI355X), head_dim 128: first product on binary16 operands
+// (rotated keys and queries; on the e4m3 codes of an fp8 cache in the QK8 variant), second product on bf16.
 //
 // SubGCache (arXiv 2505.10951) Sec. 3.4: every query of a cluster appends its question tokens to
 // the cluster's cached prompt.  One workgroup takes a tile of rows that all belong to one
@@ -7,7 +8,7 @@
 // prefix keys the same rows run causally over their own query's suffix keys, which a small
 // ingest kernel has put into pages of the same layout beforehand.
 //
-// Matrix-core mapping (v_mfma_f32_32x32x16_bf16, 64-lane wavefronts):
+// Matrix-core mapping (v_mfma_f32_32x32x16_f16 / _bf16, 64-lane wavefronts):
 //   S^T = K Q^T : A = 32 keys x 16 channels (from LDS), B = 16 channels x 32 rows (Q, registers).
 //                 Lane (n, h) = (lane % 32, lane / 32) then owns row n and, in accumulator
 //                 register r, key 8 (r / 4) + 4 h + r % 4: a row's scores sit in ONE lane pair, so

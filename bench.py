@@ -32,6 +32,21 @@ PROFILED_HBM_BYTES_PER_LAUNCH = {
 }
 TOLERANCE = {"f32": 2e-5, "bf16": 2e-2, "fp8_e4m3": 6e-2}     # max-abs bars against the fp64 oracle
 
+# Other ceilings of the matrix-core attention kernel, beside the datasheet MFMA peak (all in TFLOP/s of attention flop):
+# * per score (4 d = 512 flop at d = 128) the softmax needs one exp2 (two issue slots of 4 cycles per 64 lanes), half
+#   a conversion and half a dot2 (one slot each): 3 slots x 4 cycles / 64 lanes = 0.1875 SIMD cycles, against
+#   512 / 1024 = 0.5 SIMD cycles of matrix-core time: the vector unit alone would carry 2500 x 0.5 / 0.1875;
+# * if the two did not overlap at all (one issue port, one wavefront): 2500 x 0.5 / 0.6875;
+# * what a kernel of nothing but MFMA instructions sustains on unit-scale random operands (the chip lowers its clock
+#   under the data-dependent power): 1680 (binary16) and 1820 (bf16), 1750 for this kernel's half-and-half mix
+#   (measured: profiles/gfx950_microbenchmarks.md).
+CO_LIMITS_TFLOPS = {"valu_softmax": 2500.0 * 0.5 / 0.1875, "mfma_and_valu_not_overlapped": 2500.0 * 0.5 / 0.6875,
+                    "mfma_sustained_on_random_operands": 1750.0}
+
+
+def co_limits(achieved_tflops: float) -> dict:
+    return {k: {"peak": v, "frac": achieved_tflops / v} for k, v in CO_LIMITS_TFLOPS.items()}
+
 
 def copy_calibration() -> int:
     """A plain device copy of known size, for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters."""
@@ -113,6 +128,22 @@ def cpu_baseline(w, budget_s: float):
            "sample": f"{len(sample)} of {w.n_queries} queries (all heads, all rows), {fl:.3e} flop in {dt:.2f} s",
            "us_per_query": dt / len(sample) * 1e6}
     return rep, rows, o_ref
+
+
+def oracle_one_thread(index: int):
+    """The oracle on every query of a (small) configuration with one OpenMP thread, in a child process of its own
+    (the thread count is read when the library starts; the child never touches the GPU)."""
+    import subprocess
+    code = ("import json, sys; sys.path.insert(0, %r); import bench; from paper_2505_10951_amd import workloads; "
+            "w = workloads.config(%d); dt, fl, _, _ = bench.oracle_on_queries(w, [n for n in range(w.n_queries) if w.suffix_len[n] > 0]); "
+            "print(json.dumps({'value': fl / dt / 1e12, 'unit': 'TFLOP/s', 'cores': 1, 'kind': 'oracle', "
+            "'sample': 'all %%d queries, %%.3e flop in %%.3f s' %% (w.n_queries, fl, dt), 'us_per_query': dt / w.n_queries * 1e6}))") % (ROOT, index)
+    env = dict(os.environ, OMP_NUM_THREADS="1")
+    try:
+        r = subprocess.run([sys.executable, "-c", code], env=env, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=120)
+        return json.loads(r.stdout.strip().splitlines()[-1])
+    except Exception as e:                      # reported, never fatal: the figure is context
+        return {"error": repr(e)}
 
 
 def decode_measurement(s, w, layer, n_steps, dq, dk, dv, do, all_clusters, pq_ptrs, pk_ptrs, pv_ptrs, po_ptrs, stream):
@@ -298,6 +329,7 @@ def other_config(index: int, steps: int, warmup: int, threads: int, kernel=None)
             "timed": f"{steps} suffix launches after {warmup} untimed, caches and plan resident",
             "n_tiles": info.n_tiles, "suffix_flop": w.flops(),
             "attention_kernel_ms": attn_ms, "attention_kernel_ms_min": float(np.min([b for _, b in kernel_ms])),
+            "attention_kernel_ms_median": float(np.median([b for _, b in kernel_ms])),
             "suffix_ingest_kernel_ms": ingest_ms, "suffix_call_ms": attn_ms + ingest_ms,
             "us_per_query": (attn_ms + ingest_ms) * 1e3 / w.n_queries,
             "roofline": {"kernel": "attn_mfma_kernel (batched suffix prefill)" if mfma else "attn_generic_kernel (fp32 arithmetic)",
@@ -305,7 +337,9 @@ def other_config(index: int, steps: int, warmup: int, threads: int, kernel=None)
                          "frac": achieved / peak, "frac_of_call": w.flops() / ((attn_ms + ingest_ms) * 1e-3) / 1e12 / peak,
                          "traffic": prof[0] if prof else None, "traffic_source": prof[1] if prof else None,
                          "algorithmic_bytes": w.algorithmic_bytes(),
-                         "hbm_gbs_algorithmic": w.algorithmic_bytes() / (attn_ms * 1e-3) / 1e9, **extra},
+                         "hbm_gbs_algorithmic": w.algorithmic_bytes() / (attn_ms * 1e-3) / 1e9,
+                         "co_limits": co_limits(achieved) if mfma else None, **extra},
+            **({"cpu_baseline_one_thread": oracle_one_thread(index)} if index == 0 else {}),
             "error": error_against_oracle(o_rows, o_ref, w.kv_dtype, f"queries {picks}: all heads, all rows")}
 
 
@@ -331,6 +365,9 @@ def main() -> int:
                     help="attention kernel of the headline configuration (auto: the matrix-core kernel where it covers the shape, "
                          "with the first product on the e4m3 codes when the cache is fp8)")
     ap.add_argument("--other-steps", type=int, default=5, help="timed suffix launches per further configuration")
+    ap.add_argument("--repeat-launches", type=int, default=100,
+                    help="after the timed steps, launch the suffix call this many times back to back (after 20 untimed) and report "
+                         "median and minimum kernel time (0 = skip, at most 128)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten 256 MiB device copies and exit (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -414,6 +451,7 @@ def main() -> int:
     ingest_ms = float(np.mean([a for a, _ in kernel_ms]))
     attn_ms = float(np.mean([b for _, b in kernel_ms]))                        # the dominant kernel alone
     attn_ms_min = float(np.min([b for _, b in kernel_ms]))
+    attn_ms_median = float(np.median([b for _, b in kernel_ms]))
     other = None
     if not args.suffix_only:
         other_ms = timed_loop(bool(args.pipelined))
@@ -422,6 +460,30 @@ def main() -> int:
                  "ms_per_step": other_ms, "attention_kernel_ms": float(np.mean(other_kernel))}
 
     o_host = do.to(torch.float32).cpu().numpy()          # what the last timed step wrote, for the error figures
+    repeat = None
+    if not args.suffix_only and args.repeat_launches > 0:
+        # the suffix call alone, launched back to back with caches and plan resident: 20 untimed, then the timed ones
+        for c in range(w.n_clusters):
+            sgc.sgc_cache_alloc_cluster(s.ctx, s.cache, c, int(w.prefix_len[c]))
+        sgc.sgc_prefix_prefill_batched(s.ctx, s.cache, all_clusters, layer, pq_ptrs, pk_ptrs, pv_ptrs, po_ptrs, None, stream)
+        s.assign(labels, slen)
+        s.upload_plan()
+        n_rep = min(args.repeat_launches, 128)
+        for i in range(20 + n_rep):
+            if i == 20:
+                torch.cuda.synchronize()
+                sgc.sgc_timing_enable(s.ctx, True)
+            sgc.sgc_suffix_prefill_batched(s.ctx, s.cache, s.plan, layer, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+                                           do.data_ptr(), None, stream)
+        torch.cuda.synchronize()
+        rep_ms = [sgc.sgc_timing_get(s.ctx, back)[1] for back in range(n_rep)]
+        for c in range(w.n_clusters):
+            sgc.sgc_cache_free_cluster(s.ctx, s.cache, c)
+        med = float(np.median(rep_ms))
+        repeat = {"launches": n_rep, "untimed_before": 20, "mode": "the suffix call repeated back to back, caches and plan resident",
+                  "attention_kernel_ms_median": med, "attention_kernel_ms_min": float(np.min(rep_ms)),
+                  "attention_kernel_ms_mean": float(np.mean(rep_ms)),
+                  "roofline_frac_median": w.flops() / (med * 1e-3) / 1e12 / PEAK_TFLOPS[w.io_dtype]}
     fl_suffix = w.flops()
     fl_step = fl_suffix + (0.0 if args.suffix_only else prefix_flops(w))
     info = sgc.sgc_plan_get_info(s.ctx, s.plan)
@@ -445,6 +507,7 @@ def main() -> int:
         "step_flop": fl_step, "suffix_flop": fl_suffix,
         "suffix_launch_ms": kern_ms, "suffix_launch_ms_min": kern_ms_min,
         "suffix_ingest_kernel_ms": ingest_ms, "attention_kernel_ms": attn_ms, "attention_kernel_ms_min": attn_ms_min,
+        "attention_kernel_ms_median": attn_ms_median,
         "us_per_query": ms_per_step * 1e3 / w.n_queries,
         "suffix_us_per_query": kern_ms * 1e3 / w.n_queries,
         "pct_mfma_peak_step": 100.0 * fl_step / (ms_per_step * 1e-3) / 1e12 / peak,
@@ -456,7 +519,8 @@ def main() -> int:
                      "traffic": prof[0] if prof else None, "traffic_source": prof[1] if prof else None,
                      "algorithmic_bytes": w.algorithmic_bytes(),
                      "hbm_gbs_algorithmic": w.algorithmic_bytes() / (attn_ms * 1e-3) / 1e9,
-                     "hbm_frac_algorithmic": w.algorithmic_bytes() / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                     "hbm_frac_algorithmic": w.algorithmic_bytes() / (attn_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "co_limits": co_limits(achieved) if mfma else None},
         "paper_context": "TTFT reduction up to 6.68x, PFTT up to 15.49x (Table 2; 2x A100-SXM4-40GB, precision not stated); end-to-end LLM latencies, not this kernel",
         "input_gen_s": t_gen,
     }
@@ -465,6 +529,8 @@ def main() -> int:
         other["value"] = fl_step / (other["ms_per_step"] * 1e-3) / 1e12
         other["roofline_frac"] = fl_suffix / (other["attention_kernel_ms"] * 1e-3) / 1e12 / peak
         out["other_mode"] = other
+    if repeat is not None:
+        out["repeat_launches"] = repeat
     d_model = w.n_q_heads * w.head_dim if args.layer_d_model < 0 else args.layer_d_model
     if d_model > 0 and not args.suffix_only:
         out["layer"] = layer_measurement(s, w, layer, d_model, args.layer_reps, stream)

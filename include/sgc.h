@@ -317,12 +317,12 @@ int sgc_project_out(sgc_ctx *ctx, const void *dev_o, const void *dev_w_o, int32_
 
 /* ---- kernel timing (measurement aid; no effect on results) -----------------------------------
  * With timing on, sgc_suffix_prefill_batched records HIP events on its launch stream around the
- * suffix K/V ingest kernel and around the attention kernel; the events of the last 64 timed launches
+ * suffix K/V ingest kernel and around the attention kernel; the events of the last 128 timed launches
  * are kept, so a caller can enqueue many launches without waiting and read all durations afterwards.
  * sgc_timing_get waits for the launch recorded `back` timed launches before the last one (0 = the
  * last) to finish and returns the two durations in milliseconds (either pointer may be NULL);
  * SGC_ESTATE if timing is off or that launch was never recorded, SGC_EINVAL if back is outside
- * [0, 64).  sgc_timing_last is sgc_timing_get with back = 0.  sgc_timing_enable restarts the count.
+ * [0, 128).  sgc_timing_last is sgc_timing_get with back = 0.  sgc_timing_enable restarts the count.
  * Host-only calls. */
 int sgc_timing_enable(sgc_ctx *ctx, int on);
 int sgc_timing_get(sgc_ctx *ctx, int32_t back, float *ingest_ms, float *attention_ms);

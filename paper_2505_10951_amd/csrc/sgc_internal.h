@@ -273,7 +273,7 @@ struct sgc_ctx {
     int stage_next = 0;
     bool timing = false;            // record events around the suffix launch's kernels
     // the last kTimingRing timed suffix launches: events before ingest, between, after attention
-    static constexpr int kTimingRing = 64;
+    static constexpr int kTimingRing = 128;
     hipEvent_t ev[kTimingRing][3] = {};
     uint64_t timing_count = 0;      // timed launches recorded since timing was switched on
 };

@@ -169,8 +169,15 @@ int stage_begin(sgc_ctx *ctx, size_t bytes, char **host, int *slot)
         ctx->h_stage_cap[i] = 0;
         const size_t cap = std::max<size_t>((bytes + 65535) / 65536 * 65536, 1 << 20);
         void *p = nullptr;
-        SGC_HIP(ctx, hipHostMalloc(&p, cap, hipHostMallocDefault));
+        SGC_HIP(ctx, hipHostMalloc(&p, cap, hipHostMallocMapped | hipHostMallocCoherent));
+        void *dp = nullptr;
+        hipError_t e = hipHostGetDevicePointer(&dp, p, 0);
+        if (e != hipSuccess || !dp) {
+            (void)hipHostFree(p);
+            return fail_hip(ctx, e != hipSuccess ? e : hipErrorInvalidValue, "hipHostGetDevicePointer");
+        }
         ctx->h_stage[i] = static_cast<char *>(p);
+        ctx->h_stage_dev[i] = static_cast<const char *>(dp);
         ctx->h_stage_cap[i] = cap;
     }
     *host = ctx->h_stage[i];
@@ -180,7 +187,9 @@ int stage_begin(sgc_ctx *ctx, size_t bytes, char **host, int *slot)
 
 int stage_commit(sgc_ctx *ctx, int slot, void *dev, size_t bytes, hipStream_t s, size_t host_offset = 0)
 {
-    if (bytes) SGC_HIP(ctx, hipMemcpyAsync(dev, ctx->h_stage[slot] + host_offset, bytes, hipMemcpyHostToDevice, s));
+    if (bytes % 4 != 0 || (reinterpret_cast<uintptr_t>(dev) | host_offset) % 16 != 0)
+        return fail(ctx, SGC_EINVAL, "staged copy of %zu bytes is not aligned", bytes);
+    if (bytes) SGC_HIP(ctx, launch_copy_from_host(dev, ctx->h_stage_dev[slot] + host_offset, bytes, s));
     SGC_HIP(ctx, hipEventRecord(ctx->stage_ev[slot], s));
     ctx->stage_pending[slot] = true;
     return SGC_OK;
@@ -313,6 +322,7 @@ void build_tiles(sgc_plan *pl, int tile_rows)
     size_t slots = 0;
     for (auto &l : lists) slots = std::max(slots, l.size());
     pl->tiles.resize(slots * kXcd);
+    pl->seeds.assign(slots * kXcd, TileSeed{});
     for (int x = 0; x < kXcd; ++x) {
         for (size_t k = 0; k < slots; ++k) {
             Tile &t = pl->tiles[k * kXcd + x];
@@ -342,6 +352,7 @@ void build_tiles(sgc_plan *pl, int tile_rows)
                 else
                     t.q[q] = {INT32_MAX, 0, 0, 0};
             }
+            pl->seeds[k * kXcd + x] = {t.cluster, t.hk, t.row0, t.n_rows, t.sq_lo, t.sq_hi, t.last_qpos, 0};
         }
     }
     pl->tile_rows = tile_rows;
@@ -758,16 +769,19 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
             slots = std::max(slots, lists[x].size());
         }
     }
+    // One block: [jobs][job of each page][tile seeds] from the host in one copy, then room for the tile records, which a
+    // small kernel writes from the seeds, the jobs and the cache's page table.
     const size_t n_tiles = slots * kXcd;
     const size_t jobs_bytes = (jobs.size() * sizeof(PrefixJob) + 255) / 256 * 256;
     const size_t pj_bytes = (page_job.size() * sizeof(int32_t) + 255) / 256 * 256;
-    const size_t tiles_bytes = n_tiles * sizeof(Tile);
-    const size_t total = jobs_bytes + pj_bytes + tiles_bytes;
+    const size_t seeds_bytes = (n_tiles * sizeof(TileSeed) + 255) / 256 * 256;
+    const size_t copied = jobs_bytes + pj_bytes + seeds_bytes;
+    const size_t total = copied + n_tiles * sizeof(Tile);
     sgc_dev_block blk;
     if ((rc = dev_acquire(ctx, total, s, &blk)) != SGC_OK) return rc;
     char *host = nullptr;
     int slot = 0;
-    if ((rc = stage_begin(ctx, total, &host, &slot)) != SGC_OK) {
+    if ((rc = stage_begin(ctx, copied, &host, &slot)) != SGC_OK) {
         dev_release(ctx, blk, s);
         return rc;
     }
@@ -775,33 +789,38 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
     memcpy(host + jobs_bytes, page_job.data(), page_job.size() * sizeof(int32_t));
     const PrefixJob *d_jobs = reinterpret_cast<const PrefixJob *>(blk.p);
     const int32_t *d_page_job = reinterpret_cast<const int32_t *>(blk.p + jobs_bytes);
-    const Tile *d_tiles = reinterpret_cast<const Tile *>(blk.p + jobs_bytes + pj_bytes);
-    // The ingest kernel needs the jobs only: they go first and the kernel starts while the tile list is written.
-    hipError_t e = hipMemcpyAsync(blk.p, host, jobs_bytes + pj_bytes, hipMemcpyHostToDevice, s);
+    const TileSeed *d_seeds = reinterpret_cast<const TileSeed *>(blk.p + jobs_bytes + pj_bytes);
+    const Tile *d_tiles = reinterpret_cast<const Tile *>(blk.p + copied);
+    // The ingest kernel needs the jobs only: they go first, and the kernel runs while the tile seeds are written.
+    hipError_t e = launch_copy_from_host(blk.p, ctx->h_stage_dev[slot], jobs_bytes + pj_bytes, s);
     if (e == hipSuccess && !attend_only)
         e = launch_prefix_ingest(c->geom, layer, c->d_page_table, d_jobs, (int)jobs.size(), d_page_job, (int)page_job.size(),
                                  ctx->p.io_dtype, ctx->p.rope_base > 0.0f ? ctx->d_rope : nullptr, s);
-    Tile *ht = reinterpret_cast<Tile *>(host + jobs_bytes + pj_bytes);
+    TileSeed *hs = reinterpret_cast<TileSeed *>(host + jobs_bytes + pj_bytes);
     for (int x = 0; x < kXcd; ++x) {
         for (size_t k = 0; k < slots; ++k) {
-            Tile &t = ht[k * kXcd + x];
-            memset(&t, 0, sizeof(Tile));
-            if (k >= lists[x].size()) continue;      // padding tile: n_rows = 0
+            TileSeed &sd = hs[k * kXcd + x];
+            sd = TileSeed{};                          // padding tile: n_rows = 0
+            if (k >= lists[x].size()) continue;
             const Light &lt = lists[x][k];
-            const PrefixJob &j = jobs[lt.job];
-            t.cluster = j.cluster;
-            t.hk = lt.hk;
-            t.row0 = lt.row0;
-            t.n_rows = (int32_t)std::min<int64_t>(ctx->tile_rows, (int64_t)j.prefix_len * g - lt.row0);
-            t.prefix_len = j.prefix_len;
-            t.pt_off = j.pt_off;
-            t.tok_base = lt.job;      // prefix mode: the job index travels here
-            t.sq_hi = -1;
-            fill_first_pages(t, c->cl[j.cluster].pages);
+            sd.cluster = lt.job;
+            sd.hk = lt.hk;
+            sd.row0 = lt.row0;
+            sd.n_rows = (int32_t)std::min<int64_t>(ctx->tile_rows, (int64_t)jobs[lt.job].prefix_len * g - lt.row0);
+            sd.sq_hi = -1;
         }
     }
-    // the tiles, and the event that says the staging buffer has been read
-    rc = stage_commit(ctx, slot, blk.p + jobs_bytes + pj_bytes, e == hipSuccess ? tiles_bytes : 0, s, jobs_bytes + pj_bytes);
+    // the seeds, and the event that says the staging buffer has been read
+    rc = stage_commit(ctx, slot, blk.p + jobs_bytes + pj_bytes, e == hipSuccess ? seeds_bytes : 0, s, jobs_bytes + pj_bytes);
+    if (rc == SGC_OK && e == hipSuccess && any_q && ctx->use_mfma) {
+        ExpandArgs x{};
+        x.seeds = d_seeds;
+        x.tiles = const_cast<Tile *>(d_tiles);
+        x.n = (int32_t)n_tiles;
+        x.jobs = d_jobs;
+        x.page_table = c->d_page_table;
+        e = launch_expand_tiles(x, s);
+    }
     if (rc == SGC_OK && e == hipSuccess && any_q) {
         AttnArgs a;
         fill_common_args(a, ctx, c, layer);
@@ -949,6 +968,31 @@ int sgc_assign_clusters(sgc_ctx *ctx, const sgc_cache *c, int32_t n_queries, con
     return SGC_OK;
 }
 
+// Writes the plan's tile records on the device, from its seeds and the cache's current page tables.
+static int expand_plan_tiles(sgc_plan *pl, hipStream_t s)
+{
+    sgc_ctx *ctx = pl->ctx;
+    if (pl->tiles.empty()) return SGC_OK;
+    sgc_cache *c = const_cast<sgc_cache *>(pl->cache);
+    int rc = cache_sync(c, s);
+    if (rc != SGC_OK) return rc;
+    ExpandArgs e{};
+    e.seeds = pl->d_seeds;
+    e.tiles = const_cast<Tile *>(pl->d_tiles);
+    e.n = (int32_t)pl->tiles.size();
+    e.jobs = nullptr;
+    e.page_table = c->d_page_table;
+    e.pt_off = c->d_pt_off;
+    e.prefix_len = c->d_prefix_len;
+    e.cl_tok_off = pl->d_cl_tok_off;
+    e.sq_tok0 = pl->d_sq_tok0;
+    e.sq_src0 = pl->d_sq_src0;
+    e.sq_len = pl->d_sq_len;
+    e.sq_page0 = pl->d_sq_page0;
+    SGC_HIP(ctx, launch_expand_tiles(e, s));
+    return SGC_OK;
+}
+
 int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
 {
     if (!pl) return fail(nullptr, SGC_EINVAL, "plan is NULL");
@@ -958,6 +1002,7 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
     if (pl->uploaded && pl->tile_rows == want_rows) return SGC_OK;
     plan_free_device(pl);
     pl->tiles.clear();
+    pl->seeds.clear();
     pl->tile_rows = 0;
     pl->dtiles.clear();
     pl->dtok.clear();
@@ -976,6 +1021,7 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
     }
     pl->row_dest.clear();      // made when a projection first asks for it
 
+    // (src null: room on the device that no host data fills; such pieces come last and are not copied)
     struct Piece {
         const void *src;
         size_t bytes;
@@ -993,28 +1039,34 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
         {pl->sq_cluster.data(), pl->sq_cluster.size() * 4, (const void **)&pl->d_sq_cluster},
         {pl->sq_page0.data(), pl->sq_page0.size() * 4, (const void **)&pl->d_sq_page0},
         {pl->spage_sq.data(), pl->spage_sq.size() * 4, (const void **)&pl->d_spage_sq},
-        {pl->tiles.data(), pl->tiles.size() * sizeof(Tile), (const void **)&pl->d_tiles},
+        {pl->seeds.data(), pl->seeds.size() * sizeof(TileSeed), (const void **)&pl->d_seeds},
         {pl->tok_info.data(), pl->tok_info.size() * sizeof(TokInfo), (const void **)&pl->d_tok_info},
         {pl->sq_query.data(), pl->sq_query.size() * 4, (const void **)&pl->d_sq_query},
         {pl->dtiles.data(), pl->dtiles.size() * sizeof(Tile), (const void **)&pl->d_dtiles},
         {pl->dtok.data(), pl->dtok.size() * sizeof(TokInfo), (const void **)&pl->d_dtok},
+        // the tile records are written on the device, from the seeds
+        {nullptr, pl->tiles.size() * sizeof(Tile), (const void **)&pl->d_tiles},
     };
-    size_t total = 0;
-    for (const Piece &p : pieces) total += (p.bytes + 255) / 256 * 256 + 256;
+    size_t total = 0, copied = 0;
+    for (const Piece &p : pieces) {
+        total += (p.bytes + 255) / 256 * 256 + 256;
+        if (p.src || p.bytes == 0) copied = total;
+    }
     int rc = dev_acquire(ctx, total, s, &pl->blob);
     if (rc != SGC_OK) return rc;
     pl->d_blob = pl->blob.p;
     pl->last_stream = s;
     char *host = nullptr;
     int slot = 0;
-    if ((rc = stage_begin(ctx, total, &host, &slot)) != SGC_OK) return rc;
+    if ((rc = stage_begin(ctx, copied, &host, &slot)) != SGC_OK) return rc;
     size_t off = 0;
     for (const Piece &p : pieces) {
         *p.dst = pl->d_blob + off;
-        if (p.bytes) memcpy(host + off, p.src, p.bytes);
+        if (p.bytes && p.src) memcpy(host + off, p.src, p.bytes);
         off += (p.bytes + 255) / 256 * 256 + 256;
     }
-    if ((rc = stage_commit(ctx, slot, pl->d_blob, total, s)) != SGC_OK) return rc;
+    if ((rc = stage_commit(ctx, slot, pl->d_blob, copied, s)) != SGC_OK) return rc;
+    if ((rc = expand_plan_tiles(pl, s)) != SGC_OK) return rc;
     if (want_rows > 0 && !pl->spage_sq.empty()) {
         // suffix page pool: bf16 pages of every query's rotated suffix K and transposed V
         // (decode: one pool per layer, since the pages have to outlive the layer's suffix launch; zeroed once,
@@ -1056,9 +1108,11 @@ static int refresh_tiles(sgc_plan *pl, const sgc_cache *c, hipStream_t s)
     sgc_ctx *ctx = pl->ctx;
     if (pl->tiles.empty() || pl->tiles_generation == c->generation) return SGC_OK;
     fill_tile_pt_off(pl, c);
-    for (int which = 0; which < 2; ++which) {
-        const std::vector<Tile> &list = which ? pl->dtiles : pl->tiles;
-        const Tile *dev = which ? pl->d_dtiles : pl->d_tiles;
+    int rc0 = expand_plan_tiles(pl, s);
+    if (rc0 != SGC_OK) return rc0;
+    for (int which = 1; which < 2; ++which) {
+        const std::vector<Tile> &list = pl->dtiles;
+        const Tile *dev = pl->d_dtiles;
         if (list.empty()) continue;
         const size_t bytes = list.size() * sizeof(Tile);
         char *host = nullptr;

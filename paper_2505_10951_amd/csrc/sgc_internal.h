@@ -112,6 +112,19 @@ struct Tile {
 };
 static_assert(sizeof(Tile) == 160, "tile record layout");
 
+// What the host sends per tile; a small kernel writes the tile record from it and from tables the device already
+// holds (a fifth of the record's bytes cross the host link).
+struct TileSeed {
+    int32_t cluster;     // suffix tiles: cluster id; prefix tiles: index of the job
+    int32_t hk;
+    int32_t row0;
+    int32_t n_rows;      // 0 = padding tile
+    int32_t sq_lo, sq_hi;
+    int32_t last_qpos;
+    int32_t pad;
+};
+static_assert(sizeof(TileSeed) == 32, "tile seed layout");
+
 // Per sorted token: where it comes from and where it sits in its query.
 struct TokInfo {
     int32_t src;    // row of the token in the caller's packed arrays
@@ -267,6 +280,7 @@ struct sgc_ctx {
     std::vector<sgc_dev_block> dev_free;
     static constexpr int kStageSlots = 8;      // copies a caller can have in flight before the host waits for one
     char *h_stage[kStageSlots] = {};
+    const char *h_stage_dev[kStageSlots] = {};   // the same buffers as kernels address them
     size_t h_stage_cap[kStageSlots] = {};
     hipEvent_t stage_ev[kStageSlots] = {};
     bool stage_pending[kStageSlots] = {};
@@ -343,6 +357,8 @@ struct sgc_plan {
     const int32_t *d_sq_src0 = nullptr, *d_sq_len = nullptr, *d_sq_tok0 = nullptr, *d_sq_cluster = nullptr;
     const int32_t *d_sq_page0 = nullptr, *d_spage_sq = nullptr;
     const sgc::Tile *d_tiles = nullptr;
+    std::vector<sgc::TileSeed> seeds;         // one per entry of tiles
+    const sgc::TileSeed *d_seeds = nullptr;
     const sgc::TokInfo *d_tok_info = nullptr;
     const int32_t *d_sq_query = nullptr;
     const sgc::Tile *d_dtiles = nullptr;
@@ -370,12 +386,25 @@ hipError_t launch_cache_import(const PoolGeom &g, int layer, const int32_t *d_pa
 // Suffix ingest: rotate every query's suffix K at prefix_len + j and write K and V as bf16 pages
 // (cache page layout) into the suffix page pool; one workgroup per (suffix page, KV head).
 hipError_t launch_suffix_ingest(const AttnArgs &a, const int32_t *d_spage_sq, int n_spages, hipStream_t s);
+// Tile records from seeds.  jobs null: tiles of a suffix launch (per-cluster tables of the cache, per-query tables of
+// the plan); jobs given: tiles of a batched prefix prefill.
+struct ExpandArgs {
+    const TileSeed *seeds;
+    Tile *tiles;
+    int32_t n;
+    const PrefixJob *jobs;
+    const int32_t *page_table, *pt_off, *prefix_len;      // the cache's device tables
+    const int32_t *cl_tok_off, *sq_tok0, *sq_src0, *sq_len, *sq_page0;      // the plan's
+};
+hipError_t launch_expand_tiles(const ExpandArgs &e, hipStream_t s);
 
 hipError_t launch_attn_generic(const AttnArgs &a, int64_t n_rows, hipStream_t s);
 // Decode, per (query, head): attention over the query's own keys (the step's new token was appended to the suffix
 // pages by the cached-part launch before) merged with the cached-prefix part.  head_dim 128, bf16.
 hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s);
 hipError_t launch_fill_zero_bytes(void *p, size_t bytes, hipStream_t s);
+// bytes (a multiple of 4, both pointers 16-byte aligned) from mapped host memory to device memory, read by a kernel
+hipError_t launch_copy_from_host(void *dst, const void *mapped_src, size_t bytes, hipStream_t s);
 // Projections: the bf16 matrix-core kernel (K a multiple of 64, N a multiple of 128; qkv selects the fused
 // epilogue) and a kernel for every other shape and type that deals columns [0, n0), [n0, n0 + n1) and the rest
 // to three row-major matrices (c0 may be null to drop its columns).

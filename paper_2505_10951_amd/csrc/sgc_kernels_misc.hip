@@ -551,6 +551,64 @@ __global__ void __launch_bounds__(64) decode_own_keys_kernel(DecodeArgs a)
     }
 }
 
+// ---- tile records -----------------------------------------------------------------------------
+// One thread per tile: the record the attention kernel reads, put together from the tile's seed and from the tables
+// the device holds (the cluster's prompt length and pages, the plan's per-query records).
+__global__ void expand_tiles_kernel(ExpandArgs e)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= e.n) return;
+    const TileSeed sd = e.seeds[i];
+    Tile t;
+    t.cluster = sd.cluster;
+    t.hk = sd.hk;
+    t.row0 = sd.row0;
+    t.n_rows = sd.n_rows;
+    t.prefix_len = 0;
+    t.pt_off = 0;
+    t.tok_base = 0;
+    t.sq_lo = sd.sq_lo;
+    t.sq_hi = sd.sq_hi;
+    t.last_qpos = sd.last_qpos;
+    t.n_q = sd.sq_hi - sd.sq_lo + 1;
+    t.pad = 0;
+#pragma unroll
+    for (int k = 0; k < 12; ++k) t.first_pages[k] = 0;
+#pragma unroll
+    for (int k = 0; k < kTileQueries; ++k) t.q[k] = {INT32_MAX, 0, 0, 0};
+    if (sd.n_rows > 0) {
+        if (e.jobs) {
+            const PrefixJob &j = e.jobs[sd.cluster];
+            t.cluster = j.cluster;
+            t.prefix_len = j.prefix_len;
+            t.pt_off = j.pt_off;
+            t.tok_base = sd.cluster;          // prefix mode: the job index travels here
+            t.sq_lo = 0;
+            t.sq_hi = -1;
+            t.last_qpos = 0;
+            t.n_q = 0;
+        } else {
+            t.prefix_len = e.prefix_len[sd.cluster];
+            t.pt_off = e.pt_off[sd.cluster];
+            t.tok_base = e.cl_tok_off[sd.cluster];
+#pragma unroll
+            for (int k = 0; k < kTileQueries; ++k) {
+                const int sq = sd.sq_lo + k;
+                if (sq <= sd.sq_hi) t.q[k] = {e.sq_tok0[sq], e.sq_src0[sq], e.sq_len[sq], e.sq_page0[sq]};
+            }
+        }
+        const int n_pages = (t.prefix_len + kPageTokens - 1) / kPageTokens;
+        if (n_pages > 0) {
+#pragma unroll
+            for (int k = 0; k < 12; ++k) t.first_pages[k] = e.page_table[t.pt_off + min(k, n_pages - 1)];
+        }
+    } else {
+        t.cluster = 0;
+        t.n_q = 0;
+    }
+    e.tiles[i] = t;
+}
+
 __global__ void fill_zero_bytes_kernel(uint4 *p, size_t n16)
 {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
@@ -771,6 +829,13 @@ hipError_t launch_prefix_ingest(const PoolGeom &g, int layer, const int32_t *d_p
     return hipGetLastError();
 }
 
+hipError_t launch_expand_tiles(const ExpandArgs &e, hipStream_t s)
+{
+    if (e.n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(expand_tiles_kernel, dim3((e.n + 127) / 128), dim3(128), 0, s, e);
+    return hipGetLastError();
+}
+
 hipError_t launch_suffix_ingest(const AttnArgs &a, const int32_t *d_spage_sq, int n_spages, hipStream_t s)
 {
     if (n_spages <= 0) return hipSuccess;
@@ -792,6 +857,28 @@ hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s)
         case 2: hipLaunchKernelGGL(decode_own_keys_kernel<2>, grid, dim3(64), lds, s, d); break;
         default: hipLaunchKernelGGL(decode_own_keys_kernel<1>, grid, dim3(64), lds, s, d); break;
     }
+    return hipGetLastError();
+}
+
+// The tables a batch sends to the device are a few hundred KiB at most.  A copy engine transfer of that size spends most of
+// its 25-35 us getting started; a kernel that reads the pinned, mapped staging buffer over the host link is done in
+// the time the link needs.
+__global__ void copy_from_host_kernel(uint4 *dst, const uint4 *src, size_t n16, size_t n4)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+    uint32_t *d4 = reinterpret_cast<uint32_t *>(dst + n16);
+    const uint32_t *s4 = reinterpret_cast<const uint32_t *>(src + n16);
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) d4[i] = s4[i];
+}
+
+hipError_t launch_copy_from_host(void *dst, const void *mapped_src, size_t bytes, hipStream_t s)
+{
+    if (bytes == 0) return hipSuccess;
+    const size_t n16 = bytes / 16, n4 = (bytes % 16) / 4;
+    const unsigned blocks = (unsigned)std::min<size_t>(std::max<size_t>((n16 + 255) / 256, 1), 1024);
+    hipLaunchKernelGGL(copy_from_host_kernel, dim3(blocks), dim3(256), 0, s, static_cast<uint4 *>(dst),
+                       static_cast<const uint4 *>(mapped_src), n16, n4);
     return hipGetLastError();
 }
 

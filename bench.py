@@ -28,8 +28,14 @@ HBM_PEAK_GBS = 8000.0
 # plain copy of known size (--copy-calibration).  Keyed by workload; the runs and the arithmetic are written down
 # in the named file under profiles/.  A workload that has not been measured this way reports null.
 PROFILED_HBM_BYTES_PER_LAUNCH = {
-    "llama3_8b_layer": (3.226e8, "profiles/attn_mfma_suffix_llama3_8b_layer.md"),
+    ("llama3_8b_layer", "16bit"): (3.226e8, "profiles/attn_mfma_suffix_llama3_8b_layer.md"),
+    ("llama2_7b_ragged", "16bit"): (2.989e9, "profiles/suffix_prefill_all_configs.md"),
+    ("llama70b_fp8_long", "fp8_first_product"): (1.888e10, "profiles/suffix_prefill_all_configs.md"),
 }
+# The same for one decode step of configs[1] (cached-prompt part 58.5 MB + own-keys kernel 93.1 MB) and for the QKV
+# projection of its batch at d_model 4096.
+PROFILED_DECODE_STEP_BYTES = {"llama3_8b_layer": (1.516e8, "profiles/decode_llama3_8b_layer.md")}
+PROFILED_QKV_GEMM_BYTES = {("llama3_8b_layer", 4096): (1.532e9, "profiles/proj_gemm_llama3_8b_layer.md")}
 TOLERANCE = {"f32": 2e-5, "bf16": 2e-2, "fp8_e4m3": 6e-2}     # max-abs bars against the fp64 oracle
 
 # Other ceilings of the matrix-core attention kernel, beside the datasheet MFMA peak (all in TFLOP/s of attention flop):
@@ -193,7 +199,9 @@ def decode_measurement(s, w, layer, n_steps, dq, dk, dv, do, all_clusters, pq_pt
             "us_per_query_step": mean_ms * 1e3 / max(int(live.sum()), 1),
             "algorithmic_bytes_per_step": alg_bytes, "flop_per_step": flop,
             "roofline": {"bound": "hbm", "achieved": alg_bytes / (mean_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": alg_bytes / (mean_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None},
+                         "frac": alg_bytes / (mean_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "traffic": PROFILED_DECODE_STEP_BYTES.get(w.name, (None, None))[0],
+                         "traffic_source": PROFILED_DECODE_STEP_BYTES.get(w.name, (None, None))[1]},
             "bytes_if_every_query_read_its_prefix": per_query_read}
 
 
@@ -259,7 +267,9 @@ def layer_measurement(s, w, layer, d_model, reps, stream):
             "suffix_layer_us_per_query": suffix_ms * 1e3 / max(w.n_queries, 1),
             "roofline": {"kernel": "proj_gemm_kernel<true> (QKV projection, keys and values written into suffix pages)",
                          "bound": "mfma" if w.io_dtype == "bf16" else "alu", "achieved": gemm["tflops"], "peak": peak,
-                         "unit": "TFLOP/s", "frac": gemm["tflops"] / peak, "traffic": None}}
+                         "unit": "TFLOP/s", "frac": gemm["tflops"] / peak,
+                         "traffic": PROFILED_QKV_GEMM_BYTES.get((w.name, d_model), (None, None))[0],
+                         "traffic_source": PROFILED_QKV_GEMM_BYTES.get((w.name, d_model), (None, None))[1]}}
 
 
 def other_config(index: int, steps: int, warmup: int, threads: int, kernel=None):
@@ -322,7 +332,7 @@ def other_config(index: int, steps: int, warmup: int, threads: int, kernel=None)
                  "peak_is": "harmonic mean of the fp8 and bf16 dense peaks (half the flops at each rate)"}
     elif w.kv_dtype == "fp8_e4m3":
         path = "e4m3 codes widened to 16-bit on their way into LDS, 16-bit matrix-core products"
-    prof = PROFILED_HBM_BYTES_PER_LAUNCH.get(w.name)
+    prof = PROFILED_HBM_BYTES_PER_LAUNCH.get((w.name, "fp8_first_product" if kernel == sgc.SGC_KERNEL_MFMA_FP8 else "16bit"))
     return {"workload": f"configs[{index}] {w.name}: Hq {w.n_q_heads} Hkv {w.n_kv_heads} d {w.head_dim}, {w.n_clusters} clusters, "
                         f"prefix {int(w.prefix_len.min())}-{int(w.prefix_len.max())}, {w.n_queries} queries, "
                         f"{w.total_suffix_tokens} suffix tokens, io {w.io_dtype}, kv {w.kv_dtype}",
@@ -490,7 +500,7 @@ def main() -> int:
     dtype = w.io_dtype
     peak = PEAK_TFLOPS[dtype]
     achieved = fl_suffix / (attn_ms * 1e-3) / 1e12
-    prof = PROFILED_HBM_BYTES_PER_LAUNCH.get(w.name)
+    prof = PROFILED_HBM_BYTES_PER_LAUNCH.get((w.name, "fp8_first_product" if kinds[args.kernel] == sgc.SGC_KERNEL_MFMA_FP8 else "16bit"))
     mfma = dtype == "bf16" and w.head_dim == 128
     out = {
         "metric": "suffix-prefill attention TFLOP/s (% MFMA peak) and us/query vs CPU oracle",

@@ -28,7 +28,11 @@
  *     reference to q/k/v/o buffers after the call's work has been enqueued on the stream; the
  *     caller must keep them alive until that stream work has finished.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Launches are
- *     asynchronous on it.
+ *     asynchronous on it.  Use ONE stream for all the work of a context: the tables the library
+ *     keeps on the device (page tables, rotary table, plan arrays, pages handed back by
+ *     sgc_cache_free_cluster) are rewritten in stream order, behind the launches that read the
+ *     old content on the same stream; work that still reads them on another stream is not waited
+ *     for.  A caller that changes streams synchronises the old one first.
  *   - Argument checking happens on the host before anything is enqueued.
  *   - The library allocates small device-side metadata of its own (rotary table, page tables,
  *     plan arrays, fp8 scales) the first time a launch needs them; the big buffers (page pool,

@@ -433,8 +433,8 @@ void build_decode_tiles(sgc_plan *pl, int tile_rows)
     // A step has few rows (one per query and head), so few row tiles: the cached keys of every row tile are split
     // into S ranges of whole 64-key steps, each range a tile of its own whose partial result the own-keys kernel
     // merges.  A tile's fixed work (record, Q, store) costs about as much as eight steps, so S stays small: at
-    // most one tile per CU, at least eight steps per range (measured on 80 row tiles x 16 steps: S = 1, 2, 3, 4, 6
-    // -> 60, 57, 57, 62, 65 us per decode step).
+    // most one tile per CU, at least eight steps per range (measured on 80 row tiles x 16 steps: S = 2, 3, 4, 6
+    // -> 42, 44, 45, 49 us per decode step).
     int S = row_tiles > 0 ? (int)std::min<int64_t>(kDecodeMaxSplits, 256 / row_tiles) : 1;
     S = std::max(1, std::min(S, max_steps / 8));
     if (max_steps >= (1 << 24) / 64) S = 1;      // the position offset travels in 24 bits of the tile record
@@ -1328,6 +1328,7 @@ static int decode_step(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, int32_t 
     for (int32_t len : pl->sq_len) longest = std::max(longest, len);
     d.key_cap = (longest + pl->decode_cap + kPageTokens - 1) / kPageTokens * kPageTokens;
     d.scale_log2e = ctx->scale * 1.4426950408889634f;
+    d.use_mfma = ctx->use_mfma ? 1 : 0;
 
     AttnArgs a;
     fill_common_args(a, ctx, c, layer);

@@ -163,6 +163,7 @@ struct DecodeArgs {
     const float2 *rope;
     int32_t n_sq, n_queries, step, n_q_heads, n_kv_heads;
     int32_t key_cap;              // multiple of 16, >= every query's len + step + 1, <= kDecodeMaxKeys
+    int32_t use_mfma;             // head_dim 128 and 16-bit rows: the matrix-core form of the own-keys kernel may run
     float scale_log2e;
 };
 

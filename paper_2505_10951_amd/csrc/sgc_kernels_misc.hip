@@ -609,6 +609,182 @@ __global__ void expand_tiles_kernel(ExpandArgs e)
     e.tiles[i] = t;
 }
 
+// The same step on the matrix cores, head_dim 128, groups of up to 16 query heads per KV head: one wavefront per (sorted
+// query, KV head), no LDS.  v_mfma_f32_16x16x32: a page's 16 tokens are the 16 rows of the first product's left operand
+// (32 channels per instruction are 1 KiB of the page, in lane order), the group's heads are its columns (the unused columns
+// carry zeros), so lane (j, q) = (lane % 16, lane / 16) ends up with the scores of head j against tokens 4 q .. 4 q + 3 of
+// every page.  Those four values of two neighbouring pages are, as they stand, the lane's eight contraction slots of the
+// second product (keys x heads), whose left operand V^T takes, per lane, the 8-byte run of four tokens of channel
+// 16 cb + lane % 16 from each of the two pages.  Keys come in chunks of 4 pages with an online softmax over the chunks.
+typedef __attribute__((ext_vector_type(8))) _Float16 dec_f16x8;
+typedef __attribute__((ext_vector_type(8))) __bf16 dec_bf16x8;
+typedef __attribute__((ext_vector_type(4))) float dec_f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t dec_u32x4;
+
+__global__ void __launch_bounds__(256, 3) decode_own_keys_mfma_kernel(DecodeArgs a)
+{
+    constexpr int d = 128, half = 64, CH = 4;        // CH: pages per chunk
+    const int lane = threadIdx.x & 63;
+    const int Hq = a.n_q_heads, Hkv = a.n_kv_heads, g = Hq / Hkv;
+    const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (unit >= a.n_sq * Hkv) return;                 // (no barrier anywhere in this kernel)
+    const int sq = unit / Hkv, hk = unit - sq * Hkv;
+    const int j = lane & 15, q = lane >> 4;
+    const int n = a.sq_query[sq];
+    const int n_keys = a.sq_len[sq] + a.step + 1;
+    const int P = a.cl_prefix_len[a.sq_cluster[sq]];
+    const int n_pages = (n_keys + kPageTokens - 1) / kPageTokens;
+    const bool live = j < g;                           // the lane's column is a head of the group
+    const int h = hk * g + (live ? j : 0);
+    const int64_t io = ((int64_t)n * Hq + h) * d;
+    const int64_t part = (int64_t)kPageTokens * d * 2;
+    const int64_t page_stride = 2 * Hkv * part;
+    const char *pages = a.spool + (int64_t)a.sq_page0[sq] * page_stride + (int64_t)hk * part;
+
+    // the query rows as right operands: chunk c8 = 4 cbk + q of 8 channels for cbk = 0..3; the rotation pairs chunk c8 with
+    // chunk c8 + 8, both of which this lane holds (cbk and cbk + 2)
+    dec_f16x8 qb[4];
+    {
+        float x1[2][8], x2[2][8];
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            const int c0 = 8 * (4 * cb + q);
+            load8(a.q, io + c0, SGC_BF16, x1[cb]);
+            load8(a.q, io + half + c0, SGC_BF16, x2[cb]);
+            if (a.rope) rope8(x1[cb], x2[cb], a.rope + (int64_t)(P + n_keys - 1) * half + c0);
+        }
+        const float sc = live ? a.scale_log2e : 0.f;
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                qb[cb][e] = (_Float16)(x1[cb][e] * sc);
+                qb[cb + 2][e] = (_Float16)(x2[cb][e] * sc);
+            }
+    }
+
+    dec_f32x4 O[8];
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) O[cb] = dec_f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;
+    for (int pg0 = 0; pg0 < n_pages; pg0 += CH) {
+        // scores of the chunk (log2 units): pages past the last are read as the last page again and masked
+        dec_f32x4 S[CH];
+        {
+            dec_u32x4 ka[CH][4];
+#pragma unroll
+            for (int p = 0; p < CH; ++p) {
+                const char *kp = pages + (int64_t)min(pg0 + p, n_pages - 1) * page_stride + lane * 16;
+#pragma unroll
+                for (int cbk = 0; cbk < 4; ++cbk) ka[p][cbk] = *reinterpret_cast<const dec_u32x4 *>(kp + cbk * 1024);
+            }
+#pragma unroll
+            for (int p = 0; p < CH; ++p) {
+                dec_f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int cbk = 0; cbk < 4; ++cbk)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(dec_f16x8, ka[p][cbk]), qb[cbk], acc, 0, 0, 0);
+                S[p] = acc;
+            }
+        }
+        float cmax = -INFINITY;
+#pragma unroll
+        for (int p = 0; p < CH; ++p)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int key = (pg0 + p) * kPageTokens + 4 * q + r;
+                if (key >= n_keys) S[p][r] = -INFINITY;
+                cmax = fmaxf(cmax, S[p][r]);
+            }
+        cmax = fmaxf(cmax, __shfl_xor(cmax, 16));
+        cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
+        const float m_new = fmaxf(m_run, cmax);          // finite: every chunk holds at least one visible key
+        const float alpha = exp2f(m_run - m_new);         // 0 on the first chunk
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) O[cb][r] *= alpha;
+        // weights, rounded to bf16 (the row sum adds the rounded values), two pages = one right operand
+#pragma unroll
+        for (int pp = 0; pp < CH / 2; ++pp) {
+            if (pg0 + 2 * pp >= n_pages) break;            // (wave-uniform)
+            uint16_t w[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                w[e] = f32_to_bf16(exp2f(S[2 * pp + (e >> 2)][e & 3] - m_new));
+                l_run += bf16_to_f32(w[e]);
+            }
+            const dec_u32x4 wb = {(uint32_t)w[0] | ((uint32_t)w[1] << 16), (uint32_t)w[2] | ((uint32_t)w[3] << 16),
+                                  (uint32_t)w[4] | ((uint32_t)w[5] << 16), (uint32_t)w[6] | ((uint32_t)w[7] << 16)};
+            const char *va = pages + (int64_t)min(pg0 + 2 * pp, n_pages - 1) * page_stride + (int64_t)Hkv * part;
+            const char *vb = pages + (int64_t)min(pg0 + 2 * pp + 1, n_pages - 1) * page_stride + (int64_t)Hkv * part;
+            uint2 v0[8], v1[8];
+#pragma unroll
+            for (int cb = 0; cb < 8; ++cb) {
+                // channel 16 cb + j: 32-channel group cb / 2, token block q & 1, channel (cb % 2) * 16 + j inside it, tokens
+                // 4 q .. 4 q + 3 = the half 8 (q >> 1) of the 16-byte run
+                const int off = ((((cb >> 1) * 2 + (q & 1)) * 32 + (cb & 1) * 16 + j) * 16) + 8 * (q >> 1);
+                v0[cb] = *reinterpret_cast<const uint2 *>(va + off);
+                v1[cb] = *reinterpret_cast<const uint2 *>(vb + off);
+            }
+#pragma unroll
+            for (int cb = 0; cb < 8; ++cb) {
+                const dec_u32x4 av = {v0[cb].x, v0[cb].y, v1[cb].x, v1[cb].y};
+                O[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(dec_bf16x8, av), __builtin_bit_cast(dec_bf16x8, wb), O[cb], 0, 0, 0);
+            }
+        }
+    }
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    if (!live) return;
+    // merge with the cached-prefix part (natural-log LSE there, -inf for an empty range; log2 units here); the lane holds
+    // channels 16 cb + 4 q .. + 3 of its head
+    const uint16_t *oc = static_cast<const uint16_t *>(a.o_cached);
+    uint16_t *og = static_cast<uint16_t *>(a.o);
+    const int S_n = a.n_splits;
+    const float lse_own = m_run + log2f(l_run);
+    float lse_c[kDecodeMaxSplits];
+    float M = lse_own;
+#pragma unroll
+    for (int sp = 0; sp < kDecodeMaxSplits; ++sp) {
+        lse_c[sp] = -INFINITY;
+        if (sp < S_n && a.lse_cached) lse_c[sp] = a.lse_cached[sp * a.split_lse_elems + (int64_t)h * a.n_queries + n] * 1.4426950408889634f;
+        M = fmaxf(M, lse_c[sp]);
+    }
+    const float wo = exp2f(m_run - M);                        // weight of the unnormalised own sum
+    float denom = exp2f(lse_own - M);
+    float sum[8][4];
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sum[cb][r] = wo * O[cb][r];
+#pragma unroll
+    for (int sp = 0; sp < kDecodeMaxSplits; ++sp) {
+        if (!(lse_c[sp] > -INFINITY)) continue;
+        const float wc = exp2f(lse_c[sp] - M);
+        denom += wc;
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) {
+            const uint2 raw = *reinterpret_cast<const uint2 *>(oc + sp * a.split_o_elems + io + cb * 16 + 4 * q);
+            sum[cb][0] += wc * bf16_to_f32((uint16_t)(raw.x & 0xFFFF));
+            sum[cb][1] += wc * bf16_to_f32((uint16_t)(raw.x >> 16));
+            sum[cb][2] += wc * bf16_to_f32((uint16_t)(raw.y & 0xFFFF));
+            sum[cb][3] += wc * bf16_to_f32((uint16_t)(raw.y >> 16));
+        }
+    }
+    const float inv = 1.0f / denom;
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb) {
+        uint2 out;
+        out.x = (uint32_t)f32_to_bf16(sum[cb][0] * inv) | ((uint32_t)f32_to_bf16(sum[cb][1] * inv) << 16);
+        out.y = (uint32_t)f32_to_bf16(sum[cb][2] * inv) | ((uint32_t)f32_to_bf16(sum[cb][3] * inv) << 16);
+        *reinterpret_cast<uint2 *>(og + io + cb * 16 + 4 * q) = out;
+    }
+    if (a.lse && q == 0) a.lse[(int64_t)h * a.n_queries + n] = (M + log2f(denom)) * 0.6931471805599453f;
+}
+
 __global__ void fill_zero_bytes_kernel(uint4 *p, size_t n16)
 {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
@@ -848,6 +1024,11 @@ hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s)
 {
     if (d.n_sq <= 0) return hipSuccess;
     const int g = d.n_q_heads / d.n_kv_heads;
+    if (d.use_mfma && g <= 16) {                  // head_dim 128, bf16 rows: the matrix-core form
+        const int units = d.n_sq * d.n_kv_heads;
+        hipLaunchKernelGGL(decode_own_keys_mfma_kernel, dim3((units + 3) / 4), dim3(256), 0, s, d);
+        return hipGetLastError();
+    }
     const int G = g % 8 == 0 ? 8 : g % 4 == 0 ? 4 : g % 2 == 0 ? 2 : 1;      // heads per wavefront
     const dim3 grid((unsigned)((int64_t)d.n_sq * (d.n_q_heads / G)));
     const size_t lds = (size_t)G * (128 * 2 + (size_t)d.key_cap * (4 + 2));      // q rows (bf16), scores (fp32), weights (bf16)

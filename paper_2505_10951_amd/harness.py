@@ -4,6 +4,7 @@ order SubGCache Sec. 3.4 prescribes: allocate a cluster's cache, prefill its pre
 the batch's queries to their clusters, run every query's suffix prefill, release."""
 from __future__ import annotations
 
+import os
 from typing import Dict, List, Optional
 
 import numpy as np
@@ -246,7 +247,7 @@ def run_workload(w: Workload, layer: int = 0, kernel: int = sgc.SGC_KERNEL_AUTO,
             s.alloc_cluster(c)
             s.prefix_prefill(c, layer)
         order, off, cu = s.assign()
-        q, k, v = w.suffix_qkv(layer)
+        q, k, v = w.suffix_qkv(layer, threads=min(16, os.cpu_count() or 1))      # (the values do not depend on the thread count)
         dq, dk, dv = (to_device(x, w.io_dtype) for x in (q, k, v))
         T = q.shape[0]
         dlse = torch.zeros((w.n_q_heads, max(T, 1)), dtype=torch.float32, device="cuda:0") if want_lse else None

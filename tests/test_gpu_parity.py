@@ -309,6 +309,37 @@ def test_physical_page_order_does_not_matter():
         assert np.array_equal(to_host_f32(do), ref["o"])
 
 
+def test_plan_outlives_a_reallocation_of_its_clusters():
+    """A plan is launched, its clusters are released and allocated again on other pages (same prompts), and the same plan
+    is launched once more: the tile records it keeps on the device have to follow the new page tables."""
+    w = _small_gqa(seed=53)
+    ref = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
+    with Session(w, kernel=sgc.SGC_KERNEL_MFMA, total_pages=300, max_clusters=8) as s:
+        for c in range(3):
+            s.alloc_cluster(c)
+            s.prefix_prefill(c)
+        s.assign()
+        q, k, v = w.suffix_qkv()
+        dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+        do = s.suffix_prefill(dq, dk, dv)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host_f32(do), ref["o"])
+        before = [sgc.sgc_cache_cluster_pages(s.ctx, s.cache, c)[0].copy() for c in range(3)]
+        for c in range(3):
+            s.free_cluster(c)
+        sgc.sgc_cache_alloc_cluster(s.ctx, s.cache, 7, 50)          # takes the pages the first cluster had
+        for c in (2, 0, 1):
+            s.alloc_cluster(c)
+        after = [sgc.sgc_cache_cluster_pages(s.ctx, s.cache, c)[0] for c in range(3)]
+        assert all(not np.array_equal(a, b) for a, b in zip(before, after))
+        for c in range(3):
+            s.prefix_prefill(c)
+        do.zero_()
+        do = s.suffix_prefill(dq, dk, dv, do=do)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host_f32(do), ref["o"])
+
+
 # ---- fp8 e4m3 cache --------------------------------------------------------------------------
 def test_fp8_codec_and_quantised_cache_match_oracle():
     # all 256 codes decode as the oracle says; encoding agrees on every code point and midpoint

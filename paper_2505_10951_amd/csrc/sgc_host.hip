@@ -733,18 +733,17 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
         jobs.push_back(j);
     }
     // Tile list of the MFMA attention: units (job, KV head) are dealt, heaviest first, to the XCD with the
-    // least work so far, each XCD's tiles longest first; workgroup b runs on XCD b % 8.
-    struct Light {
-        int32_t job, hk, row0;
+    // least work so far, each XCD's tiles longest first; workgroup b runs on XCD b % 8.  Only the list's length is
+    // needed before the ingest kernel is launched; the seeds are written while it runs.
+    struct Unit {
+        int job, hk;
     };
-    std::vector<std::vector<Light>> lists(kXcd);
+    std::vector<Unit> units;
+    std::array<std::vector<int>, kXcd> of_xcd;
+    const int rows_per_tile = ctx->tile_rows;
+    auto tiles_of = [&](const Unit &u) { return (int)(((int64_t)jobs[u.job].prefix_len * g + rows_per_tile - 1) / rows_per_tile); };
     size_t slots = 0;
     if (any_q && ctx->use_mfma) {
-        const int rows_per_tile = ctx->tile_rows;
-        struct Unit {
-            int job, hk;
-        };
-        std::vector<Unit> units;
         std::vector<double> work;
         for (int ji = 0; ji < (int)jobs.size(); ++ji)
             if (jobs[ji].q)
@@ -752,21 +751,11 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
                     units.push_back({ji, hk});
                     work.push_back((double)jobs[ji].prefix_len * jobs[ji].prefix_len);
                 }
-        const auto of_xcd = deal_to_xcds(work);
-        // a unit's tile t starts at row t * rows_per_tile; descending t, units in dealing order among equals
-        auto tiles_of = [&](const Unit &u) { return (int)(((int64_t)jobs[u.job].prefix_len * g + rows_per_tile - 1) / rows_per_tile); };
+        of_xcd = deal_to_xcds(work);
         for (int x = 0; x < kXcd; ++x) {
-            int most = 0;
             size_t all = 0;
-            for (int ui : of_xcd[x]) {
-                most = std::max(most, tiles_of(units[ui]));
-                all += (size_t)tiles_of(units[ui]);
-            }
-            lists[x].reserve(all);
-            for (int t = most - 1; t >= 0; --t)
-                for (int ui : of_xcd[x])
-                    if (t < tiles_of(units[ui])) lists[x].push_back({units[ui].job, units[ui].hk, t * rows_per_tile});
-            slots = std::max(slots, lists[x].size());
+            for (int ui : of_xcd[x]) all += (size_t)tiles_of(units[ui]);
+            slots = std::max(slots, all);
         }
     }
     // One block: [jobs][job of each page][tile seeds] from the host in one copy, then room for the tile records, which a
@@ -796,19 +785,25 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
     if (e == hipSuccess && !attend_only)
         e = launch_prefix_ingest(c->geom, layer, c->d_page_table, d_jobs, (int)jobs.size(), d_page_job, (int)page_job.size(),
                                  ctx->p.io_dtype, ctx->p.rope_base > 0.0f ? ctx->d_rope : nullptr, s);
+    // a unit's tile t starts at row t * rows_per_tile; descending t, units in dealing order among equals; slot k of XCD x
+    // is tile k * 8 + x of the launch (slots a short list does not fill stay padding tiles: n_rows = 0)
     TileSeed *hs = reinterpret_cast<TileSeed *>(host + jobs_bytes + pj_bytes);
+    memset(hs, 0, n_tiles * sizeof(TileSeed));
     for (int x = 0; x < kXcd; ++x) {
-        for (size_t k = 0; k < slots; ++k) {
-            TileSeed &sd = hs[k * kXcd + x];
-            sd = TileSeed{};                          // padding tile: n_rows = 0
-            if (k >= lists[x].size()) continue;
-            const Light &lt = lists[x][k];
-            sd.cluster = lt.job;
-            sd.hk = lt.hk;
-            sd.row0 = lt.row0;
-            sd.n_rows = (int32_t)std::min<int64_t>(ctx->tile_rows, (int64_t)jobs[lt.job].prefix_len * g - lt.row0);
-            sd.sq_hi = -1;
-        }
+        int most = 0;
+        for (int ui : of_xcd[x]) most = std::max(most, tiles_of(units[ui]));
+        size_t k = 0;
+        for (int t = most - 1; t >= 0; --t)
+            for (int ui : of_xcd[x]) {
+                const Unit &u = units[ui];
+                if (t >= tiles_of(u)) continue;
+                TileSeed &sd = hs[k++ * kXcd + x];
+                sd.cluster = u.job;
+                sd.hk = u.hk;
+                sd.row0 = t * rows_per_tile;
+                sd.n_rows = (int32_t)std::min<int64_t>(rows_per_tile, (int64_t)jobs[u.job].prefix_len * g - sd.row0);
+                sd.sq_hi = -1;
+            }
     }
     // the seeds, and the event that says the staging buffer has been read
     rc = stage_commit(ctx, slot, blk.p + jobs_bytes + pj_bytes, e == hipSuccess ? seeds_bytes : 0, s, jobs_bytes + pj_bytes);

@@ -5,6 +5,7 @@ the batch's queries to their clusters, run every query's suffix prefill, release
 from __future__ import annotations
 
 import os
+from concurrent.futures import ThreadPoolExecutor
 from typing import Dict, List, Optional
 
 import numpy as np
@@ -242,12 +243,17 @@ class Session:
 def run_workload(w: Workload, layer: int = 0, kernel: int = sgc.SGC_KERNEL_AUTO, want_lse: bool = True) -> Dict:
     """Whole path for one layer: fill every cluster's cache, assign, batched suffix prefill.
     Returns host arrays: o [T][Hq][d] fp32, lse [Hq][T], order, cluster_off, cu_seqlens."""
+    threads = min(16, os.cpu_count() or 1)
     with Session(w, kernel=kernel) as s:
+        # the prompts' keys and values are generated on several threads (a cluster's values do not depend on that)
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            kvs = list(ex.map(lambda c: w.prefix_kv(c, layer), range(w.n_clusters)))
         for c in range(w.n_clusters):
             s.alloc_cluster(c)
-            s.prefix_prefill(c, layer)
+            s.prefix_prefill(c, layer, k=kvs[c][0], v=kvs[c][1])
+        del kvs
         order, off, cu = s.assign()
-        q, k, v = w.suffix_qkv(layer, threads=min(16, os.cpu_count() or 1))      # (the values do not depend on the thread count)
+        q, k, v = w.suffix_qkv(layer, threads=threads)
         dq, dk, dv = (to_device(x, w.io_dtype) for x in (q, k, v))
         T = q.shape[0]
         dlse = torch.zeros((w.n_q_heads, max(T, 1)), dtype=torch.float32, device="cuda:0") if want_lse else None

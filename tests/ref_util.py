@@ -2,6 +2,7 @@
 rounding points (numpy, dense) used only to calibrate how tight a tolerance can be."""
 from __future__ import annotations
 
+import os
 from typing import Dict, Optional, Sequence
 
 import numpy as np
@@ -10,17 +11,23 @@ from oracle import oracle as orc
 from paper_2505_10951_amd.workloads import Workload, round_to_bf16
 
 
-def oracle_caches(w: Workload, layer: int = 0, clusters: Optional[Sequence[int]] = None) -> Dict[int, tuple]:
-    """cluster -> (cache_k, cache_v) as the attention reads them (fp8: oracle-quantised, dequantised)."""
-    out = {}
-    for c in (range(w.n_clusters) if clusters is None else clusters):
+def oracle_caches(w: Workload, layer: int = 0, clusters: Optional[Sequence[int]] = None, threads: int = 1) -> Dict[int, tuple]:
+    """cluster -> (cache_k, cache_v) as the attention reads them (fp8: oracle-quantised, dequantised).  Clusters are
+    independent; with threads > 1 several are prepared at once (the oracle's routines are called as they are)."""
+    def one(c):
         k, v = w.prefix_kv(c, layer)
         ck, cv, _, _ = orc.prefix_prefill(None, k, v, w.rope_base)
         if w.kv_dtype == "fp8_e4m3":
             _, _, ck = orc.quantise_e4m3(ck)
             _, _, cv = orc.quantise_e4m3(cv)
-        out[c] = (ck, cv)
-    return out
+        return c, (ck, cv)
+
+    todo = list(range(w.n_clusters) if clusters is None else clusters)
+    if threads > 1 and len(todo) > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(threads, len(todo))) as ex:
+            return dict(ex.map(one, todo))
+    return dict(one(c) for c in todo)
 
 
 def oracle_suffix(w: Workload, layer: int = 0, queries: Optional[Sequence[int]] = None, caches=None):
@@ -29,7 +36,7 @@ def oracle_suffix(w: Workload, layer: int = 0, queries: Optional[Sequence[int]] 
     queries = list(range(w.n_queries)) if queries is None else list(queries)
     cu = w.cu_seqlens
     need = sorted({int(w.labels[n]) for n in queries})
-    caches = oracle_caches(w, layer, need) if caches is None else caches
+    caches = oracle_caches(w, layer, need, threads=min(8, os.cpu_count() or 1)) if caches is None else caches
     nc = w.n_clusters
     empty = np.zeros((0, w.n_kv_heads, w.head_dim))
     cks = [caches[c][0] if c in caches else empty for c in range(nc)]

@@ -543,8 +543,16 @@ def test_config4_llama70b_fp8_long_prefix_full_size_every_cluster(kernel):
     _check_bookkeeping(w, out)
     qs = _sampled_queries(w, 1)                     # 8 queries, one per cluster
     assert sorted(int(w.labels[n]) for n in qs) == list(range(w.n_clusters))
-    _check_suffix(w, out, queries=qs, tol=TOL_FP8)
+    if "ref" not in _CONFIG4_ORACLE:                # the oracle's rows are the same for both kernels: computed once
+        _CONFIG4_ORACLE["ref"] = oracle_suffix(w, 0, qs)
+    rows, o_ref, _ = _CONFIG4_ORACLE["ref"]
+    st = err_stats(out["o"][rows], o_ref)
+    _say(f"  {w.name}: rows {len(rows)} max_abs {st['max_abs']:.3e} rel {st['rel']:.3e} (tol {TOL_FP8:g})")
+    assert st["max_abs"] <= TOL_FP8
     assert np.isfinite(out["o"]).all()
+
+
+_CONFIG4_ORACLE = {}
 
 
 def test_streaming_schedule_release_after_each_cluster_equals_all_resident():

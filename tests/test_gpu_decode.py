@@ -118,6 +118,20 @@ def test_decode_long_prompts_split_the_cached_keys_into_ranges(kv):
     assert np.isfinite(got[0]).all() and err <= TOL[kv] and lerr <= 5e-2
 
 
+@pytest.mark.parametrize("g", [16, 1])
+def test_decode_long_questions_and_the_widest_head_group(g):
+    """Questions of up to 330 tokens (21 pages of own keys: six chunks of the own-keys kernel's online softmax, the last one
+    partly filled) and, with g = 16, as many query heads per KV head as the matrix-core form of that kernel takes."""
+    w = workloads.custom(f"decode_long_q_g{g}", n_q_heads=2 * g, n_kv_heads=2, head_dim=128, rope_base=500000.0, io_dtype="bf16",
+                         prefix_len=[90, 0], labels=[0, 1, 0, 1, 0], suffix_len=[330, 257, 63, 64, 129], seed=47)
+    n_steps = 4
+    got = _run_decode(w, n_steps)[0]
+    o_ref, lse_ref = _oracle_decode(w, 0, n_steps, oracle_caches(w, 0))
+    err, lerr = np.abs(got[0] - o_ref).max(), np.abs(got[1] - lse_ref).max()
+    print(f"  decode long questions g {g}: max_abs {err:.3e} lse {lerr:.3e}", flush=True)
+    assert np.isfinite(got[0]).all() and err <= TOL["bf16"] and lerr <= 5e-2
+
+
 @pytest.mark.parametrize("seed", [400, 401, 402, 403, 404, 405])
 def test_decode_random_shapes_against_oracle(seed):
     """Seeded random small workloads: group sizes 1-8, prompts of 0-1500 tokens (long ones split into key ranges),

@@ -171,7 +171,11 @@ def decode_measurement(s, w, layer, n_steps, dq, dk, dv, do, all_clusters, pq_pt
     to = torch.empty_like(tq)
     torch.cuda.synchronize()
     times = []
-    for rep in range(2):                      # the first pass warms up; the pages are simply overwritten again
+    t_warm = time.perf_counter()
+    rep = 0
+    while True:                               # untimed passes until the chip has worked for 60 ms, then the timed one; the pages
+        last = rep >= 1 and (time.perf_counter() - t_warm) >= 0.06      # are simply overwritten again
+        rep += 1
         times.clear()
         for t in range(n_steps):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -181,6 +185,8 @@ def decode_measurement(s, w, layer, n_steps, dq, dk, dv, do, all_clusters, pq_pt
             e1.record()
             times.append((e0, e1))
         torch.cuda.synchronize()
+        if last:
+            break
     ms = [a.elapsed_time(b) for a, b in times]
     live = w.suffix_len > 0
     S = w.suffix_len[live].astype(np.float64)
@@ -247,11 +253,16 @@ def layer_measurement(s, w, layer, d_model, reps, stream):
     s.assign(w.labels, w.suffix_len)
     s.upload_plan()
     evs = {k: [] for k in calls}
-    for rep in range(reps + 2):
+    t_warm = time.perf_counter()
+    n_warm = 0
+    while n_warm < 2 or (time.perf_counter() - t_warm) < 0.06:      # untimed rounds until the chip's clocks are up
+        for fn in calls.values():
+            fn()
+        torch.cuda.synchronize()
+        n_warm += 1
+    for rep in range(reps):
         for name, fn in calls.items():
-            pair = timed(fn)
-            if rep >= 2:
-                evs[name].append(pair)
+            evs[name].append(timed(fn))
     torch.cuda.synchronize()
     ms = {k: float(np.mean([a.elapsed_time(b) for a, b in v])) for k, v in evs.items()}
     P_total = float(w.prefix_len.sum())
@@ -299,15 +310,24 @@ def other_config(index: int, steps: int, warmup: int, threads: int, kernel=None)
         do = torch.empty_like(dq)
         s.assign(w.labels, w.suffix_len)
         s.upload_plan()
-        sgc.sgc_timing_enable(s.ctx, True)
-        for i in range(warmup + steps):
-            if i == warmup:
-                torch.cuda.synchronize()
-                sgc.sgc_timing_enable(s.ctx, True)
+        def launch():
             sgc.sgc_suffix_prefill_batched(s.ctx, s.cache, s.plan, layer, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
                                            do.data_ptr(), None, stream)
+        # untimed launches until the chip has worked for 60 ms (its clocks are up by then), at least `warmup` of them
+        t0 = time.perf_counter()
+        n_warm = 0
+        while n_warm < warmup or (time.perf_counter() - t0) < 0.06:
+            launch()
+            torch.cuda.synchronize()
+            n_warm += 1
+        per_launch = (time.perf_counter() - t0) / n_warm
+        steps = int(min(100, max(steps, np.ceil(0.06 / per_launch))))
+        warmup = n_warm
+        sgc.sgc_timing_enable(s.ctx, True)
+        for i in range(steps):
+            launch()
         torch.cuda.synchronize()
-        kernel_ms = [sgc.sgc_timing_get(s.ctx, back) for back in range(min(steps, 64))]
+        kernel_ms = [sgc.sgc_timing_get(s.ctx, back) for back in range(steps)]
         info = sgc.sgc_plan_get_info(s.ctx, s.plan)
         # two queries against the oracle: the first of the largest and of the smallest cluster
         sizes = np.bincount(w.labels, minlength=w.n_clusters)
@@ -356,8 +376,8 @@ def other_config(index: int, steps: int, warmup: int, threads: int, kernel=None)
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=1, help="which of the five benchmark configurations, 0-4 (default 1: Llama-3-8B-shaped layer)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for the CPU baseline (0 = skip)")
     ap.add_argument("--pipelined", action="store_true",
@@ -374,7 +394,11 @@ def main() -> int:
     ap.add_argument("--kernel", choices=["auto", "mfma", "mfma_fp8", "generic"], default="auto",
                     help="attention kernel of the headline configuration (auto: the matrix-core kernel where it covers the shape, "
                          "with the first product on the e4m3 codes when the cache is fp8)")
-    ap.add_argument("--other-steps", type=int, default=5, help="timed suffix launches per further configuration")
+    ap.add_argument("--other-steps", type=int, default=5,
+                    help="timed suffix launches per further configuration, at least (as many as fill 60 ms, at most 100)")
+    ap.add_argument("--settle-ms", type=float, default=100.0,
+                    help="before the warm-up steps, run untimed steps for this long: the chip raises its clocks over the first tens of "
+                         "milliseconds of work, and a handful of half-millisecond steps would be timed on the way up (0 = skip)")
     ap.add_argument("--repeat-launches", type=int, default=100,
                     help="after the timed steps, launch the suffix call this many times back to back (after 20 untimed) and report "
                          "median and minimum kernel time (0 = skip, at most 128)")
@@ -449,13 +473,18 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t_start) / args.steps * 1e3
 
+    t_settle = time.perf_counter()
+    n_settle = 0
+    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+        step(True)
+        n_settle += 1
     for _ in range(args.warmup):
         step(not args.pipelined)
     torch.cuda.synchronize()
     sgc.sgc_timing_enable(s.ctx, True)          # restart the library's count of timed launches
     ms_per_step = timed_loop(not args.pipelined)
-    # per-launch kernel durations of the timed steps, from the library's events (it keeps the last 64)
-    kernel_ms = [sgc.sgc_timing_get(s.ctx, back) for back in range(min(args.steps, 64))]
+    # per-launch kernel durations of the timed steps, from the library's events (it keeps the last 128)
+    kernel_ms = [sgc.sgc_timing_get(s.ctx, back) for back in range(min(args.steps, 128))]
     kern_ms = float(np.mean([a + b for a, b in kernel_ms]))                    # ingest + attention
     kern_ms_min = float(np.min([a + b for a, b in kernel_ms]))
     ingest_ms = float(np.mean([a for a, _ in kernel_ms]))
@@ -465,7 +494,7 @@ def main() -> int:
     other = None
     if not args.suffix_only:
         other_ms = timed_loop(bool(args.pipelined))
-        other_kernel = [sgc.sgc_timing_get(s.ctx, back)[1] for back in range(min(args.steps, 64))]
+        other_kernel = [sgc.sgc_timing_get(s.ctx, back)[1] for back in range(min(args.steps, 128))]
         other = {"mode": "host waits after every step" if args.pipelined else "steps enqueued back to back",
                  "ms_per_step": other_ms, "attention_kernel_ms": float(np.mean(other_kernel))}
 
@@ -513,7 +542,8 @@ def main() -> int:
                                f"{w.n_queries} queries, {w.total_suffix_tokens} suffix tokens, kv {w.kv_dtype}",
                    "step": "suffix launch only" if args.suffix_only else
                            "alloc + batched prefix prefill (ingest + causal attention) + assign/plan upload + batched suffix prefill + free",
-                   "tile_rows": info.tile_rows, "n_tiles": info.n_tiles},
+                   "tile_rows": info.tile_rows, "n_tiles": info.n_tiles,
+                   "settle": f"{n_settle} untimed steps ({args.settle_ms:g} ms) before the warm-up steps"},
         "step_flop": fl_step, "suffix_flop": fl_suffix,
         "suffix_launch_ms": kern_ms, "suffix_launch_ms_min": kern_ms_min,
         "suffix_ingest_kernel_ms": ingest_ms, "attention_kernel_ms": attn_ms, "attention_kernel_ms_min": attn_ms_min,

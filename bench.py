@@ -10,12 +10,26 @@ timed region.  Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import contextlib
+import gc
 import json
 import os
 import sys
 import time
 
 import numpy as np
+
+
+@contextlib.contextmanager
+def no_gc():
+    """Python's cyclic garbage collector off for a timed region, as in timeit: a full collection over the workload's
+    objects takes 35 ms of host time (seventy steps of the headline configuration) and says nothing about the path."""
+    gc.collect()
+    gc.disable()
+    try:
+        yield
+    finally:
+        gc.enable()
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
@@ -177,14 +191,15 @@ def decode_measurement(s, w, layer, n_steps, dq, dk, dv, do, all_clusters, pq_pt
         last = rep >= 1 and (time.perf_counter() - t_warm) >= 0.06      # are simply overwritten again
         rep += 1
         times.clear()
-        for t in range(n_steps):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            sgc.sgc_decode_step_batched(s.ctx, s.cache, s.plan, layer, t, tq.data_ptr(), tk.data_ptr(), tv.data_ptr(),
-                                        to.data_ptr(), None, stream)
-            e1.record()
-            times.append((e0, e1))
-        torch.cuda.synchronize()
+        with no_gc():
+            for t in range(n_steps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                sgc.sgc_decode_step_batched(s.ctx, s.cache, s.plan, layer, t, tq.data_ptr(), tk.data_ptr(), tv.data_ptr(),
+                                            to.data_ptr(), None, stream)
+                e1.record()
+                times.append((e0, e1))
+            torch.cuda.synchronize()
         if last:
             break
     ms = [a.elapsed_time(b) for a, b in times]
@@ -260,10 +275,11 @@ def layer_measurement(s, w, layer, d_model, reps, stream):
             fn()
         torch.cuda.synchronize()
         n_warm += 1
-    for rep in range(reps):
-        for name, fn in calls.items():
-            evs[name].append(timed(fn))
-    torch.cuda.synchronize()
+    with no_gc():
+        for rep in range(reps):
+            for name, fn in calls.items():
+                evs[name].append(timed(fn))
+        torch.cuda.synchronize()
     ms = {k: float(np.mean([a.elapsed_time(b) for a, b in v])) for k, v in evs.items()}
     P_total = float(w.prefix_len.sum())
     flop = {"qkv_prefix": 2.0 * P_total * d_model * (n_qkv - nq),          # the prompt's queries are not needed here
@@ -324,9 +340,10 @@ def other_config(index: int, steps: int, warmup: int, threads: int, kernel=None)
         steps = int(min(100, max(steps, np.ceil(0.06 / per_launch))))
         warmup = n_warm
         sgc.sgc_timing_enable(s.ctx, True)
-        for i in range(steps):
-            launch()
-        torch.cuda.synchronize()
+        with no_gc():
+            for i in range(steps):
+                launch()
+            torch.cuda.synchronize()
         kernel_ms = [sgc.sgc_timing_get(s.ctx, back) for back in range(steps)]
         info = sgc.sgc_plan_get_info(s.ctx, s.plan)
         # two queries against the oracle: the first of the largest and of the smallest cluster
@@ -461,17 +478,17 @@ def main() -> int:
             for c in range(w.n_clusters):
                 sgc.sgc_cache_free_cluster(s.ctx, s.cache, c)
 
-    # Default: the host waits for the GPU after every step (a step's latency; the chip gets a short rest between
-    # steps).  --pipelined enqueues the steps back to back: about 10 % more throughput, and kernels that run 8 %
-    # slower because the chip clocks lower without the rests.  The other mode is run too, after the timed steps,
+    # Default: the host waits for the GPU after every step (a step's latency).  --pipelined enqueues the steps back to
+    # back: 6-8 % more throughput, the kernels' own times the same.  The other mode is run too, after the timed steps,
     # and reported as "other_mode".
     def timed_loop(wait: bool):
         torch.cuda.synchronize()
-        t_start = time.perf_counter()
-        for _ in range(args.steps):
-            step(wait)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t_start) / args.steps * 1e3
+        with no_gc():
+            t_start = time.perf_counter()
+            for _ in range(args.steps):
+                step(wait)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t_start) / args.steps * 1e3
 
     t_settle = time.perf_counter()
     n_settle = 0

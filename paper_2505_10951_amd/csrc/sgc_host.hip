@@ -185,42 +185,46 @@ int stage_begin(sgc_ctx *ctx, size_t bytes, char **host, int *slot)
     return SGC_OK;
 }
 
-int stage_commit(sgc_ctx *ctx, int slot, void *dev, size_t bytes, hipStream_t s, size_t host_offset = 0)
+// Copies `bytes` of the slot's buffer to `dev` (and, in the same launch, bytes2 from host_offset2 to dev2) and records the
+// event that says the buffer has been read.
+int stage_commit(sgc_ctx *ctx, int slot, void *dev, size_t bytes, hipStream_t s, void *dev2 = nullptr, size_t host_offset2 = 0,
+                 size_t bytes2 = 0)
 {
-    if (bytes % 4 != 0 || (reinterpret_cast<uintptr_t>(dev) | host_offset) % 16 != 0)
-        return fail(ctx, SGC_EINVAL, "staged copy of %zu bytes is not aligned", bytes);
-    if (bytes) SGC_HIP(ctx, launch_copy_from_host(dev, ctx->h_stage_dev[slot] + host_offset, bytes, s));
+    if (bytes % 4 != 0 || bytes2 % 4 != 0 || (reinterpret_cast<uintptr_t>(dev) | reinterpret_cast<uintptr_t>(dev2) | host_offset2) % 16 != 0)
+        return fail(ctx, SGC_EINVAL, "staged copy of %zu + %zu bytes is not aligned", bytes, bytes2);
+    SGC_HIP(ctx, launch_copy_from_host(dev, ctx->h_stage_dev[slot], bytes, s, dev2, ctx->h_stage_dev[slot] + host_offset2, bytes2));
     SGC_HIP(ctx, hipEventRecord(ctx->stage_ev[slot], s));
     ctx->stage_pending[slot] = true;
     return SGC_OK;
 }
 
-// Brings the device copy of the page tables up to date with the host allocator: one array
-// [page table: total_pages][first entry per cluster: max_clusters][prefix length per cluster: max_clusters],
-// rewritten by one copy that is ordered on the stream behind the launches that read the old content.
-int cache_sync(sgc_cache *c, hipStream_t s)
+// The device copy of the page tables is one array
+// [page table: total_pages][first entry per cluster: max_clusters][prefix length per cluster: max_clusters].
+int cache_tables_ensure(sgc_cache *c)
 {
     sgc_ctx *ctx = c->ctx;
     const size_t n_pages = (size_t)c->geom.total_pages, n_cl = (size_t)c->max_clusters;
-    if (!c->d_tables) {
-        SGC_HIP(ctx, hipMalloc(&c->d_tables, sizeof(int32_t) * (n_pages + 2 * n_cl + 16)));
-        c->d_page_table = c->d_tables;
-        c->d_pt_off = c->d_tables + n_pages;
-        c->d_prefix_len = c->d_pt_off + n_cl;
-        if (ctx->p.kv_dtype == SGC_FP8_E4M3) {
-            const size_t n = n_cl * ctx->p.n_layers * 2 * ctx->p.n_kv_heads;
-            SGC_HIP(ctx, hipMalloc(&c->d_scale, sizeof(float) * n));
-            SGC_HIP(ctx, hipMemset(c->d_scale, 0, sizeof(float) * n));
-        }
-        c->dirty = true;
+    if (c->d_tables) return SGC_OK;
+    SGC_HIP(ctx, hipMalloc(&c->d_tables, sizeof(int32_t) * (n_pages + 2 * n_cl + 16)));
+    c->d_page_table = c->d_tables;
+    c->d_pt_off = c->d_tables + n_pages;
+    c->d_prefix_len = c->d_pt_off + n_cl;
+    if (ctx->p.kv_dtype == SGC_FP8_E4M3) {
+        const size_t n = n_cl * ctx->p.n_layers * 2 * ctx->p.n_kv_heads;
+        SGC_HIP(ctx, hipMalloc(&c->d_scale, sizeof(float) * n));
+        SGC_HIP(ctx, hipMemset(c->d_scale, 0, sizeof(float) * n));
     }
-    if (!c->dirty) return SGC_OK;
-    char *host = nullptr;
-    int slot = 0;
-    const size_t bytes = sizeof(int32_t) * (n_pages + 2 * n_cl);
-    int rc = stage_begin(ctx, bytes, &host, &slot);
-    if (rc != SGC_OK) return rc;
-    int32_t *flat = reinterpret_cast<int32_t *>(host), *off = flat + n_pages, *plen = off + n_cl;
+    c->dirty = true;
+    return SGC_OK;
+}
+
+size_t cache_tables_bytes(const sgc_cache *c) { return sizeof(int32_t) * ((size_t)c->geom.total_pages + 2 * (size_t)c->max_clusters); }
+
+// The tables as the host allocator has them now.
+void cache_tables_fill(const sgc_cache *c, int32_t *flat)
+{
+    const size_t n_pages = (size_t)c->geom.total_pages, n_cl = (size_t)c->max_clusters;
+    int32_t *off = flat + n_pages, *plen = off + n_cl;
     size_t n = 0;
     for (size_t i = 0; i < n_cl; ++i) {
         off[i] = (int32_t)n;
@@ -231,6 +235,21 @@ int cache_sync(sgc_cache *c, hipStream_t s)
         }
     }
     for (; n < n_pages; ++n) flat[n] = 0;
+}
+
+// Brings the device copy of the page tables up to date with the host allocator: rewritten by one copy that is ordered on
+// the stream behind the launches that read the old content.
+int cache_sync(sgc_cache *c, hipStream_t s)
+{
+    sgc_ctx *ctx = c->ctx;
+    int rc = cache_tables_ensure(c);
+    if (rc != SGC_OK) return rc;
+    if (!c->dirty) return SGC_OK;
+    char *host = nullptr;
+    int slot = 0;
+    const size_t bytes = cache_tables_bytes(c);
+    if ((rc = stage_begin(ctx, bytes, &host, &slot)) != SGC_OK) return rc;
+    cache_tables_fill(c, reinterpret_cast<int32_t *>(host));
     if ((rc = stage_commit(ctx, slot, c->d_tables, bytes, s)) != SGC_OK) return rc;
     c->dirty = false;
     return SGC_OK;
@@ -493,6 +512,7 @@ void plan_free_device(sgc_plan *pl)
     pl->d_spool = nullptr;
     pl->spool_bytes = 0;
     pl->uploaded = false;
+    pl->expand_pending = false;
 }
 
 }  // namespace
@@ -703,7 +723,7 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
     if (max_len == 0) return SGC_OK;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if ((rc = ensure_rope(ctx, max_len, s)) != SGC_OK) return rc;
-    if ((rc = cache_sync(c, s)) != SGC_OK) return rc;
+    if ((rc = cache_tables_ensure(c)) != SGC_OK) return rc;      // (the tables themselves travel with this call's own copy)
 
     // jobs, the job of every page, and (MFMA attention) the tile list, in one device block
     std::vector<int32_t> pt_off(c->max_clusters, 0);
@@ -733,8 +753,7 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
         jobs.push_back(j);
     }
     // Tile list of the MFMA attention: units (job, KV head) are dealt, heaviest first, to the XCD with the
-    // least work so far, each XCD's tiles longest first; workgroup b runs on XCD b % 8.  Only the list's length is
-    // needed before the ingest kernel is launched; the seeds are written while it runs.
+    // least work so far, each XCD's tiles longest first; workgroup b runs on XCD b % 8.
     struct Unit {
         int job, hk;
     };
@@ -758,8 +777,8 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
             slots = std::max(slots, all);
         }
     }
-    // One block: [jobs][job of each page][tile seeds] from the host in one copy, then room for the tile records, which a
-    // small kernel writes from the seeds, the jobs and the cache's page table.
+    // One block: [jobs][job of each page][tile seeds] from the host in one copy, then room for the tile records, which
+    // are written on the device from the seeds, the jobs and the cache's page table.
     const size_t n_tiles = slots * kXcd;
     const size_t jobs_bytes = (jobs.size() * sizeof(PrefixJob) + 255) / 256 * 256;
     const size_t pj_bytes = (page_job.size() * sizeof(int32_t) + 255) / 256 * 256;
@@ -770,26 +789,23 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
     if ((rc = dev_acquire(ctx, total, s, &blk)) != SGC_OK) return rc;
     char *host = nullptr;
     int slot = 0;
-    if ((rc = stage_begin(ctx, copied, &host, &slot)) != SGC_OK) {
+    const size_t table_bytes = c->dirty ? cache_tables_bytes(c) : 0;      // the cache's page tables, when they are due
+    if ((rc = stage_begin(ctx, copied + table_bytes, &host, &slot)) != SGC_OK) {
         dev_release(ctx, blk, s);
         return rc;
     }
+    if (table_bytes) cache_tables_fill(c, reinterpret_cast<int32_t *>(host + copied));
     memcpy(host, jobs.data(), jobs.size() * sizeof(PrefixJob));
     memcpy(host + jobs_bytes, page_job.data(), page_job.size() * sizeof(int32_t));
     const PrefixJob *d_jobs = reinterpret_cast<const PrefixJob *>(blk.p);
     const int32_t *d_page_job = reinterpret_cast<const int32_t *>(blk.p + jobs_bytes);
     const TileSeed *d_seeds = reinterpret_cast<const TileSeed *>(blk.p + jobs_bytes + pj_bytes);
     const Tile *d_tiles = reinterpret_cast<const Tile *>(blk.p + copied);
-    // The ingest kernel needs the jobs only: they go first, and the kernel runs while the tile seeds are written.
-    hipError_t e = launch_copy_from_host(blk.p, ctx->h_stage_dev[slot], jobs_bytes + pj_bytes, s);
-    if (e == hipSuccess && !attend_only)
-        e = launch_prefix_ingest(c->geom, layer, c->d_page_table, d_jobs, (int)jobs.size(), d_page_job, (int)page_job.size(),
-                                 ctx->p.io_dtype, ctx->p.rope_base > 0.0f ? ctx->d_rope : nullptr, s);
     // a unit's tile t starts at row t * rows_per_tile; descending t, units in dealing order among equals; slot k of XCD x
     // is tile k * 8 + x of the launch (slots a short list does not fill stay padding tiles: n_rows = 0)
     TileSeed *hs = reinterpret_cast<TileSeed *>(host + jobs_bytes + pj_bytes);
     memset(hs, 0, n_tiles * sizeof(TileSeed));
-    for (int x = 0; x < kXcd; ++x) {
+    for (int x = 0; x < kXcd && n_tiles > 0; ++x) {
         int most = 0;
         for (int ui : of_xcd[x]) most = std::max(most, tiles_of(units[ui]));
         size_t k = 0;
@@ -805,17 +821,23 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
                 sd.sq_hi = -1;
             }
     }
-    // the seeds, and the event that says the staging buffer has been read
-    rc = stage_commit(ctx, slot, blk.p + jobs_bytes + pj_bytes, e == hipSuccess ? seeds_bytes : 0, s, jobs_bytes + pj_bytes);
-    if (rc == SGC_OK && e == hipSuccess && any_q && ctx->use_mfma) {
-        ExpandArgs x{};
-        x.seeds = d_seeds;
-        x.tiles = const_cast<Tile *>(d_tiles);
-        x.n = (int32_t)n_tiles;
-        x.jobs = d_jobs;
-        x.page_table = c->d_page_table;
+    // One copy for jobs, page jobs, seeds and page tables (with the event that says the staging buffer has been read); the tile records
+    // are then written by workgroups appended to the ingest launch, or by a launch of their own when nothing is ingested.
+    rc = stage_commit(ctx, slot, blk.p, copied, s, c->d_tables, copied, table_bytes);
+    if (rc == SGC_OK) c->dirty = false;
+    hipError_t e = hipSuccess;
+    ExpandArgs x{};
+    x.seeds = d_seeds;
+    x.tiles = const_cast<Tile *>(d_tiles);
+    x.n = (int32_t)n_tiles;
+    x.jobs = d_jobs;
+    x.page_table = c->d_page_table;
+    const bool expand = n_tiles > 0;
+    if (rc == SGC_OK && !attend_only)
+        e = launch_prefix_ingest(c->geom, layer, c->d_page_table, d_jobs, (int)jobs.size(), d_page_job, (int)page_job.size(),
+                                 ctx->p.io_dtype, ctx->p.rope_base > 0.0f ? ctx->d_rope : nullptr, expand ? &x : nullptr, s);
+    else if (rc == SGC_OK && expand)
         e = launch_expand_tiles(x, s);
-    }
     if (rc == SGC_OK && e == hipSuccess && any_q) {
         AttnArgs a;
         fill_common_args(a, ctx, c, layer);
@@ -963,14 +985,10 @@ int sgc_assign_clusters(sgc_ctx *ctx, const sgc_cache *c, int32_t n_queries, con
     return SGC_OK;
 }
 
-// Writes the plan's tile records on the device, from its seeds and the cache's current page tables.
-static int expand_plan_tiles(sgc_plan *pl, hipStream_t s)
+// What writes the plan's tile records on the device, from its seeds and the cache's current page tables (which the
+// caller has brought up to date).
+static ExpandArgs plan_expand_args(const sgc_plan *pl, const sgc_cache *c)
 {
-    sgc_ctx *ctx = pl->ctx;
-    if (pl->tiles.empty()) return SGC_OK;
-    sgc_cache *c = const_cast<sgc_cache *>(pl->cache);
-    int rc = cache_sync(c, s);
-    if (rc != SGC_OK) return rc;
     ExpandArgs e{};
     e.seeds = pl->d_seeds;
     e.tiles = const_cast<Tile *>(pl->d_tiles);
@@ -984,8 +1002,7 @@ static int expand_plan_tiles(sgc_plan *pl, hipStream_t s)
     e.sq_src0 = pl->d_sq_src0;
     e.sq_len = pl->d_sq_len;
     e.sq_page0 = pl->d_sq_page0;
-    SGC_HIP(ctx, launch_expand_tiles(e, s));
-    return SGC_OK;
+    return e;
 }
 
 int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
@@ -1061,7 +1078,7 @@ int sgc_plan_upload(sgc_plan *pl, void *hip_stream)
         off += (p.bytes + 255) / 256 * 256 + 256;
     }
     if ((rc = stage_commit(ctx, slot, pl->d_blob, copied, s)) != SGC_OK) return rc;
-    if ((rc = expand_plan_tiles(pl, s)) != SGC_OK) return rc;
+    pl->expand_pending = !pl->tiles.empty();      // the records are written with the next suffix launch's ingest
     if (want_rows > 0 && !pl->spage_sq.empty()) {
         // suffix page pool: bf16 pages of every query's rotated suffix K and transposed V
         // (decode: one pool per layer, since the pages have to outlive the layer's suffix launch; zeroed once,
@@ -1097,14 +1114,13 @@ int sgc_plan_destroy(sgc_plan *pl)
 }
 
 // Clusters were allocated or released since the tiles were filled: refresh their page-table offsets and
-// first page ids, on the host and in the device copy.
+// first page ids, on the host now and in the device copy with the next suffix launch (decode tiles: now).
 static int refresh_tiles(sgc_plan *pl, const sgc_cache *c, hipStream_t s)
 {
     sgc_ctx *ctx = pl->ctx;
     if (pl->tiles.empty() || pl->tiles_generation == c->generation) return SGC_OK;
     fill_tile_pt_off(pl, c);
-    int rc0 = expand_plan_tiles(pl, s);
-    if (rc0 != SGC_OK) return rc0;
+    pl->expand_pending = true;
     for (int which = 1; which < 2; ++which) {
         const std::vector<Tile> &list = pl->dtiles;
         const Tile *dev = pl->d_dtiles;
@@ -1181,7 +1197,14 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
     a.total_tokens = pl->total_tokens;
     hipEvent_t *tev = ctx->ev[ctx->timing_count % sgc_ctx::kTimingRing];
     if (ctx->timing) SGC_HIP(ctx, hipEventRecord(tev[0], s));
-    if (ctx->use_mfma && !skip_ingest) SGC_HIP(ctx, launch_suffix_ingest(a, pl->d_spage_sq, (int)pl->spage_sq.size(), s));
+    // tile records that are due are written by workgroups appended to the ingest launch (they depend on nothing it writes)
+    const ExpandArgs ex = plan_expand_args(pl, c);
+    const bool expand = ctx->use_mfma && pl->expand_pending;
+    if (ctx->use_mfma && !skip_ingest)
+        SGC_HIP(ctx, launch_suffix_ingest(a, pl->d_spage_sq, (int)pl->spage_sq.size(), expand ? &ex : nullptr, s));
+    else if (expand)
+        SGC_HIP(ctx, launch_expand_tiles(ex, s));
+    pl->expand_pending = false;
     if (ctx->timing) SGC_HIP(ctx, hipEventRecord(tev[1], s));
     if (ctx->use_mfma) {
         SGC_HIP(ctx, launch_attn_mfma(a, s));

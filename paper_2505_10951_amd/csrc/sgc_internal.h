@@ -351,6 +351,7 @@ struct sgc_plan {
     uint64_t tiles_generation = 0;            // cache generation the tiles' page-table offsets belong to
     int32_t tile_rows = 0;
     bool uploaded = false;
+    bool expand_pending = false;              // the device's tile records are to be (re)written before the next suffix launch
     sgc_dev_block blob, spool_block;          // device blocks behind d_blob / d_spool (from the context's pool)
     hipStream_t last_stream = nullptr;        // stream of the last launch that used the plan
     char *d_blob = nullptr;                   // one device allocation holding every array below
@@ -374,19 +375,6 @@ namespace sgc {
 // Builds the (cos, sin) table for positions [0, n_pos) in double precision, stored as fp32.
 hipError_t launch_rope_table(float2 *table, int n_pos, int head_dim, double base, hipStream_t s);
 
-// Prefix ingest of n_jobs clusters: rotate K, (quantise), write K and V into the clusters' pages.
-// d_page_job[p] is the job of launch-wide page p (n_pages of them).
-hipError_t launch_prefix_ingest(const PoolGeom &g, int layer, const int32_t *d_page_table, const PrefixJob *d_jobs,
-                                int n_jobs, const int32_t *d_page_job, int n_pages, int io_dtype, const float2 *rope,
-                                hipStream_t s);
-hipError_t launch_cache_export(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len,
-                               void *k, void *v, hipStream_t s);
-hipError_t launch_cache_import(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len,
-                               const void *k, const void *v, hipStream_t s);
-
-// Suffix ingest: rotate every query's suffix K at prefix_len + j and write K and V as bf16 pages
-// (cache page layout) into the suffix page pool; one workgroup per (suffix page, KV head).
-hipError_t launch_suffix_ingest(const AttnArgs &a, const int32_t *d_spage_sq, int n_spages, hipStream_t s);
 // Tile records from seeds.  jobs null: tiles of a suffix launch (per-cluster tables of the cache, per-query tables of
 // the plan); jobs given: tiles of a batched prefix prefill.
 struct ExpandArgs {
@@ -399,13 +387,31 @@ struct ExpandArgs {
 };
 hipError_t launch_expand_tiles(const ExpandArgs &e, hipStream_t s);
 
+// Prefix ingest of n_jobs clusters: rotate K, (quantise), write K and V into the clusters' pages.
+// d_page_job[p] is the job of launch-wide page p (n_pages of them).  expand (may be null): tile records to write in the
+// same launch, by workgroups appended to the grid.
+hipError_t launch_prefix_ingest(const PoolGeom &g, int layer, const int32_t *d_page_table, const PrefixJob *d_jobs,
+                                int n_jobs, const int32_t *d_page_job, int n_pages, int io_dtype, const float2 *rope,
+                                const ExpandArgs *expand, hipStream_t s);
+hipError_t launch_cache_export(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len,
+                               void *k, void *v, hipStream_t s);
+hipError_t launch_cache_import(const PoolGeom &g, int layer, const int32_t *d_pages, int prefix_len,
+                               const void *k, const void *v, hipStream_t s);
+
+// Suffix ingest: rotate every query's suffix K at prefix_len + j and write K and V as bf16 pages
+// (cache page layout) into the suffix page pool; one workgroup per (suffix page, KV head).  expand: as above.
+hipError_t launch_suffix_ingest(const AttnArgs &a, const int32_t *d_spage_sq, int n_spages, const ExpandArgs *expand,
+                                hipStream_t s);
+
 hipError_t launch_attn_generic(const AttnArgs &a, int64_t n_rows, hipStream_t s);
 // Decode, per (query, head): attention over the query's own keys (the step's new token was appended to the suffix
 // pages by the cached-part launch before) merged with the cached-prefix part.  head_dim 128, bf16.
 hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s);
 hipError_t launch_fill_zero_bytes(void *p, size_t bytes, hipStream_t s);
-// bytes (a multiple of 4, both pointers 16-byte aligned) from mapped host memory to device memory, read by a kernel
-hipError_t launch_copy_from_host(void *dst, const void *mapped_src, size_t bytes, hipStream_t s);
+// bytes (a multiple of 4, both pointers 16-byte aligned) from mapped host memory to device memory, read by a kernel;
+// optionally a second piece in the same launch
+hipError_t launch_copy_from_host(void *dst, const void *mapped_src, size_t bytes, hipStream_t s, void *dst2 = nullptr,
+                                 const void *mapped_src2 = nullptr, size_t bytes2 = 0);
 // Projections: the bf16 matrix-core kernel (K a multiple of 64, N a multiple of 128; qkv selects the fused
 // epilogue) and a kernel for every other shape and type that deals columns [0, n0), [n0, n0 + n1) and the rest
 // to three row-major matrices (c0 may be null to drop its columns).

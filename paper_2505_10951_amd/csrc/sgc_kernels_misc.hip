@@ -238,11 +238,93 @@ __global__ void scale_slot_kernel(const PrefixJob *jobs, int n, bool to_scale)
     for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = to_scale ? (p[i] > 0.f ? p[i] / 448.0f : 1.0f) : 0.f;
 }
 
+// ---- tile records -----------------------------------------------------------------------------
+// The record the attention kernel reads for tile i, put together from the tile's seed and from the tables the device
+// holds (the cluster's prompt length and pages, the plan's per-query records).
+__device__ inline void expand_one_tile(const ExpandArgs &e, int i)
+{
+    const TileSeed sd = e.seeds[i];
+    Tile t;
+    t.cluster = sd.cluster;
+    t.hk = sd.hk;
+    t.row0 = sd.row0;
+    t.n_rows = sd.n_rows;
+    t.prefix_len = 0;
+    t.pt_off = 0;
+    t.tok_base = 0;
+    t.sq_lo = sd.sq_lo;
+    t.sq_hi = sd.sq_hi;
+    t.last_qpos = sd.last_qpos;
+    t.n_q = sd.sq_hi - sd.sq_lo + 1;
+    t.pad = 0;
+#pragma unroll
+    for (int k = 0; k < 12; ++k) t.first_pages[k] = 0;
+#pragma unroll
+    for (int k = 0; k < kTileQueries; ++k) t.q[k] = {INT32_MAX, 0, 0, 0};
+    if (sd.n_rows > 0) {
+        if (e.jobs) {
+            const PrefixJob &j = e.jobs[sd.cluster];
+            t.cluster = j.cluster;
+            t.prefix_len = j.prefix_len;
+            t.pt_off = j.pt_off;
+            t.tok_base = sd.cluster;          // prefix mode: the job index travels here
+            t.sq_lo = 0;
+            t.sq_hi = -1;
+            t.last_qpos = 0;
+            t.n_q = 0;
+        } else {
+            t.prefix_len = e.prefix_len[sd.cluster];
+            t.pt_off = e.pt_off[sd.cluster];
+            t.tok_base = e.cl_tok_off[sd.cluster];
+#pragma unroll
+            for (int k = 0; k < kTileQueries; ++k) {
+                const int sq = sd.sq_lo + k;
+                if (sq <= sd.sq_hi) t.q[k] = {e.sq_tok0[sq], e.sq_src0[sq], e.sq_len[sq], e.sq_page0[sq]};
+            }
+        }
+        const int n_pages = (t.prefix_len + kPageTokens - 1) / kPageTokens;
+        if (n_pages > 0) {
+#pragma unroll
+            for (int k = 0; k < 12; ++k) t.first_pages[k] = e.page_table[t.pt_off + min(k, n_pages - 1)];
+        }
+    } else {
+        t.cluster = 0;
+        t.n_q = 0;
+    }
+    e.tiles[i] = t;
+}
+
+// One thread per tile.
+__global__ void expand_tiles_kernel(ExpandArgs e)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < e.n) expand_one_tile(e, i);
+}
+
+// The ingest kernels below run on (pages, KV heads) grids of 128 threads.  The tile records of the attention launch that
+// follows depend on nothing the ingest writes, so they are written by workgroups appended to the same grid (columns
+// blockIdx.x >= n_pages, 128 tiles per workgroup) instead of by a launch of their own between the two.
+__device__ inline void expand_in_ingest_grid(const ExpandArgs &e, int n_pages)
+{
+    const int i = (((int)blockIdx.x - n_pages) * (int)gridDim.y + (int)blockIdx.y) * 128 + (int)threadIdx.x;
+    if (i < e.n) expand_one_tile(e, i);
+}
+// grid columns to append for e.n tiles
+inline unsigned expand_columns(int n_tiles, int n_kv_heads)
+{
+    const int groups = (n_tiles + 127) / 128;
+    return (unsigned)((groups + n_kv_heads - 1) / n_kv_heads);
+}
+
 // One workgroup per (page, KV head): rotate K, convert, write K and V parts in page order.
 // Tokens past the prefix end are written as zeros so that a whole page can always be read.
 __global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *page_table, const PrefixJob *jobs,
-                                    const int32_t *page_job, int io_dtype, const float2 *rope)
+                                    const int32_t *page_job, int n_pages, int io_dtype, const float2 *rope, ExpandArgs ex)
 {
+    if ((int)blockIdx.x >= n_pages) {
+        expand_in_ingest_grid(ex, n_pages);
+        return;
+    }
     const PrefixJob job = jobs[page_job[blockIdx.x]];
     const int pg = blockIdx.x - job.page0, hk = blockIdx.y;
     const int P = job.prefix_len;
@@ -301,8 +383,12 @@ __global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *page_t
 // (SubGCache Sec. 3.4: the question tokens are appended to the cached prompt, so suffix token j of a
 // query whose cluster has P prefix tokens is rotated at position P + j).  One workgroup per
 // (suffix page, KV head); tokens past the query's end are written as zeros.
-__global__ void suffix_ingest_kernel(AttnArgs a, const int32_t *spage_sq)
+__global__ void suffix_ingest_kernel(AttnArgs a, const int32_t *spage_sq, int n_spages, ExpandArgs ex)
 {
+    if ((int)blockIdx.x >= n_spages) {
+        expand_in_ingest_grid(ex, n_spages);
+        return;
+    }
     const int page = blockIdx.x, hk = blockIdx.y;
     const int Hkv = a.n_kv_heads, d = a.head_dim, half = d / 2, pairs = d / 16;
     const int sq = spage_sq[page];
@@ -549,64 +635,6 @@ __global__ void __launch_bounds__(64) decode_own_keys_kernel(DecodeArgs a)
         for (int cI = 0; cI < 2; ++cI) og[io + gi * d + lane + cI * 64] = f32_to_bf16(sum[cI] / denom);
         if (a.lse && lane == 0) a.lse[(int64_t)h * a.n_queries + n] = (M + log2f(denom)) * 0.6931471805599453f;
     }
-}
-
-// ---- tile records -----------------------------------------------------------------------------
-// One thread per tile: the record the attention kernel reads, put together from the tile's seed and from the tables
-// the device holds (the cluster's prompt length and pages, the plan's per-query records).
-__global__ void expand_tiles_kernel(ExpandArgs e)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= e.n) return;
-    const TileSeed sd = e.seeds[i];
-    Tile t;
-    t.cluster = sd.cluster;
-    t.hk = sd.hk;
-    t.row0 = sd.row0;
-    t.n_rows = sd.n_rows;
-    t.prefix_len = 0;
-    t.pt_off = 0;
-    t.tok_base = 0;
-    t.sq_lo = sd.sq_lo;
-    t.sq_hi = sd.sq_hi;
-    t.last_qpos = sd.last_qpos;
-    t.n_q = sd.sq_hi - sd.sq_lo + 1;
-    t.pad = 0;
-#pragma unroll
-    for (int k = 0; k < 12; ++k) t.first_pages[k] = 0;
-#pragma unroll
-    for (int k = 0; k < kTileQueries; ++k) t.q[k] = {INT32_MAX, 0, 0, 0};
-    if (sd.n_rows > 0) {
-        if (e.jobs) {
-            const PrefixJob &j = e.jobs[sd.cluster];
-            t.cluster = j.cluster;
-            t.prefix_len = j.prefix_len;
-            t.pt_off = j.pt_off;
-            t.tok_base = sd.cluster;          // prefix mode: the job index travels here
-            t.sq_lo = 0;
-            t.sq_hi = -1;
-            t.last_qpos = 0;
-            t.n_q = 0;
-        } else {
-            t.prefix_len = e.prefix_len[sd.cluster];
-            t.pt_off = e.pt_off[sd.cluster];
-            t.tok_base = e.cl_tok_off[sd.cluster];
-#pragma unroll
-            for (int k = 0; k < kTileQueries; ++k) {
-                const int sq = sd.sq_lo + k;
-                if (sq <= sd.sq_hi) t.q[k] = {e.sq_tok0[sq], e.sq_src0[sq], e.sq_len[sq], e.sq_page0[sq]};
-            }
-        }
-        const int n_pages = (t.prefix_len + kPageTokens - 1) / kPageTokens;
-        if (n_pages > 0) {
-#pragma unroll
-            for (int k = 0; k < 12; ++k) t.first_pages[k] = e.page_table[t.pt_off + min(k, n_pages - 1)];
-        }
-    } else {
-        t.cluster = 0;
-        t.n_q = 0;
-    }
-    e.tiles[i] = t;
 }
 
 // The same step on the matrix cores, head_dim 128, groups of up to 16 query heads per KV head: one wavefront per (sorted
@@ -989,9 +1017,9 @@ hipError_t launch_rope_table(float2 *table, int n_pos, int head_dim, double base
 
 hipError_t launch_prefix_ingest(const PoolGeom &g, int layer, const int32_t *d_page_table, const PrefixJob *d_jobs,
                                 int n_jobs, const int32_t *d_page_job, int n_pages, int io_dtype, const float2 *rope,
-                                hipStream_t s)
+                                const ExpandArgs *expand, hipStream_t s)
 {
-    if (n_pages == 0 || n_jobs == 0) return hipSuccess;
+    if (n_pages == 0 || n_jobs == 0) return expand ? launch_expand_tiles(*expand, s) : hipSuccess;
     const dim3 grid(n_pages, g.n_kv_heads);
     if (g.kv_dtype == SGC_FP8_E4M3) {
         const int n = 2 * g.n_kv_heads;
@@ -1000,8 +1028,11 @@ hipError_t launch_prefix_ingest(const PoolGeom &g, int layer, const int32_t *d_p
                            rope);
         hipLaunchKernelGGL(scale_slot_kernel, dim3(n_jobs), dim3(64), 0, s, d_jobs, n, true);
     }
-    hipLaunchKernelGGL(ingest_write_kernel, grid, dim3(128), 2 * (size_t)g.head_part_bytes, s, g, layer, d_page_table, d_jobs,
-                       d_page_job, io_dtype, rope);
+    ExpandArgs ex{};
+    if (expand) ex = *expand;
+    const dim3 grid_all(n_pages + expand_columns(ex.n, g.n_kv_heads), g.n_kv_heads);
+    hipLaunchKernelGGL(ingest_write_kernel, grid_all, dim3(128), 2 * (size_t)g.head_part_bytes, s, g, layer, d_page_table, d_jobs,
+                       d_page_job, n_pages, io_dtype, rope, ex);
     return hipGetLastError();
 }
 
@@ -1012,11 +1043,15 @@ hipError_t launch_expand_tiles(const ExpandArgs &e, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_suffix_ingest(const AttnArgs &a, const int32_t *d_spage_sq, int n_spages, hipStream_t s)
+hipError_t launch_suffix_ingest(const AttnArgs &a, const int32_t *d_spage_sq, int n_spages, const ExpandArgs *expand,
+                                hipStream_t s)
 {
-    if (n_spages <= 0) return hipSuccess;
+    if (n_spages <= 0) return expand ? launch_expand_tiles(*expand, s) : hipSuccess;
     const size_t lds = 2 * (size_t)kPageTokens * a.head_dim * 2;
-    hipLaunchKernelGGL(suffix_ingest_kernel, dim3(n_spages, a.n_kv_heads), dim3(128), lds, s, a, d_spage_sq);
+    ExpandArgs ex{};
+    if (expand) ex = *expand;
+    const dim3 grid(n_spages + expand_columns(ex.n, a.n_kv_heads), a.n_kv_heads);
+    hipLaunchKernelGGL(suffix_ingest_kernel, grid, dim3(128), lds, s, a, d_spage_sq, n_spages, ex);
     return hipGetLastError();
 }
 
@@ -1044,22 +1079,35 @@ hipError_t launch_decode_own_keys(const DecodeArgs &d, hipStream_t s)
 // The tables a batch sends to the device are a few hundred KiB at most.  A copy engine transfer of that size spends most of
 // its 25-35 us getting started; a kernel that reads the pinned, mapped staging buffer over the host link is done in
 // the time the link needs.
-__global__ void copy_from_host_kernel(uint4 *dst, const uint4 *src, size_t n16, size_t n4)
+// Up to two pieces per launch (a call's own tables and the cache's page tables, when both are due).
+struct CopyPiece {
+    uint4 *dst;
+    const uint4 *src;
+    size_t n16, n4;      // 16-byte chunks, then 4-byte words behind them
+};
+__device__ inline void copy_piece(const CopyPiece &p)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
-    uint32_t *d4 = reinterpret_cast<uint32_t *>(dst + n16);
-    const uint32_t *s4 = reinterpret_cast<const uint32_t *>(src + n16);
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) d4[i] = s4[i];
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < p.n16; i += stride) p.dst[i] = p.src[i];
+    uint32_t *d4 = reinterpret_cast<uint32_t *>(p.dst + p.n16);
+    const uint32_t *s4 = reinterpret_cast<const uint32_t *>(p.src + p.n16);
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < p.n4; i += stride) d4[i] = s4[i];
+}
+__global__ void copy_from_host_kernel(CopyPiece a, CopyPiece b)
+{
+    copy_piece(a);
+    copy_piece(b);
 }
 
-hipError_t launch_copy_from_host(void *dst, const void *mapped_src, size_t bytes, hipStream_t s)
+hipError_t launch_copy_from_host(void *dst, const void *mapped_src, size_t bytes, hipStream_t s, void *dst2,
+                                 const void *mapped_src2, size_t bytes2)
 {
-    if (bytes == 0) return hipSuccess;
-    const size_t n16 = bytes / 16, n4 = (bytes % 16) / 4;
-    const unsigned blocks = (unsigned)std::min<size_t>(std::max<size_t>((n16 + 255) / 256, 1), 1024);
-    hipLaunchKernelGGL(copy_from_host_kernel, dim3(blocks), dim3(256), 0, s, static_cast<uint4 *>(dst),
-                       static_cast<const uint4 *>(mapped_src), n16, n4);
+    if (bytes == 0 && bytes2 == 0) return hipSuccess;
+    const CopyPiece a{static_cast<uint4 *>(dst), static_cast<const uint4 *>(mapped_src), bytes / 16, (bytes % 16) / 4};
+    const CopyPiece b{static_cast<uint4 *>(dst2), static_cast<const uint4 *>(mapped_src2), bytes2 / 16, (bytes2 % 16) / 4};
+    const size_t most = std::max(a.n16, b.n16);
+    const unsigned blocks = (unsigned)std::min<size_t>(std::max<size_t>((most + 255) / 256, 1), 1024);
+    hipLaunchKernelGGL(copy_from_host_kernel, dim3(blocks), dim3(256), 0, s, a, b);
     return hipGetLastError();
 }
 

@@ -23,8 +23,8 @@ import numpy as np
 @contextlib.contextmanager
 def no_gc():
     """Python's cyclic garbage collector off for a timed region, as in timeit: a full collection over the workload's
-    objects takes 35 ms of host time (seventy steps of the headline configuration) and says nothing about the path."""
-    gc.collect()
+    objects takes 35 ms of host time (seventy steps of the headline configuration) and says nothing about the path.
+    (Callers collect once before their untimed phase, so that the pause does not fall between it and the timed one.)"""
     gc.disable()
     try:
         yield
@@ -184,6 +184,7 @@ def decode_measurement(s, w, layer, n_steps, dq, dk, dv, do, all_clusters, pq_pt
     tq, tk, tv = (to_device(x, w.io_dtype) for x in w.decode_qkv(0, layer))
     to = torch.empty_like(tq)
     torch.cuda.synchronize()
+    gc.collect()
     times = []
     t_warm = time.perf_counter()
     rep = 0
@@ -268,6 +269,7 @@ def layer_measurement(s, w, layer, d_model, reps, stream):
     s.assign(w.labels, w.suffix_len)
     s.upload_plan()
     evs = {k: [] for k in calls}
+    gc.collect()
     t_warm = time.perf_counter()
     n_warm = 0
     while n_warm < 2 or (time.perf_counter() - t_warm) < 0.06:      # untimed rounds until the chip's clocks are up
@@ -330,6 +332,7 @@ def other_config(index: int, steps: int, warmup: int, threads: int, kernel=None)
             sgc.sgc_suffix_prefill_batched(s.ctx, s.cache, s.plan, layer, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
                                            do.data_ptr(), None, stream)
         # untimed launches until the chip has worked for 60 ms (its clocks are up by then), at least `warmup` of them
+        gc.collect()
         t0 = time.perf_counter()
         n_warm = 0
         while n_warm < warmup or (time.perf_counter() - t0) < 0.06:
@@ -417,7 +420,7 @@ def main() -> int:
                     help="before the warm-up steps, run untimed steps for this long: the chip raises its clocks over the first tens of "
                          "milliseconds of work, and a handful of half-millisecond steps would be timed on the way up (0 = skip)")
     ap.add_argument("--repeat-launches", type=int, default=100,
-                    help="after the timed steps, launch the suffix call this many times back to back (after 20 untimed) and report "
+                    help="after the timed steps, launch the suffix call this many times back to back (after 60 ms of untimed ones) and report "
                          "median and minimum kernel time (0 = skip, at most 128)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten 256 MiB device copies and exit (counter calibration under rocprofv3 --pmc)")
@@ -490,6 +493,7 @@ def main() -> int:
             torch.cuda.synchronize()
             return (time.perf_counter() - t_start) / args.steps * 1e3
 
+    gc.collect()
     t_settle = time.perf_counter()
     n_settle = 0
     while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
@@ -518,25 +522,33 @@ def main() -> int:
     o_host = do.to(torch.float32).cpu().numpy()          # what the last timed step wrote, for the error figures
     repeat = None
     if not args.suffix_only and args.repeat_launches > 0:
-        # the suffix call alone, launched back to back with caches and plan resident: 20 untimed, then the timed ones
+        # the suffix call alone, launched back to back with caches and plan resident: 60 ms of untimed launches, then the timed ones
         for c in range(w.n_clusters):
             sgc.sgc_cache_alloc_cluster(s.ctx, s.cache, c, int(w.prefix_len[c]))
         sgc.sgc_prefix_prefill_batched(s.ctx, s.cache, all_clusters, layer, pq_ptrs, pk_ptrs, pv_ptrs, po_ptrs, None, stream)
         s.assign(labels, slen)
         s.upload_plan()
         n_rep = min(args.repeat_launches, 128)
-        for i in range(20 + n_rep):
-            if i == 20:
-                torch.cuda.synchronize()
-                sgc.sgc_timing_enable(s.ctx, True)
+        def launch():
             sgc.sgc_suffix_prefill_batched(s.ctx, s.cache, s.plan, layer, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
                                            do.data_ptr(), None, stream)
-        torch.cuda.synchronize()
+        gc.collect()
+        t_warm, n_untimed = time.perf_counter(), 0
+        while n_untimed < 20 or (time.perf_counter() - t_warm) < 0.06:      # the chip has been idle: 60 ms of launches first
+            for _ in range(20):
+                launch()
+            torch.cuda.synchronize()
+            n_untimed += 20
+        sgc.sgc_timing_enable(s.ctx, True)
+        with no_gc():
+            for _ in range(n_rep):
+                launch()
+            torch.cuda.synchronize()
         rep_ms = [sgc.sgc_timing_get(s.ctx, back)[1] for back in range(n_rep)]
         for c in range(w.n_clusters):
             sgc.sgc_cache_free_cluster(s.ctx, s.cache, c)
         med = float(np.median(rep_ms))
-        repeat = {"launches": n_rep, "untimed_before": 20, "mode": "the suffix call repeated back to back, caches and plan resident",
+        repeat = {"launches": n_rep, "untimed_before": n_untimed, "mode": "the suffix call repeated back to back, caches and plan resident",
                   "attention_kernel_ms_median": med, "attention_kernel_ms_min": float(np.min(rep_ms)),
                   "attention_kernel_ms_mean": float(np.mean(rep_ms)),
                   "roofline_frac_median": w.flops() / (med * 1e-3) / 1e12 / PEAK_TFLOPS[w.io_dtype]}

@@ -473,13 +473,13 @@ def main() -> int:
             s.upload_plan()
         sgc.sgc_suffix_prefill_batched(s.ctx, s.cache, s.plan, layer, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
                                        do.data_ptr(), None, stream)
-        if wait:
-            torch.cuda.synchronize()
         if not args.suffix_only:
             # Everything runs on one stream: the next step's ingest, which reuses these pages, is ordered behind
-            # this step's attention kernels, so the pages can be handed back without waiting for the GPU.
+            # this step's attention kernels, so the pages are handed back while the GPU still works.
             for c in range(w.n_clusters):
                 sgc.sgc_cache_free_cluster(s.ctx, s.cache, c)
+        if wait:
+            torch.cuda.synchronize()
 
     # Default: the host waits for the GPU after every step (a step's latency).  --pipelined enqueues the steps back to
     # back: 6-8 % more throughput, the kernels' own times the same.  The other mode is run too, after the timed steps,

@@ -733,6 +733,12 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
     }
     std::vector<PrefixJob> jobs;
     std::vector<int32_t> page_job;
+    jobs.reserve(n);
+    {
+        size_t listed = 0;
+        for (int32_t i = 0; i < n; ++i) listed += c->cl[cluster_ids[i]].pages.size();
+        page_job.reserve(listed);
+    }
     bool any_q = false;
     for (int32_t i = 0; i < n; ++i) {
         const int32_t id = cluster_ids[i], P = c->cl[id].prefix_len;
@@ -758,22 +764,26 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
         int job, hk;
     };
     std::vector<Unit> units;
+    std::vector<int> unit_tiles;
     std::array<std::vector<int>, kXcd> of_xcd;
     const int rows_per_tile = ctx->tile_rows;
-    auto tiles_of = [&](const Unit &u) { return (int)(((int64_t)jobs[u.job].prefix_len * g + rows_per_tile - 1) / rows_per_tile); };
     size_t slots = 0;
     if (any_q && ctx->use_mfma) {
         std::vector<double> work;
+        units.reserve(jobs.size() * Hkv);
+        unit_tiles.reserve(jobs.size() * Hkv);
+        work.reserve(jobs.size() * Hkv);
         for (int ji = 0; ji < (int)jobs.size(); ++ji)
             if (jobs[ji].q)
                 for (int hk = 0; hk < Hkv; ++hk) {
                     units.push_back({ji, hk});
+                    unit_tiles.push_back((int)(((int64_t)jobs[ji].prefix_len * g + rows_per_tile - 1) / rows_per_tile));
                     work.push_back((double)jobs[ji].prefix_len * jobs[ji].prefix_len);
                 }
         of_xcd = deal_to_xcds(work);
         for (int x = 0; x < kXcd; ++x) {
             size_t all = 0;
-            for (int ui : of_xcd[x]) all += (size_t)tiles_of(units[ui]);
+            for (int ui : of_xcd[x]) all += (size_t)unit_tiles[ui];
             slots = std::max(slots, all);
         }
     }
@@ -804,22 +814,20 @@ int sgc_prefix_prefill_batched(sgc_ctx *ctx, sgc_cache *c, int32_t n, const int3
     // a unit's tile t starts at row t * rows_per_tile; descending t, units in dealing order among equals; slot k of XCD x
     // is tile k * 8 + x of the launch (slots a short list does not fill stay padding tiles: n_rows = 0)
     TileSeed *hs = reinterpret_cast<TileSeed *>(host + jobs_bytes + pj_bytes);
-    memset(hs, 0, n_tiles * sizeof(TileSeed));
     for (int x = 0; x < kXcd && n_tiles > 0; ++x) {
         int most = 0;
-        for (int ui : of_xcd[x]) most = std::max(most, tiles_of(units[ui]));
+        for (int ui : of_xcd[x]) most = std::max(most, unit_tiles[ui]);
         size_t k = 0;
         for (int t = most - 1; t >= 0; --t)
             for (int ui : of_xcd[x]) {
+                if (t >= unit_tiles[ui]) continue;
                 const Unit &u = units[ui];
-                if (t >= tiles_of(u)) continue;
-                TileSeed &sd = hs[k++ * kXcd + x];
-                sd.cluster = u.job;
-                sd.hk = u.hk;
-                sd.row0 = t * rows_per_tile;
-                sd.n_rows = (int32_t)std::min<int64_t>(rows_per_tile, (int64_t)jobs[u.job].prefix_len * g - sd.row0);
-                sd.sq_hi = -1;
+                const int32_t row0 = t * rows_per_tile;
+                hs[k++ * kXcd + x] = TileSeed{u.job, u.hk, row0,
+                                              (int32_t)std::min<int64_t>(rows_per_tile, (int64_t)jobs[u.job].prefix_len * g - row0),
+                                              0, -1, 0, 0};
             }
+        for (; k < slots; ++k) hs[k * kXcd + x] = TileSeed{};
     }
     // One copy for jobs, page jobs, seeds and page tables (with the event that says the staging buffer has been read); the tile records
     // are then written by workgroups appended to the ingest launch, or by a launch of their own when nothing is ingested.

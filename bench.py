@@ -414,6 +414,9 @@ def main() -> int:
     ap.add_argument("--kernel", choices=["auto", "mfma", "mfma_fp8", "generic"], default="auto",
                     help="attention kernel of the headline configuration (auto: the matrix-core kernel where it covers the shape, "
                          "with the first product on the e4m3 codes when the cache is fp8)")
+    ap.add_argument("--queries-per-cluster", type=int, default=None,
+                    help="another batch size for the headline configuration, everything else as it is (sweeps of the launch size; "
+                         "the suffix-length range is the configuration's observed one, so the default size need not reproduce it exactly)")
     ap.add_argument("--other-steps", type=int, default=5,
                     help="timed suffix launches per further configuration, at least (as many as fill 60 ms, at most 100)")
     ap.add_argument("--settle-ms", type=float, default=100.0,
@@ -439,7 +442,7 @@ def main() -> int:
         return 2
     if args.copy_calibration:
         return copy_calibration()
-    w = workloads.config(args.config)
+    w = workloads.config(args.config, queries_per_cluster=args.queries_per_cluster)
     layer = 0
     t_gen = time.perf_counter()
     gen_threads = min(16, os.cpu_count() or 1)

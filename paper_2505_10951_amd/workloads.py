@@ -298,10 +298,20 @@ def custom(name: str, *, n_q_heads: int, n_kv_heads: int, head_dim: int, rope_ba
                     k_outlier_scale=k_outlier_scale, q_gain=q_gain)
 
 
-def config(index: int, seed: Optional[int] = None) -> Workload:
-    """The five benchmark workloads (index 0..4)."""
+def config(index: int, seed: Optional[int] = None, queries_per_cluster: Optional[int] = None) -> Workload:
+    """The five benchmark workloads (index 0..4).  queries_per_cluster (configurations with equal clusters only: 0, 1, 3, 4)
+    changes the batch size (and the workload's name) and nothing else: for sweeps of the launch size around the benchmark's own."""
     seed = (index + 1) * 1000 if seed is None else seed
     rng = _struct_rng(seed)
+    if queries_per_cluster is not None:
+        if index == 2:
+            raise ValueError("configs[2] has Zipf cluster sizes; queries_per_cluster does not apply")
+        base = config(index, seed)
+        return custom(f"{base.name}_qpc{int(queries_per_cluster)}", n_q_heads=base.n_q_heads, n_kv_heads=base.n_kv_heads, head_dim=base.head_dim,
+                      rope_base=base.rope_base, io_dtype=base.io_dtype, kv_dtype=base.kv_dtype, prefix_len=base.prefix_len,
+                      queries_per_cluster=int(queries_per_cluster),
+                      suffix_range=(int(base.suffix_len.min()), int(base.suffix_len.max())), n_layers=base.n_layers, seed=seed,
+                      k_outlier_scale=base.k_outlier_scale, q_gain=base.q_gain)
     if index == 0:      # tiny fp32 MHA layer, the correctness case
         return custom("tiny_f32_mha", n_q_heads=4, n_kv_heads=4, head_dim=64, rope_base=10000.0, io_dtype="f32",
                       prefix_len=[256, 192], queries_per_cluster=8, suffix_range=(16, 32), seed=seed)

@@ -295,6 +295,19 @@ def test_workload_generators_are_deterministic_and_shaped():
     assert abs(workloads.config(1).flops() / 2.2e11 - 1) < 0.1
 
 
+def test_batch_size_knob_changes_the_batch_and_nothing_else():
+    base = workloads.config(1)
+    same = workloads.config(1, queries_per_cluster=32)
+    assert np.array_equal(same.labels, base.labels) and np.array_equal(same.suffix_len, base.suffix_len)
+    assert np.array_equal(same.prefix_len, base.prefix_len) and same.name != base.name      # no profiled constant applies
+    wide = workloads.config(1, queries_per_cluster=40)
+    assert wide.n_queries == 400 and np.array_equal(np.bincount(wide.labels), np.full(10, 40))
+    assert (wide.n_q_heads, wide.n_kv_heads, wide.head_dim, wide.k_outlier_scale) == (32, 8, 128, 8.0)
+    assert 16 <= wide.suffix_len.min() and wide.suffix_len.max() <= 64
+    with pytest.raises(ValueError):
+        workloads.config(2, queries_per_cluster=8)
+
+
 def test_bf16_rounding_helper_is_round_to_nearest_even():
     x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 2 ** -7, 1.0 + 3 * 2 ** -8, -1.0 - 2 ** -8, 3.14159], dtype=np.float32)
     r = workloads.round_to_bf16(x)

@@ -400,8 +400,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=1, help="which of the five benchmark configurations, 0-4 (default 1: Llama-3-8B-shaped layer)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for the CPU baseline (0 = skip)")
-    ap.add_argument("--pipelined", action="store_true",
-                    help="enqueue the timed steps back to back instead of waiting for the GPU after every step")
+    ap.add_argument("--wait-every-step", action="store_true",
+                    help="wait for the GPU after every timed step (a step's latency) instead of enqueueing the steps back to back "
+                         "between the two synchronisations that bracket the timed region")
+    ap.add_argument("--pipelined", action="store_true", help=argparse.SUPPRESS)      # the default; accepted for older command lines
     ap.add_argument("--suffix-only", action="store_true", help="time only the batched suffix launch (profiling aid)")
     ap.add_argument("--decode-steps", type=int, default=32,
                     help="after the timed steps, time this many batched decode steps on the same workload (0 = skip)")
@@ -428,6 +430,7 @@ def main() -> int:
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run ten 256 MiB device copies and exit (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
+    args.pipelined = not args.wait_every_step
     if args.gpus != 1:
         print(f"bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus {args.gpus} is not supported",
               file=sys.stderr)
@@ -484,9 +487,9 @@ def main() -> int:
         if wait:
             torch.cuda.synchronize()
 
-    # Default: the host waits for the GPU after every step (a step's latency).  --pipelined enqueues the steps back to
-    # back: 6-8 % more throughput, the kernels' own times the same.  The other mode is run too, after the timed steps,
-    # and reported as "other_mode".
+    # Default: the K timed steps are enqueued back to back on the one stream, between the two synchronisations that bracket
+    # the timed region (throughput).  --wait-every-step waits for the GPU after every step (a step's latency): 5-6 % slower,
+    # the kernels' own times the same.  The other mode is run too, after the timed steps, and reported as "other_mode".
     def timed_loop(wait: bool):
         torch.cuda.synchronize()
         with no_gc():

@@ -44,6 +44,8 @@ HBM_PEAK_GBS = 8000.0
 PROFILED_HBM_BYTES_PER_LAUNCH = {
     ("llama3_8b_layer", "16bit"): (3.226e8, "profiles/attn_mfma_suffix_llama3_8b_layer.md"),
     ("llama2_7b_ragged", "16bit"): (2.989e9, "profiles/suffix_prefill_all_configs.md"),
+    ("llama3_8b_stack32", "16bit"): (1.026e9, "profiles/suffix_prefill_all_configs.md"),
+    ("tiny_f32_mha", "16bit"): (1.469e7, "profiles/suffix_prefill_all_configs.md"),        # (the generic kernel, fp32 operands)
     ("llama70b_fp8_long", "fp8_first_product"): (1.888e10, "profiles/suffix_prefill_all_configs.md"),
 }
 # The same for one decode step of configs[1] (cached-prompt part 58.5 MB + own-keys kernel 93.1 MB) and for the QKV

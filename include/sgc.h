@@ -326,8 +326,10 @@ int sgc_project_out(sgc_ctx *ctx, const void *dev_o, const void *dev_w_o, int32_
  * sgc_timing_get waits for the launch recorded `back` timed launches before the last one (0 = the
  * last) to finish and returns the two durations in milliseconds (either pointer may be NULL);
  * SGC_ESTATE if timing is off or that launch was never recorded, SGC_EINVAL if back is outside
- * [0, 128).  sgc_timing_last is sgc_timing_get with back = 0.  sgc_timing_enable restarts the count.
- * Host-only calls. */
+ * [0, 128).  sgc_timing_last is sgc_timing_get with back = 0.  sgc_timing_enable restarts the count;
+ * on = 0 switches timing off, on = 1 times every launch, on = n > 1 every n-th launch, the first included
+ * (three event records cost the stream about 8 us per launch; a loop that measures its own throughput
+ * samples); negative: SGC_EINVAL.  Host-only calls. */
 int sgc_timing_enable(sgc_ctx *ctx, int on);
 int sgc_timing_get(sgc_ctx *ctx, int32_t back, float *ingest_ms, float *attention_ms);
 int sgc_timing_last(sgc_ctx *ctx, float *ingest_ms, float *attention_ms);

@@ -1204,7 +1204,8 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
     a.spool = pl->d_spool + (pl->decode_cap > 0 ? (size_t)layer * pl->spool_layer_bytes : 0);
     a.total_tokens = pl->total_tokens;
     hipEvent_t *tev = ctx->ev[ctx->timing_count % sgc_ctx::kTimingRing];
-    if (ctx->timing) SGC_HIP(ctx, hipEventRecord(tev[0], s));
+    const bool timed = ctx->timing && ctx->timing_launches++ % (uint64_t)ctx->timing_period == 0;
+    if (timed) SGC_HIP(ctx, hipEventRecord(tev[0], s));
     // tile records that are due are written by workgroups appended to the ingest launch (they depend on nothing it writes)
     const ExpandArgs ex = plan_expand_args(pl, c);
     const bool expand = ctx->use_mfma && pl->expand_pending;
@@ -1213,13 +1214,13 @@ int sgc_suffix_prefill_batched(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan *pl, 
     else if (expand)
         SGC_HIP(ctx, launch_expand_tiles(ex, s));
     pl->expand_pending = false;
-    if (ctx->timing) SGC_HIP(ctx, hipEventRecord(tev[1], s));
+    if (timed) SGC_HIP(ctx, hipEventRecord(tev[1], s));
     if (ctx->use_mfma) {
         SGC_HIP(ctx, launch_attn_mfma(a, s));
     } else {
         SGC_HIP(ctx, launch_attn_generic(a, pl->total_tokens * ctx->p.n_q_heads, s));
     }
-    if (ctx->timing) {
+    if (timed) {
         SGC_HIP(ctx, hipEventRecord(tev[2], s));
         ++ctx->timing_count;
     }
@@ -1400,12 +1401,15 @@ int sgc_decode_step_batched_noalloc(sgc_ctx *ctx, const sgc_cache *cc, sgc_plan 
 int sgc_timing_enable(sgc_ctx *ctx, int on)
 {
     if (!ctx) return fail(nullptr, SGC_EINVAL, "ctx is NULL");
+    if (on < 0) return fail(ctx, SGC_EINVAL, "timing period %d is negative", on);
     if (on) {
         for (auto &triple : ctx->ev)
             for (hipEvent_t &e : triple)
                 if (!e) SGC_HIP(ctx, hipEventCreate(&e));
     }
     ctx->timing = on != 0;
+    ctx->timing_period = on > 0 ? on : 1;
+    ctx->timing_launches = 0;
     ctx->timing_count = 0;
     return SGC_OK;
 }

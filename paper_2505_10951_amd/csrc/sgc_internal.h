@@ -287,6 +287,8 @@ struct sgc_ctx {
     bool stage_pending[kStageSlots] = {};
     int stage_next = 0;
     bool timing = false;            // record events around the suffix launch's kernels
+    int timing_period = 1;          // ... of every timing_period-th suffix launch
+    uint64_t timing_launches = 0;   // suffix launches since timing was switched on
     // the last kTimingRing timed suffix launches: events before ingest, between, after attention
     static constexpr int kTimingRing = 128;
     hipEvent_t ev[kTimingRing][3] = {};

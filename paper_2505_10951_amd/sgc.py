@@ -355,8 +355,9 @@ def sgc_union_subgraphs(ctx, labels: Sequence[int], n_clusters: int, node_lists,
             [out_edges[out_eoff[k]:out_eoff[k + 1]].copy() for k in range(n_clusters)])
 
 
-def sgc_timing_enable(ctx, on: bool) -> None:
-    _check(ctx, lib().sgc_timing_enable(ctx, 1 if on else 0))
+def sgc_timing_enable(ctx, on) -> None:
+    """on: False / 0 = off, True / 1 = every suffix launch, n > 1 = every n-th."""
+    _check(ctx, lib().sgc_timing_enable(ctx, int(on)))
 
 
 def sgc_timing_last(ctx) -> Tuple[float, float]:
@@ -367,7 +368,7 @@ def sgc_timing_last(ctx) -> Tuple[float, float]:
 
 
 def sgc_timing_get(ctx, back: int) -> Tuple[float, float]:
-    """The same for the launch `back` timed launches before the last one (the last 64 are kept)."""
+    """The same for the launch `back` timed launches before the last one (the last 128 are kept)."""
     a, b = ctypes.c_float(0), ctypes.c_float(0)
     _check(ctx, lib().sgc_timing_get(ctx, int(back), ctypes.byref(a), ctypes.byref(b)))
     return a.value, b.value

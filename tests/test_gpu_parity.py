@@ -587,8 +587,8 @@ def test_streaming_schedule_release_after_each_cluster_equals_all_resident():
 
 def test_steps_enqueued_back_to_back_equal_steps_run_one_at_a_time():
     """A serving loop enqueues batch after batch on one stream without waiting for the GPU: pages, plan tables and
-    work lists of a step are recycled for the next one while earlier kernels are still running, and the table
-    uploads run on the library's copy stream beside them.  Every step's output must be bit-identical to the same
+    work lists of a step are recycled for the next one while earlier kernels are still running.  Every step's
+    output must be bit-identical to the same
     step run alone with the GPU idle before and after (different batch composition and suffix lengths per step, so
     a table or page that is overwritten too early shows)."""
     w = workloads.custom("pipelined", n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=500000.0, io_dtype="bf16",
@@ -634,6 +634,39 @@ def test_steps_enqueued_back_to_back_equal_steps_run_one_at_a_time():
     o_ref, _ = orc.suffix_prefill_batched(labels, sub_cu, [caches[c][0] for c in clusters], [caches[c][1] for c in clusters],
                                           to_host_f32(dq), to_host_f32(dk), to_host_f32(dv), w.rope_base)
     assert np.abs(alone[0] - o_ref).max() <= 2e-2
+
+
+def test_kernel_timing_of_every_nth_launch():
+    """sgc_timing_enable(ctx, n): the events go around the kernels of launches 0, n, 2 n, ... only; the durations are
+    positive, launches beyond those recorded are refused, and timing never changes a result."""
+    w = workloads.custom("timing", n_q_heads=8, n_kv_heads=2, head_dim=128, rope_base=500000.0, io_dtype="bf16",
+                         prefix_len=[200, 77], cluster_sizes=[5, 3], suffix_range=(3, 40), seed=31)
+    q, k, v = w.suffix_qkv()
+    dq, dk, dv = (to_device(x, "bf16") for x in (q, k, v))
+    with Session(w, kernel=sgc.SGC_KERNEL_MFMA) as s:
+        for c in range(w.n_clusters):
+            s.alloc_cluster(c)
+            s.prefix_prefill(c)
+        s.assign(w.labels, w.suffix_len)
+        plain = to_host_f32(s.suffix_prefill(dq, dk, dv))
+        sgc.sgc_timing_enable(s.ctx, 4)
+        outs = [to_host_f32(s.suffix_prefill(dq, dk, dv)) for _ in range(9)]          # launches 0, 4 and 8 are timed
+        for back in range(3):
+            ingest_ms, attn_ms = sgc.sgc_timing_get(s.ctx, back)
+            assert 0.0 < ingest_ms < 10.0 and 0.0 < attn_ms < 10.0
+        with pytest.raises(sgc.SgcError) as e:
+            sgc.sgc_timing_get(s.ctx, 3)
+        assert e.value.status == sgc.SGC_ESTATE
+        sgc.sgc_timing_enable(s.ctx, 1)                                                # restarts the count: every launch
+        outs.append(to_host_f32(s.suffix_prefill(dq, dk, dv)))
+        assert sgc.sgc_timing_last(s.ctx)[1] > 0.0
+        with pytest.raises(sgc.SgcError):
+            sgc.sgc_timing_get(s.ctx, 1)
+        sgc.sgc_timing_enable(s.ctx, 0)
+        with pytest.raises(sgc.SgcError):
+            sgc.sgc_timing_last(s.ctx)
+    for o in outs:
+        assert np.array_equal(o, plain)
 
 
 @pytest.mark.parametrize("seed", list(range(300, 312)))

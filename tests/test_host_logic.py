@@ -259,6 +259,7 @@ def test_projection_entry_points_validate_before_touching_the_device():
         (lambda: sgc.sgc_suffix_prefill_batched(ctx, cache, plan, 0, 256, None, 256, 256), E),   # only one of k, v
         (lambda: sgc.sgc_prefix_prefill(ctx, cache, 0, 0, None, None, None, None, None, 32), E),  # nothing to do
         (lambda: sgc.sgc_timing_get(ctx, 128), E),                                              # beyond the ring
+        (lambda: sgc.sgc_timing_enable(ctx, -1), E),                                            # a negative period
     ]
     for i, (fn, status) in enumerate(bad):
         with pytest.raises(sgc.SgcError) as e:

@@ -342,24 +342,34 @@ __global__ void ingest_write_kernel(PoolGeom g, int layer, const int32_t *page_t
         sc_k = job.scale_kv[hk];
         sc_v = job.scale_kv[Hkv + hk];
     }
+    const bool v_as_given = via_tile && io_dtype == SGC_BF16;      // bf16 values into a bf16 cache: moved, not converted
     for (int it = threadIdx.x; it < kPageTokens * pairs; it += blockDim.x) {
         const int tok = it / pairs, cc = it % pairs;
         const int j = pg * kPageTokens + tok;
         float x1[8], x2[8], y1[8], y2[8];
+        uint4 r1 = make_uint4(0, 0, 0, 0), r2 = r1;
         if (j < P) {
             const int64_t row = ((int64_t)j * Hkv + hk) * d;
             load8(k, row + cc * 8, io_dtype, x1);
             load8(k, row + half + cc * 8, io_dtype, x2);
             if (rope) rope8(x1, x2, rope + (int64_t)j * half + cc * 8);
-            load8(v, row + cc * 8, io_dtype, y1);
-            load8(v, row + half + cc * 8, io_dtype, y2);
+            if (v_as_given) {
+                r1 = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(v) + row + cc * 8);
+                r2 = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(v) + row + half + cc * 8);
+            } else {
+                load8(v, row + cc * 8, io_dtype, y1);
+                load8(v, row + half + cc * 8, io_dtype, y2);
+            }
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) x1[i] = x2[i] = y1[i] = y2[i] = 0.f;
         }
         store8(kp, k_page_index(tok, cc * 8), k_elem_type(g.kv_dtype), x1, sc_k);
         store8(kp, k_page_index(tok, half + cc * 8), k_elem_type(g.kv_dtype), x2, sc_k);
-        if (via_tile) {
+        if (v_as_given) {
+            *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(vp) + tok * 128 + vt_pos(cc, tok) * 8) = r1;
+            *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(vp) + tok * 128 + vt_pos(8 + cc, tok) * 8) = r2;
+        } else if (via_tile) {
             store8(vp, tok * 128 + vt_pos(cc, tok) * 8, SGC_BF16, y1, 1.f);
             store8(vp, tok * 128 + vt_pos(8 + cc, tok) * 8, SGC_BF16, y2, 1.f);
         } else {
@@ -403,24 +413,34 @@ __global__ void suffix_ingest_kernel(AttnArgs a, const int32_t *spage_sq, int n_
     extern __shared__ __attribute__((aligned(16))) char page_img[];     // both images are built in LDS first
     char *kp = page_img, *vp = page_img + part;
     const bool via_tile = d == 128;          // V through the staging tile (see v_part_from_tile)
+    const bool v_as_given = via_tile && a.io_dtype == SGC_BF16;      // bf16 values into bf16 pages: moved, not converted
     for (int it = threadIdx.x; it < kPageTokens * pairs; it += blockDim.x) {
         const int tok = it / pairs, cc = it % pairs;
         const int j = tok0 + tok;
         float x1[8], x2[8], y1[8], y2[8];
+        uint4 r1 = make_uint4(0, 0, 0, 0), r2 = r1;
         if (j < S) {
             const int64_t row = ((src0 + j) * Hkv + hk) * d;
             load8(a.k, row + cc * 8, a.io_dtype, x1);
             load8(a.k, row + half + cc * 8, a.io_dtype, x2);
             if (a.rope) rope8(x1, x2, a.rope + (int64_t)(P + j) * half + cc * 8);
-            load8(a.v, row + cc * 8, a.io_dtype, y1);
-            load8(a.v, row + half + cc * 8, a.io_dtype, y2);
+            if (v_as_given) {
+                r1 = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.v) + row + cc * 8);
+                r2 = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.v) + row + half + cc * 8);
+            } else {
+                load8(a.v, row + cc * 8, a.io_dtype, y1);
+                load8(a.v, row + half + cc * 8, a.io_dtype, y2);
+            }
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) x1[i] = x2[i] = y1[i] = y2[i] = 0.f;
         }
         store8(kp, k_page_index(tok, cc * 8), kElemF16, x1, 1.f);
         store8(kp, k_page_index(tok, half + cc * 8), kElemF16, x2, 1.f);
-        if (via_tile) {
+        if (v_as_given) {
+            *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(vp) + tok * 128 + vt_pos(cc, tok) * 8) = r1;
+            *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(vp) + tok * 128 + vt_pos(8 + cc, tok) * 8) = r2;
+        } else if (via_tile) {
             store8(vp, tok * 128 + vt_pos(cc, tok) * 8, SGC_BF16, y1, 1.f);
             store8(vp, tok * 128 + vt_pos(8 + cc, tok) * 8, SGC_BF16, y2, 1.f);
         } else {

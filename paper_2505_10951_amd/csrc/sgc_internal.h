@@ -112,7 +112,7 @@ struct Tile {
 };
 static_assert(sizeof(Tile) == 160, "tile record layout");
 
-// What the host sends per tile; a small kernel writes the tile record from it and from tables the device already
+// What the host sends per tile; the device writes the tile record from it and from tables it already
 // holds (a fifth of the record's bytes cross the host link).
 struct TileSeed {
     int32_t cluster;     // suffix tiles: cluster id; prefix tiles: index of the job

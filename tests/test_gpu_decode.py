@@ -16,13 +16,13 @@ pytestmark = pytest.mark.gpu
 TOL = {"bf16": 2e-2, "fp8_e4m3": 6e-2}
 
 
-def _oracle_decode(w, layer, n_steps, caches):
+def _oracle_decode(w, layer, n_steps, caches, queries=None):
     """o_ref [n_steps][n_queries][Hq][d], lse_ref [n_steps][Hq][n_queries] (a query without question tokens
-    generates from the cached prompt and its own earlier tokens alone)."""
+    generates from the cached prompt and its own earlier tokens alone).  queries: only these are filled in."""
     dec = [w.decode_qkv(t, layer) for t in range(n_steps)]
     o = np.zeros((n_steps, w.n_queries, w.n_q_heads, w.head_dim))
     lse = np.zeros((n_steps, w.n_q_heads, w.n_queries))
-    for n in range(w.n_queries):
+    for n in (range(w.n_queries) if queries is None else queries):
         S = int(w.suffix_len[n])
         q, k, v = w.suffix_qkv_query(n, layer)
         qe = np.concatenate([q] + [d[0][n:n + 1] for d in dec])
@@ -130,6 +130,23 @@ def test_decode_long_questions_and_the_widest_head_group(g):
     err, lerr = np.abs(got[0] - o_ref).max(), np.abs(got[1] - lse_ref).max()
     print(f"  decode long questions g {g}: max_abs {err:.3e} lse {lerr:.3e}", flush=True)
     assert np.isfinite(got[0]).all() and err <= TOL["bf16"] and lerr <= 5e-2
+
+
+def test_decode_config1_llama3_8b_layer_full_size_sampled():
+    """The decode measurement of the benchmark, as it is launched there: configs[1] whole (320 queries, ten 1024-token
+    prompts in two key ranges each, 80 row tiles), all 32 steps; two queries of every cluster, all heads and steps, against
+    the oracle."""
+    w = workloads.config(1)
+    n_steps = 32
+    got = _run_decode(w, n_steps, kernel=sgc.SGC_KERNEL_AUTO)[0]
+    rng = np.random.default_rng(9)
+    picks = sorted(int(n) for c in range(w.n_clusters) for n in rng.choice(np.flatnonzero(w.labels == c), 2, replace=False))
+    o_ref, lse_ref = _oracle_decode(w, 0, n_steps, oracle_caches(w, 0, threads=8), queries=picks)
+    err = np.abs(got[0][:, picks] - o_ref[:, picks]).max()
+    lerr = np.abs(got[1][:, :, picks] - lse_ref[:, :, picks]).max()
+    print(f"  decode configs[1] full size, {len(picks)} queries x {n_steps} steps: max_abs {err:.3e} lse {lerr:.3e}", flush=True)
+    assert np.isfinite(got[0]).all() and np.isfinite(got[1]).all()
+    assert err <= TOL["bf16"] and lerr <= 5e-2
 
 
 @pytest.mark.parametrize("seed", [400, 401, 402, 403, 404, 405])

@@ -469,6 +469,31 @@ def test_config1_llama3_8b_layer_full_size_every_row():
     assert np.isfinite(out["o"]).all() and np.abs(out["o"]).max() < 8
 
 
+def test_config1_prefix_prefill_batched_full_size_every_row():
+    """The first half of the benchmark's step as it is launched there: the ten 1024-token prompts of configs[1] in ONE
+    batched call with their queries (ingest + causal attention, 2560 row tiles); every row of every cluster, its LSE and
+    the exported cache against the oracle."""
+    w = workloads.config(1)
+    clusters = list(range(w.n_clusters))
+    with Session(w) as s:
+        for c in clusters:
+            s.alloc_cluster(c)
+        got = s.prefix_prefill_batched(clusters, 0, with_q=True, want_lse=True)
+        worst = worst_lse = 0.0
+        for c, (do, dlse) in zip(clusters, got):
+            pk, pv = w.prefix_kv(c)
+            ck, cv, o_ref, lse_ref = orc.prefix_prefill(w.prefix_q(c), pk, pv, w.rope_base, want_lse=True)
+            ek, ev, _, _ = s.export_cluster(c)
+            assert np.array_equal(ev, pv)
+            assert np.all(np.abs(ek - ck) <= np.abs(ck) * 2.0 ** -11 + 1e-5)
+            o = to_host_f32(do)
+            assert np.isfinite(o).all()
+            worst = max(worst, float(np.abs(o - o_ref).max()))
+            worst_lse = max(worst_lse, float(np.abs(dlse.cpu().numpy() - lse_ref).max()))
+        _say(f"  configs[1] prompts, {len(clusters)} x {int(w.prefix_len[0])} tokens x {w.n_q_heads} heads: max_abs {worst:.3e} lse {worst_lse:.3e}")
+        assert worst <= TOL_BF16 and worst_lse <= 2e-2
+
+
 def test_config2_llama2_7b_ragged_full_size_every_row():
     w = workloads.config(2)
     _say("config 2", w.name, "T", w.total_suffix_tokens, "flop %.3e" % w.flops())

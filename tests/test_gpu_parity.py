@@ -90,13 +90,12 @@ def test_mfma_small_mha_ragged():
     _check_suffix(w, out, tol=TOL_BF16, tight=tight, lse_tol=lse_bar)
 
 
-@pytest.mark.parametrize("variant", [0, 2])
-def test_mfma_other_workgroup_shapes(variant, monkeypatch):
-    """The kernel's two other shapes (8 wavefronts x 32 rows, 4 wavefronts x 64 rows: development switches read
-    when a context is created) give the same results to the same bars, prompt and batch, bf16 and fp8 cache."""
-    monkeypatch.setenv("SGC_MFMA_VARIANT", str(variant))
+@pytest.mark.parametrize("seed", [31, 33])
+def test_mfma_small_gqa_three_prompt_lengths_both_cache_types(seed):
+    """Prompts of 200, 71 and 300 tokens (four, two and five 64-key steps, the last ones ragged) without outlier channels,
+    bf16 and fp8 cache, prompt and batch to the stated bars."""
     for kv in ("bf16", "fp8_e4m3"):
-        w = _small_gqa(seed=31 + variant, kv_dtype=kv, prefix_len=[200, 71, 300], k_outlier_scale=1.0)
+        w = _small_gqa(seed=seed, kv_dtype=kv, prefix_len=[200, 71, 300], k_outlier_scale=1.0)
         out = run_workload(w, kernel=sgc.SGC_KERNEL_MFMA)
         _check_bookkeeping(w, out)
         _check_suffix(w, out, tol=TOL_BF16 if kv == "bf16" else TOL_FP8)

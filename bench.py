@@ -303,6 +303,42 @@ def layer_measurement(s, w, layer, d_model, reps, stream):
                          "traffic_source": PROFILED_QKV_GEMM_BYTES.get((w.name, d_model), (None, None))[1]}}
 
 
+def host_steps(s, w, ms_per_step: float):
+    """The host-side steps in front of the prefill (SubGCache Sec. 3.2 and 3.3; the paper puts "cluster processing" below
+    2.1 % / 6 % of a query's latency): agglomerative clustering of the batch's query embeddings under Table 3's linkages,
+    the per-cluster union of the retrieved subgraphs, and the query -> cluster -> cache mapping, each as the median of five
+    calls on the same workload (synthetic embeddings and subgraphs with the workload's cluster structure)."""
+    from paper_2505_10951_amd import sgc
+    emb = w.query_embeddings(dim=64)
+    node_lists, edge_lists = w.retrieved_subgraphs()
+
+    def med_us(fn):
+        ts = []
+        for _ in range(5):
+            t0 = time.perf_counter()
+            fn()
+            ts.append(time.perf_counter() - t0)
+        return float(np.median(ts) * 1e6)
+
+    out = {"n_queries": int(w.n_queries), "embedding_dim": 64,
+           "cluster_queries_us": {name: med_us(lambda name=name: sgc.sgc_cluster_queries(s.ctx, emb, w.n_clusters, name))
+                                  for name in sgc.LINKAGES},
+           "union_subgraphs_us": med_us(lambda: sgc.sgc_union_subgraphs(s.ctx, w.labels, w.n_clusters, node_lists, edge_lists)),
+           "assign_clusters_us": med_us(lambda: s.assign(w.labels, w.suffix_len))}
+    out["labels_recovered"] = bool(_same_partition(sgc.sgc_cluster_queries(s.ctx, emb, w.n_clusters, "ward"), w.labels))
+    total = out["cluster_queries_us"]["ward"] + out["union_subgraphs_us"] + out["assign_clusters_us"]
+    out["share_of_a_step"] = total / (ms_per_step * 1e3)
+    out["us_per_query"] = total / max(int(w.n_queries), 1)
+    return out
+
+
+def _same_partition(a, b) -> bool:
+    """Two labelings describe the same partition (cluster numbers may differ)."""
+    a, b = np.asarray(a), np.asarray(b)
+    pairs = set(zip(a.tolist(), b.tolist()))
+    return len(pairs) == len(set(a.tolist())) == len(set(b.tolist()))
+
+
 def other_config(index: int, steps: int, warmup: int, threads: int, kernel=None):
     """One of the other benchmark configurations: its batched suffix prefill launched `steps` times (caches filled
     and the plan uploaded beforehand; kernel durations from the library's HIP events on the launch stream), the
@@ -406,6 +442,8 @@ def main() -> int:
                     help="wait for the GPU after every timed step (a step's latency) instead of enqueueing the steps back to back "
                          "between the two synchronisations that bracket the timed region")
     ap.add_argument("--pipelined", action="store_true", help=argparse.SUPPRESS)      # the default; accepted for older command lines
+    ap.add_argument("--no-host-steps", dest="host_steps", action="store_false",
+                    help="skip the timing of the host steps in front of the prefill (clustering, subgraph union, assignment)")
     ap.add_argument("--kernel-timing-period", type=int, default=4,
                     help="HIP events around the suffix kernels of every n-th timed step (1 = every step)")
     ap.add_argument("--suffix-only", action="store_true", help="time only the batched suffix launch (profiling aid)")
@@ -625,6 +663,8 @@ def main() -> int:
     if args.decode_steps > 0 and dtype == "bf16":
         out["decode"] = decode_measurement(s, w, layer, args.decode_steps, dq, dk, dv, do, all_clusters,
                                            pq_ptrs, pk_ptrs, pv_ptrs, po_ptrs, stream)
+    if not args.suffix_only and args.host_steps:
+        out["host_steps"] = host_steps(s, w, ms_per_step)
     s.close()
     if args.cpu_budget > 0:
         out["cpu_baseline"], rows, o_ref = cpu_baseline(w, args.cpu_budget)

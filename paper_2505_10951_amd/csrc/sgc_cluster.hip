@@ -7,7 +7,9 @@
 //
 // The batch is small (Table 4: 50-200 queries), so the whole inter-cluster distance matrix is kept in
 // fp64 and updated after each merge with the Lance-Williams recurrence of the linkage; the closest
-// pair is found by a scan.  O(m^2) memory, O(m^3) time, no device work.
+// pair is the one a full scan would find, read off per-slot nearest partners that a merge updates in place
+// (centroid linkage, which can bring clusters closer, included: a changed row is scanned again).  O(m^2) memory,
+// O(m^2) time unless many slots share one nearest partner, no device work.
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
@@ -53,44 +55,81 @@ extern "C" int sgc_cluster_queries(sgc_ctx *ctx, int32_t m, int32_t dim, const f
 
     // Ward and centroid recur on squared Euclidean distances, the other three on plain ones.
     const bool squared = linkage == SGC_LINKAGE_WARD || linkage == SGC_LINKAGE_CENTROID;
-    std::vector<double> dist;
-    std::vector<int32_t> size, parent;
+    std::vector<double> dist, xt, acc, near_d;
+    std::vector<int32_t> size, parent, near_j;
     std::vector<char> alive;
     try {
         dist.assign((size_t)m * m, 0.0);
+        xt.resize((size_t)dim * m);
+        acc.resize(m);
+        near_d.assign(m, std::numeric_limits<double>::infinity());
+        near_j.assign(m, -1);
         size.assign(m, 1);
         parent.resize(m);
         alive.assign(m, 1);
     } catch (const std::bad_alloc &) {
         return fail_cluster(ctx, SGC_ENOMEM, "host allocation failed");
     }
+    // Distances: every pair's sum runs over the coordinates in order (t = 0, 1, ...), as a scalar loop would; with the
+    // embeddings transposed the inner loop runs over the partners j of one i and vectorises.
+    for (int i = 0; i < m; ++i)
+        for (int t = 0; t < dim; ++t) xt[(size_t)t * m + i] = (double)embeddings[(size_t)i * dim + t];
     for (int i = 0; i < m; ++i) {
         parent[i] = i;
-        for (int j = i + 1; j < m; ++j) {
-            double acc = 0.0;
-            for (int t = 0; t < dim; ++t) {
-                const double d = (double)embeddings[(size_t)i * dim + t] - (double)embeddings[(size_t)j * dim + t];
-                acc += d * d;
+        for (int j = i + 1; j < m; ++j) acc[j] = 0.0;
+        int t = 0;
+        for (; t + 4 <= dim; t += 4) {          // four coordinates per pass over the partners, added in order
+            const double *c0 = &xt[(size_t)t * m], *c1 = c0 + m, *c2 = c1 + m, *c3 = c2 + m;
+            const double x0 = c0[i], x1 = c1[i], x2 = c2[i], x3 = c3[i];
+            for (int j = i + 1; j < m; ++j) {
+                const double d0 = x0 - c0[j], d1 = x1 - c1[j], d2 = x2 - c2[j], d3 = x3 - c3[j];
+                double a = acc[j];
+                a += d0 * d0;
+                a += d1 * d1;
+                a += d2 * d2;
+                a += d3 * d3;
+                acc[j] = a;
             }
-            const double v = squared ? acc : sqrt(acc);
+        }
+        for (; t < dim; ++t) {
+            const double *col = &xt[(size_t)t * m];
+            const double xi = col[i];
+            for (int j = i + 1; j < m; ++j) {
+                const double d = xi - col[j];
+                acc[j] += d * d;
+            }
+        }
+        for (int j = i + 1; j < m; ++j) {
+            const double v = squared ? acc[j] : sqrt(acc[j]);
             dist[(size_t)i * m + j] = dist[(size_t)j * m + i] = v;
         }
     }
-    // A cluster lives in the slot of its smallest member, so scanning slots (i < j) in order and taking
-    // strict minima gives the tie rule: the pair with the smallest first members wins.
+    // A cluster lives in the slot of its smallest member.  The pair to merge is the one a scan over slots i < j in
+    // order with strict minima would find (among equally close pairs the one with the smallest first members, then the
+    // smallest second); the scan is not repeated for every merge: every slot keeps its nearest partner above it
+    // (near_j[i] > i, the smallest such j among equals), which a merge of (bi, bj) can only change for slots below bj.
+    auto rescan = [&](int i) {
+        double best = std::numeric_limits<double>::infinity();
+        int bj = -1;
+        const double *row = &dist[(size_t)i * m];
+        for (int j = i + 1; j < m; ++j)
+            if (alive[j] && row[j] < best) {
+                best = row[j];
+                bj = j;
+            }
+        near_d[i] = best;
+        near_j[i] = bj;
+    };
+    for (int i = 0; i < m; ++i) rescan(i);
     for (int remaining = m; remaining > n_clusters; --remaining) {
         double best = std::numeric_limits<double>::infinity();
-        int bi = -1, bj = -1;
-        for (int i = 0; i < m; ++i) {
-            if (!alive[i]) continue;
-            const double *row = &dist[(size_t)i * m];
-            for (int j = i + 1; j < m; ++j)
-                if (alive[j] && row[j] < best) {
-                    best = row[j];
-                    bi = i;
-                    bj = j;
-                }
-        }
+        int bi = -1;
+        for (int i = 0; i < m; ++i)
+            if (alive[i] && near_d[i] < best) {
+                best = near_d[i];
+                bi = i;
+            }
+        const int bj = near_j[bi];
         const double ni = size[bi], nj = size[bj], dij = dist[(size_t)bi * m + bj];
         for (int k = 0; k < m; ++k) {
             if (!alive[k] || k == bi || k == bj) continue;
@@ -112,6 +151,21 @@ extern "C" int sgc_cluster_queries(sgc_ctx *ctx, int32_t m, int32_t dim, const f
         size[bi] += size[bj];
         alive[bj] = 0;
         parent[bj] = bi;
+        // nearest partners: slot bi has a new row; a slot below bi sees a new distance to bi and loses bj; a slot
+        // between them loses bj; slots above bj see nothing of the pair among their partners
+        rescan(bi);
+        for (int k = 0; k < bj; ++k) {
+            if (!alive[k] || k == bi) continue;
+            if (near_j[k] == bj || near_j[k] == bi) {
+                rescan(k);
+            } else if (k < bi) {
+                const double v = dist[(size_t)k * m + bi];
+                if (v < near_d[k] || (v == near_d[k] && bi < near_j[k])) {
+                    near_d[k] = v;
+                    near_j[k] = bi;
+                }
+            }
+        }
     }
     // clusters are numbered by their first member
     std::vector<int32_t> id(m, -1);

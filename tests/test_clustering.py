@@ -28,6 +28,73 @@ def test_exact_ties_follow_the_stated_rule(linkage):
     assert sgc.sgc_cluster_queries(None, line, 7, "single").tolist() == [0, 0, 1, 2, 3, 4, 5, 6]
 
 
+def _full_scan_lance_williams(x, n_clusters, linkage):
+    """The library's algorithm without its bookkeeping: fp64 distance matrix (a pair's sum runs over the coordinates in
+    order), the closest pair found by a scan over slots i < j with strict minima at EVERY merge, the linkage's
+    Lance-Williams update written out.  Same arithmetic, so the merges must agree to the last tie."""
+    m, dim = x.shape
+    squared = linkage in ("ward", "centroid")
+    d = [[0.0] * m for _ in range(m)]
+    for i in range(m):
+        for j in range(i + 1, m):
+            acc = 0.0
+            for t in range(dim):
+                diff = float(x[i, t]) - float(x[j, t])
+                acc += diff * diff
+            d[i][j] = d[j][i] = acc if squared else float(np.sqrt(np.float64(acc)))
+    size, alive, parent = [1] * m, [True] * m, list(range(m))
+    for _ in range(m - n_clusters):
+        best, bi, bj = float("inf"), -1, -1
+        for i in range(m):
+            if alive[i]:
+                for j in range(i + 1, m):
+                    if alive[j] and d[i][j] < best:
+                        best, bi, bj = d[i][j], i, j
+        ni, nj, dij = float(size[bi]), float(size[bj]), d[bi][bj]
+        for k in range(m):
+            if not alive[k] or k in (bi, bj):
+                continue
+            dki, dkj, nk = d[k][bi], d[k][bj], float(size[k])
+            if linkage == "single":
+                v = dki if dki < dkj else dkj
+            elif linkage == "complete":
+                v = dki if dki > dkj else dkj
+            elif linkage == "average":
+                v = (ni * dki + nj * dkj) / (ni + nj)
+            elif linkage == "centroid":
+                v = (ni * dki + nj * dkj) / (ni + nj) - ni * nj * dij / ((ni + nj) * (ni + nj))
+            else:
+                v = ((nk + ni) * dki + (nk + nj) * dkj - nk * dij) / (nk + ni + nj)
+            d[k][bi] = d[bi][k] = v
+        size[bi] += size[bj]
+        alive[bj] = False
+        parent[bj] = bi
+    ids, nxt = {}, 0
+    for i in range(m):
+        if alive[i]:
+            ids[i] = nxt
+            nxt += 1
+    out = []
+    for i in range(m):
+        r = i
+        while parent[r] != r:
+            r = parent[r]
+        out.append(ids[r])
+    return out
+
+
+@pytest.mark.parametrize("linkage", orc.LINKAGES)
+def test_nearest_partner_bookkeeping_equals_a_full_scan_per_merge(linkage):
+    """Grids with many equal distances (every linkage, centroid's non-monotone merges included) and generic points: the
+    labels equal those of a scan over all pairs at every merge, whatever the ties."""
+    rng = np.random.default_rng(11)
+    for trial in range(24):
+        m, dim = int(rng.integers(2, 34)), int(rng.integers(1, 4))
+        x = (rng.integers(0, 4, size=(m, dim)) if trial % 3 else rng.standard_normal((m, dim))).astype(np.float32)
+        for c in sorted({1, max(1, m // 3), max(1, m - 2), m}):
+            assert sgc.sgc_cluster_queries(None, x, c, linkage).tolist() == _full_scan_lance_williams(x, c, linkage), (trial, m, dim, c)
+
+
 @pytest.mark.parametrize("linkage", orc.LINKAGES)
 def test_duplicates_merge_first(linkage):
     x = np.array([[5, 5], [1, 1], [5, 5], [9, 0], [1, 1]], dtype=np.float32)

@@ -311,6 +311,10 @@ def host_steps(s, w, ms_per_step: float):
     from paper_2505_10951_amd import sgc
     emb = w.query_embeddings(dim=64)
     node_lists, edge_lists = w.retrieved_subgraphs()
+    fresh = sgc.sgc_cache_free_pages(s.cache) == sgc.sgc_cache_total_pages(s.cache)
+    if fresh:                                   # the mapping needs the clusters' caches to exist (host-side allocation only)
+        for c in range(w.n_clusters):
+            sgc.sgc_cache_alloc_cluster(s.ctx, s.cache, c, int(w.prefix_len[c]))
 
     def med_us(fn):
         ts = []
@@ -329,6 +333,9 @@ def host_steps(s, w, ms_per_step: float):
     total = out["cluster_queries_us"]["ward"] + out["union_subgraphs_us"] + out["assign_clusters_us"]
     out["share_of_a_step"] = total / (ms_per_step * 1e3)
     out["us_per_query"] = total / max(int(w.n_queries), 1)
+    if fresh:
+        for c in range(w.n_clusters):
+            sgc.sgc_cache_free_cluster(s.ctx, s.cache, c)
     return out
 
 

@@ -328,18 +328,14 @@ def sgc_union_subgraphs(ctx, labels: Sequence[int], n_clusters: int, node_lists,
     m = labels.shape[0]
     if len(node_lists) != m or len(edge_lists) != m:
         raise ValueError("one node list and one edge list per query")
+    nl = [np.asarray(x, dtype=np.int32).reshape(-1) for x in node_lists]
+    el = [np.asarray(x, dtype=np.int32).reshape(-1, 2) for x in edge_lists]
     node_off = np.zeros(m + 1, dtype=np.int64)
     edge_off = np.zeros(m + 1, dtype=np.int64)
-    for i in range(m):
-        node_off[i + 1] = node_off[i] + len(node_lists[i])
-        edge_off[i + 1] = edge_off[i] + len(edge_lists[i])
-    nodes = np.zeros(max(int(node_off[m]), 1), dtype=np.int32)
-    edges = np.zeros((max(int(edge_off[m]), 1), 2), dtype=np.int32)
-    for i in range(m):
-        if len(node_lists[i]):
-            nodes[node_off[i]:node_off[i + 1]] = np.asarray(node_lists[i], dtype=np.int32)
-        if len(edge_lists[i]):
-            edges[edge_off[i]:edge_off[i + 1]] = np.asarray(edge_lists[i], dtype=np.int32).reshape(-1, 2)
+    np.cumsum([x.shape[0] for x in nl], out=node_off[1:])
+    np.cumsum([x.shape[0] for x in el], out=edge_off[1:])
+    nodes = np.ascontiguousarray(np.concatenate(nl + [np.zeros(1, dtype=np.int32)]))        # (never empty)
+    edges = np.ascontiguousarray(np.concatenate(el + [np.zeros((1, 2), dtype=np.int32)]))
     out_noff = np.zeros(n_clusters + 1, dtype=np.int64)
     out_eoff = np.zeros(n_clusters + 1, dtype=np.int64)
     out_nodes = np.zeros_like(nodes)
